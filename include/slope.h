@@ -1,0 +1,136 @@
+/*
+ * slope.h - C ABI of the MI355X (gfx950) double-pruned 2:4 sparse linear layer.
+ *
+ * The operations are those of SLoPe's sparse pretraining step for one linear layer
+ * (paper Sec. 2, Eq. 1-6, Eq. 11 and Algorithm 1):
+ *
+ *     W in R^{d_out x d_in},  X in R^{b x d_in},  Y, dY in R^{b x d_out},  dX in R^{b x d_in}
+ *     W^R      W pruned 2:4 along d_in   (inside each row of W)       forward operand
+ *     W^{R,C}  W^R pruned 2:4 once more along d_out (inside each column)  backward operand
+ *
+ * Conventions common to every call
+ *   - All tensor pointers are DEVICE pointers to caller-owned memory, 16-byte aligned,
+ *     dense tensors row-major bf16.  The library allocates nothing, keeps no state
+ *     between calls and never synchronises: work is queued on `stream`
+ *     (a hipStream_t passed as void*; NULL = the default stream).
+ *   - Return value: SLOPE_OK or a negative slope_status.  Argument errors are found on
+ *     the host before anything is launched; nothing is written in that case.
+ *     After SLOPE_ERR_HIP, slope_last_hip_error() returns the hipError_t as int.
+ *   - Packed 2:4 form of a [rows, cols] matrix pruned along cols (cols % 8 == 0):
+ *       vals bf16[rows, cols/2]   vals[r][2g+k] = k-th kept element (ascending column) of
+ *                                 the aligned group g = columns 4g..4g+3 of row r
+ *       meta u8  [rows, cols/8]   group g sits in bits 4*(g&1)..4*(g&1)+3 of meta[r][g/2]
+ *                                 as idx0 | idx1 << 2 with idx0 < idx1 (positions inside
+ *                                 the group)
+ *     A group with fewer than two kept elements names its lowest free positions as
+ *     padding; padded slots hold +0.0.  Only this encoding is produced.
+ *   - Bit masks: u8[rows, cols/8], element c of a row is bit (c & 7) of byte c/8.
+ *   - Magnitude order: the bf16 bit pattern with the sign cleared, compared as an
+ *     integer; on equal magnitude the lower index inside the group wins.  (+0 == -0;
+ *     NaN ranks above Inf.)
+ *   - Shape limits: prune calls need d_in % 8 == 0 and d_out % 8 == 0; the three product
+ *     calls need d_in % 64 == 0 and d_out % 64 == 0; b >= 1 is arbitrary; every extent
+ *     must stay below 2^31 (SLOPE_ERR_SHAPE otherwise).
+ */
+#ifndef SLOPE_H
+#define SLOPE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SLOPE_OK = 0,
+    SLOPE_ERR_NULL = -1,        /* a required pointer is NULL                          */
+    SLOPE_ERR_SHAPE = -2,       /* extent <= 0, not a multiple of its quantum, too big */
+    SLOPE_ERR_ALIGN = -3,       /* a pointer is not 16-byte aligned                    */
+    SLOPE_ERR_UNSUPPORTED = -4, /* N:M other than 2:4, adapter rank not supported      */
+    SLOPE_ERR_HIP = -5          /* a launch failed; see slope_last_hip_error()         */
+} slope_status;
+
+/* Library version (major*100 + minor) and the last hipError_t seen by this thread. */
+int slope_version(void);
+int slope_last_hip_error(void);
+const char* slope_status_string(int status);
+
+/* Byte sizes of the packed form of a [rows, cols] matrix pruned along cols
+ * (2 x 16 bits of values and 4 bits of index per group of four; Sec. 2.1 memory analysis,
+ * with two 2-bit indices instead of the 3-bit minimum of Eq. 7). 0 on invalid shape. */
+size_t slope_packed_vals_bytes(int64_t rows, int64_t cols);
+size_t slope_packed_meta_bytes(int64_t rows, int64_t cols);
+size_t slope_mask_bytes(int64_t rows, int64_t cols);
+
+/* Scratch that slope_spmm_fwd needs when adapters are active (0 for r == 0):
+ * T = X L as bf16[b, r] plus K-contiguous copies of L and R. */
+size_t slope_spmm_fwd_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out, int64_t r);
+
+/*
+ * slope_prune_rows - magnitude N:M pruning of W along d_in into W^R (Sec. 2.1; the
+ * "prune" and "compress" steps of the sparse setup, App. B and App. K).
+ *   W        in   bf16[d_out, d_in]
+ *   n, m     in   only 2, 4 is implemented (others: SLOPE_ERR_UNSUPPORTED)
+ *   Wr_vals  out  bf16[d_out, d_in/2]   packed values of W^R
+ *   Wr_meta  out  u8[d_out, d_in/8]     packed indices of W^R
+ *   mask_or_null out u8[d_out, d_in/8]  bit mask of the kept positions, or NULL to skip
+ * Exactly two positions are kept in every group, zeros included.
+ */
+slope_status slope_prune_rows(const void* W, int64_t d_out, int64_t d_in, int n, int m,
+                              void* Wr_vals, void* Wr_meta, void* mask_or_null, void* stream);
+
+/*
+ * slope_double_prune - second 2:4 prune of the already row-pruned weight, taken along
+ * d_out, giving W^{R,C} for the backward pass (Sec. 2.1, Eq. 6: transpose the N:M matrix,
+ * then impose N:M again).  Only positions named by Wr_meta compete; a group of four along
+ * d_out keeps its min(2, #candidates) largest magnitudes.
+ *   Wr_vals, Wr_meta  in   packed W^R as written by slope_prune_rows
+ *   WrcT_vals  out  bf16[d_in, d_out/2]   packed (W^{R,C})^T: rows = d_in, groups along d_out
+ *   WrcT_meta  out  u8[d_in, d_out/8]
+ *   maskrc_or_null out u8[d_out, d_in/8]  bit mask of W^{R,C} in W's orientation, or NULL
+ */
+slope_status slope_double_prune(const void* Wr_vals, const void* Wr_meta, int64_t d_out, int64_t d_in,
+                                void* WrcT_vals, void* WrcT_meta, void* maskrc_or_null, void* stream);
+
+/*
+ * slope_spmm_fwd - Y = X (W^R)^T, plus (X L) R when adapters are active
+ * (Eq. 4; Eq. 11 for the low-rank term with L in R^{d_in x r}, R in R^{r x d_out}).
+ *   X   in  bf16[b, d_in]
+ *   Wr_vals, Wr_meta in packed W^R
+ *   L_or_null in bf16[d_in, r], R_or_null in bf16[r, d_out]; both NULL or r == 0 means no
+ *       adapter (the case for all but the last 1 % of pretraining, Sec. 2.2).
+ *       r must be a multiple of 32 and at most 512.
+ *   Y   out bf16[b, d_out]; fp32 accumulation; X L is rounded to bf16 before it meets R.
+ *   workspace: device scratch of slope_spmm_fwd_workspace_bytes(...) bytes, 256-byte
+ *       aligned; may be NULL when no adapter is active.  Contents are undefined after the call.
+ */
+slope_status slope_spmm_fwd(const void* X, int64_t b, const void* Wr_vals, const void* Wr_meta,
+                            int64_t d_out, int64_t d_in,
+                            const void* L_or_null, const void* R_or_null, int64_t r,
+                            void* Y, void* workspace, void* stream);
+
+/*
+ * slope_spmm_bwd_x - dX = dY W^{R,C}  (Eq. 6; Algorithm 1 line 11).
+ *   dY  in  bf16[b, d_out]
+ *   WrcT_vals, WrcT_meta in packed (W^{R,C})^T as written by slope_double_prune
+ *   dX  out bf16[b, d_in]; fp32 accumulation.
+ */
+slope_status slope_spmm_bwd_x(const void* dY, int64_t b, const void* WrcT_vals, const void* WrcT_meta,
+                              int64_t d_out, int64_t d_in, void* dX, void* stream);
+
+/*
+ * slope_wgrad_masked - dW = dY^T X (Eq. 5) evaluated with a dense contraction over the b
+ * tokens and written only at the positions W^R keeps, in W^R's packed order
+ * (Algorithm 1 lines 12-13: dense product, then prune-and-compress with the weight's mask;
+ * App. K: the result is d_out x d_in/2).
+ *   dY in bf16[b, d_out], X in bf16[b, d_in], Wr_meta in u8[d_out, d_in/8]
+ *   dW_vals out bf16[d_out, d_in/2]; fp32 accumulation.
+ */
+slope_status slope_wgrad_masked(const void* dY, const void* X, int64_t b, const void* Wr_meta,
+                                int64_t d_out, int64_t d_in, void* dW_vals, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLOPE_H */
