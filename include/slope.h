@@ -28,9 +28,9 @@
  *   - Magnitude order: the bf16 bit pattern with the sign cleared, compared as an
  *     integer; on equal magnitude the lower index inside the group wins.  (+0 == -0;
  *     NaN ranks above Inf.)
- *   - Shape limits: prune calls need d_in % 8 == 0 and d_out % 8 == 0; the three product
- *     calls need d_in % 64 == 0 and d_out % 64 == 0; b >= 1 is arbitrary; every extent
- *     must stay below 2^31 (SLOPE_ERR_SHAPE otherwise).
+ *   - Shape limits: slope_prune_rows needs d_in % 8 == 0 (any d_out >= 1); slope_double_prune
+ *     and the three product calls need d_in % 64 == 0 and d_out % 64 == 0; b >= 1 is
+ *     arbitrary; every extent must stay below 2^31 (SLOPE_ERR_SHAPE otherwise).
  */
 #ifndef SLOPE_H
 #define SLOPE_H

@@ -1,0 +1,170 @@
+"""Thin ctypes binding of libslope.so (the C ABI declared in include/slope.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels.  PyTorch supplies
+device memory and the current stream.  There is no fallback: if the library is missing or a
+call returns an error status, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libslope.so")
+
+SLOPE_OK = 0
+SLOPE_ERR_NULL = -1
+SLOPE_ERR_SHAPE = -2
+SLOPE_ERR_ALIGN = -3
+SLOPE_ERR_UNSUPPORTED = -4
+SLOPE_ERR_HIP = -5
+
+_P, _I64, _INT, _SZ = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
+
+# name -> (restype, argtypes); mirrors include/slope.h one to one
+SIGNATURES = {
+    "slope_version": (_INT, []),
+    "slope_last_hip_error": (_INT, []),
+    "slope_status_string": (ctypes.c_char_p, [_INT]),
+    "slope_packed_vals_bytes": (_SZ, [_I64, _I64]),
+    "slope_packed_meta_bytes": (_SZ, [_I64, _I64]),
+    "slope_mask_bytes": (_SZ, [_I64, _I64]),
+    "slope_spmm_fwd_workspace_bytes": (_SZ, [_I64, _I64, _I64, _I64]),
+    "slope_prune_rows": (_INT, [_P, _I64, _I64, _INT, _INT, _P, _P, _P, _P]),
+    "slope_double_prune": (_INT, [_P, _P, _I64, _I64, _P, _P, _P, _P]),
+    "slope_spmm_fwd": (_INT, [_P, _I64, _P, _P, _I64, _I64, _P, _P, _I64, _P, _P, _P]),
+    "slope_spmm_bwd_x": (_INT, [_P, _I64, _P, _P, _I64, _I64, _P, _P]),
+    "slope_wgrad_masked": (_INT, [_P, _P, _I64, _P, _I64, _I64, _P, _P]),
+}
+
+_lib = None
+
+
+class SlopeError(RuntimeError):
+    def __init__(self, call: str, status: int):
+        self.status = status
+        msg = lib().slope_status_string(status).decode()
+        if status == SLOPE_ERR_HIP:
+            msg += " (hipError_t %d)" % lib().slope_last_hip_error()
+        super().__init__("%s failed with status %d: %s" % (call, status, msg))
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library; raises if it has not been built (run paper_2405_16325_amd/build.py)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                "%s is missing: build it with `python -m paper_2405_16325_amd.build`" % LIB_PATH)
+        handle = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(handle, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = handle
+    return _lib
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(call: str, status: int):
+    if status != SLOPE_OK:
+        raise SlopeError(call, status)
+
+
+def _dev(*tensors):
+    for t in tensors:
+        if t is not None and (not t.is_cuda or not t.is_contiguous()):
+            raise ValueError("tensors must be contiguous device tensors")
+
+
+def slope_prune_rows(W: torch.Tensor, want_mask: bool = False, out=None):
+    """W bf16[d_out, d_in] -> (vals bf16[d_out, d_in/2], meta u8[d_out, d_in/8], mask u8 or None)."""
+    _dev(W)
+    d_out, d_in = W.shape
+    if out is None:
+        vals = torch.empty((d_out, d_in // 2), dtype=torch.bfloat16, device=W.device)
+        meta = torch.empty((d_out, d_in // 8), dtype=torch.uint8, device=W.device)
+        mask = torch.empty((d_out, d_in // 8), dtype=torch.uint8, device=W.device) if want_mask else None
+    else:
+        vals, meta, mask = out
+    _check("slope_prune_rows", lib().slope_prune_rows(_ptr(W), d_out, d_in, 2, 4, _ptr(vals), _ptr(meta),
+                                                      _ptr(mask), _stream()))
+    return vals, meta, mask
+
+
+def slope_double_prune(vals: torch.Tensor, meta: torch.Tensor, want_mask: bool = False, out=None):
+    """Packed W^R -> (valsT bf16[d_in, d_out/2], metaT u8[d_in, d_out/8], maskrc u8[d_out, d_in/8] or None)."""
+    _dev(vals, meta)
+    d_out, d_in = vals.shape[0], vals.shape[1] * 2
+    if out is None:
+        vals_t = torch.empty((d_in, d_out // 2), dtype=torch.bfloat16, device=vals.device)
+        meta_t = torch.empty((d_in, d_out // 8), dtype=torch.uint8, device=vals.device)
+        mask = torch.empty((d_out, d_in // 8), dtype=torch.uint8, device=vals.device) if want_mask else None
+    else:
+        vals_t, meta_t, mask = out
+    _check("slope_double_prune", lib().slope_double_prune(_ptr(vals), _ptr(meta), d_out, d_in, _ptr(vals_t),
+                                                          _ptr(meta_t), _ptr(mask), _stream()))
+    return vals_t, meta_t, mask
+
+
+def slope_spmm_fwd_workspace_bytes(b: int, d_in: int, d_out: int, r: int) -> int:
+    return int(lib().slope_spmm_fwd_workspace_bytes(b, d_in, d_out, r))
+
+
+def slope_spmm_fwd(X: torch.Tensor, vals: torch.Tensor, meta: torch.Tensor, L=None, R=None, out=None,
+                   workspace=None):
+    """Y = X (W^R)^T [+ (X L) R].  X bf16[b, d_in]; packed W^R; L bf16[d_in, r]; R bf16[r, d_out]."""
+    _dev(X, vals, meta, L, R)
+    b, d_in = X.shape
+    d_out = vals.shape[0]
+    r = 0 if L is None else L.shape[1]
+    Y = out if out is not None else torch.empty((b, d_out), dtype=torch.bfloat16, device=X.device)
+    if r > 0 and workspace is None:
+        workspace = torch.empty(slope_spmm_fwd_workspace_bytes(b, d_in, d_out, r), dtype=torch.uint8,
+                                device=X.device)
+    _check("slope_spmm_fwd", lib().slope_spmm_fwd(_ptr(X), b, _ptr(vals), _ptr(meta), d_out, d_in, _ptr(L), _ptr(R),
+                                                  r, _ptr(Y), _ptr(workspace), _stream()))
+    return Y
+
+
+def slope_spmm_bwd_x(dY: torch.Tensor, vals_t: torch.Tensor, meta_t: torch.Tensor, out=None):
+    """dX = dY W^{R,C}.  dY bf16[b, d_out]; packed (W^{R,C})^T with rows = d_in."""
+    _dev(dY, vals_t, meta_t)
+    b, d_out = dY.shape
+    d_in = vals_t.shape[0]
+    dX = out if out is not None else torch.empty((b, d_in), dtype=torch.bfloat16, device=dY.device)
+    _check("slope_spmm_bwd_x", lib().slope_spmm_bwd_x(_ptr(dY), b, _ptr(vals_t), _ptr(meta_t), d_out, d_in, _ptr(dX),
+                                                      _stream()))
+    return dX
+
+
+def slope_wgrad_masked(dY: torch.Tensor, X: torch.Tensor, meta: torch.Tensor, out=None):
+    """dW = dY^T X at W^R's kept positions, packed bf16[d_out, d_in/2]."""
+    _dev(dY, X, meta)
+    b, d_out = dY.shape
+    d_in = X.shape[1]
+    G = out if out is not None else torch.empty((d_out, d_in // 2), dtype=torch.bfloat16, device=dY.device)
+    _check("slope_wgrad_masked", lib().slope_wgrad_masked(_ptr(dY), _ptr(X), b, _ptr(meta), d_out, d_in, _ptr(G),
+                                                          _stream()))
+    return G
+
+
+# ---------------------------------------------------------------- host <-> device helpers (plumbing)
+def bf16_to_device(bits, device="cuda"):
+    """numpy uint16 bit patterns -> bf16 device tensor."""
+    import numpy as np
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).to(device)
+
+
+def bf16_to_host(t):
+    """bf16 tensor -> numpy uint16 bit patterns."""
+    import numpy as np
+    return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)

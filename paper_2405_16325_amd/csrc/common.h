@@ -1,0 +1,47 @@
+// Shared declarations of the gfx950 kernels behind the C ABI in include/slope.h.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "slope.h"
+
+typedef uint16_t bf16_t;  // raw bf16 bit pattern
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) __bf16 bf16x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// Launchers (host side, one per kernel family).  Each returns the hipError_t of its launches.
+hipError_t launch_prune_rows(const bf16_t* W, int64_t d_out, int64_t d_in, bf16_t* vals, uint8_t* meta,
+                             uint8_t* mask, hipStream_t s);
+hipError_t launch_double_prune(const bf16_t* vals, const uint8_t* meta, int64_t d_out, int64_t d_in,
+                               bf16_t* valsT, uint8_t* metaT, uint8_t* maskrc, hipStream_t s);
+// C[n, m] = B[n, K] * Asparse[m, K]^T  (+ B2[n, K2] * A2[m, K2]^T dense when K2 > 0)
+hipError_t launch_spmm(const bf16_t* B, int64_t n, const bf16_t* A_vals, const uint8_t* A_meta, int64_t m,
+                       int64_t K, const bf16_t* B2, const bf16_t* A2, int64_t K2, bf16_t* C, hipStream_t s);
+// T[n, r] = X[n, K] * Lt[r, K]^T (dense), plus transposes of the adapter factors
+hipError_t launch_lowrank_prepare(const bf16_t* X, int64_t n, int64_t d_in, int64_t d_out, const bf16_t* L,
+                                  const bf16_t* R, int64_t r, bf16_t* T, bf16_t* Lt, bf16_t* Rt, hipStream_t s);
+hipError_t launch_wgrad_masked(const bf16_t* dY, const bf16_t* X, int64_t b, const uint8_t* meta, int64_t d_out,
+                               int64_t d_in, bf16_t* gvals, hipStream_t s);
+
+// Rank the four keys of a group by (key descending, index ascending) and return the 4-bit
+// set of the two winners.  Keys are small non-negative integers.
+__device__ __forceinline__ uint32_t top2_of_4(uint32_t k0, uint32_t k1, uint32_t k2, uint32_t k3) {
+    // c_ij = 1 when j beats i (strictly larger key); ties leave the lower index in front
+    uint32_t c01 = k1 > k0, c02 = k2 > k0, c03 = k3 > k0, c12 = k2 > k1, c13 = k3 > k1, c23 = k3 > k2;
+    uint32_t r0 = c01 + c02 + c03;
+    uint32_t r1 = (1u - c01) + c12 + c13;
+    uint32_t r2 = (2u - c02 - c12) + c23;
+    uint32_t r3 = 3u - c03 - c13 - c23;
+    return (uint32_t)(r0 < 2u) | ((uint32_t)(r1 < 2u) << 1) | ((uint32_t)(r2 < 2u) << 2) | ((uint32_t)(r3 < 2u) << 3);
+}
+
+// Metadata nibble idx0 | idx1 << 2 of a 4-bit set with exactly two members, looked up in a
+// 16 x 4-bit table: {0,1}->4 {0,2}->8 {1,2}->9 {0,3}->12 {1,3}->13 {2,3}->14.
+__device__ __forceinline__ uint32_t nibble_of_pair(uint32_t set) {
+    const uint64_t table = (4ull << 12) | (8ull << 20) | (9ull << 24) | (12ull << 36) | (13ull << 40) | (14ull << 48);
+    return (uint32_t)(table >> (4u * set)) & 0xFu;
+}

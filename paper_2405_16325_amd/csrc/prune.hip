@@ -1,0 +1,213 @@
+// slope_prune_rows and slope_double_prune: HBM-bound streams (Sec. 2.1; App. B "setup").
+//
+// prune_rows   : one lane owns 8 consecutive weights (one 16-byte load = two groups of four),
+//                ranks each group with a branch-free comparison network and writes 8 bytes of
+//                kept values, one metadata byte and (optionally) one mask byte.  A wavefront
+//                reads 1 KiB and writes 512 + 64 (+ 64) contiguous bytes.
+// double_prune : a 128 x 128 tile of W^R is decompressed into LDS, regrouped along d_out,
+//                ranked again among the surviving positions, and written out transposed
+//                through a second LDS stage so that both the read and the write are coalesced.
+#include "common.h"
+
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ void prune_chunk(u32x4 w, u32x2& packed, uint32_t& meta_byte, uint32_t& mask_byte) {
+    uint32_t lo[2] = {w.x, w.z}, hi[2] = {w.y, w.w}, pk[2], nib[2], set[2];
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+        uint32_t k0 = lo[g] & 0x7FFFu, k1 = (lo[g] >> 16) & 0x7FFFu;
+        uint32_t k2 = hi[g] & 0x7FFFu, k3 = (hi[g] >> 16) & 0x7FFFu;
+        set[g] = top2_of_4(k0, k1, k2, k3);
+        nib[g] = nibble_of_pair(set[g]);
+        uint64_t q = (uint64_t)lo[g] | ((uint64_t)hi[g] << 32);
+        uint32_t v0 = (uint32_t)(q >> (16u * (nib[g] & 3u))) & 0xFFFFu;
+        uint32_t v1 = (uint32_t)(q >> (16u * (nib[g] >> 2))) & 0xFFFFu;
+        pk[g] = v0 | (v1 << 16);
+    }
+    packed = (u32x2){pk[0], pk[1]};
+    meta_byte = nib[0] | (nib[1] << 4);
+    mask_byte = set[0] | (set[1] << 4);
+}
+
+// Four neighbouring lanes hold four consecutive output bytes: gather them into lane 4q.
+__device__ __forceinline__ uint32_t gather_quad_bytes(uint32_t b) {
+    b |= (uint32_t)__shfl_down((int)b, 1, 64) << 8;
+    b |= (uint32_t)__shfl_down((int)b, 2, 64) << 16;
+    return b;
+}
+
+constexpr int PR_UNROLL = 4;
+
+__global__ void __launch_bounds__(256) prune_rows_kernel(const u32x4* __restrict__ W, size_t nchunks,
+                                                         u32x2* __restrict__ vals, uint8_t* __restrict__ meta,
+                                                         uint8_t* __restrict__ mask) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    const size_t first = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const int sub = threadIdx.x & 3;
+    for (size_t base = first; base - sub < nchunks; base += stride * PR_UNROLL) {
+        u32x4 w[PR_UNROLL];
+#pragma unroll
+        for (int u = 0; u < PR_UNROLL; ++u) {
+            size_t c = base + u * stride;
+            w[u] = c < nchunks ? __builtin_nontemporal_load(W + c) : (u32x4){0, 0, 0, 0};
+        }
+#pragma unroll
+        for (int u = 0; u < PR_UNROLL; ++u) {
+            size_t c = base + u * stride;
+            u32x2 pk;
+            uint32_t mb, kb;
+            prune_chunk(w[u], pk, mb, kb);
+            bool ok = c < nchunks;
+            bool quad_ok = (c - sub) + 3 < nchunks;  // all four lanes of the quad are in range
+            if (ok) __builtin_nontemporal_store(pk, vals + c);
+            uint32_t m4 = gather_quad_bytes(mb);
+            if (quad_ok) {
+                if (sub == 0) __builtin_nontemporal_store(m4, (uint32_t*)(meta + c));
+            } else if (ok) {
+                meta[c] = (uint8_t)mb;
+            }
+            if (mask) {
+                uint32_t k4 = gather_quad_bytes(kb);
+                if (quad_ok) {
+                    if (sub == 0) __builtin_nontemporal_store(k4, (uint32_t*)(mask + c));
+                } else if (ok) {
+                    mask[c] = (uint8_t)kb;
+                }
+            }
+        }
+    }
+}
+
+hipError_t launch_prune_rows(const bf16_t* W, int64_t d_out, int64_t d_in, bf16_t* vals, uint8_t* meta,
+                             uint8_t* mask, hipStream_t s) {
+    size_t nchunks = (size_t)d_out * (size_t)d_in / 8;
+    size_t per_block = 256 * PR_UNROLL;
+    size_t blocks = (nchunks + per_block - 1) / per_block;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    if (blocks == 0) blocks = 1;
+    prune_rows_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>((const u32x4*)W, nchunks, (u32x2*)vals, meta, mask);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+constexpr int DP_TILE = 128;        // logical tile edge along d_out and d_in
+constexpr int DP_PITCH = 272;       // bytes per decompressed row in LDS (128 * 2 + 16)
+constexpr int DP_OPITCH = 33;       // dwords per output row [i][og] (32 + 1: conflict-free columns)
+constexpr int DP_NPITCH = 36;       // bytes per nibble row [i][og]
+
+__global__ void __launch_bounds__(256) double_prune_kernel(const bf16_t* __restrict__ vals,
+                                                           const uint8_t* __restrict__ meta, int d_out, int d_in,
+                                                           bf16_t* __restrict__ valsT, uint8_t* __restrict__ metaT,
+                                                           uint8_t* __restrict__ maskrc) {
+    __shared__ __align__(16) uint8_t sD[DP_TILE * DP_PITCH];   // decompressed W^R tile [o][i]
+    __shared__ __align__(4) uint8_t sC[DP_TILE * 16];          // candidate bits [o][i/8]
+    __shared__ uint32_t sO[DP_TILE * DP_OPITCH];               // kept value pairs [i][og]
+    __shared__ __align__(4) uint8_t sN[DP_TILE * DP_NPITCH];   // metadata nibbles [i][og]
+
+    const int t = threadIdx.x;
+    const int o0 = blockIdx.y * DP_TILE, i0 = blockIdx.x * DP_TILE;
+    const size_t vpitch = (size_t)d_in / 2, mpitch = (size_t)d_in / 8;
+
+    // phase 1: coalesced read of packed W^R (16 logical columns per lane), decompress to LDS
+#pragma unroll
+    for (int pass = 0; pass < 4; ++pass) {
+        int row = pass * 32 + (t >> 3), c = t & 7;
+        int o = o0 + row, i = i0 + 16 * c;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        uint32_t m = 0;
+        bool ok = o < d_out && i < d_in;
+        if (ok) {
+            v = *(const uint4*)(vals + (size_t)o * vpitch + i / 2);
+            m = *(const uint16_t*)(meta + (size_t)o * mpitch + i / 8);
+        }
+        uint32_t pk[4] = {v.x, v.y, v.z, v.w};
+        uint32_t dense[8];
+        uint32_t cand = 0;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            uint32_t nib = (m >> (4 * g)) & 0xFu, a = nib & 3u, b = nib >> 2;
+            uint64_t q = ((uint64_t)(pk[g] & 0xFFFFu) << (16u * a)) | ((uint64_t)(pk[g] >> 16) << (16u * b));
+            dense[2 * g] = (uint32_t)q;
+            dense[2 * g + 1] = (uint32_t)(q >> 32);
+            uint32_t bits = ok ? ((1u << a) | (1u << b)) : 0u;
+            cand |= bits << (4 * g);
+        }
+        uint4* dst = (uint4*)(sD + row * DP_PITCH + 32 * c);
+        dst[0] = make_uint4(dense[0], dense[1], dense[2], dense[3]);
+        dst[1] = make_uint4(dense[4], dense[5], dense[6], dense[7]);
+        *(uint16_t*)(sC + row * 16 + 2 * c) = (uint16_t)cand;
+    }
+    __syncthreads();
+
+    // phase 2: one lane ranks 8 columns x 4 rows (one group of four along d_out per column)
+#pragma unroll
+    for (int n = 0; n < 2; ++n) {
+        int u = t + 256 * n, og = u >> 4, i8 = u & 15;
+        uint32_t r[4][4], cb[4], keep[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            uint4 x = *(const uint4*)(sD + (4 * og + k) * DP_PITCH + 16 * i8);
+            r[k][0] = x.x; r[k][1] = x.y; r[k][2] = x.z; r[k][3] = x.w;
+            cb[k] = sC[(4 * og + k) * 16 + i8];
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            uint32_t e[4], key[4], cd[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                e[k] = (r[k][j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
+                cd[k] = (cb[k] >> j) & 1u;
+                key[k] = cd[k] ? (e[k] & 0x7FFFu) + 1u : 0u;   // survivors outrank every pruned slot
+            }
+            uint32_t set = top2_of_4(key[0], key[1], key[2], key[3]);
+            uint32_t nib = nibble_of_pair(set);
+            uint64_t q = (uint64_t)(e[0] | (e[1] << 16)) | ((uint64_t)(e[2] | (e[3] << 16)) << 32);
+            uint32_t v0 = (uint32_t)(q >> (16u * (nib & 3u))) & 0xFFFFu;
+            uint32_t v1 = (uint32_t)(q >> (16u * (nib >> 2))) & 0xFFFFu;
+            int col = 8 * i8 + j;
+            sO[col * DP_OPITCH + og] = v0 | (v1 << 16);
+            sN[col * DP_NPITCH + og] = (uint8_t)nib;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) keep[k] |= (((set >> k) & 1u) & cd[k]) << j;
+        }
+        if (maskrc) {
+            int i = i0 + 8 * i8;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                int o = o0 + 4 * og + k;
+                if (o < d_out && i < d_in) maskrc[(size_t)o * mpitch + i / 8] = (uint8_t)keep[k];
+            }
+        }
+    }
+    __syncthreads();
+
+    // phase 3: coalesced write of packed (W^{R,C})^T rows
+    const size_t vtp = (size_t)d_out / 2, mtp = (size_t)d_out / 8;
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+        int idx = t + 256 * n, row = idx >> 3, c = idx & 7;
+        int i = i0 + row, o = o0 + 16 * c;
+        if (i < d_in && o < d_out) {
+            const uint32_t* src = sO + row * DP_OPITCH + 4 * c;
+            *(uint4*)(valsT + (size_t)i * vtp + o / 2) = make_uint4(src[0], src[1], src[2], src[3]);
+        }
+    }
+#pragma unroll
+    for (int n = 0; n < 2; ++n) {
+        int idx = t + 256 * n, row = idx >> 2, c = idx & 3;
+        int i = i0 + row, o = o0 + 32 * c;
+        if (i < d_in && o < d_out) {
+            const uint32_t* src = (const uint32_t*)(sN + row * DP_NPITCH + 8 * c);
+            uint32_t x = src[0], y = src[1];
+            uint32_t lo = (x & 0xFu) | ((x >> 4) & 0xF0u) | ((x >> 8) & 0xF00u) | ((x >> 12) & 0xF000u);
+            uint32_t hi = (y & 0xFu) | ((y >> 4) & 0xF0u) | ((y >> 8) & 0xF00u) | ((y >> 12) & 0xF000u);
+            *(uint32_t*)(metaT + (size_t)i * mtp + o / 8) = lo | (hi << 16);
+        }
+    }
+}
+
+hipError_t launch_double_prune(const bf16_t* vals, const uint8_t* meta, int64_t d_out, int64_t d_in, bf16_t* valsT,
+                               uint8_t* metaT, uint8_t* maskrc, hipStream_t s) {
+    dim3 grid((unsigned)((d_in + DP_TILE - 1) / DP_TILE), (unsigned)((d_out + DP_TILE - 1) / DP_TILE));
+    double_prune_kernel<<<grid, dim3(256), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT, metaT, maskrc);
+    return hipGetLastError();
+}

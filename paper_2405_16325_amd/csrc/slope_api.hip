@@ -1,0 +1,133 @@
+// C ABI of the double-pruned 2:4 sparse linear layer (declared in include/slope.h):
+// argument checks on the host, then the launchers.  No allocation, no synchronisation, no state.
+#include "common.h"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+constexpr int64_t EXTENT_MAX = (int64_t)1 << 31;
+
+inline bool misaligned(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
+
+inline slope_status finish(hipError_t e) {
+    if (e == hipSuccess) return SLOPE_OK;
+    g_last_hip_error = (int)e;
+    return SLOPE_ERR_HIP;
+}
+
+inline bool bad_extent(int64_t v, int64_t quantum) { return v <= 0 || v >= EXTENT_MAX || (v % quantum) != 0; }
+
+}  // namespace
+
+extern "C" {
+
+int slope_version(void) { return 100; }
+
+int slope_last_hip_error(void) { return g_last_hip_error; }
+
+const char* slope_status_string(int status) {
+    switch (status) {
+        case SLOPE_OK: return "ok";
+        case SLOPE_ERR_NULL: return "a required pointer is NULL";
+        case SLOPE_ERR_SHAPE: return "an extent is not positive, not a multiple of its quantum, or too large";
+        case SLOPE_ERR_ALIGN: return "a pointer is not sufficiently aligned";
+        case SLOPE_ERR_UNSUPPORTED: return "unsupported N:M pattern or adapter rank";
+        case SLOPE_ERR_HIP: return "a HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+size_t slope_packed_vals_bytes(int64_t rows, int64_t cols) {
+    if (rows <= 0 || cols <= 0 || cols % 8) return 0;
+    return (size_t)rows * (size_t)(cols / 2) * 2;
+}
+
+size_t slope_packed_meta_bytes(int64_t rows, int64_t cols) {
+    if (rows <= 0 || cols <= 0 || cols % 8) return 0;
+    return (size_t)rows * (size_t)(cols / 8);
+}
+
+size_t slope_mask_bytes(int64_t rows, int64_t cols) { return slope_packed_meta_bytes(rows, cols); }
+
+static size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+size_t slope_spmm_fwd_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out, int64_t r) {
+    if (r <= 0 || b <= 0 || d_in <= 0 || d_out <= 0) return 0;
+    return round256((size_t)b * r * 2) + round256((size_t)d_in * r * 2) + round256((size_t)d_out * r * 2);
+}
+
+slope_status slope_prune_rows(const void* W, int64_t d_out, int64_t d_in, int n, int m, void* Wr_vals, void* Wr_meta,
+                              void* mask_or_null, void* stream) {
+    if (!W || !Wr_vals || !Wr_meta) return SLOPE_ERR_NULL;
+    if (n != 2 || m != 4) return SLOPE_ERR_UNSUPPORTED;
+    if (bad_extent(d_out, 1) || bad_extent(d_in, 8)) return SLOPE_ERR_SHAPE;
+    if (misaligned(W, 16) || misaligned(Wr_vals, 16) || misaligned(Wr_meta, 16) || misaligned(mask_or_null, 16))
+        return SLOPE_ERR_ALIGN;
+    return finish(launch_prune_rows((const bf16_t*)W, d_out, d_in, (bf16_t*)Wr_vals, (uint8_t*)Wr_meta,
+                                    (uint8_t*)mask_or_null, (hipStream_t)stream));
+}
+
+slope_status slope_double_prune(const void* Wr_vals, const void* Wr_meta, int64_t d_out, int64_t d_in,
+                                void* WrcT_vals, void* WrcT_meta, void* maskrc_or_null, void* stream) {
+    if (!Wr_vals || !Wr_meta || !WrcT_vals || !WrcT_meta) return SLOPE_ERR_NULL;
+    if (bad_extent(d_out, 64) || bad_extent(d_in, 64)) return SLOPE_ERR_SHAPE;
+    if (misaligned(Wr_vals, 16) || misaligned(Wr_meta, 16) || misaligned(WrcT_vals, 16) ||
+        misaligned(WrcT_meta, 16) || misaligned(maskrc_or_null, 16))
+        return SLOPE_ERR_ALIGN;
+    return finish(launch_double_prune((const bf16_t*)Wr_vals, (const uint8_t*)Wr_meta, d_out, d_in,
+                                      (bf16_t*)WrcT_vals, (uint8_t*)WrcT_meta, (uint8_t*)maskrc_or_null,
+                                      (hipStream_t)stream));
+}
+
+slope_status slope_spmm_fwd(const void* X, int64_t b, const void* Wr_vals, const void* Wr_meta, int64_t d_out,
+                            int64_t d_in, const void* L_or_null, const void* R_or_null, int64_t r, void* Y,
+                            void* workspace, void* stream) {
+    if (!X || !Wr_vals || !Wr_meta || !Y) return SLOPE_ERR_NULL;
+    if (bad_extent(b, 1) || bad_extent(d_out, 64) || bad_extent(d_in, 64)) return SLOPE_ERR_SHAPE;
+    const bool adapter = r > 0 && (L_or_null || R_or_null);
+    if (r < 0) return SLOPE_ERR_SHAPE;
+    if (adapter) {
+        if (!L_or_null || !R_or_null || !workspace) return SLOPE_ERR_NULL;
+        if (r % 32 != 0 || r > 512) return SLOPE_ERR_UNSUPPORTED;
+        if (misaligned(L_or_null, 16) || misaligned(R_or_null, 16) || misaligned(workspace, 256)) return SLOPE_ERR_ALIGN;
+    }
+    if (misaligned(X, 16) || misaligned(Wr_vals, 16) || misaligned(Wr_meta, 16) || misaligned(Y, 16))
+        return SLOPE_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)stream;
+    if (!adapter)
+        return finish(launch_spmm((const bf16_t*)X, b, (const bf16_t*)Wr_vals, (const uint8_t*)Wr_meta, d_out, d_in,
+                                  nullptr, nullptr, 0, (bf16_t*)Y, s));
+    uint8_t* ws = (uint8_t*)workspace;
+    bf16_t* T = (bf16_t*)ws;
+    bf16_t* Lt = (bf16_t*)(ws + round256((size_t)b * r * 2));
+    bf16_t* Rt = (bf16_t*)((uint8_t*)Lt + round256((size_t)d_in * r * 2));
+    hipError_t e = launch_lowrank_prepare((const bf16_t*)X, b, d_in, d_out, (const bf16_t*)L_or_null,
+                                          (const bf16_t*)R_or_null, r, T, Lt, Rt, s);
+    if (e != hipSuccess) return finish(e);
+    return finish(launch_spmm((const bf16_t*)X, b, (const bf16_t*)Wr_vals, (const uint8_t*)Wr_meta, d_out, d_in, T,
+                              Rt, r, (bf16_t*)Y, s));
+}
+
+slope_status slope_spmm_bwd_x(const void* dY, int64_t b, const void* WrcT_vals, const void* WrcT_meta, int64_t d_out,
+                              int64_t d_in, void* dX, void* stream) {
+    if (!dY || !WrcT_vals || !WrcT_meta || !dX) return SLOPE_ERR_NULL;
+    if (bad_extent(b, 1) || bad_extent(d_out, 64) || bad_extent(d_in, 64)) return SLOPE_ERR_SHAPE;
+    if (misaligned(dY, 16) || misaligned(WrcT_vals, 16) || misaligned(WrcT_meta, 16) || misaligned(dX, 16))
+        return SLOPE_ERR_ALIGN;
+    // sparse rows = d_in, contraction over d_out
+    return finish(launch_spmm((const bf16_t*)dY, b, (const bf16_t*)WrcT_vals, (const uint8_t*)WrcT_meta, d_in, d_out,
+                              nullptr, nullptr, 0, (bf16_t*)dX, (hipStream_t)stream));
+}
+
+slope_status slope_wgrad_masked(const void* dY, const void* X, int64_t b, const void* Wr_meta, int64_t d_out,
+                                int64_t d_in, void* dW_vals, void* stream) {
+    if (!dY || !X || !Wr_meta || !dW_vals) return SLOPE_ERR_NULL;
+    if (bad_extent(b, 1) || bad_extent(d_out, 64) || bad_extent(d_in, 64)) return SLOPE_ERR_SHAPE;
+    if (misaligned(dY, 16) || misaligned(X, 16) || misaligned(Wr_meta, 16) || misaligned(dW_vals, 16))
+        return SLOPE_ERR_ALIGN;
+    return finish(launch_wgrad_masked((const bf16_t*)dY, (const bf16_t*)X, b, (const uint8_t*)Wr_meta, d_out, d_in,
+                                      (bf16_t*)dW_vals, (hipStream_t)stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,68 @@
+"""The C-ABI library loads, exports every symbol the header declares, and rejects bad arguments
+on the host (no GPU needed: argument errors are found before anything is launched)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2405_16325_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "slope.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(slope_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_symbols()
+    assert len(names) >= 12
+    handle = ctypes.CDLL(binding.LIB_PATH)
+    for n in names:
+        assert hasattr(handle, n), n
+    assert set(names) == set(binding.SIGNATURES), "binding and header disagree"
+
+
+def test_size_queries():
+    lib = binding.lib()
+    assert lib.slope_version() >= 100
+    # 2 x 16 bits of values + 4 bits of index per group of four
+    assert lib.slope_packed_vals_bytes(3072, 768) == 3072 * 768
+    assert lib.slope_packed_meta_bytes(3072, 768) == 3072 * 768 // 8
+    assert lib.slope_mask_bytes(3072, 768) == 3072 * 768 // 8
+    assert lib.slope_packed_vals_bytes(16, 12) == 0
+    assert lib.slope_spmm_fwd_workspace_bytes(2048, 768, 3072, 0) == 0
+    ws = lib.slope_spmm_fwd_workspace_bytes(2048, 768, 3072, 64)
+    assert ws >= 2 * 64 * (2048 + 768 + 3072) and ws % 256 == 0
+
+
+def test_argument_errors_are_reported_before_launch():
+    lib = binding.lib()
+    p = ctypes.c_void_p(0x1000)       # aligned, never dereferenced: every call below must fail first
+    odd = ctypes.c_void_p(0x1008)
+    assert lib.slope_prune_rows(None, 64, 64, 2, 4, p, p, None, None) == binding.SLOPE_ERR_NULL
+    assert lib.slope_prune_rows(p, 64, 64, 1, 2, p, p, None, None) == binding.SLOPE_ERR_UNSUPPORTED
+    assert lib.slope_prune_rows(p, 64, 60, 2, 4, p, p, None, None) == binding.SLOPE_ERR_SHAPE
+    assert lib.slope_prune_rows(p, 0, 64, 2, 4, p, p, None, None) == binding.SLOPE_ERR_SHAPE
+    assert lib.slope_prune_rows(p, 64, 64, 2, 4, odd, p, None, None) == binding.SLOPE_ERR_ALIGN
+    assert lib.slope_double_prune(p, p, 64, 96, p, p, None, None) == binding.SLOPE_ERR_SHAPE
+    assert lib.slope_double_prune(p, None, 64, 64, p, p, None, None) == binding.SLOPE_ERR_NULL
+    assert lib.slope_spmm_fwd(p, 0, p, p, 64, 64, None, None, 0, p, None, None) == binding.SLOPE_ERR_SHAPE
+    assert lib.slope_spmm_fwd(p, 8, p, p, 64, 64, p, p, 48, p, p, None) == binding.SLOPE_ERR_UNSUPPORTED
+    assert lib.slope_spmm_fwd(p, 8, p, p, 64, 64, p, None, 32, p, p, None) == binding.SLOPE_ERR_NULL
+    assert lib.slope_spmm_fwd(p, 8, p, p, 64, 64, p, p, 32, p, None, None) == binding.SLOPE_ERR_NULL
+    assert lib.slope_spmm_fwd(p, 8, p, p, 64, 1 << 31, None, None, 0, p, None, None) == binding.SLOPE_ERR_SHAPE
+    assert lib.slope_spmm_bwd_x(p, 8, p, p, 64, 72, p, None) == binding.SLOPE_ERR_SHAPE
+    assert lib.slope_spmm_bwd_x(odd, 8, p, p, 64, 64, p, None) == binding.SLOPE_ERR_ALIGN
+    assert lib.slope_wgrad_masked(p, p, 8, None, 64, 64, p, None) == binding.SLOPE_ERR_NULL
+    assert lib.slope_wgrad_masked(p, p, -1, p, 64, 64, p, None) == binding.SLOPE_ERR_SHAPE
+    assert b"NULL" in lib.slope_status_string(binding.SLOPE_ERR_NULL)
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    with pytest.raises(ValueError):
+        binding.slope_prune_rows(torch.zeros((8, 8), dtype=torch.bfloat16))

@@ -1,0 +1,186 @@
+"""HIP path vs CPU oracle through the C ABI (needs an MI355X).
+
+Integer outputs (kept values, metadata, masks) must match bit for bit.  Products must satisfy
+||gpu - oracle||_F / ||oracle||_F <= 1e-2 (bf16 operands, fp32 accumulation, bf16 result: the
+output rounding alone contributes about 2^-9 / sqrt(3) ~ 1.1e-3, fp32 accumulation order far less).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import slope_oracle as so
+from paper_2405_16325_amd import binding as sl
+from paper_2405_16325_amd import inputs
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-2
+
+
+def dev(bits):
+    return sl.bf16_to_device(bits)
+
+
+def host(t):
+    return sl.bf16_to_host(t)
+
+
+def u8(t):
+    return t.cpu().numpy()
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def special_weights():
+    """Rows full of ties, zeros, infinities and NaNs."""
+    f = np.float32
+    rows = [
+        [1, 1, 1, 1, -1, 1, -1, 1], [0, 0, 0, 0, -0.0, 0.0, 0.0, -0.0], [0, 0, 0, 7, 7, 0, 0, 0],
+        [np.inf, 1, -np.inf, 2, np.nan, np.inf, 5, 1], [1e-40, -1e-40, 0, 1e-39, 3, -3, 3, -3],
+        [2, 1, 2, 1, 1, 2, 1, 2], [-5, 4, -3, 2, 2, -3, 4, -5], [0.5, 0.25, -0.5, 0.25, 1, 1, 2, 1],
+    ]
+    w = inputs.f32_to_bf16_bits(np.array(rows, dtype=f))
+    return np.tile(w, (8, 8))            # 64 x 64
+
+
+PRUNE_CASES = [
+    ("cfg1_fc1", lambda: inputs.gaussian_bf16((3072, 768), 0.02, 0, 2)),
+    ("one_row", lambda: inputs.gaussian_bf16((1, 8), 0.02, 1, 2)),
+    ("ragged_rows", lambda: inputs.gaussian_bf16((101, 72), 0.02, 2, 2)),
+    ("odd_chunks", lambda: inputs.gaussian_bf16((3, 40), 0.02, 3, 2)),
+    ("ties", lambda: inputs.coarse_weights(320, 192, 4)),
+    ("special", special_weights),
+]
+
+
+@pytest.mark.parametrize("name,make", PRUNE_CASES, ids=[c[0] for c in PRUNE_CASES])
+def test_prune_rows_bit_exact(name, make):
+    w = make()
+    say(f"prune_rows {name} {w.shape}")
+    vals, meta, mask = sl.slope_prune_rows(dev(w), want_mask=True)
+    torch.cuda.synchronize()
+    ov, om, ob = so.prune_rows_packed(w)
+    assert (host(vals) == ov).all()
+    assert (u8(meta) == om).all()
+    assert (u8(mask) == ob).all()
+    vals2, meta2, none = sl.slope_prune_rows(dev(w), want_mask=False)
+    assert none is None and (host(vals2) == ov).all() and (u8(meta2) == om).all()
+
+
+DP_CASES = [
+    ("cfg1_fc1", lambda: inputs.gaussian_bf16((3072, 768), 0.02, 0, 2)),
+    ("one_tile_part", lambda: inputs.gaussian_bf16((64, 64), 0.02, 5, 2)),
+    ("ragged_tiles", lambda: inputs.gaussian_bf16((192, 320), 0.02, 6, 2)),
+    ("ties", lambda: inputs.coarse_weights(320, 192, 7)),
+    ("zeros", lambda: np.zeros((128, 64), dtype=np.uint16)),
+    ("special", special_weights),
+]
+
+
+@pytest.mark.parametrize("name,make", DP_CASES, ids=[c[0] for c in DP_CASES])
+def test_double_prune_bit_exact(name, make):
+    w = make()
+    say(f"double_prune {name} {w.shape}")
+    ov, om, _ = so.prune_rows_packed(w)
+    vt, mt, mrc = sl.slope_double_prune(dev(ov), torch.from_numpy(om).cuda(), want_mask=True)
+    torch.cuda.synchronize()
+    evt, emt, emrc = so.double_prune_packed(ov, om)
+    assert (host(vt) == evt).all()
+    assert (u8(mt) == emt).all()
+    assert (u8(mrc) == emrc).all()
+    vt2, mt2, none = sl.slope_double_prune(dev(ov), torch.from_numpy(om).cuda())
+    assert none is None and (host(vt2) == evt).all() and (u8(mt2) == emt).all()
+
+
+def layer_on_device(b, d_out, d_in, rank, seed):
+    t = inputs.layer_inputs(b, d_out, d_in, rank, seed)
+    d = {k: dev(v) for k, v in t.items()}
+    vals, meta, _ = sl.slope_prune_rows(d["W"])
+    vals_t, meta_t, _ = sl.slope_double_prune(vals, meta)
+    d.update(vals=vals, meta=meta, vals_t=vals_t, meta_t=meta_t)
+    mask_r = so.prune_rows(t["W"])
+    mask_rc = so.double_prune(t["W"], mask_r)
+    return t, d, mask_r, mask_rc
+
+
+# (b, d_out, d_in): the first is the OPT-125m FC1 layer; the others cover ragged token counts,
+# partial tiles of the 128- and the 256-wide kernels and a single k-step
+PRODUCT_SHAPES = [
+    (2048, 3072, 768), (300, 448, 320), (1, 64, 64), (17, 192, 64),
+    (4100, 4160, 256), (4096, 4096, 128),
+]
+
+
+@pytest.mark.parametrize("b,d_out,d_in", PRODUCT_SHAPES)
+def test_spmm_fwd(b, d_out, d_in):
+    say(f"spmm_fwd b={b} d_out={d_out} d_in={d_in}")
+    t, d, mask_r, _ = layer_on_device(b, d_out, d_in, 0, seed=b + d_out)
+    y = sl.slope_spmm_fwd(d["X"], d["vals"], d["meta"])
+    torch.cuda.synchronize()
+    want = so.spmm_fwd(t["X"], t["W"], mask_r)
+    err = so.rel_fro(so.bf16_to_f64(host(y)), want)
+    say(f"  rel_fro {err:.3e}")
+    assert err <= TOL
+
+
+@pytest.mark.parametrize("b,d_out,d_in", PRODUCT_SHAPES)
+def test_spmm_bwd_x(b, d_out, d_in):
+    say(f"spmm_bwd_x b={b} d_out={d_out} d_in={d_in}")
+    t, d, _, mask_rc = layer_on_device(b, d_out, d_in, 0, seed=b + d_in)
+    dx = sl.slope_spmm_bwd_x(d["dY"], d["vals_t"], d["meta_t"])
+    torch.cuda.synchronize()
+    want = so.spmm_bwd_x(t["dY"], t["W"], mask_rc)
+    err = so.rel_fro(so.bf16_to_f64(host(dx)), want)
+    say(f"  rel_fro {err:.3e}")
+    assert err <= TOL
+
+
+@pytest.mark.parametrize("b,d_out,d_in", PRODUCT_SHAPES + [(1000, 320, 448)])
+def test_wgrad_masked(b, d_out, d_in):
+    say(f"wgrad_masked b={b} d_out={d_out} d_in={d_in}")
+    t, d, _, _ = layer_on_device(b, d_out, d_in, 0, seed=b + 7)
+    g = sl.slope_wgrad_masked(d["dY"], d["X"], d["meta"])
+    torch.cuda.synchronize()
+    want = so.wgrad_masked(t["dY"], t["X"], u8(d["meta"]))
+    err = so.rel_fro(so.bf16_to_f64(host(g)), want)
+    say(f"  rel_fro {err:.3e}")
+    assert err <= TOL
+
+
+@pytest.mark.parametrize("b,d_out,d_in,r", [(2048, 3072, 768, 64), (300, 448, 320, 32), (4100, 4160, 256, 128),
+                                            (50, 128, 192, 160)])
+def test_spmm_fwd_with_adapter(b, d_out, d_in, r):
+    say(f"spmm_fwd adapter b={b} d_out={d_out} d_in={d_in} r={r}")
+    t, d, mask_r, _ = layer_on_device(b, d_out, d_in, r, seed=r + b)
+    y = sl.slope_spmm_fwd(d["X"], d["vals"], d["meta"], d["L"], d["R"])
+    torch.cuda.synchronize()
+    want = so.spmm_fwd(t["X"], t["W"], mask_r, t["L"], t["R"])
+    err = so.rel_fro(so.bf16_to_f64(host(y)), want)
+    base = so.spmm_fwd(t["X"], t["W"], mask_r)
+    say(f"  rel_fro {err:.3e} (adapter share of the norm {np.linalg.norm(want - base) / np.linalg.norm(want):.3f})")
+    assert err <= TOL
+    # the low-rank term itself, isolated by subtracting the plain sparse product computed on the GPU
+    y0 = sl.slope_spmm_fwd(d["X"], d["vals"], d["meta"])
+    low = so.bf16_to_f64(host(y)) - so.bf16_to_f64(host(y0))
+    assert so.rel_fro(low, want - base) <= 5e-2
+
+
+def test_runs_are_bit_identical():
+    t, d, _, _ = layer_on_device(512, 256, 384, 32, seed=99)
+    a = [sl.slope_spmm_fwd(d["X"], d["vals"], d["meta"], d["L"], d["R"]),
+         sl.slope_spmm_bwd_x(d["dY"], d["vals_t"], d["meta_t"]),
+         sl.slope_wgrad_masked(d["dY"], d["X"], d["meta"])]
+    b = [sl.slope_spmm_fwd(d["X"], d["vals"], d["meta"], d["L"], d["R"]),
+         sl.slope_spmm_bwd_x(d["dY"], d["vals_t"], d["meta_t"]),
+         sl.slope_wgrad_masked(d["dY"], d["X"], d["meta"])]
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        assert (host(x) == host(y)).all()
+
+
+def test_error_status_raises():
+    w = dev(inputs.gaussian_bf16((64, 60), 0.02, 1, 2))
+    with pytest.raises(sl.SlopeError) as e:
+        sl.slope_prune_rows(w)
+    assert e.value.status == sl.SLOPE_ERR_SHAPE
