@@ -1,0 +1,254 @@
+#!/usr/bin/env python3
+"""Benchmark of the double-pruned 2:4 sparse linear layer on one MI355X.
+
+One step = one pass of the whole hot path over the linear layers of one OPT-66B-shaped
+transformer block (q, k, v, o: 9216 x 9216; fc1: 36864 x 9216; fc2: 9216 x 36864; 16384 tokens,
+rank-128 adapters in the forward): for every layer slope_prune_rows, slope_double_prune (weights
+are re-pruned from dense each step), slope_spmm_fwd with the adapter, slope_spmm_bwd_x and
+slope_wgrad_masked.  All inputs are synthetic (seeded Gaussians, generated on the device) and
+resident in HBM before the clock starts.
+
+Prints ONE JSON line.  value = effective TFLOP/s = 3 * 2 * b * d_in * d_out summed over the
+layers (the dense-equivalent flops of fwd + dX + dW; adapter flops are not credited) divided by
+the step time.  Details (per-call times, the dense bf16 GEMM comparison, the CPU-oracle baseline)
+ride in the same line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_DENSE_BF16 = 2500.0     # TFLOP/s, MI355X dense bf16 MFMA
+PEAK_SPARSE_BF16 = 5000.0    # TFLOP/s dense-equivalent, structured-sparse bf16 MFMA
+PEAK_HBM = 8000.0            # GB/s
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="opt66b", help="opt66b (headline) | opt13b | opt2.7b | opt125m_fc1")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (no collectives, no sharding); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2405_16325_amd import binding as sl
+    from paper_2405_16325_amd import inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    sl.lib()  # fails loudly if libslope.so has not been built
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    spec = inputs.LAYER_SETS[args.workload]
+    b, rank = spec["b"], spec["rank"]
+
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(inputs.SEED_BASE + 3)
+
+    def gauss(shape, std):
+        return (torch.randn(shape, generator=gen, device=dev, dtype=torch.float32) * std).to(torch.bfloat16)
+
+    # activations and output gradients are shared by layers of equal width (they are inputs only)
+    acts, grads, layers = {}, {}, []
+    for name, d_out, d_in in spec["layers"]:
+        if d_in not in acts:
+            acts[d_in] = gauss((b, d_in), inputs.STD["X"])
+        if d_out not in grads:
+            grads[d_out] = gauss((b, d_out), inputs.STD["dY"])
+        lay = {"name": name, "d_out": d_out, "d_in": d_in, "X": acts[d_in], "dY": grads[d_out],
+               "W": gauss((d_out, d_in), inputs.STD["W"])}
+        if rank:
+            lay["L"] = gauss((d_in, rank), inputs.STD["L"])
+            lay["R"] = gauss((rank, d_out), inputs.STD["R"])
+            lay["ws"] = torch.empty(sl.slope_spmm_fwd_workspace_bytes(b, d_in, d_out, rank), dtype=torch.uint8,
+                                    device=dev)
+        else:
+            lay["L"] = lay["R"] = lay["ws"] = None
+        lay["vals"] = torch.empty((d_out, d_in // 2), dtype=torch.bfloat16, device=dev)
+        lay["meta"] = torch.empty((d_out, d_in // 8), dtype=torch.uint8, device=dev)
+        lay["vals_t"] = torch.empty((d_in, d_out // 2), dtype=torch.bfloat16, device=dev)
+        lay["meta_t"] = torch.empty((d_in, d_out // 8), dtype=torch.uint8, device=dev)
+        lay["Y"] = torch.empty((b, d_out), dtype=torch.bfloat16, device=dev)
+        lay["dX"] = torch.empty((b, d_in), dtype=torch.bfloat16, device=dev)
+        lay["G"] = torch.empty((d_out, d_in // 2), dtype=torch.bfloat16, device=dev)
+        layers.append(lay)
+
+    calls = ["prune_rows", "double_prune", "spmm_fwd", "spmm_bwd_x", "wgrad_masked"]
+
+    def step(events=None):
+        for li, lay in enumerate(layers):
+            ev = events[li] if events is not None else None
+            if ev: ev[0].record()
+            sl.slope_prune_rows(lay["W"], out=(lay["vals"], lay["meta"], None))
+            if ev: ev[1].record()
+            sl.slope_double_prune(lay["vals"], lay["meta"], out=(lay["vals_t"], lay["meta_t"], None))
+            if ev: ev[2].record()
+            sl.slope_spmm_fwd(lay["X"], lay["vals"], lay["meta"], lay["L"], lay["R"], out=lay["Y"],
+                              workspace=lay["ws"])
+            if ev: ev[3].record()
+            sl.slope_spmm_bwd_x(lay["dY"], lay["vals_t"], lay["meta_t"], out=lay["dX"])
+            if ev: ev[4].record()
+            sl.slope_wgrad_masked(lay["dY"], lay["X"], lay["meta"], out=lay["G"])
+            if ev: ev[5].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # HIP events on the stream the kernels run on (torch's current stream), one set per step
+    all_events = [[[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in layers]
+                  for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(all_events[s])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    flops_layer = [2.0 * b * l["d_in"] * l["d_out"] for l in layers]
+    total_flops = 3.0 * sum(flops_layer)
+    value = total_flops / (ms_per_step * 1e-3) / 1e12
+
+    # per-call average durations (ms) from the events of the timed region
+    per_call = {c: 0.0 for c in calls}
+    per_layer_call = {}
+    for li, lay in enumerate(layers):
+        for ci, c in enumerate(calls):
+            ms = sum(all_events[s][li][ci].elapsed_time(all_events[s][li][ci + 1]) for s in range(args.steps))
+            ms /= args.steps
+            per_call[c] += ms
+            per_layer_call[(lay["name"], c)] = ms
+    sum_f = sum(flops_layer)
+    elems = sum(l["d_in"] * l["d_out"] for l in layers)
+    kernels = {
+        # dense contraction: 2 b d_in d_out flops per launch against the dense bf16 MFMA peak
+        "wgrad_masked": {"bound": "mfma", "achieved": sum_f / (per_call["wgrad_masked"] * 1e-3) / 1e12,
+                         "peak": PEAK_DENSE_BF16, "unit": "TFLOP/s", "launches_per_step": len(layers),
+                         "avg_ms": per_call["wgrad_masked"] / len(layers)},
+        # sparse contraction: credited dense-equivalent 2 b d_in d_out against the sparse bf16 peak
+        "spmm_bwd_x": {"bound": "mfma", "achieved": sum_f / (per_call["spmm_bwd_x"] * 1e-3) / 1e12,
+                       "peak": PEAK_SPARSE_BF16, "unit": "TFLOP/s", "launches_per_step": len(layers),
+                       "avg_ms": per_call["spmm_bwd_x"] / len(layers)},
+        "spmm_fwd": {"bound": "mfma", "achieved": sum_f / (per_call["spmm_fwd"] * 1e-3) / 1e12,
+                     "peak": PEAK_SPARSE_BF16, "unit": "TFLOP/s", "launches_per_step": len(layers),
+                     "avg_ms": per_call["spmm_fwd"] / len(layers), "note": "includes the adapter kernels"},
+        # streams: 3.125 B (read 2, write 1 + 1/8) and 2.25 B per weight element
+        "prune_rows": {"bound": "hbm", "achieved": 3.125 * elems / (per_call["prune_rows"] * 1e-3) / 1e9,
+                       "peak": PEAK_HBM, "unit": "GB/s", "launches_per_step": len(layers),
+                       "avg_ms": per_call["prune_rows"] / len(layers)},
+        "double_prune": {"bound": "hbm", "achieved": 2.25 * elems / (per_call["double_prune"] * 1e-3) / 1e9,
+                         "peak": PEAK_HBM, "unit": "GB/s", "launches_per_step": len(layers),
+                         "avg_ms": per_call["double_prune"] / len(layers)},
+    }
+    for k in kernels.values():
+        k["frac"] = k["achieved"] / k["peak"]
+    dominant = max(("wgrad_masked", "spmm_bwd_x", "spmm_fwd"), key=lambda c: per_call[c])
+    roofline = {"kernel": {"wgrad_masked": "wgrad_kernel", "spmm_bwd_x": "spmm_kernel",
+                           "spmm_fwd": "spmm_kernel"}[dominant],
+                "call": dominant, "bound": "mfma", "achieved": kernels[dominant]["achieved"],
+                "peak": kernels[dominant]["peak"], "unit": "TFLOP/s", "frac": kernels[dominant]["frac"],
+                "avg_launch_ms": kernels[dominant]["avg_ms"], "traffic": None}
+
+    # dense bf16 GEMM at the same shapes (the library GEMM torch.matmul dispatches to): Y = X W^T,
+    # dX = dY W, dW = dY^T X
+    dense = None
+    if not args.no_dense:
+        def dense_step():
+            for lay in layers:
+                torch.matmul(lay["X"], lay["W"].t(), out=lay["Y"])
+                torch.matmul(lay["dY"], lay["W"], out=lay["dX"])
+                torch.matmul(lay["dY"].t(), lay["X"], out=lay["Wg"])
+        for lay in layers:
+            lay["Wg"] = torch.empty((lay["d_out"], lay["d_in"]), dtype=torch.bfloat16, device=dev)
+        for _ in range(max(1, args.warmup)):
+            dense_step()
+        torch.cuda.synchronize()
+        d0 = time.perf_counter()
+        nd = max(3, args.steps // 2)
+        for _ in range(nd):
+            dense_step()
+        torch.cuda.synchronize()
+        dense_ms = (time.perf_counter() - d0) * 1e3 / nd
+        gemm_ms = per_call["spmm_fwd"] + per_call["spmm_bwd_x"] + per_call["wgrad_masked"]
+        dense = {"ms_per_step": dense_ms, "tflops": total_flops / (dense_ms * 1e-3) / 1e12,
+                 "speedup_products_only": dense_ms / gemm_ms, "speedup_with_reprune": dense_ms / ms_per_step,
+                 "library": "torch.matmul (hipBLASLt/rocBLAS)"}
+        for lay in layers:
+            del lay["Wg"]
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(layers[-2] if len(layers) > 1 else layers[0], b, rank)
+
+    out = {
+        "metric": "effective TFLOP/s of 2:4 sparse linear fwd+bwd; speedup vs dense bf16 GEMM",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s linear layers of one block: %s; tokens %d; adapter rank %d; "
+                               "re-pruned from dense every step" %
+                               (args.workload, ", ".join("%s %dx%d" % (n, o, i) for n, o, i in spec["layers"]),
+                                b, rank)},
+        "frac_of_sparse_peak": value / PEAK_SPARSE_BF16,
+        "speedup_vs_dense": None if dense is None else dense["speedup_with_reprune"],
+        "roofline": roofline, "kernels": kernels, "dense_gemm": dense, "cpu_baseline": cpu,
+        "per_call_ms": per_call,
+    }
+    print(json.dumps(out))
+
+
+def cpu_baseline(lay, b, rank):
+    """The oracle, as it stands, on a bounded slice of one layer of the workload (host cores)."""
+    import numpy as np
+    import torch
+    from oracle import slope_oracle as so
+    from paper_2405_16325_amd import binding as sl
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    rows, toks = min(2048, lay["d_out"]), min(512, b)
+    d_in = lay["d_in"]
+    w = sl.bf16_to_host(lay["W"][:rows])
+    x = sl.bf16_to_host(lay["X"][:toks])
+    dy = sl.bf16_to_host(lay["dY"][:toks, :rows].contiguous())
+    lb = sl.bf16_to_host(lay["L"]) if rank else None
+    rb = sl.bf16_to_host(lay["R"][:, :rows].contiguous()) if rank else None
+    t0 = time.perf_counter()
+    vals, meta, _ = so.prune_rows_packed(w)
+    mask_r = so.meta_to_mask(meta)
+    mask_rc = so.double_prune(w, mask_r)
+    so.pack_2to4(np.ascontiguousarray(w.T), np.ascontiguousarray(mask_rc.T))
+    so.spmm_fwd(x, w, mask_r, lb, rb)
+    so.spmm_bwd_x(dy, w, mask_rc)
+    so.wgrad_masked(dy, x, meta)
+    dt = time.perf_counter() - t0
+    flops = 3.0 * 2.0 * toks * d_in * rows
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "seconds": dt,
+            "sample": "%s layer slice: first %d of %d weight rows, first %d of %d tokens, d_in %d; prune, double "
+                      "prune, fwd (+adapter), dX, dW in fp64 numpy" % (lay["name"], rows, lay["d_out"], toks, b, d_in)}
+
+
+if __name__ == "__main__":
+    main()

@@ -12,7 +12,7 @@ import os
 import torch
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libslope.so")
+LIB_PATH = os.environ.get("SLOPE_LIB", os.path.join(HERE, "libslope.so"))
 
 SLOPE_OK = 0
 SLOPE_ERR_NULL = -1

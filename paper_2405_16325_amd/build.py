@@ -10,12 +10,12 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(ROOT, "_build")
-LIB_PATH = os.path.join(HERE, "libslope.so")
+LIB_PATH = os.environ.get("SLOPE_LIB", os.path.join(HERE, "libslope.so"))
 SOURCES = ["slope_api.hip", "prune.hip", "spmm.hip", "wgrad.hip", "lowrank.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+         "-I", os.path.join(ROOT, "include"), "-I", CSRC] + os.environ.get("SLOPE_EXTRA_FLAGS", "").split()
 
 
 def _run(cmd):
