@@ -15,15 +15,23 @@
 // so the sparse operand is the weight, rows of D are output features, and a lane's four
 // accumulators are four consecutive features of one token: an 8-byte store into row-major C.
 //
-// Data movement.  A workgroup owns a BM x BN tile of C and walks k in steps of 64.  It has 8
-// wavefronts (2 x 4 over the tile, two per SIMD) in two groups that run half a step apart: while
-// one group issues its MFMAs the other reads its fragments from LDS and queues global loads, then
-// they swap (two barriers per step), so each SIMD's matrix pipe always has a wavefront feeding it.
-// Operands travel global -> LDS with global_load_lds (no registers in between) into a ring of three
-// stages, two steps ahead of their use.  LDS holds them in fragment order: the 16 bytes a lane
-// feeds to the instruction sit at 16 * lane inside a 1 KiB fragment, so every global load
-// instruction fetches one fragment (16 rows x 64 contiguous bytes) and every ds_read_b128 is a
-// linear, conflict-free read.
+// Two kernels.  spmm_kernel is the fast one and needs K % 256 == 0; spmm_generic_kernel takes any
+// K % 64 == 0 with a plain register-staged pipeline.
+//
+// spmm_kernel.  What bounds it on MI355X is the rate at which a compute unit can pull operands
+// from L2 (about one cache-line request per 2 clocks, 64 B/clk at best), not the matrix pipe, so
+// the data path is built around full 128-byte lines:
+//   - every global -> LDS load instruction (global_load_lds_dwordx4, no registers in between)
+//     fetches 8 rows x 128 contiguous bytes, 8 consecutive lanes per row;
+//   - a row of the token operand has 128 bytes per k-step of 64, so B sits in a ring of three
+//     k-step stages; a row of the packed weight has only 64, so A is fetched for two k-steps at
+//     a time into two alternating pair buffers, and its metadata for four k-steps at a time;
+//   - inside a row the eight 16-byte chunks are rotated by (row / 2) % 8, which makes the
+//     ds_read_b128 of the MFMA layout (16 lanes = 16 rows, same chunk) hit 16 different bank groups.
+// A workgroup owns a BM x BN tile of C with 8 wavefronts (2 x 4, two per SIMD) in two groups that
+// run half a k-step apart: while one group issues its MFMAs the other reads its fragments from
+// LDS and queues global loads, then they swap (two barriers per k-step), so every SIMD's matrix
+// pipe always has a wavefront feeding it.  Loads run two k-steps ahead of their use.
 #include "common.h"
 
 namespace {
@@ -50,42 +58,37 @@ __device__ __forceinline__ bool tile_of_block(int tiles_m, int tiles_n, int& tm,
 
 template <int BM, int BN>
 struct SpmmSmem {
-    static constexpr int A_BYTES = BM * 64;     // packed values of a BM x 64 (logical k) slab
-    static constexpr int B_BYTES = BN * 128;    // dense BN x 64 slab
-    static constexpr int M_BYTES = BM * 8;      // metadata: 16 nibbles per row
-    static constexpr int STAGE = A_BYTES + B_BYTES + M_BYTES;
-    static constexpr int NST = 3;
-    static constexpr int DUMMY = NST * STAGE;   // landing zone for metadata loads of idle wavefronts
-    static constexpr int TOTAL = DUMMY + 8 * 256;
+    static constexpr int A_PAIR = BM * 128;     // packed values of BM rows x 2 k-steps
+    static constexpr int B_STAGE = BN * 128;    // BN token rows x 1 k-step
+    static constexpr int M_QUAD = BM * 32;      // metadata of BM rows x 4 k-steps
+    static constexpr int B_OFF = 2 * A_PAIR;
+    static constexpr int M_OFF = B_OFF + 3 * B_STAGE;
+    static constexpr int DUMMY = M_OFF + 2 * M_QUAD;   // landing zone for the metadata load of idle wavefronts
+    static constexpr int TOTAL = DUMMY + 1024;
 };
 
-// 64 lanes x 16 (or 4) bytes: lane l's bytes land at lds_dst + 16 (4) * l; lds_dst is wave-uniform
+// 64 lanes x 16 bytes: lane l's bytes land at lds_dst + 16 * l; lds_dst is wave-uniform
 __device__ __forceinline__ void dma16(const void* gsrc, uint8_t* lds_dst) {
     __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gsrc,
                                      (void __attribute__((address_space(3)))*)lds_dst, 16, 0, 0);
 }
-__device__ __forceinline__ void dma4(const void* gsrc, uint8_t* lds_dst) {
-    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gsrc,
-                                     (void __attribute__((address_space(3)))*)lds_dst, 4, 0, 0);
-}
-
-constexpr int SPMM_THREADS = 512;
 
 // Workgroup barrier without the memory fence of __syncthreads(): the fence would wait for every
 // outstanding global -> LDS load (vmcnt(0)), which is exactly what the ring is there to avoid.
-// Visibility of those loads is handled by explicit s_waitcnt vmcnt(n) before the barrier; LDS reads
-// are kept on their side of the barrier by the compiler-level clobbers.
+// Visibility of those loads is handled by explicit s_waitcnt vmcnt(n) before the barrier; nothing
+// is scheduled across it, so the two phases of a k-step stay phases.
 __device__ __forceinline__ void wg_barrier() {
     asm volatile("" ::: "memory");
-#ifndef SLOPE_LOOSE_PHASES
-    __builtin_amdgcn_sched_barrier(0);   // nothing is scheduled across: phases stay phases
-#endif
-    __builtin_amdgcn_s_barrier();
-#ifndef SLOPE_LOOSE_PHASES
     __builtin_amdgcn_sched_barrier(0);
-#endif
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
     asm volatile("" ::: "memory");
 }
+
+union BFrag { u32x4 u[2]; bf16x16 v; };
+union AFrag { u32x4 u; bf16x8 v; };
+
+constexpr int SPMM_THREADS = 512;
 
 template <int BM, int BN>
 __global__ void __launch_bounds__(SPMM_THREADS) spmm_kernel(const bf16_t* __restrict__ B, int n,
@@ -96,8 +99,8 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_kernel(const bf16_t* __rest
                                                             bf16_t* __restrict__ C, int tiles_m, int tiles_n) {
     using S = SpmmSmem<BM, BN>;
     constexpr int MF = BM / 32, NF = BN / 64;                // 16 x 16 fragments per wavefront
-    constexpr int A_LD = BM / 128, B_LD = BN / 64;           // fragment loads per wavefront per step
-    constexpr int NLD = A_LD + B_LD + 1;                     // + one metadata load
+    constexpr int A_LD = BM / 64, B_LD = BN / 64;            // 1 KiB loads per wavefront: per pair, per step
+    constexpr int M_WAVES = BM / 32;                         // wavefronts that load metadata (32 rows each)
     extern __shared__ __align__(16) uint8_t smem[];
 
     int tm, tn;
@@ -109,43 +112,55 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_kernel(const bf16_t* __rest
     const int wm = wave & 1, wn = wave >> 1;
     const int l16 = lane & 15, lq = lane >> 4;
 
-    // ---- per-lane global sources (rows clamped: results of out-of-range rows are never stored)
-    const size_t a_pitch = (size_t)K / 2, m_pitch = (size_t)K / 8, b_pitch = (size_t)K;
-    const bf16_t* a_src[A_LD];
+    // ---- loader lanes: 8 lanes per row, chunk rotated by (row / 2) % 8
+    const uint8_t* a_src[A_LD];
 #pragma unroll
     for (int i = 0; i < A_LD; ++i) {
-        int row = m0 + (wave * A_LD + i) * 16 + l16;
-        row = row < m ? row : m - 1;
-        a_src[i] = Av + (size_t)row * a_pitch + lq * 8;       // 8 packed values = logical k 16*lq ..
+        int rl = (wave * A_LD + i) * 8 + (lane >> 3);         // row inside the tile
+        int row = m0 + rl < m ? m0 + rl : m - 1;
+        a_src[i] = (const uint8_t*)Av + (size_t)row * K + (((lane & 7) ^ ((rl >> 1) & 7)) * 16);
     }
-    const bf16_t* b_src[B_LD];
+    const uint8_t* b_src[B_LD];
 #pragma unroll
     for (int i = 0; i < B_LD; ++i) {
-        int slot = wave * B_LD + i;                           // (fragment, half) pair
-        int row = n0 + (slot >> 1) * 16 + l16;
-        row = row < n ? row : n - 1;
-        b_src[i] = B + (size_t)row * b_pitch + (slot & 1) * 32 + lq * 8;
+        int rl = (wave * B_LD + i) * 8 + (lane >> 3);
+        int row = n0 + rl < n ? n0 + rl : n - 1;
+        b_src[i] = (const uint8_t*)B + (size_t)row * K * 2 + (((lane & 7) ^ ((rl >> 1) & 7)) * 16);
     }
-    // metadata: 32 rows per wavefront, two lanes (4 bytes each) per row
-    const bool meta_wave = wave * 32 < BM;
+    const bool meta_wave = wave < M_WAVES;                    // wave-uniform
     const uint8_t* m_src;
     {
-        int row = m0 + (meta_wave ? wave * 32 : 0) + (lane >> 1);
-        row = row < m ? row : m - 1;
-        m_src = Am + (size_t)row * m_pitch + (lane & 1) * 4;
+        int rl = (meta_wave ? wave : 0) * 32 + (lane >> 1);   // two lanes (16 bytes each) per row
+        int row = m0 + rl < m ? m0 + rl : m - 1;
+        m_src = Am + (size_t)row * (K / 8) + (lane & 1) * 16;
     }
-    const int m_dst = meta_wave ? S::A_BYTES + S::B_BYTES + wave * 256 : -1;
+    uint8_t* const m_dst0 = smem + (meta_wave ? S::M_OFF + wave * 1024 : S::DUMMY);
+    const int m_dst_step = meta_wave ? S::M_QUAD : 0;
 
-    const int ksteps = K / 64;
-    // queue this wavefront's share of k-step `ks` (clamped to the last one) into ring stage ks % 3
-    auto issue = [&](int ks) {
+    // ---- reader lanes: fragment f = rows 16f .. 16f+15 = 2 KiB; lane (l16, lq) wants chunk 4h + lq
+    const int sw = (l16 >> 1) & 7;
+    const int rd0 = l16 * 128 + ((lq ^ sw) * 16);             // h = 0
+    const int rd1 = l16 * 128 + (((4 + lq) ^ sw) * 16);       // h = 1
+    const int a_rd = (wm * MF) * 2048;
+    const int b_rd = S::B_OFF + (wn * NF) * 2048;
+    const int m_rd = S::M_OFF + (wm * MF * 16 + l16) * 32 + lq * 2;
+
+    const int ksteps = K / 64;                                // a multiple of 4
+    auto issue_b = [&](int ks, int stage) {                   // token rows of k-step ks (clamped)
         int kc = ks < ksteps ? ks : ksteps - 1;
-        uint8_t* st = smem + (ks % S::NST) * S::STAGE;
-        dma4(m_src + kc * 8, m_dst >= 0 ? st + m_dst : smem + S::DUMMY + wave * 256);
 #pragma unroll
-        for (int i = 0; i < A_LD; ++i) dma16(a_src[i] + kc * 32, st + (wave * A_LD + i) * 1024);
+        for (int i = 0; i < B_LD; ++i)
+            dma16(b_src[i] + (size_t)kc * 128, smem + S::B_OFF + stage * S::B_STAGE + (wave * B_LD + i) * 1024);
+    };
+    auto issue_a = [&](int pair, int buf) {                   // weight rows of k-steps 2 pair, 2 pair + 1
+        int pc = 2 * pair < ksteps ? pair : ksteps / 2 - 1;
 #pragma unroll
-        for (int i = 0; i < B_LD; ++i) dma16(b_src[i] + kc * 64, st + S::A_BYTES + (wave * B_LD + i) * 1024);
+        for (int i = 0; i < A_LD; ++i)
+            dma16(a_src[i] + (size_t)pc * 128, smem + buf * S::A_PAIR + (wave * A_LD + i) * 1024);
+    };
+    auto issue_m = [&](int quad, int buf) {                   // metadata of k-steps 4 quad .. 4 quad + 3
+        int qc = 4 * quad < ksteps ? quad : ksteps / 4 - 1;
+        dma16(m_src + (size_t)qc * 32, m_dst0 + buf * m_dst_step);
     };
 
     f32x4 acc[MF][NF];
@@ -154,50 +169,55 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_kernel(const bf16_t* __rest
 #pragma unroll
         for (int j = 0; j < NF; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    union BFrag { u32x4 u[2]; bf16x16 v; };
-    union AFrag { u32x4 u; bf16x8 v; };
-
-    const int a_rd = (wm * MF) * 1024 + lane * 16;
-    const int b_rd = S::A_BYTES + (wn * NF) * 2048 + lane * 16;
-    const int m_rd = S::A_BYTES + S::B_BYTES + (wm * MF * 16 + l16) * 8 + lq * 2;
-
-    // ---- prologue: two steps in flight; the second group starts half a step late
-    issue(0);
-    issue(1);
-    __builtin_amdgcn_s_waitcnt(waitcnt_imm(NLD, 15));         // step 0 has landed (this wave's share)
+    // ---- prologue: k-steps 0 and 1 in flight; the second group starts half a step late
+    issue_m(0, 0);
+    issue_a(0, 0);
+    issue_b(0, 0);
+    issue_b(1, 1);
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(B_LD, 15));        // everything but B of step 1 has landed
     wg_barrier();
 
-    // One step of one wavefront.  The wait for the wavefront's own share of step ks + 1 sits at the
-    // end of the compute phase for group 0 and at the end of the memory phase for group 1: either
-    // way it precedes the barrier after which group 0 starts reading that step.
-#define SPMM_STEP(G)                                                                                   \
+    // One k-step of one wavefront; S4 = ks % 4 is a literal so that the number of loads queued in
+    // this step, which the wait below has to leave outstanding, is a constant.  The wait for the
+    // wavefront's own share of step ks + 1 sits at the end of the compute phase for group 0 and at
+    // the end of the memory phase for group 1: either way it precedes the barrier after which
+    // group 0 starts reading that step.
+#define SPMM_STEP(G, S4)                                                                               \
     {                                                                                                  \
-        const uint8_t* st = smem + (ks % S::NST) * S::STAGE;                                           \
+        const int ks = ks0 + S4;                                                                       \
+        constexpr int QUEUED = B_LD + ((S4 & 1) == 0 ? A_LD : 0) + (S4 == 0 ? 1 : 0);                  \
+        const uint8_t* pa = smem + ((S4 >> 1) & 1) * S::A_PAIR + a_rd + ((S4 & 1) ? rd1 : rd0);        \
+        const uint8_t* pb = smem + b_rd + bst * S::B_STAGE;                                            \
+        const uint8_t* pm = smem + m_rd + ((ks0 >> 2) & 1) * S::M_QUAD + S4 * 8;                       \
         BFrag bf[NF];                                                                                  \
         AFrag af[MF];                                                                                  \
         int ai[MF];                                                                                    \
         _Pragma("unroll") for (int j = 0; j < NF; ++j) {                                               \
-            bf[j].u[0] = *(const u32x4*)(st + b_rd + j * 2048);                                        \
-            bf[j].u[1] = *(const u32x4*)(st + b_rd + j * 2048 + 1024);                                 \
+            bf[j].u[0] = *(const u32x4*)(pb + j * 2048 + rd0);                                         \
+            bf[j].u[1] = *(const u32x4*)(pb + j * 2048 + rd1);                                         \
         }                                                                                              \
         _Pragma("unroll") for (int i = 0; i < MF; ++i) {                                               \
-            af[i].u = *(const u32x4*)(st + a_rd + i * 1024);                                           \
-            ai[i] = *(const uint16_t*)(st + m_rd + i * 128);                                           \
+            af[i].u = *(const u32x4*)(pa + i * 2048);                                                  \
+            ai[i] = *(const uint16_t*)(pm + i * 512);                                                  \
         }                                                                                              \
-        issue(ks + 2);                                                                                 \
-        if (G == 1) __builtin_amdgcn_s_waitcnt(waitcnt_imm(NLD, 15));                                  \
+        issue_b(ks + 2, bst >= 1 ? bst - 1 : 2);                                                       \
+        if ((S4 & 1) == 0) issue_a((ks >> 1) + 1, ((S4 >> 1) + 1) & 1);                                \
+        if (S4 == 0) issue_m((ks >> 2) + 1, ((ks0 >> 2) + 1) & 1);                                     \
+        bst = bst == 2 ? 0 : bst + 1;                                                                  \
+        if (G == 1) __builtin_amdgcn_s_waitcnt(waitcnt_imm(QUEUED, 15));                               \
         wg_barrier();                                                                                  \
         _Pragma("unroll") for (int i = 0; i < MF; ++i) _Pragma("unroll") for (int j = 0; j < NF; ++j)  \
             acc[i][j] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(af[i].v, bf[j].v, acc[i][j], ai[i], 0, 0); \
-        if (G == 0) __builtin_amdgcn_s_waitcnt(waitcnt_imm(NLD, 15));                                  \
+        if (G == 0) __builtin_amdgcn_s_waitcnt(waitcnt_imm(QUEUED, 15));                               \
         wg_barrier();                                                                                  \
     }
+    int bst = 0;                                              // ring stage of the current k-step
     if (group == 0) {
-        for (int ks = 0; ks < ksteps; ++ks) SPMM_STEP(0)
+        for (int ks0 = 0; ks0 < ksteps; ks0 += 4) { SPMM_STEP(0, 0) SPMM_STEP(0, 1) SPMM_STEP(0, 2) SPMM_STEP(0, 3) }
         wg_barrier();
     } else {
         wg_barrier();
-        for (int ks = 0; ks < ksteps; ++ks) SPMM_STEP(1)
+        for (int ks0 = 0; ks0 < ksteps; ks0 += 4) { SPMM_STEP(1, 0) SPMM_STEP(1, 1) SPMM_STEP(1, 2) SPMM_STEP(1, 3) }
     }
 #undef SPMM_STEP
     __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 15));           // drain the clamped look-ahead loads
@@ -246,17 +266,155 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_kernel(const bf16_t* __rest
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Generic kernel (any K % 64 == 0): 128 x 128 tile, 4 wavefronts (2 x 2), operands staged through
+// registers into two LDS buffers in fragment order (the 16 bytes a lane feeds to the MFMA sit at
+// 16 * lane inside a 1 KiB fragment), one barrier per k-step.
+struct GenSmem {
+    static constexpr int A_BYTES = 128 * 64, B_BYTES = 128 * 128, M_BYTES = 128 * 8;
+    static constexpr int STAGE = A_BYTES + B_BYTES + M_BYTES;
+};
+
+__global__ void __launch_bounds__(256) spmm_generic_kernel(const bf16_t* __restrict__ B, int n,
+                                                           const bf16_t* __restrict__ Av,
+                                                           const uint8_t* __restrict__ Am, int m, int K,
+                                                           const bf16_t* __restrict__ B2,
+                                                           const bf16_t* __restrict__ A2, int K2,
+                                                           bf16_t* __restrict__ C, int tiles_m) {
+    using S = GenSmem;
+    constexpr int MF = 4, NF = 4, A_LD = 2, B_LD = 4;
+    __shared__ __align__(16) uint8_t smem[2 * S::STAGE];
+    const int m0 = (blockIdx.x % tiles_m) * 128, n0 = (blockIdx.x / tiles_m) * 128;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l16 = lane & 15, lq = lane >> 4;
+    const size_t a_pitch = (size_t)K / 2, m_pitch = (size_t)K / 8, b_pitch = (size_t)K;
+    const bf16_t* a_src[A_LD];
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i) {
+        int row = m0 + (wave * A_LD + i) * 16 + l16;
+        row = row < m ? row : m - 1;
+        a_src[i] = Av + (size_t)row * a_pitch + lq * 8;
+    }
+    const bf16_t* b_src[B_LD];
+#pragma unroll
+    for (int i = 0; i < B_LD; ++i) {
+        int slot = wave * B_LD + i;
+        int row = n0 + (slot >> 1) * 16 + l16;
+        row = row < n ? row : n - 1;
+        b_src[i] = B + (size_t)row * b_pitch + (slot & 1) * 32 + lq * 8;
+    }
+    const uint8_t* m_src;
+    {
+        int row = m0 + (t & 127);
+        row = row < m ? row : m - 1;
+        m_src = Am + (size_t)row * m_pitch;
+    }
+    f32x4 acc[MF][NF];
+#pragma unroll
+    for (int i = 0; i < MF; ++i)
+#pragma unroll
+        for (int j = 0; j < NF; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    const int ksteps = K / 64;
+    u32x4 a_reg[A_LD], b_reg[B_LD];
+    u32x2 m_reg;
+#define GEN_LOAD(kk)                                                                                   \
+    {                                                                                                  \
+        _Pragma("unroll") for (int i = 0; i < A_LD; ++i) a_reg[i] = *(const u32x4*)(a_src[i] + (kk) * 32); \
+        _Pragma("unroll") for (int i = 0; i < B_LD; ++i) b_reg[i] = *(const u32x4*)(b_src[i] + (kk) * 64); \
+        m_reg = *(const u32x2*)(m_src + (kk) * 8);                                                     \
+    }
+#define GEN_STORE(stage)                                                                               \
+    {                                                                                                  \
+        uint8_t* base = smem + (stage) * S::STAGE;                                                     \
+        _Pragma("unroll") for (int i = 0; i < A_LD; ++i) *(u32x4*)(base + (wave * A_LD + i) * 1024 + lane * 16) = a_reg[i]; \
+        _Pragma("unroll") for (int i = 0; i < B_LD; ++i)                                               \
+            *(u32x4*)(base + S::A_BYTES + (wave * B_LD + i) * 1024 + lane * 16) = b_reg[i];            \
+        if (t < 128) *(u32x2*)(base + S::A_BYTES + S::B_BYTES + t * 8) = m_reg;                        \
+    }
+    GEN_LOAD(0)
+    GEN_STORE(0)
+    __syncthreads();
+    for (int ks = 0; ks < ksteps; ++ks) {
+        const int stage = ks & 1;
+        GEN_LOAD(ks + 1 < ksteps ? ks + 1 : ks)               // the last step re-reads its own slab (unused)
+        const uint8_t* base = smem + stage * S::STAGE;
+        const uint8_t* sa = base + (wm * MF) * 1024 + lane * 16;
+        const uint8_t* sb = base + S::A_BYTES + (wn * NF) * 2048 + lane * 16;
+        const uint8_t* sm = base + S::A_BYTES + S::B_BYTES + (wm * MF * 16 + l16) * 8 + lq * 2;
+        BFrag bf[NF];
+#pragma unroll
+        for (int j = 0; j < NF; ++j) {
+            bf[j].u[0] = *(const u32x4*)(sb + j * 2048);
+            bf[j].u[1] = *(const u32x4*)(sb + j * 2048 + 1024);
+        }
+#pragma unroll
+        for (int i = 0; i < MF; ++i) {
+            AFrag a;
+            a.u = *(const u32x4*)(sa + i * 1024);
+            int idx = *(const uint16_t*)(sm + i * 128);
+#pragma unroll
+            for (int j = 0; j < NF; ++j)
+                acc[i][j] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a.v, bf[j].v, acc[i][j], idx, 0, 0);
+        }
+        GEN_STORE(stage ^ 1)
+        __syncthreads();
+    }
+#undef GEN_LOAD
+#undef GEN_STORE
+    for (int k0 = 0; k0 < K2; k0 += 32) {
+        bf16x8 a2[MF], b2[NF];
+#pragma unroll
+        for (int i = 0; i < MF; ++i) {
+            int row = m0 + (wm * MF + i) * 16 + l16;
+            row = row < m ? row : m - 1;
+            AFrag x;
+            x.u = *(const u32x4*)(A2 + (size_t)row * K2 + k0 + lq * 8);
+            a2[i] = x.v;
+        }
+#pragma unroll
+        for (int j = 0; j < NF; ++j) {
+            int row = n0 + (wn * NF + j) * 16 + l16;
+            row = row < n ? row : n - 1;
+            AFrag x;
+            x.u = *(const u32x4*)(B2 + (size_t)row * K2 + k0 + lq * 8);
+            b2[j] = x.v;
+        }
+#pragma unroll
+        for (int i = 0; i < MF; ++i)
+#pragma unroll
+            for (int j = 0; j < NF; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2[i], b2[j], acc[i][j], 0, 0, 0);
+    }
+#pragma unroll
+    for (int j = 0; j < NF; ++j) {
+        int row = n0 + (wn * NF + j) * 16 + l16;
+        if (row >= n) continue;
+#pragma unroll
+        for (int i = 0; i < MF; ++i) {
+            int col = m0 + (wm * MF + i) * 16 + lq * 4;
+            if (col >= m) continue;
+            f32x4 v = acc[i][j];
+            union { __bf16 h[4]; u32x2 u; } o;
+            o.h[0] = (__bf16)v[0]; o.h[1] = (__bf16)v[1]; o.h[2] = (__bf16)v[2]; o.h[3] = (__bf16)v[3];
+            *(u32x2*)(C + (size_t)row * m + col) = o.u;
+        }
+    }
+}
+
 template <int BM, int BN>
 hipError_t launch_tile(const bf16_t* B, int64_t n, const bf16_t* Av, const uint8_t* Am, int64_t m, int64_t K,
                        const bf16_t* B2, const bf16_t* A2, int64_t K2, bf16_t* C, hipStream_t s) {
     using S = SpmmSmem<BM, BN>;
+    static_assert(S::TOTAL <= 160 * 1024, "LDS budget");
     int tiles_m = (int)((m + BM - 1) / BM), tiles_n = (int)((n + BN - 1) / BN);
     int supers = ((tiles_m + SUPER - 1) / SUPER) * ((tiles_n + SUPER - 1) / SUPER);
     auto kern = spmm_kernel<BM, BN>;
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, S::TOTAL);
     if (e != hipSuccess) return e;
-    kern<<<dim3((unsigned)(supers * SUPER * SUPER)), dim3(SPMM_THREADS), S::TOTAL, s>>>(B, (int)n, Av, Am, (int)m, (int)K, B2,
-                                                                               A2, (int)K2, C, tiles_m, tiles_n);
+    kern<<<dim3((unsigned)(supers * SUPER * SUPER)), dim3(SPMM_THREADS), S::TOTAL, s>>>(
+        B, (int)n, Av, Am, (int)m, (int)K, B2, A2, (int)K2, C, tiles_m, tiles_n);
     return hipGetLastError();
 }
 
@@ -264,8 +422,14 @@ hipError_t launch_tile(const bf16_t* B, int64_t n, const bf16_t* Av, const uint8
 
 hipError_t launch_spmm(const bf16_t* B, int64_t n, const bf16_t* A_vals, const uint8_t* A_meta, int64_t m, int64_t K,
                        const bf16_t* B2, const bf16_t* A2, int64_t K2, bf16_t* C, hipStream_t s) {
+    if (K % 256 != 0) {
+        int tiles_m = (int)((m + 127) / 128), tiles_n = (int)((n + 127) / 128);
+        spmm_generic_kernel<<<dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 0, s>>>(
+            B, (int)n, A_vals, A_meta, (int)m, (int)K, B2, A2, (int)K2, C, tiles_m);
+        return hipGetLastError();
+    }
     // big tiles once they fill the 256 compute units, small tiles otherwise
-    int64_t big = ((m + 255) / 256) * ((n + 255) / 256);
-    if (big >= 192) return launch_tile<256, 256>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s);
+    int64_t big = ((m + 191) / 192) * ((n + 255) / 256);
+    if (big >= 192) return launch_tile<192, 256>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s);
     return launch_tile<128, 128>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s);
 }

@@ -105,10 +105,11 @@ def layer_on_device(b, d_out, d_in, rank, seed):
 
 
 # (b, d_out, d_in): the first is the OPT-125m FC1 layer; the others cover ragged token counts,
-# partial tiles of the 128- and the 256-wide kernels and a single k-step
+# partial tiles of the small and the large tile of the fast kernels (contraction length a multiple
+# of 256), the generic kernels (other multiples of 64) and a single k-step
 PRODUCT_SHAPES = [
     (2048, 3072, 768), (300, 448, 320), (1, 64, 64), (17, 192, 64),
-    (4100, 4160, 256), (4096, 4096, 128),
+    (4100, 4160, 256), (4096, 4096, 128), (1000, 1024, 1280), (4100, 4224, 512), (777, 256, 256),
 ]
 
 
