@@ -90,6 +90,9 @@ def main():
         lay["dX"] = torch.empty((b, d_in), dtype=torch.bfloat16, device=dev)
         lay["G"] = torch.empty((d_out, d_in // 2), dtype=torch.bfloat16, device=dev)
         layers.append(lay)
+    # one scratch buffer for the weight-gradient calls, sized for the largest layer
+    wg_ws = torch.empty(max(sl.slope_wgrad_workspace_bytes(b, l["d_in"], l["d_out"]) for l in layers),
+                        dtype=torch.uint8, device=dev)
 
     calls = ["prune_rows", "double_prune", "spmm_fwd", "spmm_bwd_x", "wgrad_masked"]
 
@@ -106,7 +109,7 @@ def main():
             if ev: ev[3].record()
             sl.slope_spmm_bwd_x(lay["dY"], lay["vals_t"], lay["meta_t"], out=lay["dX"])
             if ev: ev[4].record()
-            sl.slope_wgrad_masked(lay["dY"], lay["X"], lay["meta"], out=lay["G"])
+            sl.slope_wgrad_masked(lay["dY"], lay["X"], lay["meta"], out=lay["G"], workspace=wg_ws)
             if ev: ev[5].record()
 
     for _ in range(args.warmup):

@@ -126,9 +126,15 @@ slope_status slope_spmm_bwd_x(const void* dY, int64_t b, const void* WrcT_vals, 
  * App. K: the result is d_out x d_in/2).
  *   dY in bf16[b, d_out], X in bf16[b, d_in], Wr_meta in u8[d_out, d_in/8]
  *   dW_vals out bf16[d_out, d_in/2]; fp32 accumulation.
+ *   workspace_or_null: device scratch of slope_wgrad_workspace_bytes(b, d_in, d_out) bytes,
+ *       256-byte aligned, or NULL.  With scratch, large layers run on token-contiguous copies of
+ *       dY and X (faster); without it an in-place kernel is used.  The result is the same up to
+ *       fp32 summation order.  Contents are undefined after the call.
  */
+size_t slope_wgrad_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out);
 slope_status slope_wgrad_masked(const void* dY, const void* X, int64_t b, const void* Wr_meta,
-                                int64_t d_out, int64_t d_in, void* dW_vals, void* stream);
+                                int64_t d_out, int64_t d_in, void* dW_vals, void* workspace_or_null,
+                                void* stream);
 
 #ifdef __cplusplus
 }

@@ -36,7 +36,8 @@ SIGNATURES = {
     "slope_double_prune": (_INT, [_P, _P, _I64, _I64, _P, _P, _P, _P]),
     "slope_spmm_fwd": (_INT, [_P, _I64, _P, _P, _I64, _I64, _P, _P, _I64, _P, _P, _P]),
     "slope_spmm_bwd_x": (_INT, [_P, _I64, _P, _P, _I64, _I64, _P, _P]),
-    "slope_wgrad_masked": (_INT, [_P, _P, _I64, _P, _I64, _I64, _P, _P]),
+    "slope_wgrad_workspace_bytes": (_SZ, [_I64, _I64, _I64]),
+    "slope_wgrad_masked": (_INT, [_P, _P, _I64, _P, _I64, _I64, _P, _P, _P]),
 }
 
 _lib = None
@@ -146,14 +147,21 @@ def slope_spmm_bwd_x(dY: torch.Tensor, vals_t: torch.Tensor, meta_t: torch.Tenso
     return dX
 
 
-def slope_wgrad_masked(dY: torch.Tensor, X: torch.Tensor, meta: torch.Tensor, out=None):
-    """dW = dY^T X at W^R's kept positions, packed bf16[d_out, d_in/2]."""
+def slope_wgrad_workspace_bytes(b: int, d_in: int, d_out: int) -> int:
+    return int(lib().slope_wgrad_workspace_bytes(b, d_in, d_out))
+
+
+def slope_wgrad_masked(dY: torch.Tensor, X: torch.Tensor, meta: torch.Tensor, out=None, workspace="auto"):
+    """dW = dY^T X at W^R's kept positions, packed bf16[d_out, d_in/2].
+    workspace: a uint8 device tensor, None (in-place kernel), or "auto" (allocate scratch here)."""
     _dev(dY, X, meta)
     b, d_out = dY.shape
     d_in = X.shape[1]
     G = out if out is not None else torch.empty((d_out, d_in // 2), dtype=torch.bfloat16, device=dY.device)
+    if isinstance(workspace, str):
+        workspace = torch.empty(slope_wgrad_workspace_bytes(b, d_in, d_out), dtype=torch.uint8, device=dY.device)
     _check("slope_wgrad_masked", lib().slope_wgrad_masked(_ptr(dY), _ptr(X), b, _ptr(meta), d_out, d_in, _ptr(G),
-                                                          _stream()))
+                                                          _ptr(workspace), _stream()))
     return G
 
 

@@ -26,6 +26,10 @@ hipError_t launch_lowrank_prepare(const bf16_t* X, int64_t n, int64_t d_in, int6
                                   const bf16_t* R, int64_t r, bf16_t* T, bf16_t* Lt, bf16_t* Rt, hipStream_t s);
 hipError_t launch_wgrad_masked(const bf16_t* dY, const bf16_t* X, int64_t b, const uint8_t* meta, int64_t d_out,
                                int64_t d_in, bf16_t* gvals, hipStream_t s);
+// same result through token-contiguous copies of dY and X in `workspace`
+size_t wgrad_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out);
+hipError_t launch_wgrad_masked_ws(const bf16_t* dY, const bf16_t* X, int64_t b, const uint8_t* meta, int64_t d_out,
+                                  int64_t d_in, bf16_t* gvals, void* workspace, hipStream_t s);
 
 // Rank the four keys of a group by (key descending, index ascending) and return the 4-bit
 // set of the two winners.  Keys are small non-negative integers.

@@ -1,0 +1,48 @@
+// Building blocks shared by the MFMA kernels: tile order, global -> LDS loads, barriers.
+#pragma once
+#include "common.h"
+
+constexpr int XCDS = 8;
+constexpr int SUPER = 16;                 // tiles per edge of the chip-wide patch of 256 resident tiles
+
+// s_waitcnt immediate (gfx9 encoding): vmcnt <= vm, lgkmcnt <= lgkm, expcnt unconstrained.
+constexpr int waitcnt_imm(int vm, int lgkm) { return (vm & 15) | ((vm >> 4) << 14) | (7 << 4) | (lgkm << 8); }
+
+// blockIdx -> tile.  Workgroups are dealt round-robin to the 8 XCDs, 32 resident per XCD.  The 256
+// resident tiles form one 16 x 16 patch (so the whole chip shares 16 + 16 operand panels in the
+// last-level cache) and each XCD owns an 8 x 4 corner of it (sharing 8 + 4 panels in its L2).
+__device__ __forceinline__ bool tile_of_block(int tiles_m, int tiles_n, int& tm, int& tn) {
+    int b = blockIdx.x;
+    int xcd = b % XCDS, slot = b / XCDS;
+    int round = slot / 32, w = slot % 32;
+    int supers_n = (tiles_n + SUPER - 1) / SUPER;
+    int sm = round / supers_n, sn = round % supers_n;
+    tm = sm * SUPER + (xcd & 1) * 8 + (w & 7);
+    tn = sn * SUPER + (xcd >> 1) * 4 + (w >> 3);
+    return tm < tiles_m && tn < tiles_n;
+}
+
+inline int super_grid(int tiles_m, int tiles_n) {
+    return ((tiles_m + SUPER - 1) / SUPER) * ((tiles_n + SUPER - 1) / SUPER) * SUPER * SUPER;
+}
+
+// 64 lanes x 16 bytes: lane l's bytes land at lds_dst + 16 * l; lds_dst is wave-uniform
+__device__ __forceinline__ void dma16(const void* gsrc, uint8_t* lds_dst) {
+    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gsrc,
+                                     (void __attribute__((address_space(3)))*)lds_dst, 16, 0, 0);
+}
+
+// Workgroup barrier without the memory fence of __syncthreads(): the fence would wait for every
+// outstanding global -> LDS load (vmcnt(0)), which is exactly what the load rings are there to
+// avoid.  Visibility of those loads is handled by explicit s_waitcnt vmcnt(n) before the barrier;
+// nothing is scheduled across it, so the two phases of a k-step stay phases.
+__device__ __forceinline__ void wg_barrier() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("" ::: "memory");
+}
+
+union BFrag { u32x4 u[2]; bf16x16 v; };
+union AFrag { u32x4 u; bf16x8 v; };

@@ -120,12 +120,24 @@ slope_status slope_spmm_bwd_x(const void* dY, int64_t b, const void* WrcT_vals, 
                               nullptr, nullptr, 0, (bf16_t*)dX, (hipStream_t)stream));
 }
 
+size_t slope_wgrad_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out) {
+    if (b <= 0 || d_in <= 0 || d_out <= 0) return 0;
+    return round256(wgrad_workspace_bytes(b, d_in, d_out));
+}
+
 slope_status slope_wgrad_masked(const void* dY, const void* X, int64_t b, const void* Wr_meta, int64_t d_out,
-                                int64_t d_in, void* dW_vals, void* stream) {
+                                int64_t d_in, void* dW_vals, void* workspace_or_null, void* stream) {
     if (!dY || !X || !Wr_meta || !dW_vals) return SLOPE_ERR_NULL;
     if (bad_extent(b, 1) || bad_extent(d_out, 64) || bad_extent(d_in, 64)) return SLOPE_ERR_SHAPE;
-    if (misaligned(dY, 16) || misaligned(X, 16) || misaligned(Wr_meta, 16) || misaligned(dW_vals, 16))
+    if (misaligned(dY, 16) || misaligned(X, 16) || misaligned(Wr_meta, 16) || misaligned(dW_vals, 16) ||
+        misaligned(workspace_or_null, 256))
         return SLOPE_ERR_ALIGN;
+    // The token-contiguous path pays off once its 256 x 256 tiles fill the chip; small layers and
+    // callers without scratch memory take the in-place kernel.
+    const int64_t tiles = ((d_in + 255) / 256) * ((d_out + 255) / 256);
+    if (workspace_or_null && tiles >= 128)
+        return finish(launch_wgrad_masked_ws((const bf16_t*)dY, (const bf16_t*)X, b, (const uint8_t*)Wr_meta, d_out,
+                                             d_in, (bf16_t*)dW_vals, workspace_or_null, (hipStream_t)stream));
     return finish(launch_wgrad_masked((const bf16_t*)dY, (const bf16_t*)X, b, (const uint8_t*)Wr_meta, d_out, d_in,
                                       (bf16_t*)dW_vals, (hipStream_t)stream));
 }

@@ -32,29 +32,9 @@
 // run half a k-step apart: while one group issues its MFMAs the other reads its fragments from
 // LDS and queues global loads, then they swap (two barriers per k-step), so every SIMD's matrix
 // pipe always has a wavefront feeding it.  Loads run two k-steps ahead of their use.
-#include "common.h"
+#include "pipeline.h"
 
 namespace {
-
-constexpr int XCDS = 8;
-constexpr int SUPER = 16;                 // tiles per edge of the chip-wide patch of 256 resident tiles
-
-// s_waitcnt immediate (gfx9 encoding): vmcnt <= vm, lgkmcnt <= lgkm, expcnt unconstrained.
-constexpr int waitcnt_imm(int vm, int lgkm) { return (vm & 15) | ((vm >> 4) << 14) | (7 << 4) | (lgkm << 8); }
-
-// blockIdx -> tile.  Workgroups are dealt round-robin to the 8 XCDs, 32 resident per XCD.  The 256
-// resident tiles form one 16 x 16 patch (so the whole chip shares 16 + 16 operand panels in the
-// last-level cache) and each XCD owns an 8 x 4 corner of it (sharing 8 + 4 panels in its L2).
-__device__ __forceinline__ bool tile_of_block(int tiles_m, int tiles_n, int& tm, int& tn) {
-    int b = blockIdx.x;
-    int xcd = b % XCDS, slot = b / XCDS;
-    int round = slot / 32, w = slot % 32;
-    int supers_n = (tiles_n + SUPER - 1) / SUPER;
-    int sm = round / supers_n, sn = round % supers_n;
-    tm = sm * SUPER + (xcd & 1) * 8 + (w & 7);
-    tn = sn * SUPER + (xcd >> 1) * 4 + (w >> 3);
-    return tm < tiles_m && tn < tiles_n;
-}
 
 template <int BM, int BN>
 struct SpmmSmem {
@@ -66,27 +46,6 @@ struct SpmmSmem {
     static constexpr int DUMMY = M_OFF + 2 * M_QUAD;   // landing zone for the metadata load of idle wavefronts
     static constexpr int TOTAL = DUMMY + 1024;
 };
-
-// 64 lanes x 16 bytes: lane l's bytes land at lds_dst + 16 * l; lds_dst is wave-uniform
-__device__ __forceinline__ void dma16(const void* gsrc, uint8_t* lds_dst) {
-    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gsrc,
-                                     (void __attribute__((address_space(3)))*)lds_dst, 16, 0, 0);
-}
-
-// Workgroup barrier without the memory fence of __syncthreads(): the fence would wait for every
-// outstanding global -> LDS load (vmcnt(0)), which is exactly what the ring is there to avoid.
-// Visibility of those loads is handled by explicit s_waitcnt vmcnt(n) before the barrier; nothing
-// is scheduled across it, so the two phases of a k-step stay phases.
-__device__ __forceinline__ void wg_barrier() {
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_sched_barrier(0);
-    asm volatile("" ::: "memory");
-}
-
-union BFrag { u32x4 u[2]; bf16x16 v; };
-union AFrag { u32x4 u; bf16x8 v; };
 
 constexpr int SPMM_THREADS = 512;
 
@@ -192,6 +151,9 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_kernel(const bf16_t* __rest
         BFrag bf[NF];                                                                                  \
         AFrag af[MF];                                                                                  \
         int ai[MF];                                                                                    \
+        issue_b(ks + 2, bst >= 1 ? bst - 1 : 2);                                                       \
+        if ((S4 & 1) == 0) issue_a((ks >> 1) + 1, ((S4 >> 1) + 1) & 1);                                \
+        if (S4 == 0) issue_m((ks >> 2) + 1, ((ks0 >> 2) + 1) & 1);                                     \
         _Pragma("unroll") for (int j = 0; j < NF; ++j) {                                               \
             bf[j].u[0] = *(const u32x4*)(pb + j * 2048 + rd0);                                         \
             bf[j].u[1] = *(const u32x4*)(pb + j * 2048 + rd1);                                         \
@@ -200,11 +162,9 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_kernel(const bf16_t* __rest
             af[i].u = *(const u32x4*)(pa + i * 2048);                                                  \
             ai[i] = *(const uint16_t*)(pm + i * 512);                                                  \
         }                                                                                              \
-        issue_b(ks + 2, bst >= 1 ? bst - 1 : 2);                                                       \
-        if ((S4 & 1) == 0) issue_a((ks >> 1) + 1, ((S4 >> 1) + 1) & 1);                                \
-        if (S4 == 0) issue_m((ks >> 2) + 1, ((ks0 >> 2) + 1) & 1);                                     \
         bst = bst == 2 ? 0 : bst + 1;                                                                  \
-        if (G == 1) __builtin_amdgcn_s_waitcnt(waitcnt_imm(QUEUED, 15));                               \
+        /* all LDS reads of this stage have returned before anybody may overwrite it */                \
+        __builtin_amdgcn_s_waitcnt(waitcnt_imm(G == 1 ? QUEUED : 63, 0));                              \
         wg_barrier();                                                                                  \
         _Pragma("unroll") for (int i = 0; i < MF; ++i) _Pragma("unroll") for (int j = 0; j < NF; ++j)  \
             acc[i][j] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(af[i].v, bf[j].v, acc[i][j], ai[i], 0, 0); \
@@ -409,11 +369,10 @@ hipError_t launch_tile(const bf16_t* B, int64_t n, const bf16_t* Av, const uint8
     using S = SpmmSmem<BM, BN>;
     static_assert(S::TOTAL <= 160 * 1024, "LDS budget");
     int tiles_m = (int)((m + BM - 1) / BM), tiles_n = (int)((n + BN - 1) / BN);
-    int supers = ((tiles_m + SUPER - 1) / SUPER) * ((tiles_n + SUPER - 1) / SUPER);
     auto kern = spmm_kernel<BM, BN>;
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, S::TOTAL);
     if (e != hipSuccess) return e;
-    kern<<<dim3((unsigned)(supers * SUPER * SUPER)), dim3(SPMM_THREADS), S::TOTAL, s>>>(
+    kern<<<dim3((unsigned)super_grid(tiles_m, tiles_n)), dim3(SPMM_THREADS), S::TOTAL, s>>>(
         B, (int)n, Av, Am, (int)m, (int)K, B2, A2, (int)K2, C, tiles_m, tiles_n);
     return hipGetLastError();
 }

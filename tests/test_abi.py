@@ -57,8 +57,10 @@ def test_argument_errors_are_reported_before_launch():
     assert lib.slope_spmm_fwd(p, 8, p, p, 64, 1 << 31, None, None, 0, p, None, None) == binding.SLOPE_ERR_SHAPE
     assert lib.slope_spmm_bwd_x(p, 8, p, p, 64, 72, p, None) == binding.SLOPE_ERR_SHAPE
     assert lib.slope_spmm_bwd_x(odd, 8, p, p, 64, 64, p, None) == binding.SLOPE_ERR_ALIGN
-    assert lib.slope_wgrad_masked(p, p, 8, None, 64, 64, p, None) == binding.SLOPE_ERR_NULL
-    assert lib.slope_wgrad_masked(p, p, -1, p, 64, 64, p, None) == binding.SLOPE_ERR_SHAPE
+    assert lib.slope_wgrad_masked(p, p, 8, None, 64, 64, p, None, None) == binding.SLOPE_ERR_NULL
+    assert lib.slope_wgrad_masked(p, p, -1, p, 64, 64, p, None, None) == binding.SLOPE_ERR_SHAPE
+    assert lib.slope_wgrad_masked(p, p, 8, p, 64, 64, p, odd, None) == binding.SLOPE_ERR_ALIGN
+    assert lib.slope_wgrad_workspace_bytes(100, 64, 128) >= (64 + 128) * 128 * 2
     assert b"NULL" in lib.slope_status_string(binding.SLOPE_ERR_NULL)
 
 

@@ -137,11 +137,17 @@ def test_spmm_bwd_x(b, d_out, d_in):
     assert err <= TOL
 
 
-@pytest.mark.parametrize("b,d_out,d_in", PRODUCT_SHAPES + [(1000, 320, 448)])
-def test_wgrad_masked(b, d_out, d_in):
-    say(f"wgrad_masked b={b} d_out={d_out} d_in={d_in}")
+# the last three are large enough for the workspace path (256 x 256 tiles of token-contiguous
+# copies): full tiles, ragged tiles in both dimensions, a token count that is not a multiple of 64
+WGRAD_SHAPES = PRODUCT_SHAPES + [(1000, 320, 448), (200, 4096, 2048), (1000, 4160, 2112), (77, 2048, 4096)]
+
+
+@pytest.mark.parametrize("ws", ["auto", None], ids=["workspace", "in_place"])
+@pytest.mark.parametrize("b,d_out,d_in", WGRAD_SHAPES)
+def test_wgrad_masked(b, d_out, d_in, ws):
+    say(f"wgrad_masked b={b} d_out={d_out} d_in={d_in} workspace={ws}")
     t, d, _, _ = layer_on_device(b, d_out, d_in, 0, seed=b + 7)
-    g = sl.slope_wgrad_masked(d["dY"], d["X"], d["meta"])
+    g = sl.slope_wgrad_masked(d["dY"], d["X"], d["meta"], workspace=ws)
     torch.cuda.synchronize()
     want = so.wgrad_masked(t["dY"], t["X"], u8(d["meta"]))
     err = so.rel_fro(so.bf16_to_f64(host(g)), want)
