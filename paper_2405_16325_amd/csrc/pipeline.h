@@ -44,5 +44,14 @@ __device__ __forceinline__ void wg_barrier() {
     asm volatile("" ::: "memory");
 }
 
+// s_waitcnt that stays where it is written: without the fences the scheduler is free to sink the
+// MFMAs of a compute phase below the wait that ends it.
+#define WAIT_HERE(imm)                          \
+    do {                                        \
+        __builtin_amdgcn_sched_barrier(0);      \
+        __builtin_amdgcn_s_waitcnt(imm);        \
+        __builtin_amdgcn_sched_barrier(0);      \
+    } while (0)
+
 union BFrag { u32x4 u[2]; bf16x16 v; };
 union AFrag { u32x4 u; bf16x8 v; };

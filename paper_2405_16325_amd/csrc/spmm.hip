@@ -133,7 +133,7 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_kernel(const bf16_t* __rest
     issue_a(0, 0);
     issue_b(0, 0);
     issue_b(1, 1);
-    __builtin_amdgcn_s_waitcnt(waitcnt_imm(B_LD, 15));        // everything but B of step 1 has landed
+    WAIT_HERE(waitcnt_imm(B_LD, 15));        // everything but B of step 1 has landed
     wg_barrier();
 
     // One k-step of one wavefront; S4 = ks % 4 is a literal so that the number of loads queued in
@@ -164,11 +164,11 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_kernel(const bf16_t* __rest
         }                                                                                              \
         bst = bst == 2 ? 0 : bst + 1;                                                                  \
         /* all LDS reads of this stage have returned before anybody may overwrite it */                \
-        __builtin_amdgcn_s_waitcnt(waitcnt_imm(G == 1 ? QUEUED : 63, 0));                              \
+        WAIT_HERE(waitcnt_imm(G == 1 ? QUEUED : 63, 0));                              \
         wg_barrier();                                                                                  \
         _Pragma("unroll") for (int i = 0; i < MF; ++i) _Pragma("unroll") for (int j = 0; j < NF; ++j)  \
             acc[i][j] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(af[i].v, bf[j].v, acc[i][j], ai[i], 0, 0); \
-        if (G == 0) __builtin_amdgcn_s_waitcnt(waitcnt_imm(QUEUED, 15));                               \
+        if (G == 0) WAIT_HERE(waitcnt_imm(QUEUED, 15));                               \
         wg_barrier();                                                                                  \
     }
     int bst = 0;                                              // ring stage of the current k-step
@@ -180,7 +180,7 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_kernel(const bf16_t* __rest
         for (int ks0 = 0; ks0 < ksteps; ks0 += 4) { SPMM_STEP(1, 0) SPMM_STEP(1, 1) SPMM_STEP(1, 2) SPMM_STEP(1, 3) }
     }
 #undef SPMM_STEP
-    __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 15));           // drain the clamped look-ahead loads
+    WAIT_HERE(waitcnt_imm(0, 15));           // drain the clamped look-ahead loads
 
     // ---- dense K-extension: C += B2 * A2^T with v_mfma_f32_16x16x32_bf16, operands straight
     //      from global memory (lane l: row l%16, k = 8*(l/16) .. +7, for A and B alike)

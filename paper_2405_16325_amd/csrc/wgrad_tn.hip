@@ -123,7 +123,7 @@ __global__ void __launch_bounds__(TN_THREADS) wgrad_tn_kernel(const bf16_t* __re
         }                                                                                              \
         if (G == 0) issue(ks + 1);                                                                     \
         /* all LDS reads of this stage have returned before anybody may overwrite it */                \
-        __builtin_amdgcn_s_waitcnt(waitcnt_imm(G == 1 ? 0 : 63, 0));                                   \
+        WAIT_HERE(waitcnt_imm(G == 1 ? 0 : 63, 0));                                   \
         wg_barrier();                                                                                  \
         if (G == 1) issue(ks + 2);                                                                     \
         _Pragma("unroll") for (int h = 0; h < 2; ++h)                                                  \
@@ -132,11 +132,11 @@ __global__ void __launch_bounds__(TN_THREADS) wgrad_tn_kernel(const bf16_t* __re
             a.u = af[i].u[h]; b.u = bf[j].u[h];                                                        \
             acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, acc[i][j], 0, 0, 0);         \
         }                                                                                              \
-        if (G == 0) __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 15));                                    \
+        if (G == 0) WAIT_HERE(waitcnt_imm(0, 15));                                    \
         wg_barrier();                                                                                  \
     }
     issue(0);
-    __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 15));
+    WAIT_HERE(waitcnt_imm(0, 15));
     wg_barrier();
     if (group == 0) {
         for (int ks = 0; ks < ksteps; ++ks) TN_STEP(0)
@@ -147,7 +147,7 @@ __global__ void __launch_bounds__(TN_THREADS) wgrad_tn_kernel(const bf16_t* __re
         for (int ks = 0; ks < ksteps; ++ks) TN_STEP(1)
     }
 #undef TN_STEP
-    __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 15));           // drain the clamped look-ahead loads
+    WAIT_HERE(waitcnt_imm(0, 15));           // drain the clamped look-ahead loads
 
     // epilogue: a lane's four accumulators are one group of four along d_in of row o
     const size_t mpitch = (size_t)m / 8, gpitch = (size_t)m / 2;
