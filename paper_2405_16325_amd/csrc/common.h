@@ -31,6 +31,10 @@ size_t wgrad_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out);
 hipError_t launch_wgrad_masked_ws(const bf16_t* dY, const bf16_t* X, int64_t b, const uint8_t* meta, int64_t d_out,
                                   int64_t d_in, bf16_t* gvals, void* workspace, hipStream_t s);
 
+// C[n, m] = B[n, K] * A[m, K]^T (dense bf16, fp32 accumulation), K % 64 == 0
+hipError_t launch_dense_tn_plain(const bf16_t* B, int64_t n, const bf16_t* A, int64_t m, int64_t K, bf16_t* C,
+                                 hipStream_t s);
+
 // Rank the four keys of a group by (key descending, index ascending) and return the 4-bit
 // set of the two winners.  Keys are small non-negative integers.
 __device__ __forceinline__ uint32_t top2_of_4(uint32_t k0, uint32_t k1, uint32_t k2, uint32_t k3) {

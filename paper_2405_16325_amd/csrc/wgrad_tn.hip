@@ -42,28 +42,33 @@ __global__ void __launch_bounds__(256) transpose_pad_kernel(const bf16_t* __rest
     }
 }
 
+template <int BM, int BN>
 struct TnSmem {
-    static constexpr int BM = 256, BN = 256;
-    static constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128;   // one k-step of 64 tokens
+    static constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128;   // one k-step of 64
     static constexpr int STAGE = A_BYTES + B_BYTES;
     static constexpr int TOTAL = 2 * STAGE;
 };
 
 constexpr int TN_THREADS = 512;
+enum { EPI_MASKED_PACKED = 0, EPI_PLAIN = 1 };
 
-// At: [m][kp] (d_in rows), Bt: [n][kp] (d_out rows), kp % 64 == 0.  G: packed gradient [n][m/2].
-__global__ void __launch_bounds__(TN_THREADS) wgrad_tn_kernel(const bf16_t* __restrict__ At, int m,
+// D[i, j] = sum_k At[i, k] * Bt[j, k];  At: [m][kp], Bt: [n][kp], kp % 64 == 0.
+//   EPI_MASKED_PACKED: out = packed gradient [n][m/2] selected by meta (u8[n][m/8])
+//   EPI_PLAIN        : out = bf16 [n][m]  (row j, four consecutive i per lane)
+template <int BM, int BN, int EPI>
+__global__ void __launch_bounds__(TN_THREADS) dense_tn_kernel(const bf16_t* __restrict__ At, int m,
                                                               const bf16_t* __restrict__ Bt, int n, int kp,
                                                               const uint8_t* __restrict__ meta,
-                                                              bf16_t* __restrict__ G, int tiles_m, int tiles_n) {
-    using S = TnSmem;
-    constexpr int MF = 8, NF = 4;                            // wavefront tile 128 (d_in) x 64 (d_out)
-    constexpr int LD = 4;                                    // 1 KiB loads per wavefront per operand per step
+                                                              bf16_t* __restrict__ out, int tiles_m, int tiles_n) {
+    using S = TnSmem<BM, BN>;
+    constexpr int MF = BM / 32, NF = BN / 64;                // 16 x 16 fragments per wavefront (2 x 4 waves)
+    constexpr int LD_A = BM / 64, LD_B = BN / 64;            // 1 KiB loads per wavefront per step
+    constexpr int WM = BM / 2;                               // rows of D per wavefront
     extern __shared__ __align__(16) uint8_t smem[];
 
     int tm, tn;
     if (!tile_of_block(tiles_m, tiles_n, tm, tn)) return;
-    const int m0 = tm * S::BM, n0 = tn * S::BN;
+    const int m0 = tm * BM, n0 = tn * BN;
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int group = wave >> 2;
@@ -71,25 +76,29 @@ __global__ void __launch_bounds__(TN_THREADS) wgrad_tn_kernel(const bf16_t* __re
     const int l16 = lane & 15, lq = lane >> 4;
 
     // loader lanes: 8 lanes per row, chunk rotated by (row / 2) % 8 (rows clamped, never stored)
-    const uint8_t* a_src[LD];
-    const uint8_t* b_src[LD];
+    const uint8_t* a_src[LD_A];
+    const uint8_t* b_src[LD_B];
 #pragma unroll
-    for (int i = 0; i < LD; ++i) {
-        int rl = (wave * LD + i) * 8 + (lane >> 3);
-        int chunk = ((lane & 7) ^ ((rl >> 1) & 7)) * 16;
+    for (int i = 0; i < LD_A; ++i) {
+        int rl = (wave * LD_A + i) * 8 + (lane >> 3);
         int ra = m0 + rl < m ? m0 + rl : m - 1;
+        a_src[i] = (const uint8_t*)At + (size_t)ra * kp * 2 + (((lane & 7) ^ ((rl >> 1) & 7)) * 16);
+    }
+#pragma unroll
+    for (int i = 0; i < LD_B; ++i) {
+        int rl = (wave * LD_B + i) * 8 + (lane >> 3);
         int rb = n0 + rl < n ? n0 + rl : n - 1;
-        a_src[i] = (const uint8_t*)At + (size_t)ra * kp * 2 + chunk;
-        b_src[i] = (const uint8_t*)Bt + (size_t)rb * kp * 2 + chunk;
+        b_src[i] = (const uint8_t*)Bt + (size_t)rb * kp * 2 + (((lane & 7) ^ ((rl >> 1) & 7)) * 16);
     }
     const int ksteps = kp / 64;
     auto issue = [&](int ks) {                               // k-step ks (clamped) into stage ks % 2
         int kc = ks < ksteps ? ks : ksteps - 1;
-        uint8_t* st = smem + (ks & 1) * S::STAGE + wave * LD * 1024;
+        uint8_t* st = smem + (ks & 1) * S::STAGE;
 #pragma unroll
-        for (int i = 0; i < LD; ++i) dma16(a_src[i] + (size_t)kc * 128, st + i * 1024);
+        for (int i = 0; i < LD_A; ++i) dma16(a_src[i] + (size_t)kc * 128, st + (wave * LD_A + i) * 1024);
 #pragma unroll
-        for (int i = 0; i < LD; ++i) dma16(b_src[i] + (size_t)kc * 128, st + S::A_BYTES + i * 1024);
+        for (int i = 0; i < LD_B; ++i)
+            dma16(b_src[i] + (size_t)kc * 128, st + S::A_BYTES + (wave * LD_B + i) * 1024);
     };
 
     // reader lanes: fragment f = rows 16f .. 16f+15 = 2 KiB; lane (l16, lq) wants chunk 4h + lq
@@ -123,7 +132,7 @@ __global__ void __launch_bounds__(TN_THREADS) wgrad_tn_kernel(const bf16_t* __re
         }                                                                                              \
         if (G == 0) issue(ks + 1);                                                                     \
         /* all LDS reads of this stage have returned before anybody may overwrite it */                \
-        WAIT_HERE(waitcnt_imm(G == 1 ? 0 : 63, 0));                                   \
+        WAIT_HERE(waitcnt_imm(G == 1 ? 0 : 63, 0));                                                    \
         wg_barrier();                                                                                  \
         if (G == 1) issue(ks + 2);                                                                     \
         _Pragma("unroll") for (int h = 0; h < 2; ++h)                                                  \
@@ -132,7 +141,7 @@ __global__ void __launch_bounds__(TN_THREADS) wgrad_tn_kernel(const bf16_t* __re
             a.u = af[i].u[h]; b.u = bf[j].u[h];                                                        \
             acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, acc[i][j], 0, 0, 0);         \
         }                                                                                              \
-        if (G == 0) WAIT_HERE(waitcnt_imm(0, 15));                                    \
+        if (G == 0) WAIT_HERE(waitcnt_imm(0, 15));                                                     \
         wg_barrier();                                                                                  \
     }
     issue(0);
@@ -147,40 +156,66 @@ __global__ void __launch_bounds__(TN_THREADS) wgrad_tn_kernel(const bf16_t* __re
         for (int ks = 0; ks < ksteps; ++ks) TN_STEP(1)
     }
 #undef TN_STEP
-    WAIT_HERE(waitcnt_imm(0, 15));           // drain the clamped look-ahead loads
+    WAIT_HERE(waitcnt_imm(0, 15));                            // drain the clamped look-ahead loads
 
-    // epilogue: a lane's four accumulators are one group of four along d_in of row o
+    if (EPI == EPI_PLAIN) {
+#pragma unroll
+        for (int j = 0; j < NF; ++j) {
+            int row = n0 + (wn * NF + j) * 16 + l16;
+            if (row >= n) continue;
+#pragma unroll
+            for (int i = 0; i < MF; ++i) {
+                int col = m0 + wm * WM + i * 16 + lq * 4;
+                if (col >= m) continue;
+                f32x4 v = acc[i][j];
+                union { __bf16 h[4]; u32x2 u; } o;
+                o.h[0] = (__bf16)v[0]; o.h[1] = (__bf16)v[1]; o.h[2] = (__bf16)v[2]; o.h[3] = (__bf16)v[3];
+                *(u32x2*)(out + (size_t)row * m + col) = o.u;
+            }
+        }
+        return;
+    }
+    // masked, packed epilogue: a lane's four accumulators are one group of four along d_in of row o
     const size_t mpitch = (size_t)m / 8, gpitch = (size_t)m / 2;
 #pragma unroll
     for (int j = 0; j < NF; ++j) {
         int o = n0 + (wn * NF + j) * 16 + l16;
         if (o >= n) continue;
-        // metadata of the wavefront's 128 d_in columns of row o: 32 groups = 16 bytes
-        int c0 = m0 + wm * (S::BM / 2);
-        u32x4 mw = {0u, 0u, 0u, 0u};
-        if (c0 + 128 <= m) {
-            mw = *(const u32x4*)(meta + (size_t)o * mpitch + c0 / 8);
-        } else {
+        // metadata of the wavefront's WM d_in columns of row o: WM / 4 groups = WM / 8 bytes
+        int c0 = m0 + wm * WM;
+        uint32_t mw[WM / 32];
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                if (c0 + 32 * q < m) mw[q] = *(const uint32_t*)(meta + (size_t)o * mpitch + c0 / 8 + 4 * q);
-        }
+        for (int q = 0; q < WM / 32; ++q)
+            mw[q] = c0 + 32 * q < m ? *(const uint32_t*)(meta + (size_t)o * mpitch + c0 / 8 + 4 * q) : 0u;
 #pragma unroll
         for (int i = 0; i < MF; ++i) {
             int col = c0 + i * 16 + lq * 4;               // first d_in index of the group
             if (col >= m) continue;
-            int gl = i * 4 + lq;                          // group index inside the 128 columns
-            uint32_t nib = (mw[gl >> 3] >> (4 * (gl & 7))) & 0xFu;
+            int gl = i * 4 + lq;                          // group index inside the WM columns
+            uint32_t nib = (mw[i >> 1] >> (4 * (gl & 7))) & 0xFu;
             uint32_t a = nib & 3u, c = nib >> 2;
             f32x4 v = acc[i][j];
             float v0 = a == 0 ? v[0] : (a == 1 ? v[1] : v[2]);
             float v1 = c == 1 ? v[1] : (c == 2 ? v[2] : v[3]);
-            union { __bf16 h[2]; uint32_t u; } out;
-            out.h[0] = (__bf16)v0;
-            out.h[1] = (__bf16)v1;
-            *(uint32_t*)(G + (size_t)o * gpitch + (col >> 1)) = out.u;
+            union { __bf16 h[2]; uint32_t u; } pr;
+            pr.h[0] = (__bf16)v0;
+            pr.h[1] = (__bf16)v1;
+            *(uint32_t*)(out + (size_t)o * gpitch + (col >> 1)) = pr.u;
         }
     }
+}
+
+template <int BM, int BN, int EPI>
+hipError_t launch_dense_tn(const bf16_t* At, int64_t m, const bf16_t* Bt, int64_t n, int64_t kp, const uint8_t* meta,
+                           bf16_t* out, hipStream_t s) {
+    using S = TnSmem<BM, BN>;
+    int tiles_m = (int)((m + BM - 1) / BM), tiles_n = (int)((n + BN - 1) / BN);
+    auto kern = dense_tn_kernel<BM, BN, EPI>;
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, S::TOTAL);
+    if (e != hipSuccess) return e;
+    kern<<<dim3((unsigned)super_grid(tiles_m, tiles_n)), dim3(TN_THREADS), S::TOTAL, s>>>(
+        At, (int)m, Bt, (int)n, (int)kp, meta, out, tiles_m, tiles_n);
+    return hipGetLastError();
 }
 
 }  // namespace
@@ -199,10 +234,12 @@ hipError_t launch_wgrad_masked_ws(const bf16_t* dY, const bf16_t* X, int64_t b, 
     transpose_pad_kernel<<<dim3((unsigned)(bp / 64), (unsigned)(d_out / 64)), dim3(256), 0, s>>>(dY, (int)b, (int)d_out, bp, dYt);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    int tiles_m = (int)((d_in + 255) / 256), tiles_n = (int)((d_out + 255) / 256);
-    e = hipFuncSetAttribute((const void*)wgrad_tn_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, TnSmem::TOTAL);
-    if (e != hipSuccess) return e;
-    wgrad_tn_kernel<<<dim3((unsigned)super_grid(tiles_m, tiles_n)), dim3(TN_THREADS), TnSmem::TOTAL, s>>>(
-        Xt, (int)d_in, dYt, (int)d_out, bp, meta, gvals, tiles_m, tiles_n);
-    return hipGetLastError();
+    return launch_dense_tn<256, 256, EPI_MASKED_PACKED>(Xt, d_in, dYt, d_out, bp, meta, gvals, s);
+}
+
+// C[n, m] = B[n, K] * A[m, K]^T, all bf16 row-major, K % 64 == 0 (the skinny product T = X L of the
+// adapter: m = rank).  Small tiles so that even m = 128 spreads over many compute units.
+hipError_t launch_dense_tn_plain(const bf16_t* B, int64_t n, const bf16_t* A, int64_t m, int64_t K, bf16_t* C,
+                                 hipStream_t s) {
+    return launch_dense_tn<128, 128, EPI_PLAIN>(A, m, B, n, K, nullptr, C, s);
 }
