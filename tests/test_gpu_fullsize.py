@@ -1,0 +1,97 @@
+"""Parity at the benchmark's full layer sizes (OPT-66B-shaped FC1 and FC2, 16384 tokens), in the
+launch configuration bench.py times.  The oracle cannot evaluate 11 TFLOP products, so it
+computes seeded samples of the outputs one by one:
+
+  * prune_rows is local to a row: sampled rows of W are pruned by the oracle and compared bit for
+    bit with the same rows of the GPU's packed W^R;
+  * double_prune is local to a group of four columns of W: for sampled column groups the oracle
+    prunes W[:, group] along rows, then along d_out, and the GPU's packed (W^{R,C})^T rows of those
+    columns must match bit for bit;
+  * Y, dX and dW are compared on (sampled tokens x sampled features) blocks whose operands the
+    oracle derives from those same sampled rows / column groups of W.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import slope_oracle as so
+from paper_2405_16325_amd import binding as sl
+from paper_2405_16325_amd import inputs
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-2
+
+
+def host(t):
+    return sl.bf16_to_host(t)
+
+
+@pytest.mark.parametrize("name,d_out,d_in", [("fc1", 36864, 9216), ("fc2", 9216, 36864)])
+def test_opt66b_layer_sampled(name, d_out, d_in):
+    b, rank = 16384, 128
+    print(f"full-size {name}: b={b} d_out={d_out} d_in={d_in} rank={rank}", flush=True)
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(inputs.SEED_BASE + 66)
+
+    def gauss(shape, std):
+        return (torch.randn(shape, generator=gen, device=dev, dtype=torch.float32) * std).to(torch.bfloat16)
+
+    X, W, dY = gauss((b, d_in), 1.0), gauss((d_out, d_in), 0.02), gauss((b, d_out), 1e-3)
+    L, R = gauss((d_in, rank), 0.02), gauss((rank, d_out), 0.02)
+    vals, meta, _ = sl.slope_prune_rows(W)
+    vals_t, meta_t, _ = sl.slope_double_prune(vals, meta)
+    Y = sl.slope_spmm_fwd(X, vals, meta, L, R)
+    dX = sl.slope_spmm_bwd_x(dY, vals_t, meta_t)
+    G = sl.slope_wgrad_masked(dY, X, meta)
+    torch.cuda.synchronize()
+
+    rng = np.random.default_rng(66)
+    rows = np.sort(rng.choice(d_out, 48, replace=False))            # sampled rows of W (features of Y)
+    groups = np.sort(rng.choice(d_in // 4, 12, replace=False))      # sampled column groups of W
+    cols = (groups[:, None] * 4 + np.arange(4)).ravel()             # 48 columns of W (features of dX)
+    toks = np.sort(rng.choice(b, 40, replace=False))
+    rows_t, cols_t, toks_t = (torch.from_numpy(a).to(dev) for a in (rows, cols, toks))
+
+    # ---- prune_rows on sampled rows
+    w_rows = host(W[rows_t])                                        # [48, d_in]
+    ov, om, _ = so.prune_rows_packed(w_rows)
+    assert (host(vals[rows_t]) == ov).all()
+    assert (meta[rows_t].cpu().numpy() == om).all()
+
+    # ---- double_prune on sampled column groups: W[:, cols] is a complete set of row-prune groups
+    w_cols = host(W[:, cols_t].contiguous())                        # [d_out, 48]
+    cv, cm, _ = so.prune_rows_packed(w_cols)
+    evt, emt, _ = so.double_prune_packed(cv, cm)                    # rows = the 48 columns, along d_out
+    assert (host(vals_t[cols_t]) == evt).all()
+    assert (meta_t[cols_t].cpu().numpy() == emt).all()
+
+    # ---- forward block: sampled tokens x sampled rows of W
+    mask_rows = so.prune_rows(w_rows)
+    want_y = so.spmm_fwd(host(X[toks_t]), w_rows, mask_rows, host(L), host(R[:, rows_t].contiguous()))
+    got_y = so.bf16_to_f64(host(Y[toks_t][:, rows_t].contiguous()))
+    err_y = so.rel_fro(got_y, want_y)
+
+    # ---- input-gradient block: sampled tokens x sampled columns of W
+    mask_cols_r = so.prune_rows(w_cols)
+    mask_cols_rc = so.double_prune(w_cols, mask_cols_r)
+    want_dx = so.spmm_bwd_x(host(dY[toks_t]), w_cols, mask_cols_rc)
+    got_dx = so.bf16_to_f64(host(dX[toks_t][:, cols_t].contiguous()))
+    err_dx = so.rel_fro(got_dx, want_dx)
+
+    # ---- weight-gradient block: sampled rows x sampled column groups, packed order
+    sub_meta = om.reshape(len(rows), d_in // 8)
+    nib = np.where((groups % 2) == 0, sub_meta[:, groups // 2] & 0xF, sub_meta[:, groups // 2] >> 4)
+    pairs = (nib[:, 0::2] | (nib[:, 1::2] << 4)).astype(np.uint8)   # metadata of the 12 groups, re-packed
+    want_g = so.wgrad_masked(host(dY[:, rows_t].contiguous()), host(X[:, cols_t].contiguous()), pairs)
+    gidx = (groups[:, None] * 2 + np.arange(2)).ravel()
+    got_g = so.bf16_to_f64(host(G[rows_t][:, torch.from_numpy(gidx).to(dev)].contiguous()))
+    err_g = so.rel_fro(got_g, want_g)
+
+    print(f"  rel_fro fwd {err_y:.3e}  bwd_x {err_dx:.3e}  wgrad {err_g:.3e}", flush=True)
+    assert err_y <= TOL and err_dx <= TOL and err_g <= TOL
+    # every group of the full-size packed outputs names two distinct ascending positions
+    for m in (meta, meta_t):
+        lo, hi = m & 3, (m >> 2) & 3
+        lo2, hi2 = (m >> 4) & 3, m >> 6
+        assert bool((lo < hi).all()) and bool((lo2 < hi2).all())
