@@ -387,6 +387,16 @@ hipError_t launch_spmm(const bf16_t* B, int64_t n, const bf16_t* A_vals, const u
             B, (int)n, A_vals, A_meta, (int)m, (int)K, B2, A2, (int)K2, C, tiles_m);
         return hipGetLastError();
     }
+    // Few tokens (inference): the product is a single pass over the packed weight, bound by HBM.
+    // Narrow token tiles, and weight tiles small enough that every compute unit streams its share.
+    if (n <= 128) {
+        const bool many = (m + 127) / 128 >= 200;
+        if (n <= 64)
+            return many ? launch_tile<128, 64>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s)
+                        : launch_tile<64, 64>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s);
+        return many ? launch_tile<128, 128>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s)
+                    : launch_tile<64, 128>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s);
+    }
     // big tiles once they fill the 256 compute units, small tiles otherwise
     int64_t big = ((m + 191) / 192) * ((n + 255) / 256);
     if (big >= 192) return launch_tile<192, 256>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s);

@@ -113,7 +113,11 @@ PRODUCT_SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("b,d_out,d_in", PRODUCT_SHAPES)
+# few tokens (inference): the narrow-token tiles, with few and with many weight tiles
+SKINNY_SHAPES = [(1, 512, 512), (7, 25600, 256), (100, 512, 768), (128, 25600, 256), (16, 256, 25600)]
+
+
+@pytest.mark.parametrize("b,d_out,d_in", PRODUCT_SHAPES + SKINNY_SHAPES)
 def test_spmm_fwd(b, d_out, d_in):
     say(f"spmm_fwd b={b} d_out={d_out} d_in={d_in}")
     t, d, mask_r, _ = layer_on_device(b, d_out, d_in, 0, seed=b + d_out)
@@ -125,7 +129,7 @@ def test_spmm_fwd(b, d_out, d_in):
     assert err <= TOL
 
 
-@pytest.mark.parametrize("b,d_out,d_in", PRODUCT_SHAPES)
+@pytest.mark.parametrize("b,d_out,d_in", PRODUCT_SHAPES + SKINNY_SHAPES)
 def test_spmm_bwd_x(b, d_out, d_in):
     say(f"spmm_bwd_x b={b} d_out={d_out} d_in={d_in}")
     t, d, _, mask_rc = layer_on_device(b, d_out, d_in, 0, seed=b + d_in)
