@@ -3,27 +3,46 @@
 #include "common.h"
 
 constexpr int XCDS = 8;
-constexpr int SUPER = 16;                 // tiles per edge of the chip-wide patch of 256 resident tiles
-
+constexpr int SUPER = 16;                 // tiles per edge of the chip-wide patch of resident tiles
+constexpr int RESIDENT = 256;             // tiles in flight on the chip: one per compute unit
 // s_waitcnt immediate (gfx9 encoding): vmcnt <= vm, lgkmcnt <= lgkm, expcnt unconstrained.
 constexpr int waitcnt_imm(int vm, int lgkm) { return (vm & 15) | ((vm >> 4) << 14) | (7 << 4) | (lgkm << 8); }
 
-// blockIdx -> tile.  Workgroups are dealt round-robin to the 8 XCDs, 32 resident per XCD.  The 256
-// resident tiles form one 16 x 16 patch (so the whole chip shares 16 + 16 operand panels in the
-// last-level cache) and each XCD owns an 8 x 4 corner of it (sharing 8 + 4 panels in its L2).
+// blockIdx -> tile.  Workgroups are dealt round-robin to the 8 XCDs, 32 resident per XCD.
+//  * At least SUPER tiles along both axes: the 256 resident tiles form one 16 x 16 patch (the chip
+//    shares 16 + 16 operand panels in the last-level cache) and each XCD owns an 8 x 4 corner of
+//    it (sharing 8 + 4 panels in its L2).
+//  * A narrow grid (skinny products, inference-size batches): tiles are numbered short axis first
+//    and each XCD takes runs of consecutive tiles: at most 32, sized so that all 8 XCDs get equal
+//    shares in every round, also when there are fewer than 256 tiles.
+__host__ __device__ inline int narrow_run(int tiles) {
+    int rounds = (tiles + RESIDENT - 1) / RESIDENT;        // even shares in every round, the last included
+    return (tiles + XCDS * rounds - 1) / (XCDS * rounds);
+}
+
 __device__ __forceinline__ bool tile_of_block(int tiles_m, int tiles_n, int& tm, int& tn) {
     int b = blockIdx.x;
     int xcd = b % XCDS, slot = b / XCDS;
-    int round = slot / 32, w = slot % 32;
-    int supers_n = (tiles_n + SUPER - 1) / SUPER;
-    int sm = round / supers_n, sn = round % supers_n;
-    tm = sm * SUPER + (xcd & 1) * 8 + (w & 7);
-    tn = sn * SUPER + (xcd >> 1) * 4 + (w >> 3);
+    if (tiles_m >= SUPER && tiles_n >= SUPER) {
+        int round = slot / 32, w = slot % 32;
+        int supers_n = (tiles_n + SUPER - 1) / SUPER;
+        int sm = round / supers_n, sn = round % supers_n;
+        tm = sm * SUPER + (xcd & 1) * 8 + (w & 7);
+        tn = sn * SUPER + (xcd >> 1) * 4 + (w >> 3);
+        return tm < tiles_m && tn < tiles_n;
+    }
+    int run = narrow_run(tiles_m * tiles_n);
+    int t = ((slot / run) * XCDS + xcd) * run + slot % run;
+    if (tiles_m <= tiles_n) { tm = t % tiles_m; tn = t / tiles_m; }
+    else { tn = t % tiles_n; tm = t / tiles_n; }
     return tm < tiles_m && tn < tiles_n;
 }
 
 inline int super_grid(int tiles_m, int tiles_n) {
-    return ((tiles_m + SUPER - 1) / SUPER) * ((tiles_n + SUPER - 1) / SUPER) * SUPER * SUPER;
+    if (tiles_m >= SUPER && tiles_n >= SUPER)
+        return ((tiles_m + SUPER - 1) / SUPER) * ((tiles_n + SUPER - 1) / SUPER) * SUPER * SUPER;
+    int tiles = tiles_m * tiles_n, chunk = XCDS * narrow_run(tiles);
+    return (tiles + chunk - 1) / chunk * chunk;
 }
 
 // 64 lanes x 16 bytes: lane l's bytes land at lds_dst + 16 * l; lds_dst is wave-uniform

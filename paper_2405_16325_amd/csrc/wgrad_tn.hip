@@ -42,11 +42,11 @@ __global__ void __launch_bounds__(256) transpose_pad_kernel(const bf16_t* __rest
     }
 }
 
-template <int BM, int BN>
+template <int BM, int BN, int NS>
 struct TnSmem {
     static constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128;   // one k-step of 64
     static constexpr int STAGE = A_BYTES + B_BYTES;
-    static constexpr int TOTAL = 2 * STAGE;
+    static constexpr int TOTAL = NS * STAGE;                       // ring of NS stages
 };
 
 constexpr int TN_THREADS = 512;
@@ -55,15 +55,18 @@ enum { EPI_MASKED_PACKED = 0, EPI_PLAIN = 1 };
 // D[i, j] = sum_k At[i, k] * Bt[j, k];  At: [m][kp], Bt: [n][kp], kp % 64 == 0.
 //   EPI_MASKED_PACKED: out = packed gradient [n][m/2] selected by meta (u8[n][m/8])
 //   EPI_PLAIN        : out = bf16 [n][m]  (row j, four consecutive i per lane)
-template <int BM, int BN, int EPI>
+// NS = ring depth: loads run NS - 1 k-steps ahead.  Two stages are all that fits beside a 256 x 256
+// tile; small tiles (memory-bound skinny products) take a deeper ring to cover the HBM latency.
+template <int BM, int BN, int EPI, int NS>
 __global__ void __launch_bounds__(TN_THREADS) dense_tn_kernel(const bf16_t* __restrict__ At, int m,
                                                               const bf16_t* __restrict__ Bt, int n, int kp,
                                                               const uint8_t* __restrict__ meta,
                                                               bf16_t* __restrict__ out, int tiles_m, int tiles_n) {
-    using S = TnSmem<BM, BN>;
+    using S = TnSmem<BM, BN, NS>;
     constexpr int MF = BM / 32, NF = BN / 64;                // 16 x 16 fragments per wavefront (2 x 4 waves)
     constexpr int LD_A = BM / 64, LD_B = BN / 64;            // 1 KiB loads per wavefront per step
     constexpr int WM = BM / 2;                               // rows of D per wavefront
+    constexpr int AHEAD = (NS - 2) * (LD_A + LD_B);          // loads that may stay in flight at a wait
     extern __shared__ __align__(16) uint8_t smem[];
 
     int tm, tn;
@@ -91,9 +94,9 @@ __global__ void __launch_bounds__(TN_THREADS) dense_tn_kernel(const bf16_t* __re
         b_src[i] = (const uint8_t*)Bt + (size_t)rb * kp * 2 + (((lane & 7) ^ ((rl >> 1) & 7)) * 16);
     }
     const int ksteps = kp / 64;
-    auto issue = [&](int ks) {                               // k-step ks (clamped) into stage ks % 2
+    auto issue = [&](int ks) {                               // k-step ks (clamped) into stage ks % NS
         int kc = ks < ksteps ? ks : ksteps - 1;
-        uint8_t* st = smem + (ks & 1) * S::STAGE;
+        uint8_t* st = smem + (ks % NS) * S::STAGE;
 #pragma unroll
         for (int i = 0; i < LD_A; ++i) dma16(a_src[i] + (size_t)kc * 128, st + (wave * LD_A + i) * 1024);
 #pragma unroll
@@ -114,13 +117,14 @@ __global__ void __launch_bounds__(TN_THREADS) dense_tn_kernel(const bf16_t* __re
 #pragma unroll
         for (int j = 0; j < NF; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    // One k-step.  Loads of step s + 1 are queued in the even phase in which stage (s + 1) % 2 has
-    // just been released: group 0 is then in its memory phase of step s, group 1 in its compute
-    // phase of step s - 1.  Every wavefront waits for its own loads one phase later, before the
-    // barrier after which group 0 reads them.
+    // One k-step.  Loads of step s + NS - 1 are queued in the even phase in which their stage, last
+    // read for step s - 1, has just been released: group 0 is then in its memory phase of step s,
+    // group 1 in its compute phase of step s - 1.  One phase later every wavefront waits until only
+    // the loads of steps beyond s + 1 are outstanding, before the barrier after which group 0 reads
+    // step s + 1.
 #define TN_STEP(G)                                                                                     \
     {                                                                                                  \
-        const uint8_t* st = smem + (ks & 1) * S::STAGE;                                                \
+        const uint8_t* st = smem + (ks % NS) * S::STAGE;                                               \
         BFrag af[MF], bf[NF];                                                                          \
         _Pragma("unroll") for (int i = 0; i < MF; ++i) {                                               \
             af[i].u[0] = *(const u32x4*)(st + a_rd + i * 2048 + rd0);                                  \
@@ -130,28 +134,29 @@ __global__ void __launch_bounds__(TN_THREADS) dense_tn_kernel(const bf16_t* __re
             bf[j].u[0] = *(const u32x4*)(st + b_rd + j * 2048 + rd0);                                  \
             bf[j].u[1] = *(const u32x4*)(st + b_rd + j * 2048 + rd1);                                  \
         }                                                                                              \
-        if (G == 0) issue(ks + 1);                                                                     \
+        if (G == 0) issue(ks + NS - 1);                                                                \
         /* all LDS reads of this stage have returned before anybody may overwrite it */                \
-        WAIT_HERE(waitcnt_imm(G == 1 ? 0 : 63, 0));                                                    \
+        WAIT_HERE(waitcnt_imm(G == 1 ? AHEAD : 63, 0));                                                \
         wg_barrier();                                                                                  \
-        if (G == 1) issue(ks + 2);                                                                     \
+        if (G == 1) issue(ks + NS);                                                                    \
         _Pragma("unroll") for (int h = 0; h < 2; ++h)                                                  \
         _Pragma("unroll") for (int i = 0; i < MF; ++i) _Pragma("unroll") for (int j = 0; j < NF; ++j) { \
             AFrag a, b;                                                                                \
             a.u = af[i].u[h]; b.u = bf[j].u[h];                                                        \
             acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, acc[i][j], 0, 0, 0);         \
         }                                                                                              \
-        if (G == 0) WAIT_HERE(waitcnt_imm(0, 15));                                                     \
+        if (G == 0) WAIT_HERE(waitcnt_imm(AHEAD, 15));                                                 \
         wg_barrier();                                                                                  \
     }
-    issue(0);
-    WAIT_HERE(waitcnt_imm(0, 15));
+#pragma unroll
+    for (int p = 0; p < NS - 1; ++p) issue(p);
+    WAIT_HERE(waitcnt_imm(AHEAD, 15));                        // step 0 has landed (this wave's share)
     wg_barrier();
     if (group == 0) {
         for (int ks = 0; ks < ksteps; ++ks) TN_STEP(0)
         wg_barrier();
     } else {
-        issue(1);
+        issue(NS - 1);
         wg_barrier();
         for (int ks = 0; ks < ksteps; ++ks) TN_STEP(1)
     }
@@ -205,12 +210,13 @@ __global__ void __launch_bounds__(TN_THREADS) dense_tn_kernel(const bf16_t* __re
     }
 }
 
-template <int BM, int BN, int EPI>
+template <int BM, int BN, int EPI, int NS>
 hipError_t launch_dense_tn(const bf16_t* At, int64_t m, const bf16_t* Bt, int64_t n, int64_t kp, const uint8_t* meta,
                            bf16_t* out, hipStream_t s) {
-    using S = TnSmem<BM, BN>;
+    using S = TnSmem<BM, BN, NS>;
+    static_assert(S::TOTAL <= 160 * 1024, "LDS budget");
     int tiles_m = (int)((m + BM - 1) / BM), tiles_n = (int)((n + BN - 1) / BN);
-    auto kern = dense_tn_kernel<BM, BN, EPI>;
+    auto kern = dense_tn_kernel<BM, BN, EPI, NS>;
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, S::TOTAL);
     if (e != hipSuccess) return e;
     kern<<<dim3((unsigned)super_grid(tiles_m, tiles_n)), dim3(TN_THREADS), S::TOTAL, s>>>(
@@ -234,12 +240,13 @@ hipError_t launch_wgrad_masked_ws(const bf16_t* dY, const bf16_t* X, int64_t b, 
     transpose_pad_kernel<<<dim3((unsigned)(bp / 64), (unsigned)(d_out / 64)), dim3(256), 0, s>>>(dY, (int)b, (int)d_out, bp, dYt);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    return launch_dense_tn<256, 256, EPI_MASKED_PACKED>(Xt, d_in, dYt, d_out, bp, meta, gvals, s);
+    return launch_dense_tn<256, 256, EPI_MASKED_PACKED, 2>(Xt, d_in, dYt, d_out, bp, meta, gvals, s);
 }
 
 // C[n, m] = B[n, K] * A[m, K]^T, all bf16 row-major, K % 64 == 0 (the skinny product T = X L of the
-// adapter: m = rank).  Small tiles so that even m = 128 spreads over many compute units.
+// adapter: m = rank).  The product is bound by streaming B once: narrow token tiles so that even
+// m = 128 gives every compute unit a tile, and a six-deep ring to keep enough reads in flight.
 hipError_t launch_dense_tn_plain(const bf16_t* B, int64_t n, const bf16_t* A, int64_t m, int64_t K, bf16_t* C,
                                  hipStream_t s) {
-    return launch_dense_tn<128, 128, EPI_PLAIN>(A, m, B, n, K, nullptr, C, s);
+    return launch_dense_tn<128, 64, EPI_PLAIN, 6>(A, m, B, n, K, nullptr, C, s);
 }
