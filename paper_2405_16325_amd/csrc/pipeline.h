@@ -3,18 +3,23 @@
 #include "common.h"
 
 constexpr int XCDS = 8;
-constexpr int SUPER = 16;                 // tiles per edge of the chip-wide patch of resident tiles
+constexpr int SUPER = 16;                 // fewer tiles than this along an axis make a grid narrow
 constexpr int RESIDENT = 256;             // tiles in flight on the chip: one per compute unit
 // s_waitcnt immediate (gfx9 encoding): vmcnt <= vm, lgkmcnt <= lgkm, expcnt unconstrained.
 constexpr int waitcnt_imm(int vm, int lgkm) { return (vm & 15) | ((vm >> 4) << 14) | (7 << 4) | (lgkm << 8); }
 
 // blockIdx -> tile.  Workgroups are dealt round-robin to the 8 XCDs, 32 resident per XCD.
-//  * At least SUPER tiles along both axes: the 256 resident tiles form one 16 x 16 patch (the chip
-//    shares 16 + 16 operand panels in the last-level cache) and each XCD owns an 8 x 4 corner of
-//    it (sharing 8 + 4 panels in its L2).
+//  * At least SUPER tiles along both axes: the grid is cut into chunks of 8 x 4 tiles, the 32 tiles
+//    an XCD holds at a time (they share 8 + 4 operand panels in its L2).  Chunks are numbered so
+//    that eight consecutive ones form a 16 x 16 patch (2 x 4 chunks; the chip then shares 16 + 16
+//    panels in the last-level cache), patch after patch along n, then along m, with the chunks
+//    that the grid's ragged edges leave out skipped.  Chunk c goes to XCD c % 8, so every XCD
+//    gets the same number of chunks, give or take one, whatever the grid's shape.
 //  * A narrow grid (skinny products, inference-size batches): tiles are numbered short axis first
 //    and each XCD takes runs of consecutive tiles: at most 32, sized so that all 8 XCDs get equal
 //    shares in every round, also when there are fewer than 256 tiles.
+constexpr int CHUNK_M = 8, CHUNK_N = 4;
+
 __host__ __device__ inline int narrow_run(int tiles) {
     int rounds = (tiles + RESIDENT - 1) / RESIDENT;        // even shares in every round, the last included
     return (tiles + XCDS * rounds - 1) / (XCDS * rounds);
@@ -25,10 +30,15 @@ __device__ __forceinline__ bool tile_of_block(int tiles_m, int tiles_n, int& tm,
     int xcd = b % XCDS, slot = b / XCDS;
     if (tiles_m >= SUPER && tiles_n >= SUPER) {
         int round = slot / 32, w = slot % 32;
-        int supers_n = (tiles_n + SUPER - 1) / SUPER;
-        int sm = round / supers_n, sn = round % supers_n;
-        tm = sm * SUPER + (xcd & 1) * 8 + (w & 7);
-        tn = sn * SUPER + (xcd >> 1) * 4 + (w >> 3);
+        int chunks_m = (tiles_m + CHUNK_M - 1) / CHUNK_M, chunks_n = (tiles_n + CHUNK_N - 1) / CHUNK_N;
+        int c = round * XCDS + xcd;
+        if (c >= chunks_m * chunks_n) return false;
+        int sm = c / (2 * chunks_n), rem = c - sm * 2 * chunks_n;   // patch row: 2 chunk rows (1 in a ragged last)
+        int hm = chunks_m - 2 * sm < 2 ? 1 : 2;
+        int sn = rem / (4 * hm), r2 = rem - sn * 4 * hm;            // patch: 4 chunk columns (fewer at the edge)
+        int wn = chunks_n - 4 * sn < 4 ? chunks_n - 4 * sn : 4;
+        tm = (2 * sm + r2 / wn) * CHUNK_M + (w & 7);
+        tn = (4 * sn + r2 % wn) * CHUNK_N + (w >> 3);
         return tm < tiles_m && tn < tiles_n;
     }
     int run = narrow_run(tiles_m * tiles_n);
@@ -39,8 +49,10 @@ __device__ __forceinline__ bool tile_of_block(int tiles_m, int tiles_n, int& tm,
 }
 
 inline int super_grid(int tiles_m, int tiles_n) {
-    if (tiles_m >= SUPER && tiles_n >= SUPER)
-        return ((tiles_m + SUPER - 1) / SUPER) * ((tiles_n + SUPER - 1) / SUPER) * SUPER * SUPER;
+    if (tiles_m >= SUPER && tiles_n >= SUPER) {
+        int chunks = ((tiles_m + CHUNK_M - 1) / CHUNK_M) * ((tiles_n + CHUNK_N - 1) / CHUNK_N);
+        return (chunks + XCDS - 1) / XCDS * RESIDENT;
+    }
     int tiles = tiles_m * tiles_n, chunk = XCDS * narrow_run(tiles);
     return (tiles + chunk - 1) / chunk * chunk;
 }

@@ -52,6 +52,42 @@ struct TnSmem {
 constexpr int TN_THREADS = 512;
 enum { EPI_MASKED_PACKED = 0, EPI_PLAIN = 1 };
 
+// Masked, packed epilogue of one wavefront: acc[i][j] is the 16 x 16 fragment at D rows
+// c0 + 16 i (d_in) and D columns o0 + 16 j (d_out).  A lane's four accumulators are one group of
+// four along d_in of row o: the group's metadata nibble picks the two that W^R keeps.
+template <int MF, int NF>
+__device__ __forceinline__ void store_masked_packed(const f32x4 (&acc)[MF][NF], int m, int n, int c0, int o0,
+                                                    int l16, int lq, const uint8_t* __restrict__ meta,
+                                                    bf16_t* __restrict__ out) {
+    constexpr int WM = MF * 16;
+    const size_t mpitch = (size_t)m / 8, gpitch = (size_t)m / 2;
+#pragma unroll
+    for (int j = 0; j < NF; ++j) {
+        int o = o0 + j * 16 + l16;
+        if (o >= n) continue;
+        // metadata of the wavefront's WM d_in columns of row o: WM / 4 groups = WM / 8 bytes
+        uint32_t mw[WM / 32];
+#pragma unroll
+        for (int q = 0; q < WM / 32; ++q)
+            mw[q] = c0 + 32 * q < m ? *(const uint32_t*)(meta + (size_t)o * mpitch + c0 / 8 + 4 * q) : 0u;
+#pragma unroll
+        for (int i = 0; i < MF; ++i) {
+            int col = c0 + i * 16 + lq * 4;               // first d_in index of the group
+            if (col >= m) continue;
+            int gl = i * 4 + lq;                          // group index inside the WM columns
+            uint32_t nib = (mw[i >> 1] >> (4 * (gl & 7))) & 0xFu;
+            uint32_t a = nib & 3u, c = nib >> 2;
+            f32x4 v = acc[i][j];
+            float v0 = a == 0 ? v[0] : (a == 1 ? v[1] : v[2]);
+            float v1 = c == 1 ? v[1] : (c == 2 ? v[2] : v[3]);
+            union { __bf16 h[2]; uint32_t u; } pr;
+            pr.h[0] = (__bf16)v0;
+            pr.h[1] = (__bf16)v1;
+            *(uint32_t*)(out + (size_t)o * gpitch + (col >> 1)) = pr.u;
+        }
+    }
+}
+
 // D[i, j] = sum_k At[i, k] * Bt[j, k];  At: [m][kp], Bt: [n][kp], kp % 64 == 0.
 //   EPI_MASKED_PACKED: out = packed gradient [n][m/2] selected by meta (u8[n][m/8])
 //   EPI_PLAIN        : out = bf16 [n][m]  (row j, four consecutive i per lane)
@@ -180,34 +216,148 @@ __global__ void __launch_bounds__(TN_THREADS) dense_tn_kernel(const bf16_t* __re
         }
         return;
     }
-    // masked, packed epilogue: a lane's four accumulators are one group of four along d_in of row o
-    const size_t mpitch = (size_t)m / 8, gpitch = (size_t)m / 2;
+    store_masked_packed<MF, NF>(acc, m, n, m0 + wm * WM, n0 + wn * NF * 16, l16, lq, meta, out);
+}
+
+// The 256 x 256 tile of the weight gradient with split rings.  A plain two-stage ring (all that
+// fits beside such a tile) makes every k-step a burst: nothing may be queued for a stage before
+// both groups have read it, and everything queued must have landed one k-step later, so the load
+// path runs dry at every step.  Here the two groups take the two column halves of the tile, which
+// makes each half of the B panel private to one group, free again as soon as that group has read
+// it, while the A panel, read by both, gets a ring of three:
+//     A ring  3 x 32 KiB | B half of group 0  2 x 16 KiB | B half of group 1  2 x 16 KiB  = 160 KiB
+// Every phase (half a k-step) each wavefront queues four 1 KiB loads
+//     even phase 2k  :  B1(k+1), lower half of A(k+2)        odd phase 2k+1 :  upper half of A(k+2), B0(k+2)
+// and at the end of every phase waits only for what it queued two or more phases ago (at most
+// eight loads stay in flight), which is what the next phase reads.  A stage is always rewritten in
+// the first phase after its last reader's barrier.
+struct SplitSmem {
+    static constexpr int BM = 256, BN = 256;
+    static constexpr int A_STAGE = BM * 128, B_HALF = BN / 2 * 128;
+    static constexpr int B_OFF = 3 * A_STAGE;                 // then [group][stage] halves of B
+    static constexpr int TOTAL = 3 * A_STAGE + 4 * B_HALF;
+};
+
+__global__ void __launch_bounds__(TN_THREADS) dense_tn_split_kernel(const bf16_t* __restrict__ At, int m,
+                                                                    const bf16_t* __restrict__ Bt, int n, int kp,
+                                                                    const uint8_t* __restrict__ meta,
+                                                                    bf16_t* __restrict__ out, int tiles_m,
+                                                                    int tiles_n) {
+    using S = SplitSmem;
+    constexpr int MF = 8, NF = 4, WM = 128;                  // wavefront tile 128 x 64, 2 x 4 wavefronts
+    extern __shared__ __align__(16) uint8_t smem[];
+
+    int tm, tn;
+    if (!tile_of_block(tiles_m, tiles_n, tm, tn)) return;
+    const int m0 = tm * S::BM, n0 = tn * S::BN;
+    const int t = threadIdx.x, lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int group = wave >> 2;                             // = column half of the tile
+    const int wm = wave & 1, wn = wave >> 1;
+    const int l16 = lane & 15, lq = lane >> 4;
+
+    // loader lanes: 8 lanes per row, chunk rotated by (row / 2) % 8 (rows clamped, never stored).
+    // Each load set (half of A, half of B) is 16 loads of 8 rows: two per wavefront.
+    const uint8_t* a_src[4];                                 // [half * 2 + i]
+    const uint8_t* b_src[4];                                 // [group * 2 + i]
 #pragma unroll
-    for (int j = 0; j < NF; ++j) {
-        int o = n0 + (wn * NF + j) * 16 + l16;
-        if (o >= n) continue;
-        // metadata of the wavefront's WM d_in columns of row o: WM / 4 groups = WM / 8 bytes
-        int c0 = m0 + wm * WM;
-        uint32_t mw[WM / 32];
+    for (int q = 0; q < 4; ++q) {
+        int rl = ((q >> 1) * 16 + wave * 2 + (q & 1)) * 8 + (lane >> 3);     // row inside the tile
+        int sw16 = ((lane & 7) ^ ((rl >> 1) & 7)) * 16;
+        int ra = m0 + rl < m ? m0 + rl : m - 1;
+        int rb = n0 + rl < n ? n0 + rl : n - 1;
+        a_src[q] = (const uint8_t*)At + (size_t)ra * kp * 2 + sw16;
+        b_src[q] = (const uint8_t*)Bt + (size_t)rb * kp * 2 + sw16;
+    }
+    const int ksteps = kp / 64;
+    auto issue_a = [&](int half, int ks) {                   // rows 128 half .. +127 of A(ks), ks clamped
+        int kc = ks < ksteps ? ks : ksteps - 1;
+        uint8_t* st = smem + (ks % 3) * S::A_STAGE + (half * 16 + wave * 2) * 1024;
+        dma16(a_src[half * 2] + (size_t)kc * 128, st);
+        dma16(a_src[half * 2 + 1] + (size_t)kc * 128, st + 1024);
+    };
+    auto issue_b = [&](int g, int ks) {                      // B half of group g, step ks (clamped)
+        int kc = ks < ksteps ? ks : ksteps - 1;
+        uint8_t* st = smem + S::B_OFF + (g * 2 + (ks & 1)) * S::B_HALF + (wave * 2) * 1024;
+        dma16(b_src[g * 2] + (size_t)kc * 128, st);
+        dma16(b_src[g * 2 + 1] + (size_t)kc * 128, st + 1024);
+    };
+
+    // reader lanes: fragment f = rows 16f .. 16f+15 = 2 KiB; lane (l16, lq) wants chunk 4h + lq
+    const int sw = (l16 >> 1) & 7;
+    const int rd0 = l16 * 128 + ((lq ^ sw) * 16);
+    const int rd1 = l16 * 128 + (((4 + lq) ^ sw) * 16);
+    const int a_rd = (wm * MF) * 2048;
+    const int b_rd = S::B_OFF + group * 2 * S::B_HALF + ((wn & 1) * NF) * 2048;
+
+    f32x4 acc[MF][NF];
 #pragma unroll
-        for (int q = 0; q < WM / 32; ++q)
-            mw[q] = c0 + 32 * q < m ? *(const uint32_t*)(meta + (size_t)o * mpitch + c0 / 8 + 4 * q) : 0u;
+    for (int i = 0; i < MF; ++i)
 #pragma unroll
-        for (int i = 0; i < MF; ++i) {
-            int col = c0 + i * 16 + lq * 4;               // first d_in index of the group
-            if (col >= m) continue;
-            int gl = i * 4 + lq;                          // group index inside the WM columns
-            uint32_t nib = (mw[i >> 1] >> (4 * (gl & 7))) & 0xFu;
-            uint32_t a = nib & 3u, c = nib >> 2;
-            f32x4 v = acc[i][j];
-            float v0 = a == 0 ? v[0] : (a == 1 ? v[1] : v[2]);
-            float v1 = c == 1 ? v[1] : (c == 2 ? v[2] : v[3]);
-            union { __bf16 h[2]; uint32_t u; } pr;
-            pr.h[0] = (__bf16)v0;
-            pr.h[1] = (__bf16)v1;
-            *(uint32_t*)(out + (size_t)o * gpitch + (col >> 1)) = pr.u;
+        for (int j = 0; j < NF; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    constexpr int KEEP = 8;                                  // loads of the last two phases
+#define SPLIT_READ(ks)                                                                                 \
+        const uint8_t* sa = smem + ((ks) % 3) * S::A_STAGE + a_rd;                                     \
+        const uint8_t* sb = smem + b_rd + ((ks) & 1) * S::B_HALF;                                      \
+        BFrag af[MF], bf[NF];                                                                          \
+        _Pragma("unroll") for (int i = 0; i < MF; ++i) {                                               \
+            af[i].u[0] = *(const u32x4*)(sa + i * 2048 + rd0);                                         \
+            af[i].u[1] = *(const u32x4*)(sa + i * 2048 + rd1);                                         \
+        }                                                                                              \
+        _Pragma("unroll") for (int j = 0; j < NF; ++j) {                                               \
+            bf[j].u[0] = *(const u32x4*)(sb + j * 2048 + rd0);                                         \
+            bf[j].u[1] = *(const u32x4*)(sb + j * 2048 + rd1);                                         \
+        }
+#define SPLIT_MFMA                                                                                     \
+        _Pragma("unroll") for (int h = 0; h < 2; ++h)                                                  \
+        _Pragma("unroll") for (int i = 0; i < MF; ++i) _Pragma("unroll") for (int j = 0; j < NF; ++j) { \
+            AFrag a, b;                                                                                \
+            a.u = af[i].u[h]; b.u = bf[j].u[h];                                                        \
+            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, acc[i][j], 0, 0, 0);         \
+        }
+#define EVEN_LOADS(k) { issue_b(1, (k) + 1); issue_a(0, (k) + 2); }
+#define ODD_LOADS(k)  { issue_a(1, (k) + 2); issue_b(0, (k) + 2); }
+
+    // steps 0 and 1 as far as the schedule would have queued them before phase 0
+    issue_a(0, 0); issue_a(1, 0); issue_b(0, 0);
+    issue_b(1, 0); issue_a(0, 1);
+    issue_a(1, 1); issue_b(0, 1);
+    WAIT_HERE(waitcnt_imm(KEEP, 15));                         // A(0) and B0(0) have landed
+    wg_barrier();
+    if (group == 0) {
+        for (int ks = 0; ks < ksteps; ++ks) {
+            SPLIT_READ(ks)                                    // phase 2 ks
+            EVEN_LOADS(ks)
+            WAIT_HERE(waitcnt_imm(KEEP, 0));
+            wg_barrier();
+            ODD_LOADS(ks)                                     // phase 2 ks + 1
+            SPLIT_MFMA
+            WAIT_HERE(waitcnt_imm(KEEP, 15));
+            wg_barrier();
+        }
+        wg_barrier();                                         // group 1's last compute phase
+    } else {
+        EVEN_LOADS(0)                                         // phase 0: nothing to compute yet
+        WAIT_HERE(waitcnt_imm(KEEP, 15));
+        wg_barrier();
+        for (int ks = 0; ks < ksteps; ++ks) {
+            SPLIT_READ(ks)                                    // phase 2 ks + 1
+            ODD_LOADS(ks)
+            WAIT_HERE(waitcnt_imm(KEEP, 0));
+            wg_barrier();
+            EVEN_LOADS(ks + 1)                                // phase 2 ks + 2
+            SPLIT_MFMA
+            WAIT_HERE(waitcnt_imm(KEEP, 15));
+            wg_barrier();
         }
     }
+#undef SPLIT_READ
+#undef SPLIT_MFMA
+#undef EVEN_LOADS
+#undef ODD_LOADS
+    WAIT_HERE(waitcnt_imm(0, 15));                            // drain the clamped look-ahead loads
+    store_masked_packed<MF, NF>(acc, m, n, m0 + wm * WM, n0 + wn * NF * 16, l16, lq, meta, out);
 }
 
 template <int BM, int BN, int EPI, int NS>
@@ -220,6 +370,19 @@ hipError_t launch_dense_tn(const bf16_t* At, int64_t m, const bf16_t* Bt, int64_
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, S::TOTAL);
     if (e != hipSuccess) return e;
     kern<<<dim3((unsigned)super_grid(tiles_m, tiles_n)), dim3(TN_THREADS), S::TOTAL, s>>>(
+        At, (int)m, Bt, (int)n, (int)kp, meta, out, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
+hipError_t launch_dense_tn_split(const bf16_t* At, int64_t m, const bf16_t* Bt, int64_t n, int64_t kp,
+                                 const uint8_t* meta, bf16_t* out, hipStream_t s) {
+    using S = SplitSmem;
+    static_assert(S::TOTAL <= 160 * 1024, "LDS budget");
+    int tiles_m = (int)((m + S::BM - 1) / S::BM), tiles_n = (int)((n + S::BN - 1) / S::BN);
+    hipError_t e = hipFuncSetAttribute((const void*)dense_tn_split_kernel,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, S::TOTAL);
+    if (e != hipSuccess) return e;
+    dense_tn_split_kernel<<<dim3((unsigned)super_grid(tiles_m, tiles_n)), dim3(TN_THREADS), S::TOTAL, s>>>(
         At, (int)m, Bt, (int)n, (int)kp, meta, out, tiles_m, tiles_n);
     return hipGetLastError();
 }
@@ -240,7 +403,11 @@ hipError_t launch_wgrad_masked_ws(const bf16_t* dY, const bf16_t* X, int64_t b, 
     transpose_pad_kernel<<<dim3((unsigned)(bp / 64), (unsigned)(d_out / 64)), dim3(256), 0, s>>>(dY, (int)b, (int)d_out, bp, dYt);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+#ifdef SLOPE_WGRAD_PLAIN_RING
     return launch_dense_tn<256, 256, EPI_MASKED_PACKED, 2>(Xt, d_in, dYt, d_out, bp, meta, gvals, s);
+#else
+    return launch_dense_tn_split(Xt, d_in, dYt, d_out, bp, meta, gvals, s);
+#endif
 }
 
 // C[n, m] = B[n, K] * A[m, K]^T, all bf16 row-major, K % 64 == 0 (the skinny product T = X L of the
