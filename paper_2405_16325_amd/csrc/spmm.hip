@@ -36,6 +36,55 @@
 
 namespace {
 
+// Tail shared by the tile kernels, for one wavefront whose acc[i][j] is the 16 x 16 fragment at
+// features f0 + 16 i, tokens t0 + 16 j.
+//  - dense K-extension: C += B2 * A2^T with v_mfma_f32_16x16x32_bf16, operands straight from
+//    global memory (lane l: row l%16, k = 8*(l/16) .. +7, for A and B alike);
+//  - epilogue: four consecutive features of one token per lane, one 8-byte store.
+template <int MF, int NF>
+__device__ __forceinline__ void extend_and_store(f32x4 (&acc)[MF][NF], int f0, int t0, int m, int n, int l16, int lq,
+                                                 const bf16_t* __restrict__ B2, const bf16_t* __restrict__ A2,
+                                                 int K2, bf16_t* __restrict__ C) {
+    for (int k0 = 0; k0 < K2; k0 += 32) {
+        bf16x8 a2[MF], b2[NF];
+#pragma unroll
+        for (int i = 0; i < MF; ++i) {
+            int row = f0 + i * 16 + l16;
+            row = row < m ? row : m - 1;
+            AFrag x;
+            x.u = *(const u32x4*)(A2 + (size_t)row * K2 + k0 + lq * 8);
+            a2[i] = x.v;
+        }
+#pragma unroll
+        for (int j = 0; j < NF; ++j) {
+            int row = t0 + j * 16 + l16;
+            row = row < n ? row : n - 1;
+            AFrag x;
+            x.u = *(const u32x4*)(B2 + (size_t)row * K2 + k0 + lq * 8);
+            b2[j] = x.v;
+        }
+#pragma unroll
+        for (int i = 0; i < MF; ++i)
+#pragma unroll
+            for (int j = 0; j < NF; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2[i], b2[j], acc[i][j], 0, 0, 0);
+    }
+#pragma unroll
+    for (int j = 0; j < NF; ++j) {
+        int row = t0 + j * 16 + l16;                      // token
+        if (row >= n) continue;
+#pragma unroll
+        for (int i = 0; i < MF; ++i) {
+            int col = f0 + i * 16 + lq * 4;               // feature
+            if (col >= m) continue;
+            f32x4 v = acc[i][j];
+            union { __bf16 h[4]; u32x2 u; } o;
+            o.h[0] = (__bf16)v[0]; o.h[1] = (__bf16)v[1]; o.h[2] = (__bf16)v[2]; o.h[3] = (__bf16)v[3];
+            *(u32x2*)(C + (size_t)row * m + col) = o.u;
+        }
+    }
+}
+
 template <int BM, int BN>
 struct SpmmSmem {
     static constexpr int A_PAIR = BM * 128;     // packed values of BM rows x 2 k-steps
@@ -182,48 +231,186 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_kernel(const bf16_t* __rest
 #undef SPMM_STEP
     WAIT_HERE(waitcnt_imm(0, 15));           // drain the clamped look-ahead loads
 
-    // ---- dense K-extension: C += B2 * A2^T with v_mfma_f32_16x16x32_bf16, operands straight
-    //      from global memory (lane l: row l%16, k = 8*(l/16) .. +7, for A and B alike)
-    for (int k0 = 0; k0 < K2; k0 += 32) {
-        bf16x8 a2[MF], b2[NF];
+    extend_and_store<MF, NF>(acc, m0 + wm * MF * 16, n0 + wn * NF * 16, m, n, l16, lq, B2, A2, K2, C);
+}
+
+// ------------------------------------------------------------------------------------------
+// spmm_split_kernel: the 256 x 256 tile.  A fifth fewer operand bytes per flop than the
+// 192 x 256 tile, but a ring of three B stages no longer fits beside it.  The two wavefront groups
+// own the two token halves of the tile, so each half of a B stage is private to one group and free
+// again as soon as that group has read it; two stages per half then give every load the same two
+// to three phases (half k-steps) of flight that the shared ring of three gave:
+//     A pair buffers 2 x 32 KiB | B half of group 0  2 x 16 KiB | of group 1  2 x 16 KiB | metadata 2 x 8 KiB
+// Queued by every wavefront, k = k-step, phases 2k (group 0 reads step k) and 2k + 1 (group 1 does):
+//     phase 2k     : B1(k+1);  lower half of A pair k/2 + 1 if k is even;  metadata quad (k+3)/4 if k % 4 == 1
+//     phase 2k + 1 : B0(k+2);  upper half of A pair k/2 + 1 if k is even
+// and at the end of each phase a wavefront waits for everything it queued two or more phases ago,
+// which covers all that the next phase reads.  Every buffer is rewritten in the first phase after
+// the barrier that ends its last reader's phase.
+struct SplitSmem {
+    static constexpr int BM = 256, BN = 256;
+    static constexpr int A_PAIR = BM * 128, B_HALF = BN / 2 * 128, M_QUAD = BM * 32;
+    static constexpr int B_OFF = 2 * A_PAIR;                  // then [group][stage] halves of B
+    static constexpr int M_OFF = B_OFF + 4 * B_HALF;
+    static constexpr int TOTAL = M_OFF + 2 * M_QUAD;
+};
+
+// loads one wavefront queues in the even / odd phase of k-step k (k taken mod 4)
+constexpr int split_even(int k) { return 2 + ((k & 1) == 0 ? 2 : 0) + ((k & 3) == 1 ? 1 : 0); }
+constexpr int split_odd(int k) { return 2 + ((k & 1) == 0 ? 2 : 0); }
+
+__global__ void __launch_bounds__(SPMM_THREADS) spmm_split_kernel(const bf16_t* __restrict__ B, int n,
+                                                                  const bf16_t* __restrict__ Av,
+                                                                  const uint8_t* __restrict__ Am, int m, int K,
+                                                                  const bf16_t* __restrict__ B2,
+                                                                  const bf16_t* __restrict__ A2, int K2,
+                                                                  bf16_t* __restrict__ C, int tiles_m, int tiles_n) {
+    using S = SplitSmem;
+    constexpr int MF = 8, NF = 4;                            // wavefront tile 128 features x 64 tokens
+    extern __shared__ __align__(16) uint8_t smem[];
+
+    int tm, tn;
+    if (!tile_of_block(tiles_m, tiles_n, tm, tn)) return;
+    const int m0 = tm * S::BM, n0 = tn * S::BN;
+    const int t = threadIdx.x, lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int group = wave >> 2;                             // = token half of the tile
+    const int wm = wave & 1, wn = wave >> 1;
+    const int l16 = lane & 15, lq = lane >> 4;
+
+    // ---- loader lanes: 8 lanes per row, chunk rotated by (row / 2) % 8.  A half of A and a half of
+    //      B are 16 loads of 8 rows each: two per wavefront.
+    const uint8_t* a_src[4];                                 // [half * 2 + i]
+    const uint8_t* b_src[4];                                 // [group * 2 + i]
 #pragma unroll
-        for (int i = 0; i < MF; ++i) {
-            int row = m0 + (wm * MF + i) * 16 + l16;
-            row = row < m ? row : m - 1;
-            AFrag x;
-            x.u = *(const u32x4*)(A2 + (size_t)row * K2 + k0 + lq * 8);
-            a2[i] = x.v;
-        }
-#pragma unroll
-        for (int j = 0; j < NF; ++j) {
-            int row = n0 + (wn * NF + j) * 16 + l16;
-            row = row < n ? row : n - 1;
-            AFrag x;
-            x.u = *(const u32x4*)(B2 + (size_t)row * K2 + k0 + lq * 8);
-            b2[j] = x.v;
-        }
-#pragma unroll
-        for (int i = 0; i < MF; ++i)
-#pragma unroll
-            for (int j = 0; j < NF; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2[i], b2[j], acc[i][j], 0, 0, 0);
+    for (int q = 0; q < 4; ++q) {
+        int rl = ((q >> 1) * 16 + wave * 2 + (q & 1)) * 8 + (lane >> 3);     // row inside the tile
+        int sw16 = ((lane & 7) ^ ((rl >> 1) & 7)) * 16;
+        int ra = m0 + rl < m ? m0 + rl : m - 1;
+        int rb = n0 + rl < n ? n0 + rl : n - 1;
+        a_src[q] = (const uint8_t*)Av + (size_t)ra * K + sw16;
+        b_src[q] = (const uint8_t*)B + (size_t)rb * K * 2 + sw16;
+    }
+    const uint8_t* m_src;                                    // 32 rows per wavefront, two lanes per row
+    {
+        int rl = wave * 32 + (lane >> 1);
+        int row = m0 + rl < m ? m0 + rl : m - 1;
+        m_src = Am + (size_t)row * (K / 8) + (lane & 1) * 16;
     }
 
-    // ---- epilogue: four consecutive features of one token per lane
+    // ---- reader lanes: fragment f = rows 16f .. 16f+15 = 2 KiB; lane (l16, lq) wants chunk 4h + lq
+    const int sw = (l16 >> 1) & 7;
+    const int rd0 = l16 * 128 + ((lq ^ sw) * 16);             // h = 0
+    const int rd1 = l16 * 128 + (((4 + lq) ^ sw) * 16);       // h = 1
+    const int a_rd = (wm * MF) * 2048;
+    const int b_rd = S::B_OFF + group * 2 * S::B_HALF + ((wn & 1) * NF) * 2048;
+    const int m_rd = S::M_OFF + (wm * MF * 16 + l16) * 32 + lq * 2;
+
+    const int ksteps = K / 64;                                // a multiple of 4
+    auto issue_b = [&](int g, int ks) {                       // token half g of k-step ks (clamped)
+        int kc = ks < ksteps ? ks : ksteps - 1;
+        uint8_t* st = smem + S::B_OFF + (g * 2 + (ks & 1)) * S::B_HALF + (wave * 2) * 1024;
+        dma16(b_src[g * 2] + (size_t)kc * 128, st);
+        dma16(b_src[g * 2 + 1] + (size_t)kc * 128, st + 1024);
+    };
+    auto issue_a = [&](int half, int pair) {                  // weight rows 128 half .. +127, k-steps 2 pair, 2 pair + 1
+        int pc = 2 * pair < ksteps ? pair : ksteps / 2 - 1;
+        uint8_t* st = smem + (pair & 1) * S::A_PAIR + (half * 16 + wave * 2) * 1024;
+        dma16(a_src[half * 2] + (size_t)pc * 128, st);
+        dma16(a_src[half * 2 + 1] + (size_t)pc * 128, st + 1024);
+    };
+    auto issue_m = [&](int quad) {                            // metadata of k-steps 4 quad .. 4 quad + 3
+        int qc = 4 * quad < ksteps ? quad : ksteps / 4 - 1;
+        dma16(m_src + (size_t)qc * 32, smem + S::M_OFF + (quad & 1) * S::M_QUAD + wave * 1024);
+    };
+
+    f32x4 acc[MF][NF];
 #pragma unroll
-    for (int j = 0; j < NF; ++j) {
-        int row = n0 + (wn * NF + j) * 16 + l16;          // token
-        if (row >= n) continue;
+    for (int i = 0; i < MF; ++i)
 #pragma unroll
-        for (int i = 0; i < MF; ++i) {
-            int col = m0 + (wm * MF + i) * 16 + lq * 4;   // feature
-            if (col >= m) continue;
-            f32x4 v = acc[i][j];
-            union { __bf16 h[4]; u32x2 u; } o;
-            o.h[0] = (__bf16)v[0]; o.h[1] = (__bf16)v[1]; o.h[2] = (__bf16)v[2]; o.h[3] = (__bf16)v[3];
-            *(u32x2*)(C + (size_t)row * m + col) = o.u;
-        }
+        for (int j = 0; j < NF; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    // S4 = k % 4 is a literal, so the number of loads a wait may leave in flight is a constant.
+#define EVEN_LOADS(k, S4)                                                                              \
+    {                                                                                                  \
+        issue_b(1, (k) + 1);                                                                           \
+        if (((S4) & 1) == 0) issue_a(0, ((k) >> 1) + 1);                                               \
+        if (((S4) & 3) == 1) issue_m(((k) + 3) >> 2);                                                  \
     }
+#define ODD_LOADS(k, S4)                                                                               \
+    {                                                                                                  \
+        issue_b(0, (k) + 2);                                                                           \
+        if (((S4) & 1) == 0) issue_a(1, ((k) >> 1) + 1);                                               \
+    }
+#define SPLIT_READ(S4)                                                                                 \
+        const uint8_t* pa = smem + (((S4) >> 1) & 1) * S::A_PAIR + a_rd + (((S4) & 1) ? rd1 : rd0);    \
+        const uint8_t* pb = smem + b_rd + ((S4) & 1) * S::B_HALF;                                      \
+        const uint8_t* pm = smem + m_rd + ((ks0 >> 2) & 1) * S::M_QUAD + (S4) * 8;                     \
+        BFrag bf[NF];                                                                                  \
+        AFrag af[MF];                                                                                  \
+        int ai[MF];                                                                                    \
+        _Pragma("unroll") for (int j = 0; j < NF; ++j) {                                               \
+            bf[j].u[0] = *(const u32x4*)(pb + j * 2048 + rd0);                                         \
+            bf[j].u[1] = *(const u32x4*)(pb + j * 2048 + rd1);                                         \
+        }                                                                                              \
+        _Pragma("unroll") for (int i = 0; i < MF; ++i) {                                               \
+            af[i].u = *(const u32x4*)(pa + i * 2048);                                                  \
+            ai[i] = *(const uint16_t*)(pm + i * 512);                                                  \
+        }
+#define SPLIT_MFMA                                                                                     \
+        _Pragma("unroll") for (int i = 0; i < MF; ++i) _Pragma("unroll") for (int j = 0; j < NF; ++j)  \
+            acc[i][j] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(af[i].v, bf[j].v, acc[i][j], ai[i], 0, 0);
+    // group 0: phase 2k reads step k, phase 2k + 1 multiplies it
+#define SPLIT_STEP0(S4)                                                                                \
+    {                                                                                                  \
+        const int ks = ks0 + (S4);                                                                     \
+        SPLIT_READ(S4)                                                                                 \
+        EVEN_LOADS(ks, S4)                                                                             \
+        WAIT_HERE(waitcnt_imm(split_even(S4) + split_odd((S4) + 3), 0));                               \
+        wg_barrier();                                                                                  \
+        ODD_LOADS(ks, S4)                                                                              \
+        SPLIT_MFMA                                                                                     \
+        WAIT_HERE(waitcnt_imm(split_odd(S4) + split_even(S4), 15));                                    \
+        wg_barrier();                                                                                  \
+    }
+    // group 1: phase 2k + 1 reads step k, phase 2k + 2 multiplies it
+#define SPLIT_STEP1(S4)                                                                                \
+    {                                                                                                  \
+        const int ks = ks0 + (S4);                                                                     \
+        SPLIT_READ(S4)                                                                                 \
+        ODD_LOADS(ks, S4)                                                                              \
+        WAIT_HERE(waitcnt_imm(split_odd(S4) + split_even(S4), 0));                                     \
+        wg_barrier();                                                                                  \
+        EVEN_LOADS(ks + 1, (S4) + 1)                                                                   \
+        SPLIT_MFMA                                                                                     \
+        WAIT_HERE(waitcnt_imm(split_even((S4) + 1) + split_odd(S4), 15));                              \
+        wg_barrier();                                                                                  \
+    }
+
+    // ---- prologue: what the schedule would have queued in the phases before phase 0
+    issue_m(0);
+    issue_a(0, 0); issue_a(1, 0); issue_b(0, 0);
+    issue_b(1, 0);
+    issue_b(0, 1);                                            // = the odd phase of step -1
+    WAIT_HERE(waitcnt_imm(4, 15));                            // metadata, A pair 0 and B0(0) have landed
+    wg_barrier();
+    if (group == 0) {
+        for (int ks0 = 0; ks0 < ksteps; ks0 += 4) { SPLIT_STEP0(0) SPLIT_STEP0(1) SPLIT_STEP0(2) SPLIT_STEP0(3) }
+        wg_barrier();                                         // group 1's last compute phase
+    } else {
+        EVEN_LOADS(0, 0)                                      // phase 0: nothing to multiply yet
+        WAIT_HERE(waitcnt_imm(split_even(0) + split_odd(3), 15));
+        wg_barrier();
+        for (int ks0 = 0; ks0 < ksteps; ks0 += 4) { SPLIT_STEP1(0) SPLIT_STEP1(1) SPLIT_STEP1(2) SPLIT_STEP1(3) }
+    }
+#undef EVEN_LOADS
+#undef ODD_LOADS
+#undef SPLIT_READ
+#undef SPLIT_MFMA
+#undef SPLIT_STEP0
+#undef SPLIT_STEP1
+    WAIT_HERE(waitcnt_imm(0, 15));                            // drain the clamped look-ahead loads
+    extend_and_store<MF, NF>(acc, m0 + wm * MF * 16, n0 + wn * NF * 16, m, n, l16, lq, B2, A2, K2, C);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -323,44 +510,7 @@ __global__ void __launch_bounds__(256) spmm_generic_kernel(const bf16_t* __restr
     }
 #undef GEN_LOAD
 #undef GEN_STORE
-    for (int k0 = 0; k0 < K2; k0 += 32) {
-        bf16x8 a2[MF], b2[NF];
-#pragma unroll
-        for (int i = 0; i < MF; ++i) {
-            int row = m0 + (wm * MF + i) * 16 + l16;
-            row = row < m ? row : m - 1;
-            AFrag x;
-            x.u = *(const u32x4*)(A2 + (size_t)row * K2 + k0 + lq * 8);
-            a2[i] = x.v;
-        }
-#pragma unroll
-        for (int j = 0; j < NF; ++j) {
-            int row = n0 + (wn * NF + j) * 16 + l16;
-            row = row < n ? row : n - 1;
-            AFrag x;
-            x.u = *(const u32x4*)(B2 + (size_t)row * K2 + k0 + lq * 8);
-            b2[j] = x.v;
-        }
-#pragma unroll
-        for (int i = 0; i < MF; ++i)
-#pragma unroll
-            for (int j = 0; j < NF; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2[i], b2[j], acc[i][j], 0, 0, 0);
-    }
-#pragma unroll
-    for (int j = 0; j < NF; ++j) {
-        int row = n0 + (wn * NF + j) * 16 + l16;
-        if (row >= n) continue;
-#pragma unroll
-        for (int i = 0; i < MF; ++i) {
-            int col = m0 + (wm * MF + i) * 16 + lq * 4;
-            if (col >= m) continue;
-            f32x4 v = acc[i][j];
-            union { __bf16 h[4]; u32x2 u; } o;
-            o.h[0] = (__bf16)v[0]; o.h[1] = (__bf16)v[1]; o.h[2] = (__bf16)v[2]; o.h[3] = (__bf16)v[3];
-            *(u32x2*)(C + (size_t)row * m + col) = o.u;
-        }
-    }
+    extend_and_store<MF, NF>(acc, m0 + wm * MF * 16, n0 + wn * NF * 16, m, n, l16, lq, B2, A2, K2, C);
 }
 
 template <int BM, int BN>
@@ -373,6 +523,19 @@ hipError_t launch_tile(const bf16_t* B, int64_t n, const bf16_t* Av, const uint8
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, S::TOTAL);
     if (e != hipSuccess) return e;
     kern<<<dim3((unsigned)super_grid(tiles_m, tiles_n)), dim3(SPMM_THREADS), S::TOTAL, s>>>(
+        B, (int)n, Av, Am, (int)m, (int)K, B2, A2, (int)K2, C, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
+hipError_t launch_split(const bf16_t* B, int64_t n, const bf16_t* Av, const uint8_t* Am, int64_t m, int64_t K,
+                        const bf16_t* B2, const bf16_t* A2, int64_t K2, bf16_t* C, hipStream_t s) {
+    using S = SplitSmem;
+    static_assert(S::TOTAL <= 160 * 1024, "LDS budget");
+    int tiles_m = (int)((m + S::BM - 1) / S::BM), tiles_n = (int)((n + S::BN - 1) / S::BN);
+    hipError_t e = hipFuncSetAttribute((const void*)spmm_split_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       S::TOTAL);
+    if (e != hipSuccess) return e;
+    spmm_split_kernel<<<dim3((unsigned)super_grid(tiles_m, tiles_n)), dim3(SPMM_THREADS), S::TOTAL, s>>>(
         B, (int)n, Av, Am, (int)m, (int)K, B2, A2, (int)K2, C, tiles_m, tiles_n);
     return hipGetLastError();
 }
@@ -399,6 +562,9 @@ hipError_t launch_spmm(const bf16_t* B, int64_t n, const bf16_t* A_vals, const u
     }
     // big tiles once they fill the 256 compute units, small tiles otherwise
     int64_t big = ((m + 191) / 192) * ((n + 255) / 256);
+#ifndef SLOPE_SPMM_NO_SPLIT
+    if (((m + 255) / 256) * ((n + 255) / 256) >= 256) return launch_split(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s);
+#endif
     if (big >= 192) return launch_tile<192, 256>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s);
     return launch_tile<128, 128>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s);
 }

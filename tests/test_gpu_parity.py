@@ -110,6 +110,7 @@ def layer_on_device(b, d_out, d_in, rank, seed):
 PRODUCT_SHAPES = [
     (2048, 3072, 768), (300, 448, 320), (1, 64, 64), (17, 192, 64),
     (4100, 4160, 256), (4096, 4096, 128), (1000, 1024, 1280), (4100, 4224, 512), (777, 256, 256),
+    (4100, 768, 4160),
 ]
 
 
