@@ -164,15 +164,15 @@ def main():
     }
     for k in kernels.values():
         k["frac"] = k["achieved"] / k["peak"]
-    # Dominant kernel = spmm_kernel (forward and input-gradient products; the largest share of GPU
+    # Dominant kernel = spmm_split_kernel (forward and input-gradient products; the largest share of GPU
     # time in the rocprofv3 trace).  A slope_spmm_bwd_x call is exactly one launch of it, so the
     # events around those calls time the kernel itself: achieved = credited (dense-equivalent) flops
     # per launch / average launch duration, against the structured-sparse bf16 peak.
     n_launch = len(layers)
-    roofline = {"kernel": "spmm_kernel", "timed_on": "slope_spmm_bwd_x launches", "bound": "mfma",
+    roofline = {"kernel": "spmm_split_kernel", "timed_on": "slope_spmm_bwd_x launches", "bound": "mfma",
                 "achieved": kernels["spmm_bwd_x"]["achieved"], "peak": PEAK_SPARSE_BF16, "unit": "TFLOP/s",
                 "frac": kernels["spmm_bwd_x"]["frac"], "avg_launch_ms": per_call["spmm_bwd_x"] / n_launch,
-                "flops_per_launch": sum_f / n_launch, "traffic": read_traffic("spmm_kernel")}
+                "flops_per_launch": sum_f / n_launch, "traffic": read_traffic("spmm_split_kernel")}
 
     # dense bf16 GEMM at the same shapes (the library GEMM torch.matmul dispatches to): Y = X W^T,
     # dX = dY W, dW = dY^T X
@@ -225,7 +225,7 @@ def main():
 def read_traffic(kernel):
     """HBM-side bytes per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE,
     calibrated against a plain copy), or None if the summary is absent."""
-    path = os.path.join(ROOT, "profiles", "spmm_kernel_opt66b_pmc.txt")
+    path = os.path.join(ROOT, "profiles", "spmm_split_kernel_opt66b_pmc.txt")
     try:
         for line in open(path):
             t = line.split()
