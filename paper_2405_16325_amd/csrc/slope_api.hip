@@ -132,10 +132,10 @@ slope_status slope_wgrad_masked(const void* dY, const void* X, int64_t b, const 
     if (misaligned(dY, 16) || misaligned(X, 16) || misaligned(Wr_meta, 16) || misaligned(dW_vals, 16) ||
         misaligned(workspace_or_null, 256))
         return SLOPE_ERR_ALIGN;
-    // The token-contiguous path pays off once its 256 x 256 tiles fill the chip; small layers and
-    // callers without scratch memory take the in-place kernel.
-    const int64_t tiles = ((d_in + 255) / 256) * ((d_out + 255) / 256);
-    if (workspace_or_null && tiles >= 128)
+    // The token-contiguous path pays off once its tiles (128 x 128 at the least) give most compute
+    // units one; tiny layers and callers without scratch memory take the in-place kernel.
+    const int64_t tiles = ((d_in + 127) / 128) * ((d_out + 127) / 128);
+    if (workspace_or_null && tiles >= 96)
         return finish(launch_wgrad_masked_ws((const bf16_t*)dY, (const bf16_t*)X, b, (const uint8_t*)Wr_meta, d_out,
                                              d_in, (bf16_t*)dW_vals, workspace_or_null, (hipStream_t)stream));
     return finish(launch_wgrad_masked((const bf16_t*)dY, (const bf16_t*)X, b, (const uint8_t*)Wr_meta, d_out, d_in,

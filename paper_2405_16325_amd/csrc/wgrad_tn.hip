@@ -403,11 +403,19 @@ hipError_t launch_wgrad_masked_ws(const bf16_t* dY, const bf16_t* X, int64_t b, 
     transpose_pad_kernel<<<dim3((unsigned)(bp / 64), (unsigned)(d_out / 64)), dim3(256), 0, s>>>(dY, (int)b, (int)d_out, bp, dYt);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-#ifdef SLOPE_WGRAD_PLAIN_RING
-    return launch_dense_tn<256, 256, EPI_MASKED_PACKED, 2>(Xt, d_in, dYt, d_out, bp, meta, gvals, s);
-#else
-    return launch_dense_tn_split(Xt, d_in, dYt, d_out, bp, meta, gvals, s);
-#endif
+    // The kernel runs at the rate its compute units pull operands from L2: a launch costs about
+    // (rounds of 256 resident tiles) x (rows per tile).  Take the cheapest shape, the larger on ties.
+    const int bms[3] = {256, 256, 128}, bns[3] = {256, 128, 128};
+    int best = 0;
+    int64_t best_cost = INT64_MAX;
+    for (int c = 0; c < 3; ++c) {
+        int64_t tiles = ((d_in + bms[c] - 1) / bms[c]) * ((d_out + bns[c] - 1) / bns[c]);
+        int64_t cost = ((tiles + RESIDENT - 1) / RESIDENT) * (bms[c] + bns[c]);
+        if (cost < best_cost) { best_cost = cost; best = c; }
+    }
+    if (best == 0) return launch_dense_tn_split(Xt, d_in, dYt, d_out, bp, meta, gvals, s);
+    if (best == 1) return launch_dense_tn<256, 128, EPI_MASKED_PACKED, 3>(Xt, d_in, dYt, d_out, bp, meta, gvals, s);
+    return launch_dense_tn<128, 128, EPI_MASKED_PACKED, 4>(Xt, d_in, dYt, d_out, bp, meta, gvals, s);
 }
 
 // C[n, m] = B[n, K] * A[m, K]^T, all bf16 row-major, K % 64 == 0 (the skinny product T = X L of the

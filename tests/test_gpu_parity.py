@@ -110,7 +110,7 @@ def layer_on_device(b, d_out, d_in, rank, seed):
 PRODUCT_SHAPES = [
     (2048, 3072, 768), (300, 448, 320), (1, 64, 64), (17, 192, 64),
     (4100, 4160, 256), (4096, 4096, 128), (1000, 1024, 1280), (4100, 4224, 512), (777, 256, 256),
-    (4100, 768, 4160),
+    (4100, 768, 4160), (4000, 4032, 512), (4000, 512, 4032),   # the last two: 256 x 256 tiles, ragged both ways
 ]
 
 
@@ -160,7 +160,7 @@ def test_wgrad_masked(b, d_out, d_in, ws):
     assert err <= TOL
 
 
-@pytest.mark.parametrize("b,d_out,d_in,r", [(2048, 3072, 768, 64), (300, 448, 320, 32), (4100, 4160, 256, 128),
+@pytest.mark.parametrize("b,d_out,d_in,r", [(2048, 3072, 768, 64), (300, 448, 320, 32), (4100, 4160, 256, 128), (4000, 4032, 256, 128),
                                             (50, 128, 192, 160)])
 def test_spmm_fwd_with_adapter(b, d_out, d_in, r):
     say(f"spmm_fwd adapter b={b} d_out={d_out} d_in={d_in} r={r}")
