@@ -184,6 +184,36 @@ def wgrad_masked(dy_bits, x_bits, wr_meta) -> np.ndarray:
     return np.take_along_axis(g.reshape(d_out, d_in // 4, 4), idx, axis=-1).reshape(d_out, d_in // 2)
 
 
+# ----------------------------------------------------------------------------- optimizer side
+def sparse_add(a_vals: np.ndarray, b_vals: np.ndarray, beta: float, gamma: float) -> np.ndarray:
+    """beta A + gamma B on the packed values of two matrices that share one sparsity pattern
+    (App. K "sparse matrix addition"; Alg. 1 line 15 is the case A = masked gradient,
+    beta = 1 / gradient scale, B = W^R, gamma = weight decay).  The two scalars cross the C ABI
+    as fp32, so they are rounded to fp32 first; the sum itself is fp64.  fp64, shape of a_vals."""
+    be = float(np.float32(beta))
+    ga = float(np.float32(gamma))
+    return be * bf16_to_f64(a_vals) + ga * bf16_to_f64(b_vals)
+
+
+def update_sparse(wnew_vals: np.ndarray, wr_meta: np.ndarray, wrct_meta: np.ndarray):
+    """The two sparse copies after the optimizer produced new values for W^R's kept positions
+    (Alg. 1 lines 17-18, App. K "update sparse matrix").  Masks are static (Sec. 2.1), so both
+    metadata arrays stay as they are: W^R's packed values become wnew_vals, and every slot of
+    packed (W^{R,C})^T takes the new value of the position it names.  A slot that names a
+    position outside the row-prune mask is padding and stays +0.0.  wr_meta must name exactly
+    W^R's kept positions (what the row prune emits).  Returns (wr_vals, wrct_vals) as bf16 bits."""
+    w_new = unpack_2to4(wnew_vals, wr_meta)                     # dense bits [d_out, d_in], zero off the mask
+    mask_r = meta_to_mask(wr_meta)
+    dense_t = np.ascontiguousarray(np.where(mask_r, w_new, np.uint16(0)).T)   # [d_in, d_out]
+    d_in, gb = wrct_meta.shape
+    nib = np.empty((d_in, gb * 2), dtype=np.uint8)
+    nib[:, 0::2] = wrct_meta & 0xF
+    nib[:, 1::2] = wrct_meta >> 4
+    idx = np.stack([nib & 3, (nib >> 2) & 3], axis=-1).astype(np.int64)
+    vals_t = np.take_along_axis(dense_t.reshape(d_in, gb * 2, 4), idx, axis=-1).reshape(d_in, gb * 4)
+    return np.array(wnew_vals, dtype=np.uint16, copy=True), vals_t.astype(np.uint16)
+
+
 # ----------------------------------------------------------------------------- comparison helper
 def rel_fro(got: np.ndarray, want: np.ndarray) -> float:
     """||got - want||_F / ||want||_F in fp64."""

@@ -564,10 +564,10 @@ hipError_t launch_spmm(const bf16_t* B, int64_t n, const bf16_t* A_vals, const u
     // about (rounds of 256 resident tiles) x (operand bytes per tile and k-step: 72 per weight row,
     // 128 per token row).  Take the tile shape for which that is least; ties go to the larger tile.
     struct Cand { int bm, bn; };
-    const Cand cands[4] = {{256, 256}, {192, 256}, {256, 128}, {128, 128}};
+    const Cand cands[6] = {{256, 256}, {192, 256}, {256, 128}, {128, 128}, {128, 64}, {64, 128}};
     int best = 0;
     int64_t best_cost = INT64_MAX;
-    for (int c = 0; c < 4; ++c) {
+    for (int c = 0; c < 6; ++c) {
         int64_t tiles = ((m + cands[c].bm - 1) / cands[c].bm) * ((n + cands[c].bn - 1) / cands[c].bn);
         int64_t cost = ((tiles + RESIDENT - 1) / RESIDENT) * (72 * cands[c].bm + 128 * cands[c].bn);
         if (cost < best_cost) { best_cost = cost; best = c; }
@@ -576,6 +576,8 @@ hipError_t launch_spmm(const bf16_t* B, int64_t n, const bf16_t* A_vals, const u
         case 0: return launch_split(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s);
         case 1: return launch_tile<192, 256>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s);
         case 2: return launch_tile<256, 128>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s);
-        default: return launch_tile<128, 128>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s);
+        case 3: return launch_tile<128, 128>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s);
+        case 4: return launch_tile<128, 64>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s);
+        default: return launch_tile<64, 128>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s);
     }
 }
