@@ -136,6 +136,36 @@ slope_status slope_wgrad_masked(const void* dY, const void* X, int64_t b, const 
                                 int64_t d_out, int64_t d_in, void* dW_vals, void* workspace_or_null,
                                 void* stream);
 
+/*
+ * slope_sparse_add - out = beta * A + gamma * B on the packed values of two matrices that share
+ * one sparsity pattern (App. K, sparse matrix addition).  Algorithm 1 line 15 is the case
+ * A = packed masked gradient, beta = 1 / gradient scale, B = packed W^R, gamma = weight decay.
+ *   A_vals, B_vals  in   bf16[rows, cols/2]   packed values of two [rows, cols] matrices
+ *   rows, cols           logical extents; cols % 16 == 0
+ *   out_vals        out  bf16[rows, cols/2]   may be A_vals or B_vals (in place)
+ * Each element is fma(beta, a, gamma * b) in fp32, rounded to bf16 (nearest even).  The metadata
+ * is not touched: the result has the operands' pattern.
+ */
+slope_status slope_sparse_add(const void* A_vals, const void* B_vals, int64_t rows, int64_t cols, float beta,
+                              float gamma, void* out_vals, void* stream);
+
+/*
+ * slope_update_sparse - both sparse copies take the values the optimizer produced for W^R's kept
+ * positions (Algorithm 1 lines 17-18; App. K, update sparse matrix).  The masks are static
+ * (Sec. 2.1), so no metadata changes: W^R's packed values become Wnew_vals, and every slot of
+ * packed (W^{R,C})^T takes the new value of the position it names; slots that name a position
+ * outside W^R's mask (padding of groups with fewer than two survivors) stay +0.0.
+ * To re-select W^{R,C} by magnitude from the new values instead, call slope_double_prune.
+ *   Wnew_vals  in   bf16[d_out, d_in/2]   new packed values, in W^R's pattern
+ *   Wr_meta    in   u8[d_out, d_in/8]     metadata of W^R as written by slope_prune_rows
+ *   Wr_vals    out  bf16[d_out, d_in/2]   receives a copy of Wnew_vals (no copy if it is Wnew_vals)
+ *   WrcT_meta  in   u8[d_in, d_out/8]     metadata of (W^{R,C})^T as written by slope_double_prune
+ *   WrcT_vals  out  bf16[d_in, d_out/2]   rewritten completely
+ * d_in % 64 == 0 and d_out % 64 == 0.
+ */
+slope_status slope_update_sparse(const void* Wnew_vals, const void* Wr_meta, int64_t d_out, int64_t d_in,
+                                 void* Wr_vals, const void* WrcT_meta, void* WrcT_vals, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

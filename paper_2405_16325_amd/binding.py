@@ -38,6 +38,8 @@ SIGNATURES = {
     "slope_spmm_bwd_x": (_INT, [_P, _I64, _P, _P, _I64, _I64, _P, _P]),
     "slope_wgrad_workspace_bytes": (_SZ, [_I64, _I64, _I64]),
     "slope_wgrad_masked": (_INT, [_P, _P, _I64, _P, _I64, _I64, _P, _P, _P]),
+    "slope_sparse_add": (_INT, [_P, _P, _I64, _I64, ctypes.c_float, ctypes.c_float, _P, _P]),
+    "slope_update_sparse": (_INT, [_P, _P, _I64, _I64, _P, _P, _P, _P]),
 }
 
 _lib = None
@@ -163,6 +165,26 @@ def slope_wgrad_masked(dY: torch.Tensor, X: torch.Tensor, meta: torch.Tensor, ou
     _check("slope_wgrad_masked", lib().slope_wgrad_masked(_ptr(dY), _ptr(X), b, _ptr(meta), d_out, d_in, _ptr(G),
                                                           _ptr(workspace), _stream()))
     return G
+
+
+def slope_sparse_add(A_vals: torch.Tensor, B_vals: torch.Tensor, beta: float, gamma: float, out=None):
+    """beta * A + gamma * B on packed values bf16[rows, cols/2] of two matrices with one pattern."""
+    _dev(A_vals, B_vals)
+    rows, half = A_vals.shape
+    G = out if out is not None else torch.empty_like(A_vals)
+    _check("slope_sparse_add", lib().slope_sparse_add(_ptr(A_vals), _ptr(B_vals), rows, 2 * half, beta, gamma,
+                                                      _ptr(G), _stream()))
+    return G
+
+
+def slope_update_sparse(Wnew_vals: torch.Tensor, meta: torch.Tensor, vals: torch.Tensor, meta_t: torch.Tensor,
+                        vals_t: torch.Tensor):
+    """New packed values into W^R (vals) and into packed (W^{R,C})^T (vals_t); metadata unchanged."""
+    _dev(Wnew_vals, meta, vals, meta_t, vals_t)
+    d_out, d_in = Wnew_vals.shape[0], 2 * Wnew_vals.shape[1]
+    _check("slope_update_sparse", lib().slope_update_sparse(_ptr(Wnew_vals), _ptr(meta), d_out, d_in, _ptr(vals),
+                                                            _ptr(meta_t), _ptr(vals_t), _stream()))
+    return vals, vals_t
 
 
 # ---------------------------------------------------------------- host <-> device helpers (plumbing)

@@ -18,6 +18,10 @@ hipError_t launch_prune_rows(const bf16_t* W, int64_t d_out, int64_t d_in, bf16_
                              uint8_t* mask, hipStream_t s);
 hipError_t launch_double_prune(const bf16_t* vals, const uint8_t* meta, int64_t d_out, int64_t d_in,
                                bf16_t* valsT, uint8_t* metaT, uint8_t* maskrc, hipStream_t s);
+hipError_t launch_update_transposed(const bf16_t* vals, const uint8_t* meta, int64_t d_out, int64_t d_in,
+                                    const uint8_t* metaT, bf16_t* valsT, hipStream_t s);
+hipError_t launch_sparse_add(const bf16_t* a, const bf16_t* b, size_t count, float beta, float gamma, bf16_t* out,
+                             hipStream_t s);
 // C[n, m] = B[n, K] * Asparse[m, K]^T  (+ B2[n, K2] * A2[m, K2]^T dense when K2 > 0)
 hipError_t launch_spmm(const bf16_t* B, int64_t n, const bf16_t* A_vals, const uint8_t* A_meta, int64_t m,
                        int64_t K, const bf16_t* B2, const bf16_t* A2, int64_t K2, bf16_t* C, hipStream_t s);

@@ -94,10 +94,18 @@ constexpr int DP_PITCH = 272;       // bytes per decompressed row in LDS (128 * 
 constexpr int DP_OPITCH = 33;       // dwords per output row [i][og] (32 + 1: conflict-free columns)
 constexpr int DP_NPITCH = 36;       // bytes per nibble row [i][og]
 
+// GIVEN = false: slope_double_prune, the pairs are chosen here by magnitude among the survivors
+//                 and their metadata is written.
+// GIVEN = true : slope_update_sparse, the pairs are the ones metaT_in already names (static
+//                 masks, Alg. 1 line 18); only the values of the transposed copy are rewritten.
+//                 A slot that names a position outside W^R's mask reads the zero that the
+//                 decompression left there, so padding stays +0.0.
+template <bool GIVEN>
 __global__ void __launch_bounds__(256) double_prune_kernel(const bf16_t* __restrict__ vals,
                                                            const uint8_t* __restrict__ meta, int d_out, int d_in,
                                                            bf16_t* __restrict__ valsT, uint8_t* __restrict__ metaT,
-                                                           uint8_t* __restrict__ maskrc) {
+                                                           uint8_t* __restrict__ maskrc,
+                                                           const uint8_t* __restrict__ metaT_in) {
     __shared__ __align__(16) uint8_t sD[DP_TILE * DP_PITCH];   // decompressed W^R tile [o][i]
     __shared__ __align__(4) uint8_t sC[DP_TILE * 16];          // candidate bits [o][i/8]
     __shared__ uint32_t sO[DP_TILE * DP_OPITCH];               // kept value pairs [i][og]
@@ -136,6 +144,18 @@ __global__ void __launch_bounds__(256) double_prune_kernel(const bf16_t* __restr
         dst[1] = make_uint4(dense[4], dense[5], dense[6], dense[7]);
         *(uint16_t*)(sC + row * 16 + 2 * c) = (uint16_t)cand;
     }
+    if (GIVEN) {   // the tile of the given metadata, one nibble per byte: 128 rows (d_in) x 32 groups along d_out
+        int row = t >> 1, half = t & 1;
+        int i = i0 + row, o = o0 + 64 * half;
+        uint2 x = make_uint2(0, 0);
+        if (i < d_in && o < d_out) x = *(const uint2*)(metaT_in + (size_t)i * ((size_t)d_out / 8) + o / 8);
+        uint8_t* dst = sN + row * DP_NPITCH + 16 * half;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            dst[q] = (uint8_t)((x.x >> (4 * q)) & 0xFu);
+            dst[8 + q] = (uint8_t)((x.y >> (4 * q)) & 0xFu);
+        }
+    }
     __syncthreads();
 
     // phase 2: one lane ranks 8 columns x 4 rows (one group of four along d_out per column)
@@ -158,18 +178,23 @@ __global__ void __launch_bounds__(256) double_prune_kernel(const bf16_t* __restr
                 cd[k] = (cb[k] >> j) & 1u;
                 key[k] = cd[k] ? (e[k] & 0x7FFFu) + 1u : 0u;   // survivors outrank every pruned slot
             }
-            uint32_t set = top2_of_4(key[0], key[1], key[2], key[3]);
-            uint32_t nib = nibble_of_pair(set);
+            const int col = 8 * i8 + j;
+            uint32_t set = 0, nib;
+            if (GIVEN) {
+                nib = sN[col * DP_NPITCH + og];
+            } else {
+                set = top2_of_4(key[0], key[1], key[2], key[3]);
+                nib = nibble_of_pair(set);
+            }
             uint64_t q = (uint64_t)(e[0] | (e[1] << 16)) | ((uint64_t)(e[2] | (e[3] << 16)) << 32);
             uint32_t v0 = (uint32_t)(q >> (16u * (nib & 3u))) & 0xFFFFu;
             uint32_t v1 = (uint32_t)(q >> (16u * (nib >> 2))) & 0xFFFFu;
-            int col = 8 * i8 + j;
             sO[col * DP_OPITCH + og] = v0 | (v1 << 16);
-            sN[col * DP_NPITCH + og] = (uint8_t)nib;
+            if (!GIVEN) sN[col * DP_NPITCH + og] = (uint8_t)nib;
 #pragma unroll
             for (int k = 0; k < 4; ++k) keep[k] |= (((set >> k) & 1u) & cd[k]) << j;
         }
-        if (maskrc) {
+        if (!GIVEN && maskrc) {
             int i = i0 + 8 * i8;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
@@ -191,6 +216,7 @@ __global__ void __launch_bounds__(256) double_prune_kernel(const bf16_t* __restr
             *(uint4*)(valsT + (size_t)i * vtp + o / 2) = make_uint4(src[0], src[1], src[2], src[3]);
         }
     }
+    if (GIVEN) return;
 #pragma unroll
     for (int n = 0; n < 2; ++n) {
         int idx = t + 256 * n, row = idx >> 2, c = idx & 3;
@@ -208,6 +234,66 @@ __global__ void __launch_bounds__(256) double_prune_kernel(const bf16_t* __restr
 hipError_t launch_double_prune(const bf16_t* vals, const uint8_t* meta, int64_t d_out, int64_t d_in, bf16_t* valsT,
                                uint8_t* metaT, uint8_t* maskrc, hipStream_t s) {
     dim3 grid((unsigned)((d_in + DP_TILE - 1) / DP_TILE), (unsigned)((d_out + DP_TILE - 1) / DP_TILE));
-    double_prune_kernel<<<grid, dim3(256), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT, metaT, maskrc);
+    double_prune_kernel<false><<<grid, dim3(256), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT, metaT, maskrc,
+                                                          nullptr);
+    return hipGetLastError();
+}
+
+// Values of packed (W^{R,C})^T from new packed values of W^R, metadata of both unchanged.
+hipError_t launch_update_transposed(const bf16_t* vals, const uint8_t* meta, int64_t d_out, int64_t d_in,
+                                    const uint8_t* metaT, bf16_t* valsT, hipStream_t s) {
+    dim3 grid((unsigned)((d_in + DP_TILE - 1) / DP_TILE), (unsigned)((d_out + DP_TILE - 1) / DP_TILE));
+    double_prune_kernel<true><<<grid, dim3(256), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT, nullptr, nullptr,
+                                                         metaT);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// out = beta * a + gamma * b on packed values (App. K, sparse matrix addition): one fp32 fused
+// multiply-add per element on top of the fp32 product gamma * b, rounded to bf16 (nearest even).
+// A plain stream: 16 bytes of each operand per lane, 6 bytes of traffic per element.
+constexpr int SA_UNROLL = 4;
+
+__global__ void __launch_bounds__(256) sparse_add_kernel(const u32x4* __restrict__ a, const u32x4* __restrict__ b,
+                                                         size_t nvec, float beta, float gamma,
+                                                         u32x4* __restrict__ out) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (size_t base = (size_t)blockIdx.x * 256 + threadIdx.x; base < nvec; base += stride * SA_UNROLL) {
+        u32x4 va[SA_UNROLL], vb[SA_UNROLL];
+#pragma unroll
+        for (int u = 0; u < SA_UNROLL; ++u) {
+            size_t i = base + u * stride;
+            if (i < nvec) {
+                va[u] = __builtin_nontemporal_load(a + i);
+                vb[u] = __builtin_nontemporal_load(b + i);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < SA_UNROLL; ++u) {
+            size_t i = base + u * stride;
+            if (i >= nvec) continue;
+            u32x4 r;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                float a0 = __uint_as_float(va[u][w] << 16), a1 = __uint_as_float(va[u][w] & 0xFFFF0000u);
+                float b0 = __uint_as_float(vb[u][w] << 16), b1 = __uint_as_float(vb[u][w] & 0xFFFF0000u);
+                union { __bf16 h[2]; uint32_t x; } o;
+                o.h[0] = (__bf16)__builtin_fmaf(beta, a0, gamma * b0);
+                o.h[1] = (__bf16)__builtin_fmaf(beta, a1, gamma * b1);
+                r[w] = o.x;
+            }
+            __builtin_nontemporal_store(r, out + i);
+        }
+    }
+}
+
+hipError_t launch_sparse_add(const bf16_t* a, const bf16_t* b, size_t count, float beta, float gamma, bf16_t* out,
+                             hipStream_t s) {
+    size_t nvec = count / 8;                                  // count is a multiple of 8
+    size_t blocks = (nvec + 256 * SA_UNROLL - 1) / (256 * SA_UNROLL);
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    if (blocks == 0) blocks = 1;
+    sparse_add_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>((const u32x4*)a, (const u32x4*)b, nvec, beta, gamma,
+                                                                   (u32x4*)out);
     return hipGetLastError();
 }

@@ -142,4 +142,30 @@ slope_status slope_wgrad_masked(const void* dY, const void* X, int64_t b, const 
                                       (bf16_t*)dW_vals, (hipStream_t)stream));
 }
 
+slope_status slope_sparse_add(const void* A_vals, const void* B_vals, int64_t rows, int64_t cols, float beta,
+                              float gamma, void* out_vals, void* stream) {
+    if (!A_vals || !B_vals || !out_vals) return SLOPE_ERR_NULL;
+    if (bad_extent(rows, 1) || bad_extent(cols, 16)) return SLOPE_ERR_SHAPE;
+    if (misaligned(A_vals, 16) || misaligned(B_vals, 16) || misaligned(out_vals, 16)) return SLOPE_ERR_ALIGN;
+    return finish(launch_sparse_add((const bf16_t*)A_vals, (const bf16_t*)B_vals, (size_t)rows * (size_t)(cols / 2),
+                                    beta, gamma, (bf16_t*)out_vals, (hipStream_t)stream));
+}
+
+slope_status slope_update_sparse(const void* Wnew_vals, const void* Wr_meta, int64_t d_out, int64_t d_in,
+                                 void* Wr_vals, const void* WrcT_meta, void* WrcT_vals, void* stream) {
+    if (!Wnew_vals || !Wr_meta || !Wr_vals || !WrcT_meta || !WrcT_vals) return SLOPE_ERR_NULL;
+    if (bad_extent(d_out, 64) || bad_extent(d_in, 64)) return SLOPE_ERR_SHAPE;
+    if (misaligned(Wnew_vals, 16) || misaligned(Wr_meta, 16) || misaligned(Wr_vals, 16) ||
+        misaligned(WrcT_meta, 16) || misaligned(WrcT_vals, 16))
+        return SLOPE_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)stream;
+    if (Wr_vals != Wnew_vals) {
+        hipError_t e = hipMemcpyAsync(Wr_vals, Wnew_vals, (size_t)d_out * (size_t)(d_in / 2) * 2,
+                                      hipMemcpyDeviceToDevice, s);
+        if (e != hipSuccess) return finish(e);
+    }
+    return finish(launch_update_transposed((const bf16_t*)Wnew_vals, (const uint8_t*)Wr_meta, d_out, d_in,
+                                           (const uint8_t*)WrcT_meta, (bf16_t*)WrcT_vals, s));
+}
+
 }  // extern "C"

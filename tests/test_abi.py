@@ -60,6 +60,12 @@ def test_argument_errors_are_reported_before_launch():
     assert lib.slope_wgrad_masked(p, p, 8, None, 64, 64, p, None, None) == binding.SLOPE_ERR_NULL
     assert lib.slope_wgrad_masked(p, p, -1, p, 64, 64, p, None, None) == binding.SLOPE_ERR_SHAPE
     assert lib.slope_wgrad_masked(p, p, 8, p, 64, 64, p, odd, None) == binding.SLOPE_ERR_ALIGN
+    assert lib.slope_sparse_add(p, None, 4, 64, 1.0, 1.0, p, None) == binding.SLOPE_ERR_NULL
+    assert lib.slope_sparse_add(p, p, 4, 24, 1.0, 1.0, p, None) == binding.SLOPE_ERR_SHAPE
+    assert lib.slope_sparse_add(p, p, 4, 64, 1.0, 1.0, odd, None) == binding.SLOPE_ERR_ALIGN
+    assert lib.slope_update_sparse(p, p, 64, 64, p, None, p, None) == binding.SLOPE_ERR_NULL
+    assert lib.slope_update_sparse(p, p, 64, 96, p, p, p, None) == binding.SLOPE_ERR_SHAPE
+    assert lib.slope_update_sparse(p, p, 64, 64, p, p, odd, None) == binding.SLOPE_ERR_ALIGN
     assert lib.slope_wgrad_workspace_bytes(100, 64, 128) >= (64 + 128) * 128 * 2
     assert b"NULL" in lib.slope_status_string(binding.SLOPE_ERR_NULL)
 

@@ -1,0 +1,93 @@
+"""Optimizer-side packed operations (Alg. 1 lines 15-18): HIP path vs CPU oracle through the C ABI.
+
+slope_update_sparse moves bit patterns only: bit-exact.  slope_sparse_add computes
+fma(beta, a, gamma * b) in fp32 and rounds to bf16: against the fp64 oracle that is half a bf16
+ulp of the result (2^-9 relative) plus the fp32 rounding of the two terms.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import slope_oracle as so
+from paper_2405_16325_amd import binding as sl
+from paper_2405_16325_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def packed(d_out, d_in, seed, coarse=False):
+    w = inputs.coarse_weights(d_out, d_in, seed) if coarse else inputs.gaussian_bf16((d_out, d_in), 0.02, seed, 0)
+    vals, meta, _ = so.prune_rows_packed(w)
+    vt, mt, _ = so.double_prune_packed(vals, meta)
+    return w, vals, meta, vt, mt
+
+
+ADD_CASES = [(64, 64, 1.0 / 1024, 0.01), (3072, 768, 1.0 / 65536, 0.1), (101, 80, -0.5, 2.0), (1, 16, 1.0, 0.0),
+             (1000, 4160, 0.0, 1.0), (257, 4112, 3.0, -3.0)]
+
+
+@pytest.mark.parametrize("rows,cols,beta,gamma", ADD_CASES)
+def test_sparse_add(rows, cols, beta, gamma):
+    say(f"sparse_add rows={rows} cols={cols} beta={beta} gamma={gamma}")
+    a = inputs.gaussian_bf16((rows, cols // 2), 1e-3, rows, 1)
+    b = inputs.gaussian_bf16((rows, cols // 2), 0.02, rows, 2)
+    got = so.bf16_to_f64(sl.bf16_to_host(sl.slope_sparse_add(sl.bf16_to_device(a), sl.bf16_to_device(b), beta, gamma)))
+    torch.cuda.synchronize()
+    want = so.sparse_add(a, b, beta, gamma)
+    be, ga = float(np.float32(beta)), float(np.float32(gamma))
+    terms = np.abs(be * so.bf16_to_f64(a)) + np.abs(ga * so.bf16_to_f64(b))
+    bound = 2.0 ** -8 * np.abs(want) + 2.0 ** -22 * terms + 1e-45
+    assert (np.abs(got - want) <= bound).all()
+    if gamma == 0.0 and beta == 1.0:
+        assert (sl.bf16_to_host(sl.slope_sparse_add(sl.bf16_to_device(a), sl.bf16_to_device(b), 1.0, 0.0)) == a).all()
+
+
+def test_sparse_add_in_place_and_same_operand():
+    a = inputs.gaussian_bf16((128, 256), 1e-3, 3, 1)
+    b = inputs.gaussian_bf16((128, 256), 0.02, 3, 2)
+    da, db = sl.bf16_to_device(a), sl.bf16_to_device(b)
+    ref = sl.bf16_to_host(sl.slope_sparse_add(da, db, 0.25, 0.5))
+    sl.slope_sparse_add(da, db, 0.25, 0.5, out=da)
+    torch.cuda.synchronize()
+    assert (sl.bf16_to_host(da) == ref).all()
+    # a + (-1) a == 0 exactly, whatever the values
+    z = sl.bf16_to_host(sl.slope_sparse_add(db, db, 2.0, -2.0))
+    assert (so.bf16_to_f64(z) == 0.0).all()
+
+
+UPDATE_CASES = [(64, 64, False), (3072, 768, False), (448, 320, False), (320, 192, True), (4160, 256, False),
+                (192, 4160, False), (1024, 1280, False)]
+
+
+@pytest.mark.parametrize("d_out,d_in,coarse", UPDATE_CASES)
+def test_update_sparse_bit_exact(d_out, d_in, coarse):
+    say(f"update_sparse d_out={d_out} d_in={d_in} coarse={coarse}")
+    w, vals, meta, vt, mt = packed(d_out, d_in, seed=d_out + d_in, coarse=coarse)
+    mask_r = so.meta_to_mask(meta)
+    fresh = inputs.gaussian_bf16((d_out, d_in), 0.02, d_out + d_in + 1, 3)
+    fresh = np.where(fresh == 0, np.uint16(0x3F80), fresh)          # no zeros: a wrongly filled padding slot shows
+    wnew, _ = so.pack_2to4(fresh, mask_r)
+    want_vals, want_vt = so.update_sparse(wnew, meta, mt)
+    d_vals = sl.bf16_to_device(vals)
+    d_vt = sl.bf16_to_device(np.full_like(vt, 0x7FC0))              # NaN fill: every slot must be rewritten
+    sl.slope_update_sparse(sl.bf16_to_device(wnew), torch.from_numpy(meta).cuda(), d_vals,
+                           torch.from_numpy(mt).cuda(), d_vt)
+    torch.cuda.synchronize()
+    assert (sl.bf16_to_host(d_vals) == want_vals).all()
+    got_vt = sl.bf16_to_host(d_vt)
+    assert (got_vt == want_vt).all()
+
+
+def test_update_with_current_values_matches_double_prune_on_gpu():
+    """The GPU's own slope_double_prune output is reproduced when nothing changed (both from the oracle's view)."""
+    w, vals, meta, vt, mt = packed(512, 384, seed=77)
+    d_vals = sl.bf16_to_device(vals)
+    d_vt = sl.bf16_to_device(np.zeros_like(vt))
+    sl.slope_update_sparse(d_vals, torch.from_numpy(meta).cuda(), d_vals, torch.from_numpy(mt).cuda(), d_vt)
+    torch.cuda.synchronize()
+    assert (sl.bf16_to_host(d_vt) == vt).all()
+    assert (sl.bf16_to_host(d_vals) == vals).all()
