@@ -25,7 +25,8 @@ Readings taken where the paper is silent (all listed in the design notes):
     fewer than two kept positions is padded with its lowest free positions, which
     carry +0.0;
   * the weight gradient is restricted to the row-prune (forward) mask;
-  * adapter shapes follow Eq. 11: L is d_in x r, R is r x d_out.
+  * adapter shapes follow Eq. 11: L is d_in x r, R is r x d_out; its backward pass is
+    the chain rule of Eq. 11 (the sparse term still uses W^{R,C}, Eq. 6).
 Parity pins: every function here is pinned by tests/test_oracle_*.py.
 """
 from __future__ import annotations
@@ -166,9 +167,24 @@ def spmm_fwd(x_bits, w_bits, mask_r, l_bits=None, r_bits=None) -> np.ndarray:
     return y
 
 
-def spmm_bwd_x(dy_bits, w_bits, mask_rc) -> np.ndarray:
-    """dX = dY W^{R,C}   (Eq. 6).  fp64[b, d_in]."""
-    return bf16_to_f64(dy_bits) @ masked_weight(w_bits, mask_rc)
+def spmm_bwd_x(dy_bits, w_bits, mask_rc, l_bits=None, r_bits=None) -> np.ndarray:
+    """dX = dY W^{R,C}   (Eq. 6)  [+ (dY R^T) L^T with adapters: the derivative of the low-rank
+    term of Eq. 11 with respect to X, which the paper leaves to autograd].  fp64[b, d_in]."""
+    dy = bf16_to_f64(dy_bits)
+    dx = dy @ masked_weight(w_bits, mask_rc)
+    if l_bits is not None and r_bits is not None and l_bits.shape[1] > 0:
+        dx = dx + (dy @ bf16_to_f64(r_bits).T) @ bf16_to_f64(l_bits).T
+    return dx
+
+
+def adapter_grads(dy_bits, x_bits, l_bits, r_bits):
+    """Gradients of the low-rank term Y2 = (X L) R of Eq. 11 (Sec. 2.2), by the chain rule:
+    dL = X^T (dY R^T)  fp64[d_in, r],   dR = (X L)^T dY  fp64[r, d_out]."""
+    x = bf16_to_f64(x_bits)
+    dy = bf16_to_f64(dy_bits)
+    dl = x.T @ (dy @ bf16_to_f64(r_bits).T)
+    dr = (x @ bf16_to_f64(l_bits)).T @ dy
+    return dl, dr
 
 
 def wgrad_masked(dy_bits, x_bits, wr_meta) -> np.ndarray:

@@ -126,3 +126,61 @@ def test_rel_fro():
     a = np.array([[3.0, 4.0]])
     assert so.rel_fro(a, a) == 0.0
     assert so.rel_fro(a * 1.01, a) == pytest.approx(0.01)
+
+
+# ---------------------------------------------------------------- adapter backward (chain rule of Eq. 11)
+def test_adapter_backward_against_scalar_loops():
+    t, mr, mrc = layer(b=4, d_out=8, d_in=12, rank=3)
+    x = so.bf16_to_f64(t["X"]).tolist()
+    dy = so.bf16_to_f64(t["dY"]).tolist()
+    lo = so.bf16_to_f64(t["L"]).tolist()
+    ro = so.bf16_to_f64(t["R"]).tolist()
+    b, d_out, d_in, r = 4, 8, 12, 3
+    dl, dr = so.adapter_grads(t["dY"], t["X"], t["L"], t["R"])
+    dx = so.spmm_bwd_x(t["dY"], t["W"], mrc, t["L"], t["R"]) - so.spmm_bwd_x(t["dY"], t["W"], mrc)
+    for i in range(d_in):
+        for k in range(r):
+            acc = sum(x[tt][i] * sum(dy[tt][o] * ro[k][o] for o in range(d_out)) for tt in range(b))
+            assert dl[i, k] == pytest.approx(acc, rel=1e-12, abs=1e-18)
+    for k in range(r):
+        for o in range(d_out):
+            acc = sum(sum(x[tt][i] * lo[i][k] for i in range(d_in)) * dy[tt][o] for tt in range(b))
+            assert dr[k, o] == pytest.approx(acc, rel=1e-12, abs=1e-18)
+    for tt in range(b):
+        for i in range(d_in):
+            acc = sum(sum(dy[tt][o] * ro[k][o] for o in range(d_out)) * lo[i][k] for k in range(r))
+            assert dx[tt, i] == pytest.approx(acc, rel=1e-12, abs=1e-18)
+
+
+def test_adapter_gradients_are_the_derivatives_of_the_forward():
+    """f(X, L, R) = <(X L) R, dY> is linear in each argument, so each gradient satisfies
+    <grad, delta> = f(with that argument replaced by delta), exactly (up to fp64 rounding)."""
+    t, mr, mrc = layer(b=10, d_out=16, d_in=24, rank=5, seed=44)
+    dyf = so.bf16_to_f64(t["dY"])
+    zero_w = np.zeros_like(t["W"])
+
+    def f(x_bits, l_bits, r_bits):
+        return float((so.spmm_fwd(x_bits, zero_w, mr, l_bits, r_bits) * dyf).sum())
+
+    dl, dr = so.adapter_grads(t["dY"], t["X"], t["L"], t["R"])
+    dx_low = so.spmm_bwd_x(t["dY"], zero_w, mrc, t["L"], t["R"])
+    d_l = inputs.gaussian_bf16(t["L"].shape, 1.0, 45, 1)
+    d_r = inputs.gaussian_bf16(t["R"].shape, 1.0, 45, 2)
+    d_x = inputs.gaussian_bf16(t["X"].shape, 1.0, 45, 3)
+    assert (dl * so.bf16_to_f64(d_l)).sum() == pytest.approx(f(t["X"], d_l, t["R"]), rel=1e-11)
+    assert (dr * so.bf16_to_f64(d_r)).sum() == pytest.approx(f(t["X"], t["L"], d_r), rel=1e-11)
+    assert (dx_low * so.bf16_to_f64(d_x)).sum() == pytest.approx(f(d_x, t["L"], t["R"]), rel=1e-11)
+
+
+def test_adapter_backward_degenerate_cases():
+    t, mr, mrc = layer(b=6, d_out=8, d_in=16, rank=4, seed=46)
+    plain = so.spmm_bwd_x(t["dY"], t["W"], mrc)
+    assert (so.spmm_bwd_x(t["dY"], t["W"], mrc, None, None) == plain).all()
+    assert (so.spmm_bwd_x(t["dY"], t["W"], mrc, np.zeros_like(t["L"]), t["R"]) == plain).all()
+    assert (so.spmm_bwd_x(t["dY"], t["W"], mrc, t["L"], np.zeros_like(t["R"])) == plain).all()
+    dl, dr = so.adapter_grads(t["dY"], t["X"], np.zeros_like(t["L"]), t["R"])
+    assert (dr == 0).all() and np.abs(dl).max() > 0          # dR needs L, dL does not
+    dl, dr = so.adapter_grads(t["dY"], t["X"], t["L"], np.zeros_like(t["R"]))
+    assert (dl == 0).all() and np.abs(dr).max() > 0
+    dl, dr = so.adapter_grads(np.zeros_like(t["dY"]), t["X"], t["L"], t["R"])
+    assert (dl == 0).all() and (dr == 0).all()
