@@ -220,6 +220,32 @@ def main():
     optimizer = {"ms_per_step": opt_ms, "achieved": 7.25 * elems / (opt_ms * 1e-3) / 1e9, "unit": "GB/s",
                  "peak": PEAK_HBM, "calls": "slope_sparse_add + slope_update_sparse per layer"}
 
+    # Backward pass with adapters (chain rule of Eq. 11), timed apart from the step: the same step with
+    # slope_spmm_bwd_x_adapter and slope_wgrad_adapter in place of the plain backward calls.
+    adapter_bwd = None
+    if rank > 0:
+        big_ws = torch.empty(max(sl.slope_wgrad_adapter_workspace_bytes(b, l["d_in"], l["d_out"], rank)
+                                 for l in layers), dtype=torch.uint8, device=dev)
+        for lay in layers:
+            lay["dL"] = torch.empty((lay["d_in"], rank), dtype=torch.bfloat16, device=dev)
+            lay["dR"] = torch.empty((rank, lay["d_out"]), dtype=torch.bfloat16, device=dev)
+
+        def adapter_step():
+            for lay in layers:
+                sl.slope_spmm_bwd_x_adapter(lay["dY"], lay["vals_t"], lay["meta_t"], lay["L"], lay["R"],
+                                            out=lay["dX"], workspace=lay["ws"])
+                sl.slope_wgrad_adapter(lay["dY"], lay["X"], lay["meta"], lay["L"], lay["R"],
+                                       out=(lay["G"], lay["dL"], lay["dR"]), workspace=big_ws)
+        adapter_step()
+        torch.cuda.synchronize()
+        a0 = time.perf_counter()
+        for _ in range(3):
+            adapter_step()
+        torch.cuda.synchronize()
+        ab_ms = (time.perf_counter() - a0) * 1e3 / 3
+        adapter_bwd = {"ms_per_step": ab_ms, "plain_backward_ms": per_call["spmm_bwd_x"] + per_call["wgrad_masked"],
+                       "calls": "slope_spmm_bwd_x_adapter + slope_wgrad_adapter per layer"}
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(layers[-2] if len(layers) > 1 else layers[0], b, rank)
@@ -236,7 +262,7 @@ def main():
         "frac_of_sparse_peak": value / PEAK_SPARSE_BF16,
         "speedup_vs_dense": None if dense is None else dense["speedup_with_reprune"],
         "roofline": roofline, "kernels": kernels, "dense_gemm": dense, "cpu_baseline": cpu,
-        "per_call_ms": per_call, "optimizer_side": optimizer,
+        "per_call_ms": per_call, "optimizer_side": optimizer, "adapter_backward": adapter_bwd,
     }
     print(json.dumps(out))
 

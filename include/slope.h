@@ -137,6 +137,36 @@ slope_status slope_wgrad_masked(const void* dY, const void* X, int64_t b, const 
                                 void* stream);
 
 /*
+ * slope_spmm_bwd_x_adapter - input gradient of a layer with adapters:
+ *     dX = dY W^{R,C} + (dY R^T) L^T
+ * Eq. 6 plus the derivative of the low-rank term of Eq. 11 with respect to X (Sec. 2.2; the
+ * paper leaves it to autograd).  dY R^T is rounded to bf16 before it meets L.
+ *   dY, WrcT_vals, WrcT_meta, dX   as for slope_spmm_bwd_x
+ *   L   in  bf16[d_in, r]    R  in  bf16[r, d_out]    r % 32 == 0, 32 <= r <= 512
+ *   workspace  slope_spmm_bwd_x_adapter_workspace_bytes(b, r) bytes, 256-byte aligned
+ */
+size_t slope_spmm_bwd_x_adapter_workspace_bytes(int64_t b, int64_t r);
+slope_status slope_spmm_bwd_x_adapter(const void* dY, int64_t b, const void* WrcT_vals, const void* WrcT_meta,
+                                      int64_t d_out, int64_t d_in, const void* L, const void* R, int64_t r, void* dX,
+                                      void* workspace, void* stream);
+
+/*
+ * slope_wgrad_adapter - all weight gradients of a layer with adapters in one call: the packed,
+ * masked dW of slope_wgrad_masked (Eq. 5, Algorithm 1 lines 12-13) and the gradients of the
+ * low-rank term of Eq. 11 by the chain rule,
+ *     dL = X^T (dY R^T)   bf16[d_in, r]          dR = (X L)^T dY   bf16[r, d_out].
+ * The three contractions over the tokens share one pair of token-contiguous copies of X and dY.
+ * X L and dY R^T are rounded to bf16 before the second product.
+ *   dY, X, Wr_meta, dW_vals   as for slope_wgrad_masked
+ *   L, R, r                    as for slope_spmm_fwd (r % 32 == 0, 32 <= r <= 512)
+ *   workspace  slope_wgrad_adapter_workspace_bytes(b, d_in, d_out, r) bytes, 256-byte aligned, required
+ */
+size_t slope_wgrad_adapter_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out, int64_t r);
+slope_status slope_wgrad_adapter(const void* dY, const void* X, int64_t b, const void* Wr_meta, int64_t d_out,
+                                 int64_t d_in, const void* L, const void* R, int64_t r, void* dW_vals, void* dL,
+                                 void* dR, void* workspace, void* stream);
+
+/*
  * slope_sparse_add - out = beta * A + gamma * B on the packed values of two matrices that share
  * one sparsity pattern (App. K, sparse matrix addition).  Algorithm 1 line 15 is the case
  * A = packed masked gradient, beta = 1 / gradient scale, B = packed W^R, gamma = weight decay.

@@ -38,6 +38,10 @@ SIGNATURES = {
     "slope_spmm_bwd_x": (_INT, [_P, _I64, _P, _P, _I64, _I64, _P, _P]),
     "slope_wgrad_workspace_bytes": (_SZ, [_I64, _I64, _I64]),
     "slope_wgrad_masked": (_INT, [_P, _P, _I64, _P, _I64, _I64, _P, _P, _P]),
+    "slope_spmm_bwd_x_adapter_workspace_bytes": (_SZ, [_I64, _I64]),
+    "slope_spmm_bwd_x_adapter": (_INT, [_P, _I64, _P, _P, _I64, _I64, _P, _P, _I64, _P, _P, _P]),
+    "slope_wgrad_adapter_workspace_bytes": (_SZ, [_I64, _I64, _I64, _I64]),
+    "slope_wgrad_adapter": (_INT, [_P, _P, _I64, _P, _I64, _I64, _P, _P, _I64, _P, _P, _P, _P, _P]),
     "slope_sparse_add": (_INT, [_P, _P, _I64, _I64, ctypes.c_float, ctypes.c_float, _P, _P]),
     "slope_update_sparse": (_INT, [_P, _P, _I64, _I64, _P, _P, _P, _P]),
 }
@@ -165,6 +169,44 @@ def slope_wgrad_masked(dY: torch.Tensor, X: torch.Tensor, meta: torch.Tensor, ou
     _check("slope_wgrad_masked", lib().slope_wgrad_masked(_ptr(dY), _ptr(X), b, _ptr(meta), d_out, d_in, _ptr(G),
                                                           _ptr(workspace), _stream()))
     return G
+
+
+def slope_spmm_bwd_x_adapter(dY, vals_t, meta_t, L, R, out=None, workspace=None):
+    """dX = dY W^{R,C} + (dY R^T) L^T.  L bf16[d_in, r]; R bf16[r, d_out]."""
+    _dev(dY, vals_t, meta_t, L, R)
+    b, d_out = dY.shape
+    d_in, r = L.shape
+    dX = out if out is not None else torch.empty((b, d_in), dtype=torch.bfloat16, device=dY.device)
+    if workspace is None:
+        workspace = torch.empty(int(lib().slope_spmm_bwd_x_adapter_workspace_bytes(b, r)), dtype=torch.uint8,
+                                device=dY.device)
+    _check("slope_spmm_bwd_x_adapter",
+           lib().slope_spmm_bwd_x_adapter(_ptr(dY), b, _ptr(vals_t), _ptr(meta_t), d_out, d_in, _ptr(L), _ptr(R), r,
+                                          _ptr(dX), _ptr(workspace), _stream()))
+    return dX
+
+
+def slope_wgrad_adapter_workspace_bytes(b: int, d_in: int, d_out: int, r: int) -> int:
+    return int(lib().slope_wgrad_adapter_workspace_bytes(b, d_in, d_out, r))
+
+
+def slope_wgrad_adapter(dY, X, meta, L, R, out=None, workspace=None):
+    """(dW packed, dL, dR) of a layer with adapters; one call, shared token-contiguous copies."""
+    _dev(dY, X, meta, L, R)
+    b, d_out = dY.shape
+    d_in, r = L.shape
+    if out is None:
+        out = (torch.empty((d_out, d_in // 2), dtype=torch.bfloat16, device=dY.device),
+               torch.empty((d_in, r), dtype=torch.bfloat16, device=dY.device),
+               torch.empty((r, d_out), dtype=torch.bfloat16, device=dY.device))
+    G, dL, dR = out
+    if workspace is None:
+        workspace = torch.empty(slope_wgrad_adapter_workspace_bytes(b, d_in, d_out, r), dtype=torch.uint8,
+                                device=dY.device)
+    _check("slope_wgrad_adapter",
+           lib().slope_wgrad_adapter(_ptr(dY), _ptr(X), b, _ptr(meta), d_out, d_in, _ptr(L), _ptr(R), r, _ptr(G),
+                                     _ptr(dL), _ptr(dR), _ptr(workspace), _stream()))
+    return G, dL, dR
 
 
 def slope_sparse_add(A_vals: torch.Tensor, B_vals: torch.Tensor, beta: float, gamma: float, out=None):

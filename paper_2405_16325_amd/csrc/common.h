@@ -38,6 +38,11 @@ hipError_t launch_wgrad_masked_ws(const bf16_t* dY, const bf16_t* X, int64_t b, 
 // C[n, m] = B[n, K] * A[m, K]^T (dense bf16, fp32 accumulation), K % 64 == 0
 hipError_t launch_dense_tn_plain(const bf16_t* B, int64_t n, const bf16_t* A, int64_t m, int64_t K, bf16_t* C,
                                  hipStream_t s);
+// dW (packed) + dL + dR of a layer with adapters, sharing the token-contiguous copies
+size_t wgrad_adapter_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out, int64_t r);
+hipError_t launch_wgrad_adapter(const bf16_t* dY, const bf16_t* X, int64_t b, const uint8_t* meta, int64_t d_out,
+                                int64_t d_in, const bf16_t* L, const bf16_t* R, int64_t r, bf16_t* gvals, bf16_t* dL,
+                                bf16_t* dR, void* workspace, hipStream_t s);
 
 // Rank the four keys of a group by (key descending, index ascending) and return the 4-bit
 // set of the two winners.  Keys are small non-negative integers.

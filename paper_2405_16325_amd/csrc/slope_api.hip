@@ -142,6 +142,49 @@ slope_status slope_wgrad_masked(const void* dY, const void* X, int64_t b, const 
                                       (bf16_t*)dW_vals, (hipStream_t)stream));
 }
 
+size_t slope_spmm_bwd_x_adapter_workspace_bytes(int64_t b, int64_t r) {
+    if (b <= 0 || r <= 0) return 0;
+    return round256((size_t)b * r * 2);
+}
+
+slope_status slope_spmm_bwd_x_adapter(const void* dY, int64_t b, const void* WrcT_vals, const void* WrcT_meta,
+                                      int64_t d_out, int64_t d_in, const void* L, const void* R, int64_t r, void* dX,
+                                      void* workspace, void* stream) {
+    if (!dY || !WrcT_vals || !WrcT_meta || !dX || !L || !R || !workspace) return SLOPE_ERR_NULL;
+    if (bad_extent(b, 1) || bad_extent(d_out, 64) || bad_extent(d_in, 64) || r <= 0) return SLOPE_ERR_SHAPE;
+    if (r % 32 != 0 || r > 512) return SLOPE_ERR_UNSUPPORTED;
+    if (misaligned(dY, 16) || misaligned(WrcT_vals, 16) || misaligned(WrcT_meta, 16) || misaligned(dX, 16) ||
+        misaligned(L, 16) || misaligned(R, 16) || misaligned(workspace, 256))
+        return SLOPE_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)stream;
+    bf16_t* T2 = (bf16_t*)workspace;                          // dY R^T, bf16[b, r]
+    hipError_t e = launch_dense_tn_plain((const bf16_t*)dY, b, (const bf16_t*)R, r, d_out, T2, s);
+    if (e != hipSuccess) return finish(e);
+    // sparse rows = d_in, contraction over d_out, then r more k-steps on T2 and L (K-contiguous as stored)
+    return finish(launch_spmm((const bf16_t*)dY, b, (const bf16_t*)WrcT_vals, (const uint8_t*)WrcT_meta, d_in, d_out,
+                              T2, (const bf16_t*)L, r, (bf16_t*)dX, s));
+}
+
+size_t slope_wgrad_adapter_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out, int64_t r) {
+    if (b <= 0 || d_in <= 0 || d_out <= 0 || r <= 0) return 0;
+    return round256(wgrad_adapter_workspace_bytes(b, d_in, d_out, r));
+}
+
+slope_status slope_wgrad_adapter(const void* dY, const void* X, int64_t b, const void* Wr_meta, int64_t d_out,
+                                 int64_t d_in, const void* L, const void* R, int64_t r, void* dW_vals, void* dL,
+                                 void* dR, void* workspace, void* stream) {
+    if (!dY || !X || !Wr_meta || !dW_vals || !L || !R || !dL || !dR || !workspace) return SLOPE_ERR_NULL;
+    if (bad_extent(b, 1) || bad_extent(d_out, 64) || bad_extent(d_in, 64) || r <= 0) return SLOPE_ERR_SHAPE;
+    if (r % 32 != 0 || r > 512) return SLOPE_ERR_UNSUPPORTED;
+    if (misaligned(dY, 16) || misaligned(X, 16) || misaligned(Wr_meta, 16) || misaligned(dW_vals, 16) ||
+        misaligned(L, 16) || misaligned(R, 16) || misaligned(dL, 16) || misaligned(dR, 16) ||
+        misaligned(workspace, 256))
+        return SLOPE_ERR_ALIGN;
+    return finish(launch_wgrad_adapter((const bf16_t*)dY, (const bf16_t*)X, b, (const uint8_t*)Wr_meta, d_out, d_in,
+                                       (const bf16_t*)L, (const bf16_t*)R, r, (bf16_t*)dW_vals, (bf16_t*)dL,
+                                       (bf16_t*)dR, workspace, (hipStream_t)stream));
+}
+
 slope_status slope_sparse_add(const void* A_vals, const void* B_vals, int64_t rows, int64_t cols, float beta,
                               float gamma, void* out_vals, void* stream) {
     if (!A_vals || !B_vals || !out_vals) return SLOPE_ERR_NULL;

@@ -18,8 +18,9 @@
 
 namespace {
 
-// out[c][r] = in[r][c] for r < rows, zero for rows <= r < rows_pad; in is [rows][cols] bf16,
-// out is [cols][rows_pad].  64 x 64 tiles through LDS, 16-byte global accesses on both sides.
+// out[c][r] = in[r][c] for r < rows, zero for rows <= r < rows_pad; in is [rows][cols] bf16 with
+// cols % 8 == 0, out is [cols][rows_pad] with rows_pad % 64 == 0.  64 x 64 tiles through LDS,
+// 16-byte global accesses on both sides.
 __global__ void __launch_bounds__(256) transpose_pad_kernel(const bf16_t* __restrict__ in, int rows, int cols,
                                                             int rows_pad, bf16_t* __restrict__ out) {
     __shared__ bf16_t tile[64][66];
@@ -28,7 +29,7 @@ __global__ void __launch_bounds__(256) transpose_pad_kernel(const bf16_t* __rest
     for (int p = 0; p < 2; ++p) {
         int r = (t >> 3) + 32 * p, c8 = (t & 7) * 8;
         u32x4 v = {0u, 0u, 0u, 0u};
-        if (r0 + r < rows) v = *(const u32x4*)(in + (size_t)(r0 + r) * cols + c0 + c8);
+        if (r0 + r < rows && c0 + c8 < cols) v = *(const u32x4*)(in + (size_t)(r0 + r) * cols + c0 + c8);
 #pragma unroll
         for (int e = 0; e < 8; ++e) tile[c8 + e][r] = (bf16_t)(v[e >> 1] >> (16 * (e & 1)));
     }
@@ -36,10 +37,17 @@ __global__ void __launch_bounds__(256) transpose_pad_kernel(const bf16_t* __rest
 #pragma unroll
     for (int p = 0; p < 2; ++p) {
         int c = (t >> 3) + 32 * p, r8 = (t & 7) * 8;
+        if (c0 + c >= cols) continue;
         const uint32_t* src = (const uint32_t*)&tile[c][r8];
         u32x4 v = {src[0], src[1], src[2], src[3]};
         *(u32x4*)(out + (size_t)(c0 + c) * rows_pad + r0 + r8) = v;
     }
+}
+
+inline void launch_transpose_pad(const bf16_t* in, int64_t rows, int64_t cols, int64_t rows_pad, bf16_t* out,
+                                 hipStream_t s) {
+    transpose_pad_kernel<<<dim3((unsigned)(rows_pad / 64), (unsigned)((cols + 63) / 64)), dim3(256), 0, s>>>(
+        in, (int)rows, (int)cols, (int)rows_pad, out);
 }
 
 template <int BM, int BN, int NS>
@@ -399,8 +407,8 @@ hipError_t launch_wgrad_masked_ws(const bf16_t* dY, const bf16_t* X, int64_t b, 
     int bp = (int)((b + 63) / 64 * 64);
     bf16_t* Xt = (bf16_t*)workspace;
     bf16_t* dYt = Xt + (size_t)d_in * bp;
-    transpose_pad_kernel<<<dim3((unsigned)(bp / 64), (unsigned)(d_in / 64)), dim3(256), 0, s>>>(X, (int)b, (int)d_in, bp, Xt);
-    transpose_pad_kernel<<<dim3((unsigned)(bp / 64), (unsigned)(d_out / 64)), dim3(256), 0, s>>>(dY, (int)b, (int)d_out, bp, dYt);
+    launch_transpose_pad(X, b, d_in, bp, Xt, s);
+    launch_transpose_pad(dY, b, d_out, bp, dYt, s);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     // The kernel runs at the rate its compute units pull operands from L2: a launch costs about
@@ -424,4 +432,46 @@ hipError_t launch_wgrad_masked_ws(const bf16_t* dY, const bf16_t* X, int64_t b, 
 hipError_t launch_dense_tn_plain(const bf16_t* B, int64_t n, const bf16_t* A, int64_t m, int64_t K, bf16_t* C,
                                  hipStream_t s) {
     return launch_dense_tn<128, 64, EPI_PLAIN, 6>(A, m, B, n, K, nullptr, C, s);
+}
+
+// ------------------------------------------------------------------------------------------
+// Weight gradient of a layer with adapters: the packed dW as above plus the adapter gradients
+// (chain rule of Eq. 11)   dL = X^T (dY R^T)  [d_in, r],   dR = (X L)^T dY  [r, d_out],
+// all three contractions over the tokens sharing the token-contiguous copies of X and dY.
+// Workspace: Xt | dYt | Lt [r][d_in] | T = X L [b][r] | T2 = dY R^T [b][r] | Tt [r][bp] | T2t [r][bp].
+namespace {
+inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
+}  // namespace
+
+size_t wgrad_adapter_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out, int64_t r) {
+    size_t bp = ((size_t)b + 63) / 64 * 64;
+    return round256(wgrad_workspace_bytes(b, d_in, d_out)) + round256((size_t)r * d_in * 2) +
+           2 * round256((size_t)b * r * 2) + 2 * round256((size_t)r * bp * 2);
+}
+
+hipError_t launch_wgrad_adapter(const bf16_t* dY, const bf16_t* X, int64_t b, const uint8_t* meta, int64_t d_out,
+                                int64_t d_in, const bf16_t* L, const bf16_t* R, int64_t r, bf16_t* gvals, bf16_t* dL,
+                                bf16_t* dR, void* workspace, hipStream_t s) {
+    const int64_t bp = (b + 63) / 64 * 64;
+    uint8_t* w = (uint8_t*)workspace;
+    bf16_t* Xt = (bf16_t*)w;
+    bf16_t* dYt = Xt + (size_t)d_in * bp;
+    w += round256(wgrad_workspace_bytes(b, d_in, d_out));
+    bf16_t* Lt = (bf16_t*)w;   w += round256((size_t)r * d_in * 2);
+    bf16_t* T = (bf16_t*)w;    w += round256((size_t)b * r * 2);
+    bf16_t* T2 = (bf16_t*)w;   w += round256((size_t)b * r * 2);
+    bf16_t* Tt = (bf16_t*)w;   w += round256((size_t)r * bp * 2);
+    bf16_t* T2t = (bf16_t*)w;
+
+    hipError_t e = launch_wgrad_masked_ws(dY, X, b, meta, d_out, d_in, gvals, workspace, s);   // fills Xt, dYt
+    if (e != hipSuccess) return e;
+    launch_transpose_pad(L, d_in, r, d_in, Lt, s);                                // Lt[r][d_in]
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if ((e = launch_dense_tn_plain(X, b, Lt, r, d_in, T, s)) != hipSuccess) return e;      // T  = X L
+    if ((e = launch_dense_tn_plain(dY, b, R, r, d_out, T2, s)) != hipSuccess) return e;    // T2 = dY R^T
+    launch_transpose_pad(T, b, r, bp, Tt, s);
+    launch_transpose_pad(T2, b, r, bp, T2t, s);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if ((e = launch_dense_tn_plain(Xt, d_in, T2t, r, bp, dL, s)) != hipSuccess) return e;  // dL[d_in][r]
+    return launch_dense_tn_plain(Tt, r, dYt, d_out, bp, dR, s);                            // dR[r][d_out]
 }

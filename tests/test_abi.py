@@ -60,6 +60,13 @@ def test_argument_errors_are_reported_before_launch():
     assert lib.slope_wgrad_masked(p, p, 8, None, 64, 64, p, None, None) == binding.SLOPE_ERR_NULL
     assert lib.slope_wgrad_masked(p, p, -1, p, 64, 64, p, None, None) == binding.SLOPE_ERR_SHAPE
     assert lib.slope_wgrad_masked(p, p, 8, p, 64, 64, p, odd, None) == binding.SLOPE_ERR_ALIGN
+    assert lib.slope_spmm_bwd_x_adapter(p, 8, p, p, 64, 64, p, None, 32, p, p, None) == binding.SLOPE_ERR_NULL
+    assert lib.slope_spmm_bwd_x_adapter(p, 8, p, p, 64, 64, p, p, 48, p, p, None) == binding.SLOPE_ERR_UNSUPPORTED
+    assert lib.slope_spmm_bwd_x_adapter(p, 8, p, p, 64, 64, p, p, 32, p, odd, None) == binding.SLOPE_ERR_ALIGN
+    assert lib.slope_wgrad_adapter(p, p, 8, p, 64, 64, p, p, 32, p, p, p, None, None) == binding.SLOPE_ERR_NULL
+    assert lib.slope_wgrad_adapter(p, p, 8, p, 64, 72, p, p, 32, p, p, p, p, None) == binding.SLOPE_ERR_SHAPE
+    assert lib.slope_wgrad_adapter(p, p, 8, p, 64, 64, p, p, 1024, p, p, p, p, None) == binding.SLOPE_ERR_UNSUPPORTED
+    assert lib.slope_wgrad_adapter_workspace_bytes(100, 64, 128, 32) > lib.slope_wgrad_workspace_bytes(100, 64, 128)
     assert lib.slope_sparse_add(p, None, 4, 64, 1.0, 1.0, p, None) == binding.SLOPE_ERR_NULL
     assert lib.slope_sparse_add(p, p, 4, 24, 1.0, 1.0, p, None) == binding.SLOPE_ERR_SHAPE
     assert lib.slope_sparse_add(p, p, 4, 64, 1.0, 1.0, odd, None) == binding.SLOPE_ERR_ALIGN
