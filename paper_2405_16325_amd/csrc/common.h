@@ -25,6 +25,14 @@ hipError_t launch_sparse_add(const bf16_t* a, const bf16_t* b, size_t count, flo
 // C[n, m] = B[n, K] * Asparse[m, K]^T  (+ B2[n, K2] * A2[m, K2]^T dense when K2 > 0)
 hipError_t launch_spmm(const bf16_t* B, int64_t n, const bf16_t* A_vals, const uint8_t* A_meta, int64_t m,
                        int64_t K, const bf16_t* B2, const bf16_t* A2, int64_t K2, bf16_t* C, hipStream_t s);
+// the same product for n <= 32 tokens (any K % 64 == 0); adapters as T[n, K2] and R[K2, m] as stored
+constexpr int64_t STREAM_MAX_TOKENS = 32;
+hipError_t launch_spmm_stream(const bf16_t* B, int64_t n, const bf16_t* A_vals, const uint8_t* A_meta, int64_t m,
+                              int64_t K, const bf16_t* T, const bf16_t* R, int64_t K2, bf16_t* C, hipStream_t s);
+// T = X L for n <= 32 tokens, split over d_in with fp32 partial sums in `scratch`
+size_t xl_small_scratch_bytes(int64_t n, int64_t d_in, int64_t r);
+hipError_t launch_xl_small(const bf16_t* X, int64_t n, int64_t d_in, const bf16_t* L, int64_t r, float* scratch,
+                           bf16_t* T, hipStream_t s);
 // T[n, r] = X[n, K] * Lt[r, K]^T (dense), plus transposes of the adapter factors
 hipError_t launch_lowrank_prepare(const bf16_t* X, int64_t n, int64_t d_in, int64_t d_out, const bf16_t* L,
                                   const bf16_t* R, int64_t r, bf16_t* T, bf16_t* Lt, bf16_t* Rt, hipStream_t s);

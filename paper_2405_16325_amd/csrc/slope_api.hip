@@ -54,7 +54,9 @@ static size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 size_t slope_spmm_fwd_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out, int64_t r) {
     if (r <= 0 || b <= 0 || d_in <= 0 || d_out <= 0) return 0;
-    return round256((size_t)b * r * 2) + round256((size_t)d_in * r * 2) + round256((size_t)d_out * r * 2);
+    size_t tiles = round256((size_t)b * r * 2) + round256((size_t)d_in * r * 2) + round256((size_t)d_out * r * 2);
+    size_t small = b <= STREAM_MAX_TOKENS ? round256((size_t)b * r * 2) + round256(xl_small_scratch_bytes(b, d_in, r)) : 0;
+    return tiles > small ? tiles : small;
 }
 
 slope_status slope_prune_rows(const void* W, int64_t d_out, int64_t d_in, int n, int m, void* Wr_vals, void* Wr_meta,
@@ -95,11 +97,21 @@ slope_status slope_spmm_fwd(const void* X, int64_t b, const void* Wr_vals, const
     if (misaligned(X, 16) || misaligned(Wr_vals, 16) || misaligned(Wr_meta, 16) || misaligned(Y, 16))
         return SLOPE_ERR_ALIGN;
     hipStream_t s = (hipStream_t)stream;
+    uint8_t* ws = (uint8_t*)workspace;
+    bf16_t* T = (bf16_t*)ws;
+    if (b <= STREAM_MAX_TOKENS && d_in >= 128) {   // inference-size batch: one HBM-bound pass over the packed weight
+        if (adapter) {
+            hipError_t e = launch_xl_small((const bf16_t*)X, b, d_in, (const bf16_t*)L_or_null, r,
+                                           (float*)(ws + round256((size_t)b * r * 2)), T, s);
+            if (e != hipSuccess) return finish(e);
+        }
+        return finish(launch_spmm_stream((const bf16_t*)X, b, (const bf16_t*)Wr_vals, (const uint8_t*)Wr_meta, d_out,
+                                         d_in, adapter ? T : nullptr, adapter ? (const bf16_t*)R_or_null : nullptr,
+                                         adapter ? r : 0, (bf16_t*)Y, s));
+    }
     if (!adapter)
         return finish(launch_spmm((const bf16_t*)X, b, (const bf16_t*)Wr_vals, (const uint8_t*)Wr_meta, d_out, d_in,
                                   nullptr, nullptr, 0, (bf16_t*)Y, s));
-    uint8_t* ws = (uint8_t*)workspace;
-    bf16_t* T = (bf16_t*)ws;
     bf16_t* Lt = (bf16_t*)(ws + round256((size_t)b * r * 2));
     bf16_t* Rt = (bf16_t*)((uint8_t*)Lt + round256((size_t)d_in * r * 2));
     hipError_t e = launch_lowrank_prepare((const bf16_t*)X, b, d_in, d_out, (const bf16_t*)L_or_null,
@@ -116,6 +128,9 @@ slope_status slope_spmm_bwd_x(const void* dY, int64_t b, const void* WrcT_vals, 
     if (misaligned(dY, 16) || misaligned(WrcT_vals, 16) || misaligned(WrcT_meta, 16) || misaligned(dX, 16))
         return SLOPE_ERR_ALIGN;
     // sparse rows = d_in, contraction over d_out
+    if (b <= STREAM_MAX_TOKENS && d_out >= 128)
+        return finish(launch_spmm_stream((const bf16_t*)dY, b, (const bf16_t*)WrcT_vals, (const uint8_t*)WrcT_meta,
+                                         d_in, d_out, nullptr, nullptr, 0, (bf16_t*)dX, (hipStream_t)stream));
     return finish(launch_spmm((const bf16_t*)dY, b, (const bf16_t*)WrcT_vals, (const uint8_t*)WrcT_meta, d_in, d_out,
                               nullptr, nullptr, 0, (bf16_t*)dX, (hipStream_t)stream));
 }
