@@ -13,7 +13,7 @@
 //     adapter term is added there with plain fp32 FMAs on T = X L and the factor R as stored.
 // T itself comes from a split over d_in (xl_partial_kernel, fp32 partial sums in the workspace)
 // followed by a fixed-order reduction that rounds to bf16 (xl_reduce_kernel).
-#include "common.h"
+#include "pipeline.h"
 
 namespace {
 
@@ -28,7 +28,7 @@ constexpr int ST_WAVES = 8;
 #define ST_LOAD(p) (*(p))
 #endif
 constexpr int ST_DEPTH = ST_DEPTH_PAIRS;   // pairs of k-steps each wavefront keeps in flight
-constexpr int XL_CHUNK = 128;       // rows of L per workgroup of xl_partial_kernel
+constexpr int XL_CHUNK = 64;        // rows of L per workgroup of xl_partial_kernel
 
 union StB { u32x4 u[2]; bf16x16 v; };
 union StA { u32x4 u; bf16x8 v; };
@@ -204,27 +204,217 @@ __global__ void __launch_bounds__(ST_WAVES * 64) spmm_stream_kernel(const bf16_t
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Up to 16 tokens: the same k-split, but every operand takes the route of the tile kernels,
+// global -> LDS loads of full 128-byte lines into a ring that is private to the wavefront (two
+// pairs of k-steps deep), then ds_read_b128 in MFMA order.  Nothing is shared between wavefronts,
+// so the main loop needs no barrier, only the wavefront's own s_waitcnt; the lane permutations of
+// the register variant, which cap a compute unit near 23 B/ns, are gone, and one workgroup per
+// compute unit is enough to saturate HBM.  Ring stage of one wavefront:
+//     A: MF fragments x (16 rows x 128 B: both steps of the pair) | B: 2 steps x (16 tokens x 128 B)
+//     | metadata: 16 MF rows x 16 B
+template <int MF, int WAVES>
+struct StreamLds {
+    static constexpr int BM = 16 * MF;
+    static constexpr int A_BYTES = MF * 2048, B_BYTES = 2 * 2048, M_BYTES = MF * 256;
+    static constexpr int STAGE = A_BYTES + B_BYTES + M_BYTES;
+    static constexpr int OPS = 2 * MF + 4 + 1;                // loads per wavefront and pair
+    static constexpr int RING = WAVES * 2 * STAGE;
+    static constexpr int PART_PITCH = 17;
+    static constexpr int TOTAL = RING + WAVES * BM * PART_PITCH * 4;
+};
+
+template <int MF, int WAVES>
+__global__ void __launch_bounds__(WAVES * 64) spmm_stream_lds_kernel(const bf16_t* __restrict__ B, int n,
+                                                                   const bf16_t* __restrict__ Av,
+                                                                   const uint8_t* __restrict__ Am, int m, int K,
+                                                                   const bf16_t* __restrict__ T,
+                                                                   const bf16_t* __restrict__ R, int K2,
+                                                                   bf16_t* __restrict__ C) {
+    using S = StreamLds<MF, WAVES>;
+    extern __shared__ __align__(16) uint8_t smem[];
+    float* part = (float*)(smem + S::RING);                   // [wave][row][PART_PITCH]
+
+    const int t = threadIdx.x, lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int l16 = lane & 15, lq = lane >> 4;
+    const int m0 = blockIdx.x * S::BM;
+    const int ksteps = K / 64, kpairs = (ksteps + 1) / 2;
+    const bool odd_tail = (ksteps & 1) != 0;                 // the last pair has one step only
+    uint8_t* const ring = smem + wave * 2 * S::STAGE;
+
+    // loader lanes: 8 lanes per row, the 16-byte chunks of a row rotated by (row / 2) % 8
+    const int ld_row = lane >> 3, ld_slot = lane & 7;
+    const uint8_t* a_src[MF][2];
+#pragma unroll
+    for (int i = 0; i < MF; ++i)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            int rl = 8 * h + ld_row;
+            int row = m0 + 16 * i + rl;
+            row = row < m ? row : m - 1;
+            a_src[i][h] = (const uint8_t*)Av + (size_t)row * K + ((ld_slot ^ ((rl >> 1) & 7)) * 16);
+        }
+    const uint8_t* b_src[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        int rl = 8 * h + ld_row;
+        int tok = rl < n ? rl : n - 1;
+        b_src[h] = (const uint8_t*)B + (size_t)tok * K * 2 + ((ld_slot ^ ((rl >> 1) & 7)) * 16);
+    }
+    const bool meta_lane = lane < 16 * MF;
+    const uint8_t* m_src;
+    {
+        int row = m0 + (meta_lane ? lane : 0);
+        row = row < m ? row : m - 1;
+        m_src = Am + (size_t)row * (K / 8);
+    }
+    auto issue = [&](int stage, int p) {                      // pair p (valid) into ring stage `stage`
+        // an odd number of steps: the last pair is read as steps (ksteps - 2, ksteps - 1) and only
+        // its second half is used, so that no load runs past the row
+        const size_t s0 = (odd_tail && p == kpairs - 1) ? (size_t)ksteps - 2 : (size_t)2 * p;
+        uint8_t* st = ring + stage * S::STAGE;
+#pragma unroll
+        for (int i = 0; i < MF; ++i) {
+            dma16(a_src[i][0] + s0 * 64, st + i * 2048);
+            dma16(a_src[i][1] + s0 * 64, st + i * 2048 + 1024);
+        }
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            dma16(b_src[0] + (s0 + e) * 128, st + S::A_BYTES + e * 2048);
+            dma16(b_src[1] + (s0 + e) * 128, st + S::A_BYTES + e * 2048 + 1024);
+        }
+        if (meta_lane) dma16(m_src + s0 * 8, st + S::A_BYTES + S::B_BYTES);
+    };
+
+    const int sw = (l16 >> 1) & 7;
+    f32x4 acc[MF];
+#pragma unroll
+    for (int i = 0; i < MF; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    auto multiply = [&](int stage, int e) {                   // step e (0 or 1) of the pair in `stage`
+        const uint8_t* st = ring + stage * S::STAGE;
+        StB b;
+        b.u[0] = *(const u32x4*)(st + S::A_BYTES + e * 2048 + l16 * 128 + ((lq ^ sw) * 16));
+        b.u[1] = *(const u32x4*)(st + S::A_BYTES + e * 2048 + l16 * 128 + (((4 + lq) ^ sw) * 16));
+#pragma unroll
+        for (int i = 0; i < MF; ++i) {
+            StA a;
+            a.u = *(const u32x4*)(st + i * 2048 + l16 * 128 + (((4 * e + lq) ^ sw) * 16));
+            int idx = *(const uint16_t*)(st + S::A_BYTES + S::B_BYTES + (16 * i + l16) * 16 + 8 * e + 2 * lq);
+            acc[i] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a.v, b.v, acc[i], idx, 0, 0);
+        }
+    };
+
+    // workgroups start at different places of the k range and wrap around
+    const int rot = (int)((blockIdx.x * 37u) % (unsigned)kpairs);
+    auto pair_of = [&](int q) {                               // q-th pair of this workgroup; late ones clamped
+        if (q >= kpairs) return kpairs - 1;
+        int p = q + rot;
+        return p >= kpairs ? p - kpairs : p;
+    };
+    issue(0, pair_of(wave));
+    issue(1, pair_of(wave + WAVES));
+    for (int q = wave; q < kpairs; q += 2 * WAVES) {
+#pragma unroll
+        for (int d = 0; d < 2; ++d) {
+            const int qq = q + d * WAVES;                     // wave-uniform
+            WAIT_HERE(waitcnt_imm(S::OPS, 15));               // the older of the two pairs in flight has landed
+            if (qq < kpairs) {
+                const int p = pair_of(qq);
+                if (!(odd_tail && p == kpairs - 1)) multiply(d, 0);
+                multiply(d, 1);
+            }
+            // the MFMAs above consumed every LDS read of this stage: it may be refilled
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
+            issue(d, pair_of(qq + 2 * WAVES));
+        }
+    }
+    WAIT_HERE(waitcnt_imm(0, 15));                            // drain the clamped look-ahead loads
+
+    // partial tiles: lane (l16, lq) holds token l16, rows 16 i + 4 lq .. + 3
+#pragma unroll
+    for (int i = 0; i < MF; ++i)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            part[(wave * S::BM + 16 * i + 4 * lq + e) * S::PART_PITCH + l16] = acc[i][e];
+    __syncthreads();
+
+    // adapter operands into the ring, which is free now: T[n][K2] and the tile R[K2][BM] of the factor
+    bf16_t* const t_lds = (bf16_t*)smem;                      // [tok][K2]
+    bf16_t* const r_lds = t_lds + 16 * K2;                    // [k][BM]
+    if (K2 > 0) {
+        for (int idx = t; idx < n * K2 / 8; idx += WAVES * 64)
+            ((u32x4*)t_lds)[idx] = ((const u32x4*)T)[idx];
+        constexpr int SEG = S::BM / 8;                        // 16-byte segments per row of the tile
+        for (int idx = t; idx < K2 * SEG; idx += WAVES * 64) {
+            int k = idx / SEG, sg = idx % SEG;
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (m0 + 8 * sg < m) v = *(const u32x4*)(R + (size_t)k * m + m0 + 8 * sg);
+            *(u32x4*)(r_lds + k * S::BM + 8 * sg) = v;
+        }
+        __syncthreads();
+    }
+
+    // fixed-order sum, adapter term, store: thread = (feature o, token tok)
+    const int o = t % S::BM;
+    for (int tok = t / S::BM; tok < n; tok += WAVES * 64 / S::BM) {
+        float v = 0.f;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) v += part[(w * S::BM + o) * S::PART_PITCH + tok];
+        if (m0 + o < m) {
+            if (K2 > 0) {
+                float low = 0.f;
+#pragma unroll 8
+                for (int k = 0; k < K2; ++k)
+                    low = __builtin_fmaf(__uint_as_float((uint32_t)t_lds[tok * K2 + k] << 16),
+                                         __uint_as_float((uint32_t)r_lds[k * S::BM + o] << 16), low);
+                v += low;
+            }
+            union { __bf16 h; bf16_t u; } r;
+            r.h = (__bf16)v;
+            C[(size_t)tok * m + m0 + o] = r.u;
+        }
+    }
+}
+
+template <int MF, int WAVES>
+hipError_t launch_stream_lds(const bf16_t* B, int64_t n, const bf16_t* Av, const uint8_t* Am, int64_t m, int64_t K,
+                             const bf16_t* T, const bf16_t* R, int64_t K2, bf16_t* C, hipStream_t s) {
+    using S = StreamLds<MF, WAVES>;
+    static_assert(S::TOTAL <= 160 * 1024, "LDS budget");
+    auto kern = spmm_stream_lds_kernel<MF, WAVES>;
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, S::TOTAL);
+    if (e != hipSuccess) return e;
+    kern<<<dim3((unsigned)((m + S::BM - 1) / S::BM)), dim3(WAVES * 64), S::TOTAL, s>>>(B, (int)n, Av, Am, (int)m, (int)K,
+                                                                                     T, R, (int)K2, C);
+    return hipGetLastError();
+}
+
 // P[c][t][k] = sum over the rows i of chunk c of X[t][i] * L[i][k]   (fp32; c = blockIdx.x)
-// thread = column k of L: its loads of a row of L are contiguous across the wavefront; the token
-// values are the same for all lanes and come through scalar loads.
+// thread = column k of L: its loads of a row of L are contiguous across the wavefront, and all 64
+// rows of the chunk are requested before the first is used; the token values are the same for
+// all lanes and come through scalar loads.
 template <int NT>
 __global__ void __launch_bounds__(256) xl_partial_kernel(const bf16_t* __restrict__ X, int n, int d_in,
                                                          const bf16_t* __restrict__ L, int r,
                                                          float* __restrict__ P) {
-    const int c = blockIdx.x, i0 = c * XL_CHUNK;
+    const int c = blockIdx.x, i0 = c * XL_CHUNK;             // d_in % 64 == 0: every chunk is full
     const int k = blockIdx.y * 256 + threadIdx.x;
-    const int rows = d_in - i0 < XL_CHUNK ? d_in - i0 : XL_CHUNK;       // a multiple of 64
     const int kc = k < r ? k : r - 1;
+    uint16_t lv[XL_CHUNK];
+#pragma unroll
+    for (int i = 0; i < XL_CHUNK; ++i) lv[i] = L[(size_t)(i0 + i) * r + kc];
     float acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = 0.f;
-    for (int i = 0; i < rows; i += 2) {
-        float l0 = __uint_as_float((uint32_t)L[(size_t)(i0 + i) * r + kc] << 16);
-        float l1 = __uint_as_float((uint32_t)L[(size_t)(i0 + i + 1) * r + kc] << 16);
+#pragma unroll
+    for (int i = 0; i < XL_CHUNK; i += 2) {
+        float l0 = __uint_as_float((uint32_t)lv[i] << 16), l1 = __uint_as_float((uint32_t)lv[i + 1] << 16);
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             int tt = t < n ? t : n - 1;                                        // uniform
-            uint32_t w = *(const uint32_t*)(X + (size_t)tt * d_in + i0 + i);   // uniform address: two tokens' worth of k
+            uint32_t w = *(const uint32_t*)(X + (size_t)tt * d_in + i0 + i);   // uniform address: X[t][i], X[t][i+1]
             acc[t] = __builtin_fmaf(__uint_as_float(w << 16), l0, acc[t]);
             acc[t] = __builtin_fmaf(__uint_as_float(w & 0xFFFF0000u), l1, acc[t]);
         }
@@ -235,16 +425,36 @@ __global__ void __launch_bounds__(256) xl_partial_kernel(const bf16_t* __restric
             if (t < n) P[((size_t)c * n + t) * r + k] = acc[t];
 }
 
-// T[t][k] = bf16( sum over chunks, in order, of P[c][t][k] )
+// T[idx] = bf16( sum over chunks of P[c][idx] ), idx = t * r + k, in a fixed order: a workgroup
+// takes 32 outputs; its 8 wavefront-halves each sum every 8th chunk, then the 8 sums are added
+// in order through LDS.
 __global__ void __launch_bounds__(256) xl_reduce_kernel(const float* __restrict__ P, int chunks, int count,
                                                         bf16_t* __restrict__ T) {
-    int idx = blockIdx.x * 256 + threadIdx.x;
-    if (idx >= count) return;
+    __shared__ float red[8][33];
+    const int o = threadIdx.x & 31, cl = threadIdx.x >> 5;
+    const int idx = blockIdx.x * 32 + o;
     float v = 0.f;
-    for (int c = 0; c < chunks; ++c) v += P[(size_t)c * count + idx];
-    union { __bf16 h; bf16_t u; } o;
-    o.h = (__bf16)v;
-    T[idx] = o.u;
+    if (idx < count) {
+        int c = cl;
+        for (; c + 56 < chunks; c += 64) {                    // 8 loads in flight
+            float x[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) x[u] = P[(size_t)(c + 8 * u) * count + idx];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v += x[u];
+        }
+        for (; c < chunks; c += 8) v += P[(size_t)c * count + idx];
+    }
+    red[cl][o] = v;
+    __syncthreads();
+    if (cl == 0 && idx < count) {
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < 8; ++w) sum += red[w][o];
+        union { __bf16 h; bf16_t u; } out;
+        out.h = (__bf16)sum;
+        T[idx] = out.u;
+    }
 }
 
 }  // namespace
@@ -252,15 +462,26 @@ __global__ void __launch_bounds__(256) xl_reduce_kernel(const float* __restrict_
 // n <= 32, K % 64 == 0, K >= 128; T (bf16[n][K2]) and R (bf16[K2][m]) only when K2 > 0
 hipError_t launch_spmm_stream(const bf16_t* B, int64_t n, const bf16_t* A_vals, const uint8_t* A_meta, int64_t m,
                               int64_t K, const bf16_t* T, const bf16_t* R, int64_t K2, bf16_t* C, hipStream_t s) {
+    if (n <= 16) {
+#ifdef ST_FORCE_BM
+        const bool wide = ST_FORCE_BM == 64;
+#else
+        // One workgroup per compute unit saturates HBM once about 140 of them run, so what costs
+        // time is a last round with few workgroups: take 64 rows per workgroup instead of 32 when
+        // that leaves a fuller last round.
+        auto last_round = [](int64_t blocks) { int64_t r = blocks % RESIDENT; return r == 0 ? RESIDENT : r; };
+        const int64_t b32 = (m + 31) / 32, b64 = (m + 63) / 64;
+        const bool wide = last_round(b32) < 140 && last_round(b64) > last_round(b32) && b32 < 8 * RESIDENT;
+#endif
+        return wide ? launch_stream_lds<4, 4>(B, n, A_vals, A_meta, m, K, T, R, K2, C, s)
+                    : launch_stream_lds<2, 8>(B, n, A_vals, A_meta, m, K, T, R, K2, C, s);
+    }
     dim3 grid((unsigned)((m + ST_BM - 1) / ST_BM)), block(ST_WAVES * 64);
-    if (n <= 16)
-        spmm_stream_kernel<1><<<grid, block, 0, s>>>(B, (int)n, A_vals, A_meta, (int)m, (int)K, T, R, (int)K2, C);
-    else
-        spmm_stream_kernel<2><<<grid, block, 0, s>>>(B, (int)n, A_vals, A_meta, (int)m, (int)K, T, R, (int)K2, C);
+    spmm_stream_kernel<2><<<grid, block, 0, s>>>(B, (int)n, A_vals, A_meta, (int)m, (int)K, T, R, (int)K2, C);
     return hipGetLastError();
 }
 
-// T = X L for n <= 32 tokens; scratch holds ceil(d_in / 128) * n * r floats
+// T = X L for n <= 32 tokens; scratch holds (d_in / 64) * n * r floats
 size_t xl_small_scratch_bytes(int64_t n, int64_t d_in, int64_t r) {
     return (size_t)((d_in + XL_CHUNK - 1) / XL_CHUNK) * (size_t)n * (size_t)r * 4;
 }
@@ -276,6 +497,6 @@ hipError_t launch_xl_small(const bf16_t* X, int64_t n, int64_t d_in, const bf16_
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int count = (int)(n * r);
-    xl_reduce_kernel<<<dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s>>>(scratch, chunks, count, T);
+    xl_reduce_kernel<<<dim3((unsigned)((count + 31) / 32)), dim3(256), 0, s>>>(scratch, chunks, count, T);
     return hipGetLastError();
 }
