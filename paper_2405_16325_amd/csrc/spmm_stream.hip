@@ -463,18 +463,24 @@ __global__ void __launch_bounds__(256) xl_reduce_kernel(const float* __restrict_
 hipError_t launch_spmm_stream(const bf16_t* B, int64_t n, const bf16_t* A_vals, const uint8_t* A_meta, int64_t m,
                               int64_t K, const bf16_t* T, const bf16_t* R, int64_t K2, bf16_t* C, hipStream_t s) {
     if (n <= 16) {
-#ifdef ST_FORCE_BM
-        const bool wide = ST_FORCE_BM == 64;
-#else
-        // One workgroup per compute unit saturates HBM once about 140 of them run, so what costs
-        // time is a last round with few workgroups: take 64 rows per workgroup instead of 32 when
-        // that leaves a fuller last round.
-        auto last_round = [](int64_t blocks) { int64_t r = blocks % RESIDENT; return r == 0 ? RESIDENT : r; };
-        const int64_t b32 = (m + 31) / 32, b64 = (m + 63) / 64;
-        const bool wide = last_round(b32) < 140 && last_round(b64) > last_round(b32) && b32 < 8 * RESIDENT;
-#endif
-        return wide ? launch_stream_lds<4, 4>(B, n, A_vals, A_meta, m, K, T, R, K2, C, s)
-                    : launch_stream_lds<2, 8>(B, n, A_vals, A_meta, m, K, T, R, K2, C, s);
+        // Workgroups of 32, 48 or 64 weight rows (8, 6, 4 wavefronts: what fits in LDS).  One per
+        // compute unit is resident; a round of 256 of them is bound by HBM, a thin last round by
+        // what one workgroup can pull (measured per shape).  Take the shape with the least estimate.
+        const double hbm = 5.8e3, cap[3] = {44.0, 36.0, 29.0};   // bytes per ns: the chip, one workgroup
+        const int rows[3] = {32, 48, 64};
+        int best = 0;
+        double best_t = 1e300;
+        for (int c = 0; c < 3; ++c) {
+            const double bytes = 1.125 * (double)rows[c] * (double)K;
+            const int64_t blocks = (m + rows[c] - 1) / rows[c];
+            const int64_t full = blocks / RESIDENT, rest = blocks % RESIDENT;
+            auto round_ns = [&](int64_t nb) { double a = nb * bytes / hbm, b = bytes / cap[c]; return a > b ? a : b; };
+            const double est = full * round_ns(RESIDENT) + (rest ? round_ns(rest) : 0.0);
+            if (est < best_t) { best_t = est; best = c; }
+        }
+        if (best == 0) return launch_stream_lds<2, 8>(B, n, A_vals, A_meta, m, K, T, R, K2, C, s);
+        if (best == 1) return launch_stream_lds<3, 6>(B, n, A_vals, A_meta, m, K, T, R, K2, C, s);
+        return launch_stream_lds<4, 4>(B, n, A_vals, A_meta, m, K, T, R, K2, C, s);
     }
     dim3 grid((unsigned)((m + ST_BM - 1) / ST_BM)), block(ST_WAVES * 64);
     spmm_stream_kernel<2><<<grid, block, 0, s>>>(B, (int)n, A_vals, A_meta, (int)m, (int)K, T, R, (int)K2, C);
