@@ -34,7 +34,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="opt66b", help="opt66b (headline) | opt13b | opt2.7b | opt125m_fc1")
+    ap.add_argument("--workload", default="opt66b",
+                    help="opt66b (headline) | opt13b | opt2.7b | opt125m_fc1 | opt66b_infer (forward at 1/16/128 tokens)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     return ap.parse_args()
@@ -57,6 +58,8 @@ def main():
     sl.lib()  # fails loudly if libslope.so has not been built
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.workload.endswith("_infer"):
+        return inference(args, torch, sl, inputs, dev)
     spec = inputs.LAYER_SETS[args.workload]
     b, rank = spec["b"], spec["rank"]
 
@@ -263,6 +266,84 @@ def main():
         "speedup_vs_dense": None if dense is None else dense["speedup_with_reprune"],
         "roofline": roofline, "kernels": kernels, "dense_gemm": dense, "cpu_baseline": cpu,
         "per_call_ms": per_call, "optimizer_side": optimizer, "adapter_backward": adapter_bwd,
+    }
+    print(json.dumps(out))
+
+
+def inference(args, torch, sl, inputs, dev):
+    """slope_spmm_fwd with adapters at inference batch sizes (1, 16, 128 tokens) on the fc1, fc2 and one
+    attention projection of the layer set: a pass over the packed weight, reported as the HBM rate of the
+    bytes the call has to move.  One JSON line; value = the rate at 16 tokens over the three layers."""
+    spec = inputs.LAYER_SETS[args.workload[:-len("_infer")]]
+    rank = spec["rank"]
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(inputs.SEED_BASE + 5)
+
+    def gauss(shape, std):
+        return (torch.randn(shape, generator=gen, device=dev, dtype=torch.float32) * std).to(torch.bfloat16)
+
+    picked = {}
+    for name, d_out, d_in in spec["layers"]:
+        picked[(d_out, d_in)] = name                      # one layer per distinct shape
+    cases, tot_bytes, tot_ms, tot_dense_ms = [], {}, {}, {}
+    for (d_out, d_in), name in picked.items():
+        # enough copies of the weight that consecutive calls cannot be served from the 256 MB last-level cache
+        copies = max(1, -(-600 * 2 ** 20 // int(1.125 * d_out * d_in)))
+        packed, dense = [], []
+        for _ in range(copies):
+            W = gauss((d_out, d_in), inputs.STD["W"])
+            vals, meta, _ = sl.slope_prune_rows(W)
+            packed.append((vals, meta))
+            dense.append(W)
+        L = gauss((d_in, rank), inputs.STD["L"]) if rank else None
+        R = gauss((rank, d_out), inputs.STD["R"]) if rank else None
+        for b in (1, 16, 128):
+            X = gauss((b, d_in), inputs.STD["X"])
+            Y = torch.empty((b, d_out), dtype=torch.bfloat16, device=dev)
+            ws = torch.empty(max(256, sl.slope_spmm_fwd_workspace_bytes(b, d_in, d_out, rank)), dtype=torch.uint8,
+                             device=dev) if rank else None
+
+            def ours(i):
+                v, m_ = packed[i % copies]
+                sl.slope_spmm_fwd(X, v, m_, L, R, out=Y, workspace=ws)
+
+            def lib_dense(i):
+                torch.matmul(X, dense[i % copies].t(), out=Y)
+
+            def timed(fn):
+                for i in range(max(2, args.warmup)):
+                    fn(i)
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                n_it = max(10, args.steps)
+                e0.record()
+                for i in range(n_it):
+                    fn(i)
+                e1.record()
+                torch.cuda.synchronize()
+                return e0.elapsed_time(e1) / n_it
+
+            ms, dms = timed(ours), timed(lib_dense)
+            # bytes the call has to move: packed weight, adapter factors, activations in and out
+            nbytes = 1.125 * d_out * d_in + 2.0 * rank * (d_in + d_out) + 2.0 * b * (d_in + d_out)
+            cases.append({"layer": name, "d_out": d_out, "d_in": d_in, "tokens": b, "ms": ms,
+                          "GB/s": nbytes / ms / 1e6, "dense_gemm_ms": dms, "speedup_vs_dense": dms / ms})
+            tot_bytes[b] = tot_bytes.get(b, 0.0) + nbytes
+            tot_ms[b] = tot_ms.get(b, 0.0) + ms
+            tot_dense_ms[b] = tot_dense_ms.get(b, 0.0) + dms
+        del packed, dense
+    value = tot_bytes[16] / tot_ms[16] / 1e6
+    out = {
+        "metric": "HBM rate of the 2:4 sparse linear forward (with adapters) at inference batch size",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": max(10, args.steps), "warmup": max(2, args.warmup),
+        "ms_per_step": tot_ms[16], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s forward at 16 tokens: %s; adapter rank %d; weights rotated past the last-level cache"
+                               % (args.workload, ", ".join("%s %dx%d" % (n, o, i) for (o, i), n in picked.items()), rank)},
+        "roofline": {"bound": "hbm", "achieved": value, "peak": PEAK_HBM, "unit": "GB/s", "frac": value / PEAK_HBM,
+                     "traffic": None, "kernel": "spmm_stream_lds_kernel (+ the split-K X L kernels)"},
+        "speedup_vs_dense": {str(b): tot_dense_ms[b] / tot_ms[b] for b in tot_ms},
+        "cases": cases, "cpu_baseline": None,
     }
     print(json.dumps(out))
 

@@ -29,13 +29,15 @@ hipError_t launch_spmm(const bf16_t* B, int64_t n, const bf16_t* A_vals, const u
 constexpr int64_t STREAM_MAX_TOKENS = 32;
 hipError_t launch_spmm_stream(const bf16_t* B, int64_t n, const bf16_t* A_vals, const uint8_t* A_meta, int64_t m,
                               int64_t K, const bf16_t* T, const bf16_t* R, int64_t K2, bf16_t* C, hipStream_t s);
-// T = X L for n <= 32 tokens, split over d_in with fp32 partial sums in `scratch`
+// T = X L for few tokens (n <= XL_SMALL_MAX_TOKENS), split over d_in with fp32 partial sums in `scratch`
+constexpr int64_t XL_SMALL_MAX_TOKENS = 128;
 size_t xl_small_scratch_bytes(int64_t n, int64_t d_in, int64_t r);
 hipError_t launch_xl_small(const bf16_t* X, int64_t n, int64_t d_in, const bf16_t* L, int64_t r, float* scratch,
                            bf16_t* T, hipStream_t s);
 // T[n, r] = X[n, K] * Lt[r, K]^T (dense), plus transposes of the adapter factors
 hipError_t launch_lowrank_prepare(const bf16_t* X, int64_t n, int64_t d_in, int64_t d_out, const bf16_t* L,
                                   const bf16_t* R, int64_t r, bf16_t* T, bf16_t* Lt, bf16_t* Rt, hipStream_t s);
+hipError_t launch_transpose_factor(const bf16_t* in, int64_t rows, int64_t cols, bf16_t* out, hipStream_t s);
 hipError_t launch_wgrad_masked(const bf16_t* dY, const bf16_t* X, int64_t b, const uint8_t* meta, int64_t d_out,
                                int64_t d_in, bf16_t* gvals, hipStream_t s);
 // same result through token-contiguous copies of dY and X in `workspace`

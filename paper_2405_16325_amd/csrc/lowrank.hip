@@ -26,6 +26,13 @@ __global__ void __launch_bounds__(256) transpose_kernel(const bf16_t* __restrict
 
 }  // namespace
 
+// Rt[cols][rows] = R[rows][cols]^T (the adapter factor made K-contiguous)
+hipError_t launch_transpose_factor(const bf16_t* in, int64_t rows, int64_t cols, bf16_t* out, hipStream_t s) {
+    transpose_kernel<<<dim3((unsigned)((cols + 63) / 64), (unsigned)((rows + 63) / 64)), dim3(256), 0, s>>>(
+        in, (int)rows, (int)cols, out);
+    return hipGetLastError();
+}
+
 hipError_t launch_lowrank_prepare(const bf16_t* X, int64_t n, int64_t d_in, int64_t d_out, const bf16_t* L,
                                   const bf16_t* R, int64_t r, bf16_t* T, bf16_t* Lt, bf16_t* Rt, hipStream_t s) {
     // L[d_in, r] -> Lt[r, d_in];  R[r, d_out] -> Rt[d_out, r]

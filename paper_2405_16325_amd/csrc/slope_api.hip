@@ -55,7 +55,8 @@ static size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
 size_t slope_spmm_fwd_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out, int64_t r) {
     if (r <= 0 || b <= 0 || d_in <= 0 || d_out <= 0) return 0;
     size_t tiles = round256((size_t)b * r * 2) + round256((size_t)d_in * r * 2) + round256((size_t)d_out * r * 2);
-    size_t small = b <= STREAM_MAX_TOKENS ? round256((size_t)b * r * 2) + round256(xl_small_scratch_bytes(b, d_in, r)) : 0;
+    // few tokens: T = X L comes from a split over d_in whose partial sums also live here
+    size_t small = b <= XL_SMALL_MAX_TOKENS ? tiles + round256(xl_small_scratch_bytes(b, d_in, r)) : 0;
     return tiles > small ? tiles : small;
 }
 
@@ -114,6 +115,14 @@ slope_status slope_spmm_fwd(const void* X, int64_t b, const void* Wr_vals, const
                                   nullptr, nullptr, 0, (bf16_t*)Y, s));
     bf16_t* Lt = (bf16_t*)(ws + round256((size_t)b * r * 2));
     bf16_t* Rt = (bf16_t*)((uint8_t*)Lt + round256((size_t)d_in * r * 2));
+    if (b <= XL_SMALL_MAX_TOKENS) {   // too few tokens for the tile kernel to spread X L over the chip
+        float* scratch = (float*)((uint8_t*)Rt + round256((size_t)d_out * r * 2));
+        hipError_t e = launch_xl_small((const bf16_t*)X, b, d_in, (const bf16_t*)L_or_null, r, scratch, T, s);
+        if (e == hipSuccess) e = launch_transpose_factor((const bf16_t*)R_or_null, r, d_out, Rt, s);
+        if (e != hipSuccess) return finish(e);
+        return finish(launch_spmm((const bf16_t*)X, b, (const bf16_t*)Wr_vals, (const uint8_t*)Wr_meta, d_out, d_in,
+                                  T, Rt, r, (bf16_t*)Y, s));
+    }
     hipError_t e = launch_lowrank_prepare((const bf16_t*)X, b, d_in, d_out, (const bf16_t*)L_or_null,
                                           (const bf16_t*)R_or_null, r, T, Lt, Rt, s);
     if (e != hipSuccess) return finish(e);

@@ -391,38 +391,55 @@ hipError_t launch_stream_lds(const bf16_t* B, int64_t n, const bf16_t* Av, const
     return hipGetLastError();
 }
 
-// P[c][t][k] = sum over the rows i of chunk c of X[t][i] * L[i][k]   (fp32; c = blockIdx.x)
+// P[c][t][k] = sum over the rows i of slab c of X[t][i] * L[i][k]   (fp32; c = blockIdx.x, a slab is
+// `subs` chunks of 64 rows; blockIdx.z picks a group of NT tokens)
 // thread = column k of L: its loads of a row of L are contiguous across the wavefront, and all 64
-// rows of the chunk are requested before the first is used; the token values are the same for
-// all lanes and come through scalar loads.
+// rows of a chunk are requested before the first is used; the token values, the same for all
+// lanes, are staged in LDS as fp32 and read back as broadcasts.
 template <int NT>
 __global__ void __launch_bounds__(256) xl_partial_kernel(const bf16_t* __restrict__ X, int n, int d_in,
-                                                         const bf16_t* __restrict__ L, int r,
+                                                         const bf16_t* __restrict__ L, int r, int subs,
                                                          float* __restrict__ P) {
-    const int c = blockIdx.x, i0 = c * XL_CHUNK;             // d_in % 64 == 0: every chunk is full
+    __shared__ __align__(16) float xs[NT][XL_CHUNK];          // the tokens' values of one chunk, as fp32
+    const int c = blockIdx.x, t0 = blockIdx.z * NT;
     const int k = blockIdx.y * 256 + threadIdx.x;
     const int kc = k < r ? k : r - 1;
-    uint16_t lv[XL_CHUNK];
-#pragma unroll
-    for (int i = 0; i < XL_CHUNK; ++i) lv[i] = L[(size_t)(i0 + i) * r + kc];
     float acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = 0.f;
+    for (int sb = 0; sb < subs; ++sb) {
+        const int i0 = (c * subs + sb) * XL_CHUNK;           // d_in % 64 == 0: a chunk is full or absent
+        if (i0 >= d_in) break;                               // uniform
+        uint16_t lv[XL_CHUNK];
 #pragma unroll
-    for (int i = 0; i < XL_CHUNK; i += 2) {
-        float l0 = __uint_as_float((uint32_t)lv[i] << 16), l1 = __uint_as_float((uint32_t)lv[i + 1] << 16);
+        for (int i = 0; i < XL_CHUNK; ++i) lv[i] = L[(size_t)(i0 + i) * r + kc];
+        __syncthreads();                                     // the previous chunk's xs has been read
+        for (int idx = threadIdx.x; idx < NT * XL_CHUNK / 2; idx += 256) {
+            int t = idx / (XL_CHUNK / 2), i2 = idx % (XL_CHUNK / 2);
+            int tt = t0 + t < n ? t0 + t : n - 1;
+            uint32_t w = *(const uint32_t*)(X + (size_t)tt * d_in + i0 + 2 * i2);
+            xs[t][2 * i2] = __uint_as_float(w << 16);
+            xs[t][2 * i2 + 1] = __uint_as_float(w & 0xFFFF0000u);
+        }
+        __syncthreads();
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            int tt = t < n ? t : n - 1;                                        // uniform
-            uint32_t w = *(const uint32_t*)(X + (size_t)tt * d_in + i0 + i);   // uniform address: X[t][i], X[t][i+1]
-            acc[t] = __builtin_fmaf(__uint_as_float(w << 16), l0, acc[t]);
-            acc[t] = __builtin_fmaf(__uint_as_float(w & 0xFFFF0000u), l1, acc[t]);
+        for (int i = 0; i < XL_CHUNK; i += 4) {
+            float l0 = __uint_as_float((uint32_t)lv[i] << 16), l1 = __uint_as_float((uint32_t)lv[i + 1] << 16);
+            float l2 = __uint_as_float((uint32_t)lv[i + 2] << 16), l3 = __uint_as_float((uint32_t)lv[i + 3] << 16);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                f32x4 xv = *(const f32x4*)&xs[t][i];          // same address in every lane: an LDS broadcast
+                acc[t] = __builtin_fmaf(xv[0], l0, acc[t]);
+                acc[t] = __builtin_fmaf(xv[1], l1, acc[t]);
+                acc[t] = __builtin_fmaf(xv[2], l2, acc[t]);
+                acc[t] = __builtin_fmaf(xv[3], l3, acc[t]);
+            }
         }
     }
     if (k < r)
 #pragma unroll
         for (int t = 0; t < NT; ++t)
-            if (t < n) P[((size_t)c * n + t) * r + k] = acc[t];
+            if (t0 + t < n) P[((size_t)c * n + t0 + t) * r + k] = acc[t];
 }
 
 // T[idx] = bf16( sum over chunks of P[c][idx] ), idx = t * r + k, in a fixed order: a workgroup
@@ -487,22 +504,30 @@ hipError_t launch_spmm_stream(const bf16_t* B, int64_t n, const bf16_t* A_vals, 
     return hipGetLastError();
 }
 
-// T = X L for n <= 32 tokens; scratch holds (d_in / 64) * n * r floats
+// T = X L for few tokens (up to 128), split over d_in; scratch holds xl_small_scratch_bytes
+// slabs of L per launch: single chunks of 64 rows for up to 32 tokens, four chunks beyond (the
+// partial sums then stay a few MB)
+static int xl_subs(int64_t n) { return n <= 32 ? 1 : 4; }
+
 size_t xl_small_scratch_bytes(int64_t n, int64_t d_in, int64_t r) {
-    return (size_t)((d_in + XL_CHUNK - 1) / XL_CHUNK) * (size_t)n * (size_t)r * 4;
+    const int64_t rows = (int64_t)XL_CHUNK * xl_subs(n);
+    return (size_t)((d_in + rows - 1) / rows) * (size_t)n * (size_t)r * 4;
 }
 
 hipError_t launch_xl_small(const bf16_t* X, int64_t n, int64_t d_in, const bf16_t* L, int64_t r, float* scratch,
                            bf16_t* T, hipStream_t s) {
-    const int chunks = (int)((d_in + XL_CHUNK - 1) / XL_CHUNK);
-    dim3 grid((unsigned)chunks, (unsigned)((r + 255) / 256));
-    if (n <= 16)
-        xl_partial_kernel<16><<<grid, dim3(256), 0, s>>>(X, (int)n, (int)d_in, L, (int)r, scratch);
-    else
-        xl_partial_kernel<32><<<grid, dim3(256), 0, s>>>(X, (int)n, (int)d_in, L, (int)r, scratch);
+    const int subs = xl_subs(n);
+    const int slabs = (int)((d_in + XL_CHUNK * subs - 1) / (XL_CHUNK * subs));
+    if (n <= 16) {
+        dim3 grid((unsigned)slabs, (unsigned)((r + 255) / 256), 1);
+        xl_partial_kernel<16><<<grid, dim3(256), 0, s>>>(X, (int)n, (int)d_in, L, (int)r, subs, scratch);
+    } else {
+        dim3 grid((unsigned)slabs, (unsigned)((r + 255) / 256), (unsigned)((n + 31) / 32));
+        xl_partial_kernel<32><<<grid, dim3(256), 0, s>>>(X, (int)n, (int)d_in, L, (int)r, subs, scratch);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int count = (int)(n * r);
-    xl_reduce_kernel<<<dim3((unsigned)((count + 31) / 32)), dim3(256), 0, s>>>(scratch, chunks, count, T);
+    xl_reduce_kernel<<<dim3((unsigned)((count + 31) / 32)), dim3(256), 0, s>>>(scratch, slabs, count, T);
     return hipGetLastError();
 }
