@@ -63,8 +63,10 @@ size_t slope_packed_vals_bytes(int64_t rows, int64_t cols);
 size_t slope_packed_meta_bytes(int64_t rows, int64_t cols);
 size_t slope_mask_bytes(int64_t rows, int64_t cols);
 
-/* Scratch that slope_spmm_fwd needs when adapters are active (0 for r == 0):
- * T = X L as bf16[b, r] plus K-contiguous copies of L and R. */
+/* Scratch of slope_spmm_fwd.  Required when adapters are active (T = X L as bf16[b, r],
+ * K-contiguous copies of L and R, partial sums); optional otherwise: for a few dozen to a few
+ * hundred tokens the call, given this many bytes, also splits the contraction over d_in and keeps
+ * fp32 partial sums there, which is much faster at those sizes.  0 = no scratch is of use. */
 size_t slope_spmm_fwd_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out, int64_t r);
 
 /*
@@ -103,7 +105,8 @@ slope_status slope_double_prune(const void* Wr_vals, const void* Wr_meta, int64_
  *       r must be a multiple of 32 and at most 512.
  *   Y   out bf16[b, d_out]; fp32 accumulation; X L is rounded to bf16 before it meets R.
  *   workspace: device scratch of slope_spmm_fwd_workspace_bytes(...) bytes, 256-byte
- *       aligned; may be NULL when no adapter is active.  Contents are undefined after the call.
+ *       aligned; may be NULL when no adapter is active (if given, it must have that many
+ *       bytes all the same).  Contents are undefined after the call.
  */
 slope_status slope_spmm_fwd(const void* X, int64_t b, const void* Wr_vals, const void* Wr_meta,
                             int64_t d_out, int64_t d_in,

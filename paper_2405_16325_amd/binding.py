@@ -134,9 +134,10 @@ def slope_spmm_fwd(X: torch.Tensor, vals: torch.Tensor, meta: torch.Tensor, L=No
     d_out = vals.shape[0]
     r = 0 if L is None else L.shape[1]
     Y = out if out is not None else torch.empty((b, d_out), dtype=torch.bfloat16, device=X.device)
-    if r > 0 and workspace is None:
-        workspace = torch.empty(slope_spmm_fwd_workspace_bytes(b, d_in, d_out, r), dtype=torch.uint8,
-                                device=X.device)
+    if workspace is None:
+        nbytes = slope_spmm_fwd_workspace_bytes(b, d_in, d_out, r)
+        if nbytes > 0:
+            workspace = torch.empty(nbytes, dtype=torch.uint8, device=X.device)
     _check("slope_spmm_fwd", lib().slope_spmm_fwd(_ptr(X), b, _ptr(vals), _ptr(meta), d_out, d_in, _ptr(L), _ptr(R),
                                                   r, _ptr(Y), _ptr(workspace), _stream()))
     return Y

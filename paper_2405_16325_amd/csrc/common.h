@@ -25,6 +25,13 @@ hipError_t launch_sparse_add(const bf16_t* a, const bf16_t* b, size_t count, flo
 // C[n, m] = B[n, K] * Asparse[m, K]^T  (+ B2[n, K2] * A2[m, K2]^T dense when K2 > 0)
 hipError_t launch_spmm(const bf16_t* B, int64_t n, const bf16_t* A_vals, const uint8_t* A_meta, int64_t m,
                        int64_t K, const bf16_t* B2, const bf16_t* A2, int64_t K2, bf16_t* C, hipStream_t s);
+// the same product for a few dozen to a few hundred tokens, split over K with fp32 partial sums in `slabs`
+// (spmm_slab_bytes of them; 0 = this shape does not take the path)
+int spmm_slab_count(int64_t n, int64_t m, int64_t K);
+size_t spmm_slab_bytes(int64_t n, int64_t m, int64_t K);
+hipError_t launch_spmm_slabs(const bf16_t* B, int64_t n, const bf16_t* A_vals, const uint8_t* A_meta, int64_t m,
+                             int64_t K, const bf16_t* B2, const bf16_t* A2, int64_t K2, bf16_t* C, float* slabs,
+                             hipStream_t s);
 // the same product for n <= 32 tokens (any K % 64 == 0); adapters as T[n, K2] and R[K2, m] as stored
 constexpr int64_t STREAM_MAX_TOKENS = 32;
 hipError_t launch_spmm_stream(const bf16_t* B, int64_t n, const bf16_t* A_vals, const uint8_t* A_meta, int64_t m,

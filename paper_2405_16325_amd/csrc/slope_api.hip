@@ -52,12 +52,17 @@ size_t slope_mask_bytes(int64_t rows, int64_t cols) { return slope_packed_meta_b
 
 static size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
 
-size_t slope_spmm_fwd_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out, int64_t r) {
-    if (r <= 0 || b <= 0 || d_in <= 0 || d_out <= 0) return 0;
+// [ T | Lt | Rt | partial sums of X L ] when adapters are active, then the slab buffer of the split over K
+static size_t adapter_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out, int64_t r) {
+    if (r <= 0) return 0;
     size_t tiles = round256((size_t)b * r * 2) + round256((size_t)d_in * r * 2) + round256((size_t)d_out * r * 2);
     // few tokens: T = X L comes from a split over d_in whose partial sums also live here
-    size_t small = b <= XL_SMALL_MAX_TOKENS ? tiles + round256(xl_small_scratch_bytes(b, d_in, r)) : 0;
-    return tiles > small ? tiles : small;
+    return b <= XL_SMALL_MAX_TOKENS ? tiles + round256(xl_small_scratch_bytes(b, d_in, r)) : tiles;
+}
+
+size_t slope_spmm_fwd_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out, int64_t r) {
+    if (b <= 0 || d_in <= 0 || d_out <= 0) return 0;
+    return adapter_workspace_bytes(b, d_in, d_out, r) + round256(spmm_slab_bytes(b, d_out, d_in));
 }
 
 slope_status slope_prune_rows(const void* W, int64_t d_out, int64_t d_in, int n, int m, void* Wr_vals, void* Wr_meta,
@@ -93,41 +98,49 @@ slope_status slope_spmm_fwd(const void* X, int64_t b, const void* Wr_vals, const
     if (adapter) {
         if (!L_or_null || !R_or_null || !workspace) return SLOPE_ERR_NULL;
         if (r % 32 != 0 || r > 512) return SLOPE_ERR_UNSUPPORTED;
-        if (misaligned(L_or_null, 16) || misaligned(R_or_null, 16) || misaligned(workspace, 256)) return SLOPE_ERR_ALIGN;
+        if (misaligned(L_or_null, 16) || misaligned(R_or_null, 16)) return SLOPE_ERR_ALIGN;
     }
-    if (misaligned(X, 16) || misaligned(Wr_vals, 16) || misaligned(Wr_meta, 16) || misaligned(Y, 16))
+    if (misaligned(X, 16) || misaligned(Wr_vals, 16) || misaligned(Wr_meta, 16) || misaligned(Y, 16) ||
+        misaligned(workspace, 256))
         return SLOPE_ERR_ALIGN;
     hipStream_t s = (hipStream_t)stream;
+    const bf16_t* x = (const bf16_t*)X;
+    const bf16_t* wv = (const bf16_t*)Wr_vals;
+    const uint8_t* wm = (const uint8_t*)Wr_meta;
     uint8_t* ws = (uint8_t*)workspace;
     bf16_t* T = (bf16_t*)ws;
     if (b <= STREAM_MAX_TOKENS && d_in >= 128) {   // inference-size batch: one HBM-bound pass over the packed weight
         if (adapter) {
-            hipError_t e = launch_xl_small((const bf16_t*)X, b, d_in, (const bf16_t*)L_or_null, r,
+            hipError_t e = launch_xl_small(x, b, d_in, (const bf16_t*)L_or_null, r,
                                            (float*)(ws + round256((size_t)b * r * 2)), T, s);
             if (e != hipSuccess) return finish(e);
         }
-        return finish(launch_spmm_stream((const bf16_t*)X, b, (const bf16_t*)Wr_vals, (const uint8_t*)Wr_meta, d_out,
-                                         d_in, adapter ? T : nullptr, adapter ? (const bf16_t*)R_or_null : nullptr,
-                                         adapter ? r : 0, (bf16_t*)Y, s));
+        return finish(launch_spmm_stream(x, b, wv, wm, d_out, d_in, adapter ? T : nullptr,
+                                         adapter ? (const bf16_t*)R_or_null : nullptr, adapter ? r : 0, (bf16_t*)Y, s));
     }
-    if (!adapter)
-        return finish(launch_spmm((const bf16_t*)X, b, (const bf16_t*)Wr_vals, (const uint8_t*)Wr_meta, d_out, d_in,
-                                  nullptr, nullptr, 0, (bf16_t*)Y, s));
-    bf16_t* Lt = (bf16_t*)(ws + round256((size_t)b * r * 2));
-    bf16_t* Rt = (bf16_t*)((uint8_t*)Lt + round256((size_t)d_in * r * 2));
-    if (b <= XL_SMALL_MAX_TOKENS) {   // too few tokens for the tile kernel to spread X L over the chip
-        float* scratch = (float*)((uint8_t*)Rt + round256((size_t)d_out * r * 2));
-        hipError_t e = launch_xl_small((const bf16_t*)X, b, d_in, (const bf16_t*)L_or_null, r, scratch, T, s);
-        if (e == hipSuccess) e = launch_transpose_factor((const bf16_t*)R_or_null, r, d_out, Rt, s);
+    // With scratch memory a batch of a few dozen to a few hundred tokens is split over K as well.
+    float* slabs = workspace && spmm_slab_count(b, d_out, d_in) > 0
+                       ? (float*)(ws + adapter_workspace_bytes(b, d_in, d_out, adapter ? r : 0)) : nullptr;
+    const bf16_t* B2 = nullptr;
+    const bf16_t* A2 = nullptr;
+    if (adapter) {
+        bf16_t* Lt = (bf16_t*)(ws + round256((size_t)b * r * 2));
+        bf16_t* Rt = (bf16_t*)((uint8_t*)Lt + round256((size_t)d_in * r * 2));
+        hipError_t e;
+        if (b <= XL_SMALL_MAX_TOKENS) {   // too few tokens for the tile kernel to spread X L over the chip
+            float* scratch = (float*)((uint8_t*)Rt + round256((size_t)d_out * r * 2));
+            e = launch_xl_small(x, b, d_in, (const bf16_t*)L_or_null, r, scratch, T, s);
+            if (e == hipSuccess) e = launch_transpose_factor((const bf16_t*)R_or_null, r, d_out, Rt, s);
+        } else {
+            e = launch_lowrank_prepare(x, b, d_in, d_out, (const bf16_t*)L_or_null, (const bf16_t*)R_or_null, r, T, Lt,
+                                       Rt, s);
+        }
         if (e != hipSuccess) return finish(e);
-        return finish(launch_spmm((const bf16_t*)X, b, (const bf16_t*)Wr_vals, (const uint8_t*)Wr_meta, d_out, d_in,
-                                  T, Rt, r, (bf16_t*)Y, s));
+        B2 = T;
+        A2 = Rt;
     }
-    hipError_t e = launch_lowrank_prepare((const bf16_t*)X, b, d_in, d_out, (const bf16_t*)L_or_null,
-                                          (const bf16_t*)R_or_null, r, T, Lt, Rt, s);
-    if (e != hipSuccess) return finish(e);
-    return finish(launch_spmm((const bf16_t*)X, b, (const bf16_t*)Wr_vals, (const uint8_t*)Wr_meta, d_out, d_in, T,
-                              Rt, r, (bf16_t*)Y, s));
+    if (slabs) return finish(launch_spmm_slabs(x, b, wv, wm, d_out, d_in, B2, A2, adapter ? r : 0, (bf16_t*)Y, slabs, s));
+    return finish(launch_spmm(x, b, wv, wm, d_out, d_in, B2, A2, adapter ? r : 0, (bf16_t*)Y, s));
 }
 
 slope_status slope_spmm_bwd_x(const void* dY, int64_t b, const void* WrcT_vals, const void* WrcT_meta, int64_t d_out,

@@ -41,10 +41,12 @@ namespace {
 //  - dense K-extension: C += B2 * A2^T with v_mfma_f32_16x16x32_bf16, operands straight from
 //    global memory (lane l: row l%16, k = 8*(l/16) .. +7, for A and B alike);
 //  - epilogue: four consecutive features of one token per lane, one 8-byte store.
+//  - with a slab buffer (a split over k, see launch_spmm_slabs): the fp32 accumulators go to
+//    partial[token][feature] instead, 16 bytes per lane, and a reduction kernel finishes.
 template <int MF, int NF>
 __device__ __forceinline__ void extend_and_store(f32x4 (&acc)[MF][NF], int f0, int t0, int m, int n, int l16, int lq,
                                                  const bf16_t* __restrict__ B2, const bf16_t* __restrict__ A2,
-                                                 int K2, bf16_t* __restrict__ C) {
+                                                 int K2, bf16_t* __restrict__ C, float* __restrict__ partial = nullptr) {
     for (int k0 = 0; k0 < K2; k0 += 32) {
         bf16x8 a2[MF], b2[NF];
 #pragma unroll
@@ -78,6 +80,10 @@ __device__ __forceinline__ void extend_and_store(f32x4 (&acc)[MF][NF], int f0, i
             int col = f0 + i * 16 + lq * 4;               // feature
             if (col >= m) continue;
             f32x4 v = acc[i][j];
+            if (partial) {
+                *(f32x4*)(partial + (size_t)row * m + col) = v;
+                continue;
+            }
             union { __bf16 h[4]; u32x2 u; } o;
             o.h[0] = (__bf16)v[0]; o.h[1] = (__bf16)v[1]; o.h[2] = (__bf16)v[2]; o.h[3] = (__bf16)v[3];
             *(u32x2*)(C + (size_t)row * m + col) = o.u;
@@ -104,7 +110,8 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_kernel(const bf16_t* __rest
                                                             const uint8_t* __restrict__ Am, int m, int K,
                                                             const bf16_t* __restrict__ B2,
                                                             const bf16_t* __restrict__ A2, int K2,
-                                                            bf16_t* __restrict__ C, int tiles_m, int tiles_n) {
+                                                            bf16_t* __restrict__ C, int tiles_m, int tiles_n,
+                                                            int slab_steps, float* __restrict__ slabs) {
     using S = SpmmSmem<BM, BN>;
     constexpr int MF = BM / 32, NF = BN / 64;                // 16 x 16 fragments per wavefront
     constexpr int A_LD = BM / 64, B_LD = BN / 64;            // 1 KiB loads per wavefront: per pair, per step
@@ -153,7 +160,15 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_kernel(const bf16_t* __rest
     const int b_rd = S::B_OFF + (wn * NF) * 2048;
     const int m_rd = S::M_OFF + (wm * MF * 16 + l16) * 32 + lq * 2;
 
-    const int ksteps = K / 64;                                // a multiple of 4
+    // A split over k: workgroup row blockIdx.y takes k-steps [k_first, k_first + ksteps) and leaves
+    // fp32 partial sums in its slab; without a slab buffer there is one row and it takes all of K.
+    const int k_first = blockIdx.y * slab_steps;              // a multiple of 4
+    const int ksteps = K / 64 - k_first < slab_steps ? K / 64 - k_first : slab_steps;   // a multiple of 4
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i) a_src[i] += (size_t)k_first * 64;
+#pragma unroll
+    for (int i = 0; i < B_LD; ++i) b_src[i] += (size_t)k_first * 128;
+    m_src += (size_t)k_first * 8;
     auto issue_b = [&](int ks, int stage) {                   // token rows of k-step ks (clamped)
         int kc = ks < ksteps ? ks : ksteps - 1;
 #pragma unroll
@@ -231,7 +246,10 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_kernel(const bf16_t* __rest
 #undef SPMM_STEP
     WAIT_HERE(waitcnt_imm(0, 15));           // drain the clamped look-ahead loads
 
-    extend_and_store<MF, NF>(acc, m0 + wm * MF * 16, n0 + wn * NF * 16, m, n, l16, lq, B2, A2, K2, C);
+    // the dense extension is added once, by the first slab
+    extend_and_store<MF, NF>(acc, m0 + wm * MF * 16, n0 + wn * NF * 16, m, n, l16, lq, B2, A2,
+                             blockIdx.y == 0 ? K2 : 0, C,
+                             slabs ? slabs + (size_t)blockIdx.y * (size_t)n * (size_t)m : nullptr);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -515,16 +533,33 @@ __global__ void __launch_bounds__(256) spmm_generic_kernel(const bf16_t* __restr
 
 template <int BM, int BN>
 hipError_t launch_tile(const bf16_t* B, int64_t n, const bf16_t* Av, const uint8_t* Am, int64_t m, int64_t K,
-                       const bf16_t* B2, const bf16_t* A2, int64_t K2, bf16_t* C, hipStream_t s) {
+                       const bf16_t* B2, const bf16_t* A2, int64_t K2, bf16_t* C, hipStream_t s, int nslabs = 1,
+                       int slab_steps = 0, float* slabs = nullptr) {
     using S = SpmmSmem<BM, BN>;
     static_assert(S::TOTAL <= 160 * 1024, "LDS budget");
     int tiles_m = (int)((m + BM - 1) / BM), tiles_n = (int)((n + BN - 1) / BN);
     auto kern = spmm_kernel<BM, BN>;
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, S::TOTAL);
     if (e != hipSuccess) return e;
-    kern<<<dim3((unsigned)super_grid(tiles_m, tiles_n)), dim3(SPMM_THREADS), S::TOTAL, s>>>(
-        B, (int)n, Av, Am, (int)m, (int)K, B2, A2, (int)K2, C, tiles_m, tiles_n);
+    if (!slabs) { nslabs = 1; slab_steps = (int)(K / 64); }
+    kern<<<dim3((unsigned)super_grid(tiles_m, tiles_n), (unsigned)nslabs), dim3(SPMM_THREADS), S::TOTAL, s>>>(
+        B, (int)n, Av, Am, (int)m, (int)K, B2, A2, (int)K2, C, tiles_m, tiles_n, slab_steps, slabs);
     return hipGetLastError();
+}
+
+// C[idx] = bf16( sum over slabs, in order, of P[s][idx] ), four elements per thread
+__global__ void __launch_bounds__(256) slab_reduce_kernel(const f32x4* __restrict__ P, int nslabs, size_t count4,
+                                                          u32x2* __restrict__ C) {
+    size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= count4) return;
+    f32x4 v = P[idx];
+    for (int sl = 1; sl < nslabs; ++sl) {
+        f32x4 w = P[(size_t)sl * count4 + idx];
+        v[0] += w[0]; v[1] += w[1]; v[2] += w[2]; v[3] += w[3];
+    }
+    union { __bf16 h[4]; u32x2 u; } o;
+    o.h[0] = (__bf16)v[0]; o.h[1] = (__bf16)v[1]; o.h[2] = (__bf16)v[2]; o.h[3] = (__bf16)v[3];
+    C[idx] = o.u;
 }
 
 hipError_t launch_split(const bf16_t* B, int64_t n, const bf16_t* Av, const uint8_t* Am, int64_t m, int64_t K,
@@ -541,6 +576,52 @@ hipError_t launch_split(const bf16_t* B, int64_t n, const bf16_t* Av, const uint
 }
 
 }  // namespace
+
+// A few dozen to a few hundred tokens: the token tile is so narrow that small weight tiles would
+// re-read it from L2 for every few weight rows (the tile kernels run at the L2 -> LDS rate), and
+// tall weight tiles alone are too few to fill the chip.  So: 256-row weight tiles, the k range
+// cut into slabs that run as separate workgroups and leave fp32 partial sums in `slabs`, and a
+// short reduction kernel (fixed order: bit-identical runs) that rounds to bf16.
+constexpr int64_t SLAB_MAX_TOKENS = 256;
+
+int spmm_slab_count(int64_t n, int64_t m, int64_t K) {
+    if (n <= STREAM_MAX_TOKENS || n > SLAB_MAX_TOKENS || K % 256 != 0) return 0;
+    const int64_t tiles = ((m + 255) / 256) * ((n + 127) / 128);
+    const int64_t quads = K / 256;                            // slabs are whole quads of k-steps
+    // Estimate per slab count: the rounds of 256 workgroups, each pulling its share of the packed
+    // weight at what one compute unit sustains with this tile (about 24 B/ns of weight bytes), plus
+    // writing and re-reading the partial sums at HBM speed.  One slab means: not worth it.
+    const double weight = 1.125 * (double)m * (double)K, cu = 24.0, hbm = 5.0e3;   // bytes, bytes per ns
+    int best = 1;
+    double best_ns = 1e300;
+    for (int sl = 1; sl <= 16 && sl * 4 <= quads; ++sl) {
+        const double rounds = (double)((tiles * sl + RESIDENT - 1) / RESIDENT);
+        const double ns = rounds * weight / (double)(tiles * sl) / cu
+                          + (sl > 1 ? 2.0 * sl * (double)n * (double)m * 4.0 / hbm : 0.0);
+        if (ns < best_ns) { best_ns = ns; best = sl; }
+    }
+    return best < 2 ? 0 : best;
+}
+
+size_t spmm_slab_bytes(int64_t n, int64_t m, int64_t K) {
+    return (size_t)spmm_slab_count(n, m, K) * (size_t)n * (size_t)m * 4;
+}
+
+hipError_t launch_spmm_slabs(const bf16_t* B, int64_t n, const bf16_t* A_vals, const uint8_t* A_meta, int64_t m,
+                             int64_t K, const bf16_t* B2, const bf16_t* A2, int64_t K2, bf16_t* C, float* slabs,
+                             hipStream_t s) {
+    const int want = spmm_slab_count(n, m, K);
+    const int64_t quads = K / 256;
+    const int slab_steps = (int)((quads + want - 1) / want) * 4;
+    const int nslabs = (int)((K / 64 + slab_steps - 1) / slab_steps);       // <= want
+    hipError_t e = n <= 64 ? launch_tile<256, 64>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s, nslabs, slab_steps, slabs)
+                           : launch_tile<256, 128>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s, nslabs, slab_steps, slabs);
+    if (e != hipSuccess) return e;
+    const size_t count4 = (size_t)n * (size_t)m / 4;
+    slab_reduce_kernel<<<dim3((unsigned)((count4 + 255) / 256)), dim3(256), 0, s>>>((const f32x4*)slabs, nslabs, count4,
+                                                                                   (u32x2*)C);
+    return hipGetLastError();
+}
 
 hipError_t launch_spmm(const bf16_t* B, int64_t n, const bf16_t* A_vals, const uint8_t* A_meta, int64_t m, int64_t K,
                        const bf16_t* B2, const bf16_t* A2, int64_t K2, bf16_t* C, hipStream_t s) {

@@ -392,27 +392,33 @@ hipError_t launch_stream_lds(const bf16_t* B, int64_t n, const bf16_t* Av, const
 }
 
 // P[c][t][k] = sum over the rows i of slab c of X[t][i] * L[i][k]   (fp32; c = blockIdx.x, a slab is
-// `subs` chunks of 64 rows; blockIdx.z picks a group of NT tokens)
-// thread = column k of L: its loads of a row of L are contiguous across the wavefront, and all 64
-// rows of a chunk are requested before the first is used; the token values, the same for all
-// lanes, are staged in LDS as fp32 and read back as broadcasts.
+// `subs` chunks of 64 rows; blockIdx.y picks 128 columns of L, blockIdx.z a group of NT tokens)
+// A lane owns two columns of L (k and k + 64: its loads of a row are contiguous across the
+// wavefront, and all 64 rows of a chunk are requested before the first is used); the four
+// wavefronts split the NT tokens, whose values, the same for all lanes, are staged in LDS as fp32
+// and read back as broadcasts, each feeding two multiply-adds.
 template <int NT>
 __global__ void __launch_bounds__(256) xl_partial_kernel(const bf16_t* __restrict__ X, int n, int d_in,
                                                          const bf16_t* __restrict__ L, int r, int subs,
                                                          float* __restrict__ P) {
-    __shared__ __align__(16) float xs[NT][XL_CHUNK];          // the tokens' values of one chunk, as fp32
-    const int c = blockIdx.x, t0 = blockIdx.z * NT;
-    const int k = blockIdx.y * 256 + threadIdx.x;
-    const int kc = k < r ? k : r - 1;
-    float acc[NT];
+    constexpr int TW = NT / 4;                                // tokens per wavefront
+    __shared__ __align__(16) float xs[NT][XL_CHUNK];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = blockIdx.x, t0 = blockIdx.z * NT, tw0 = wave * TW;
+    const int k0 = blockIdx.y * 128 + lane, k1 = k0 + 64;
+    const int kc0 = k0 < r ? k0 : r - 1, kc1 = k1 < r ? k1 : r - 1;
+    float acc[TW][2];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) acc[t] = 0.f;
+    for (int t = 0; t < TW; ++t) acc[t][0] = acc[t][1] = 0.f;
     for (int sb = 0; sb < subs; ++sb) {
         const int i0 = (c * subs + sb) * XL_CHUNK;           // d_in % 64 == 0: a chunk is full or absent
         if (i0 >= d_in) break;                               // uniform
-        uint16_t lv[XL_CHUNK];
+        uint16_t la[XL_CHUNK], lb[XL_CHUNK];
 #pragma unroll
-        for (int i = 0; i < XL_CHUNK; ++i) lv[i] = L[(size_t)(i0 + i) * r + kc];
+        for (int i = 0; i < XL_CHUNK; ++i) {
+            la[i] = L[(size_t)(i0 + i) * r + kc0];
+            lb[i] = L[(size_t)(i0 + i) * r + kc1];
+        }
         __syncthreads();                                     // the previous chunk's xs has been read
         for (int idx = threadIdx.x; idx < NT * XL_CHUNK / 2; idx += 256) {
             int t = idx / (XL_CHUNK / 2), i2 = idx % (XL_CHUNK / 2);
@@ -424,22 +430,32 @@ __global__ void __launch_bounds__(256) xl_partial_kernel(const bf16_t* __restric
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < XL_CHUNK; i += 4) {
-            float l0 = __uint_as_float((uint32_t)lv[i] << 16), l1 = __uint_as_float((uint32_t)lv[i + 1] << 16);
-            float l2 = __uint_as_float((uint32_t)lv[i + 2] << 16), l3 = __uint_as_float((uint32_t)lv[i + 3] << 16);
+            float a0 = __uint_as_float((uint32_t)la[i] << 16), a1 = __uint_as_float((uint32_t)la[i + 1] << 16);
+            float a2 = __uint_as_float((uint32_t)la[i + 2] << 16), a3 = __uint_as_float((uint32_t)la[i + 3] << 16);
+            float b0 = __uint_as_float((uint32_t)lb[i] << 16), b1 = __uint_as_float((uint32_t)lb[i + 1] << 16);
+            float b2 = __uint_as_float((uint32_t)lb[i + 2] << 16), b3 = __uint_as_float((uint32_t)lb[i + 3] << 16);
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                f32x4 xv = *(const f32x4*)&xs[t][i];          // same address in every lane: an LDS broadcast
-                acc[t] = __builtin_fmaf(xv[0], l0, acc[t]);
-                acc[t] = __builtin_fmaf(xv[1], l1, acc[t]);
-                acc[t] = __builtin_fmaf(xv[2], l2, acc[t]);
-                acc[t] = __builtin_fmaf(xv[3], l3, acc[t]);
+            for (int t = 0; t < TW; ++t) {
+                f32x4 xv = *(const f32x4*)&xs[tw0 + t][i];    // same address in every lane: an LDS broadcast
+                acc[t][0] = __builtin_fmaf(xv[0], a0, acc[t][0]);
+                acc[t][1] = __builtin_fmaf(xv[0], b0, acc[t][1]);
+                acc[t][0] = __builtin_fmaf(xv[1], a1, acc[t][0]);
+                acc[t][1] = __builtin_fmaf(xv[1], b1, acc[t][1]);
+                acc[t][0] = __builtin_fmaf(xv[2], a2, acc[t][0]);
+                acc[t][1] = __builtin_fmaf(xv[2], b2, acc[t][1]);
+                acc[t][0] = __builtin_fmaf(xv[3], a3, acc[t][0]);
+                acc[t][1] = __builtin_fmaf(xv[3], b3, acc[t][1]);
             }
         }
     }
-    if (k < r)
 #pragma unroll
-        for (int t = 0; t < NT; ++t)
-            if (t0 + t < n) P[((size_t)c * n + t0 + t) * r + k] = acc[t];
+    for (int t = 0; t < TW; ++t) {
+        const int tok = t0 + tw0 + t;
+        if (tok >= n) continue;
+        float* row = P + ((size_t)c * n + tok) * r;
+        if (k0 < r) row[k0] = acc[t][0];
+        if (k1 < r) row[k1] = acc[t][1];
+    }
 }
 
 // T[idx] = bf16( sum over chunks of P[c][idx] ), idx = t * r + k, in a fixed order: a workgroup
@@ -519,10 +535,10 @@ hipError_t launch_xl_small(const bf16_t* X, int64_t n, int64_t d_in, const bf16_
     const int subs = xl_subs(n);
     const int slabs = (int)((d_in + XL_CHUNK * subs - 1) / (XL_CHUNK * subs));
     if (n <= 16) {
-        dim3 grid((unsigned)slabs, (unsigned)((r + 255) / 256), 1);
+        dim3 grid((unsigned)slabs, (unsigned)((r + 127) / 128), 1);
         xl_partial_kernel<16><<<grid, dim3(256), 0, s>>>(X, (int)n, (int)d_in, L, (int)r, subs, scratch);
     } else {
-        dim3 grid((unsigned)slabs, (unsigned)((r + 255) / 256), (unsigned)((n + 31) / 32));
+        dim3 grid((unsigned)slabs, (unsigned)((r + 127) / 128), (unsigned)((n + 31) / 32));
         xl_partial_kernel<32><<<grid, dim3(256), 0, s>>>(X, (int)n, (int)d_in, L, (int)r, subs, scratch);
     }
     hipError_t e = hipGetLastError();
