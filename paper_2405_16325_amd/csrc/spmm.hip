@@ -47,29 +47,42 @@ template <int MF, int NF>
 __device__ __forceinline__ void extend_and_store(f32x4 (&acc)[MF][NF], int f0, int t0, int m, int n, int l16, int lq,
                                                  const bf16_t* __restrict__ B2, const bf16_t* __restrict__ A2,
                                                  int K2, bf16_t* __restrict__ C, float* __restrict__ partial = nullptr) {
-    for (int k0 = 0; k0 < K2; k0 += 32) {
-        bf16x8 a2[MF], b2[NF];
+    if (K2 > 0) {
+        // operands of step k0 + 32 are requested before the MFMAs of step k0 are issued
+        const bf16_t* a_row[MF];
+        const bf16_t* b_row[NF];
 #pragma unroll
         for (int i = 0; i < MF; ++i) {
             int row = f0 + i * 16 + l16;
-            row = row < m ? row : m - 1;
-            AFrag x;
-            x.u = *(const u32x4*)(A2 + (size_t)row * K2 + k0 + lq * 8);
-            a2[i] = x.v;
+            a_row[i] = A2 + (size_t)(row < m ? row : m - 1) * K2 + lq * 8;
         }
 #pragma unroll
         for (int j = 0; j < NF; ++j) {
             int row = t0 + j * 16 + l16;
-            row = row < n ? row : n - 1;
-            AFrag x;
-            x.u = *(const u32x4*)(B2 + (size_t)row * K2 + k0 + lq * 8);
-            b2[j] = x.v;
+            b_row[j] = B2 + (size_t)(row < n ? row : n - 1) * K2 + lq * 8;
         }
+        AFrag a2[2][MF], b2[2][NF];
 #pragma unroll
-        for (int i = 0; i < MF; ++i)
+        for (int i = 0; i < MF; ++i) a2[0][i].u = *(const u32x4*)(a_row[i]);
 #pragma unroll
-            for (int j = 0; j < NF; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2[i], b2[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < NF; ++j) b2[0][j].u = *(const u32x4*)(b_row[j]);
+        for (int k0 = 0; k0 < K2; k0 += 64) {                 // K2 % 32 == 0: two steps per trip, the second maybe absent
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int kk = k0 + 32 * h;                   // uniform
+                if (kk >= K2) break;
+                const int kn = kk + 32 < K2 ? kk + 32 : kk;   // the last step re-reads itself (unused)
+#pragma unroll
+                for (int i = 0; i < MF; ++i) a2[h ^ 1][i].u = *(const u32x4*)(a_row[i] + kn);
+#pragma unroll
+                for (int j = 0; j < NF; ++j) b2[h ^ 1][j].u = *(const u32x4*)(b_row[j] + kn);
+#pragma unroll
+                for (int i = 0; i < MF; ++i)
+#pragma unroll
+                    for (int j = 0; j < NF; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a2[h][i].v, b2[h][j].v, acc[i][j], 0, 0, 0);
+            }
+        }
     }
 #pragma unroll
     for (int j = 0; j < NF; ++j) {
