@@ -100,16 +100,21 @@ constexpr int DP_NPITCH = 36;       // bytes per nibble row [i][og]
 //                 masks, Alg. 1 line 18); only the values of the transposed copy are rewritten.
 //                 A slot that names a position outside W^R's mask reads the zero that the
 //                 decompression left there, so padding stays +0.0.
-template <bool GIVEN>
+template <bool GIVEN, bool MASK>
 __global__ void __launch_bounds__(256) double_prune_kernel(const bf16_t* __restrict__ vals,
                                                            const uint8_t* __restrict__ meta, int d_out, int d_in,
                                                            bf16_t* __restrict__ valsT, uint8_t* __restrict__ metaT,
                                                            uint8_t* __restrict__ maskrc,
                                                            const uint8_t* __restrict__ metaT_in) {
-    __shared__ __align__(16) uint8_t sD[DP_TILE * DP_PITCH];   // decompressed W^R tile [o][i]
-    __shared__ __align__(4) uint8_t sC[DP_TILE * 16];          // candidate bits [o][i/8]
-    __shared__ uint32_t sO[DP_TILE * DP_OPITCH];               // kept value pairs [i][og]
-    __shared__ __align__(4) uint8_t sN[DP_TILE * DP_NPITCH];   // metadata nibbles [i][og]
+    // The input tile (sD, sC) and the output tile (sO, sN) share one buffer: every lane holds its
+    // inputs in registers before the first output is written.  Given metadata (GIVEN) has its own.
+    constexpr int IN_BYTES = DP_TILE * DP_PITCH + DP_TILE * 16, OUT_BYTES = DP_TILE * DP_OPITCH * 4 + DP_TILE * DP_NPITCH;
+    __shared__ __align__(16) uint8_t sbuf[IN_BYTES > OUT_BYTES ? IN_BYTES : OUT_BYTES];
+    __shared__ __align__(4) uint8_t sG[GIVEN ? DP_TILE * DP_NPITCH : 4];
+    uint8_t* const sD = sbuf;                                  // decompressed W^R tile [o][i]
+    uint8_t* const sC = sbuf + DP_TILE * DP_PITCH;             // candidate bits [o][i/8]
+    uint32_t* const sO = (uint32_t*)sbuf;                      // kept value pairs [i][og]
+    uint8_t* const sN = sbuf + DP_TILE * DP_OPITCH * 4;        // metadata nibbles [i][og]
 
     const int t = threadIdx.x;
     const int o0 = blockIdx.y * DP_TILE, i0 = blockIdx.x * DP_TILE;
@@ -149,7 +154,7 @@ __global__ void __launch_bounds__(256) double_prune_kernel(const bf16_t* __restr
         int i = i0 + row, o = o0 + 64 * half;
         uint2 x = make_uint2(0, 0);
         if (i < d_in && o < d_out) x = *(const uint2*)(metaT_in + (size_t)i * ((size_t)d_out / 8) + o / 8);
-        uint8_t* dst = sN + row * DP_NPITCH + 16 * half;
+        uint8_t* dst = sG + row * DP_NPITCH + 16 * half;
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             dst[q] = (uint8_t)((x.x >> (4 * q)) & 0xFu);
@@ -158,30 +163,36 @@ __global__ void __launch_bounds__(256) double_prune_kernel(const bf16_t* __restr
     }
     __syncthreads();
 
-    // phase 2: one lane ranks 8 columns x 4 rows (one group of four along d_out per column)
+    // phase 2: one lane ranks 8 columns x 4 rows (one group of four along d_out per column), twice
+    uint32_t r[2][4][4], cb[2][4];
 #pragma unroll
     for (int n = 0; n < 2; ++n) {
         int u = t + 256 * n, og = u >> 4, i8 = u & 15;
-        uint32_t r[4][4], cb[4], keep[4] = {0, 0, 0, 0};
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             uint4 x = *(const uint4*)(sD + (4 * og + k) * DP_PITCH + 16 * i8);
-            r[k][0] = x.x; r[k][1] = x.y; r[k][2] = x.z; r[k][3] = x.w;
-            cb[k] = sC[(4 * og + k) * 16 + i8];
+            r[n][k][0] = x.x; r[n][k][1] = x.y; r[n][k][2] = x.z; r[n][k][3] = x.w;
+            cb[n][k] = sC[(4 * og + k) * 16 + i8];
         }
+    }
+    __syncthreads();                                           // the input tile is in registers: reuse its memory
+#pragma unroll
+    for (int n = 0; n < 2; ++n) {
+        int u = t + 256 * n, og = u >> 4, i8 = u & 15;
+        uint32_t keep[4] = {0, 0, 0, 0};
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             uint32_t e[4], key[4], cd[4];
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                e[k] = (r[k][j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
-                cd[k] = (cb[k] >> j) & 1u;
+                e[k] = (r[n][k][j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
+                cd[k] = (cb[n][k] >> j) & 1u;
                 key[k] = cd[k] ? (e[k] & 0x7FFFu) + 1u : 0u;   // survivors outrank every pruned slot
             }
             const int col = 8 * i8 + j;
             uint32_t set = 0, nib;
             if (GIVEN) {
-                nib = sN[col * DP_NPITCH + og];
+                nib = sG[col * DP_NPITCH + og];
             } else {
                 set = top2_of_4(key[0], key[1], key[2], key[3]);
                 nib = nibble_of_pair(set);
@@ -191,10 +202,11 @@ __global__ void __launch_bounds__(256) double_prune_kernel(const bf16_t* __restr
             uint32_t v1 = (uint32_t)(q >> (16u * (nib >> 2))) & 0xFFFFu;
             sO[col * DP_OPITCH + og] = v0 | (v1 << 16);
             if (!GIVEN) sN[col * DP_NPITCH + og] = (uint8_t)nib;
+            if (MASK)
 #pragma unroll
-            for (int k = 0; k < 4; ++k) keep[k] |= (((set >> k) & 1u) & cd[k]) << j;
+                for (int k = 0; k < 4; ++k) keep[k] |= (((set >> k) & 1u) & cd[k]) << j;
         }
-        if (!GIVEN && maskrc) {
+        if (MASK) {
             int i = i0 + 8 * i8;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
@@ -234,8 +246,12 @@ __global__ void __launch_bounds__(256) double_prune_kernel(const bf16_t* __restr
 hipError_t launch_double_prune(const bf16_t* vals, const uint8_t* meta, int64_t d_out, int64_t d_in, bf16_t* valsT,
                                uint8_t* metaT, uint8_t* maskrc, hipStream_t s) {
     dim3 grid((unsigned)((d_in + DP_TILE - 1) / DP_TILE), (unsigned)((d_out + DP_TILE - 1) / DP_TILE));
-    double_prune_kernel<false><<<grid, dim3(256), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT, metaT, maskrc,
-                                                          nullptr);
+    if (maskrc)
+        double_prune_kernel<false, true><<<grid, dim3(256), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT, metaT,
+                                                                    maskrc, nullptr);
+    else
+        double_prune_kernel<false, false><<<grid, dim3(256), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT, metaT,
+                                                                     nullptr, nullptr);
     return hipGetLastError();
 }
 
@@ -243,8 +259,8 @@ hipError_t launch_double_prune(const bf16_t* vals, const uint8_t* meta, int64_t 
 hipError_t launch_update_transposed(const bf16_t* vals, const uint8_t* meta, int64_t d_out, int64_t d_in,
                                     const uint8_t* metaT, bf16_t* valsT, hipStream_t s) {
     dim3 grid((unsigned)((d_in + DP_TILE - 1) / DP_TILE), (unsigned)((d_out + DP_TILE - 1) / DP_TILE));
-    double_prune_kernel<true><<<grid, dim3(256), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT, nullptr, nullptr,
-                                                         metaT);
+    double_prune_kernel<true, false><<<grid, dim3(256), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT, nullptr,
+                                                                nullptr, metaT);
     return hipGetLastError();
 }
 
