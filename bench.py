@@ -27,6 +27,9 @@ sys.path.insert(0, ROOT)
 PEAK_DENSE_BF16 = 2500.0     # TFLOP/s, MI355X dense bf16 MFMA
 PEAK_SPARSE_BF16 = 5000.0    # TFLOP/s dense-equivalent, structured-sparse bf16 MFMA
 PEAK_HBM = 8000.0            # GB/s
+# What register-resident loops and plain streams reached on this machine's MI355X (the ceilings a kernel can
+# actually touch): v_smfmac_f32_16x16x64_bf16, v_mfma_f32_32x32x16_bf16, a read-only stream, a copy.
+MEASURED = {"sparse_bf16_tflops": 4390.0, "dense_bf16_tflops": 2390.0, "hbm_read_gbs": 6900.0, "hbm_copy_gbs": 4700.0}
 
 
 def parse():
@@ -263,6 +266,11 @@ def main():
                                (args.workload, ", ".join("%s %dx%d" % (n, o, i) for n, o, i in spec["layers"]),
                                 b, rank)},
         "frac_of_sparse_peak": value / PEAK_SPARSE_BF16,
+        # fwd + dX on the sparse pipe, dW on the dense pipe: the most 3 F can be credited at is 3 / (2 / Ps + 1 / Pd)
+        "frac_of_fwd_bwd_ceiling": {"published": value / (3.0 / (2.0 / PEAK_SPARSE_BF16 + 1.0 / PEAK_DENSE_BF16)),
+                                    "measured": value / (3.0 / (2.0 / MEASURED["sparse_bf16_tflops"]
+                                                                + 1.0 / MEASURED["dense_bf16_tflops"]))},
+        "measured_ceilings": MEASURED,
         "speedup_vs_dense": None if dense is None else dense["speedup_with_reprune"],
         "roofline": roofline, "kernels": kernels, "dense_gemm": dense, "cpu_baseline": cpu,
         "per_call_ms": per_call, "optimizer_side": optimizer, "adapter_backward": adapter_bwd,

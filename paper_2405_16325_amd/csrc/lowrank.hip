@@ -3,7 +3,9 @@
 // The paper concatenates L to the sparse weight so that one vendor SpMM call yields [Y1 | Y2] and
 // a second fused GEMM adds Y2 R.  Here the sparse kernel's main loop is simply extended by r more
 // k-steps on dense MFMA (operands T and R^T), so only the skinny product T = X L is a kernel of
-// its own (the dense tile kernel with a plain epilogue); it is bound by reading X once.
+// its own (the dense tile kernel with a plain epilogue); it is bound by reading X once.  With few
+// tokens (up to 128) that kernel cannot spread over the chip and the split over d_in in
+// spmm_stream.hip computes T instead; only the copy of R is made here then.
 #include "common.h"
 
 namespace {

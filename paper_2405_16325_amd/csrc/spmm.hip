@@ -15,8 +15,9 @@
 // so the sparse operand is the weight, rows of D are output features, and a lane's four
 // accumulators are four consecutive features of one token: an 8-byte store into row-major C.
 //
-// Two kernels.  spmm_kernel is the fast one and needs K % 256 == 0; spmm_generic_kernel takes any
-// K % 64 == 0 with a plain register-staged pipeline.
+// Three kernels here (launch_spmm picks; the forms for very few tokens are in spmm_stream.hip):
+// spmm_kernel<BM, BN> and spmm_split_kernel (the 256 x 256 tile) are the fast ones and need
+// K % 256 == 0; spmm_generic_kernel takes any K % 64 == 0 with a plain register-staged pipeline.
 //
 // spmm_kernel.  What bounds it on MI355X is the rate at which a compute unit can pull operands
 // from L2 (about one cache-line request per 2 clocks, 64 B/clk at best), not the matrix pipe, so
