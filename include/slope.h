@@ -170,6 +170,34 @@ slope_status slope_wgrad_adapter(const void* dY, const void* X, int64_t b, const
                                  void* dR, void* workspace, void* stream);
 
 /*
+ * slope_prune_mask - magnitude N:M pruning for the patterns that have no sparse MFMA (Sec. 2.1:
+ * any N:M, e.g. the 1:2 and 2:8 of Lemma 2.1), as a bit mask plus masked dense weights; the
+ * products then run on dense MFMA (slope_gemm_tn).  Same magnitude order and tie rule as
+ * slope_prune_rows.
+ *   W     in   bf16[rows, cols]            cols % 8 == 0
+ *   n, m       keep n of every m; m in {2, 4, 8}, 1 <= n <= m (others: SLOPE_ERR_UNSUPPORTED)
+ *   axis       0: groups of m consecutive elements inside a row (the row prune, W^R)
+ *              1: groups inside a column (the second prune of W^{R,C}); rows % m == 0
+ *   candidates_or_null in u8[rows, cols/8]  bit mask; only set positions compete and can be kept
+ *              (double pruning: pass the mask of the first prune); NULL = all positions
+ *   mask_out   out u8[rows, cols/8]         kept positions
+ *   masked_out_or_null    out bf16[rows, cols]   W where kept, +0.0 elsewhere
+ *   masked_t_out_or_null  out bf16[cols, rows]   the transpose of the same (the backward operand)
+ */
+slope_status slope_prune_mask(const void* W, int64_t rows, int64_t cols, int n, int m, int axis,
+                              const void* candidates_or_null, void* mask_out, void* masked_out_or_null,
+                              void* masked_t_out_or_null, void* stream);
+
+/*
+ * slope_gemm_tn - C = B A^T on dense MFMA: the forward (Eq. 1 with a masked weight: B = X,
+ * A = masked W) and input-gradient (Eq. 3: B = dY, A = transposed masked W) products of the
+ * emulated patterns.
+ *   B  in  bf16[n, K]    A  in  bf16[m, K]    C  out bf16[n, m]; fp32 accumulation
+ *   K % 64 == 0, m % 4 == 0, any n >= 1
+ */
+slope_status slope_gemm_tn(const void* B, int64_t n, const void* A, int64_t m, int64_t K, void* C, void* stream);
+
+/*
  * slope_sparse_add - out = beta * A + gamma * B on the packed values of two matrices that share
  * one sparsity pattern (App. K, sparse matrix addition).  Algorithm 1 line 15 is the case
  * A = packed masked gradient, beta = 1 / gradient scale, B = packed W^R, gamma = weight decay.

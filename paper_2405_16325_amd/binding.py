@@ -42,6 +42,8 @@ SIGNATURES = {
     "slope_spmm_bwd_x_adapter": (_INT, [_P, _I64, _P, _P, _I64, _I64, _P, _P, _I64, _P, _P, _P]),
     "slope_wgrad_adapter_workspace_bytes": (_SZ, [_I64, _I64, _I64, _I64]),
     "slope_wgrad_adapter": (_INT, [_P, _P, _I64, _P, _I64, _I64, _P, _P, _I64, _P, _P, _P, _P, _P]),
+    "slope_prune_mask": (_INT, [_P, _I64, _I64, _INT, _INT, _INT, _P, _P, _P, _P, _P]),
+    "slope_gemm_tn": (_INT, [_P, _I64, _P, _I64, _I64, _P, _P]),
     "slope_sparse_add": (_INT, [_P, _P, _I64, _I64, ctypes.c_float, ctypes.c_float, _P, _P]),
     "slope_update_sparse": (_INT, [_P, _P, _I64, _I64, _P, _P, _P, _P]),
 }
@@ -208,6 +210,29 @@ def slope_wgrad_adapter(dY, X, meta, L, R, out=None, workspace=None):
            lib().slope_wgrad_adapter(_ptr(dY), _ptr(X), b, _ptr(meta), d_out, d_in, _ptr(L), _ptr(R), r, _ptr(G),
                                      _ptr(dL), _ptr(dR), _ptr(workspace), _stream()))
     return G, dL, dR
+
+
+def slope_prune_mask(W: torch.Tensor, n: int, m: int, axis: int = 0, candidates=None, masked=True, masked_t=False):
+    """General N:M magnitude mask (m in 2, 4, 8) of W bf16[rows, cols]; returns (mask u8[rows, cols/8],
+    masked W or None, transposed masked W or None)."""
+    _dev(W, candidates)
+    rows, cols = W.shape
+    mask = torch.empty((rows, cols // 8), dtype=torch.uint8, device=W.device)
+    wm = torch.empty_like(W) if masked else None
+    wt = torch.empty((cols, rows), dtype=torch.bfloat16, device=W.device) if masked_t else None
+    _check("slope_prune_mask", lib().slope_prune_mask(_ptr(W), rows, cols, n, m, axis, _ptr(candidates), _ptr(mask),
+                                                      _ptr(wm), _ptr(wt), _stream()))
+    return mask, wm, wt
+
+
+def slope_gemm_tn(B: torch.Tensor, A: torch.Tensor, out=None):
+    """C[n, m] = B[n, K] A[m, K]^T (dense bf16, fp32 accumulation)."""
+    _dev(B, A)
+    n, K = B.shape
+    m = A.shape[0]
+    C = out if out is not None else torch.empty((n, m), dtype=torch.bfloat16, device=B.device)
+    _check("slope_gemm_tn", lib().slope_gemm_tn(_ptr(B), n, _ptr(A), m, K, _ptr(C), _stream()))
+    return C
 
 
 def slope_sparse_add(A_vals: torch.Tensor, B_vals: torch.Tensor, beta: float, gamma: float, out=None):

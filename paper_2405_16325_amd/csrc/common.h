@@ -55,6 +55,11 @@ hipError_t launch_wgrad_masked_ws(const bf16_t* dY, const bf16_t* X, int64_t b, 
 // C[n, m] = B[n, K] * A[m, K]^T (dense bf16, fp32 accumulation), K % 64 == 0
 hipError_t launch_dense_tn_plain(const bf16_t* B, int64_t n, const bf16_t* A, int64_t m, int64_t K, bf16_t* C,
                                  hipStream_t s);
+hipError_t launch_dense_tn_any(const bf16_t* B, int64_t n, const bf16_t* A, int64_t m, int64_t K, bf16_t* C,
+                               hipStream_t s);
+// general N:M magnitude mask (M in {2, 4, 8}); axis 0: groups inside a row, axis 1: inside a column
+hipError_t launch_nm_mask(const bf16_t* W, int64_t rows, int64_t cols, int n, int m, int axis, const uint8_t* cand,
+                          uint8_t* mask, bf16_t* masked, bf16_t* masked_t, hipStream_t s);
 // dW (packed) + dL + dR of a layer with adapters, sharing the token-contiguous copies
 size_t wgrad_adapter_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out, int64_t r);
 hipError_t launch_wgrad_adapter(const bf16_t* dY, const bf16_t* X, int64_t b, const uint8_t* meta, int64_t d_out,

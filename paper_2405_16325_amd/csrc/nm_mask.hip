@@ -1,0 +1,133 @@
+// General N:M magnitude masks (Sec. 2.1; the paper's other patterns, e.g. 1:2 and 2:8 of Lemma 2.1)
+// for M in {2, 4, 8} and any 1 <= N <= M.  Only 2:4 has a sparse MFMA, so these patterns run as
+// masked dense weights ("emulation"): the kernels here emit the bit mask, the masked weight and,
+// for the backward operand, its transpose; the products are plain dense tile kernels.
+//
+// Order inside a group: magnitude (bf16 bits with the sign cleared) descending, index ascending;
+// positions outside the optional candidate mask never win and never count (double pruning:
+// groups along the other axis, candidates = the first mask).
+#include "common.h"
+
+namespace {
+
+// keep bits of one group: score[i] = candidate ? magnitude + 1 : 0
+template <int M>
+__device__ __forceinline__ uint32_t keep_of_group(const uint32_t (&score)[M], int n) {
+    uint32_t keep = 0;
+#pragma unroll
+    for (int i = 0; i < M; ++i) {
+        uint32_t rank = 0;
+#pragma unroll
+        for (int j = 0; j < M; ++j)
+            if (j != i) rank += (score[j] > score[i]) || (score[j] == score[i] && j < i);
+        keep |= (uint32_t)(score[i] != 0u && rank < (uint32_t)n) << i;
+    }
+    return keep;
+}
+
+__device__ __forceinline__ uint32_t half_of(const u32x4& v, int e) { return (v[e >> 1] >> (16 * (e & 1))) & 0xFFFFu; }
+
+// groups of M consecutive elements inside a row; one lane = 8 consecutive elements of a row
+template <int M>
+__global__ void __launch_bounds__(256) nm_mask_rows_kernel(const u32x4* __restrict__ W, size_t chunks, int rows,
+                                                           int cols, int n, const uint8_t* __restrict__ cand,
+                                                           uint8_t* __restrict__ mask, u32x4* __restrict__ masked,
+                                                           bf16_t* __restrict__ masked_t) {
+    for (size_t c = (size_t)blockIdx.x * 256 + threadIdx.x; c < chunks; c += (size_t)gridDim.x * 256) {
+        const u32x4 v = W[c];
+        const uint32_t cb = cand ? cand[c] : 0xFFu;
+        uint32_t keep = 0;
+#pragma unroll
+        for (int g = 0; g < 8 / M; ++g) {
+            uint32_t score[M];
+#pragma unroll
+            for (int i = 0; i < M; ++i) {
+                int e = g * M + i;
+                score[i] = ((cb >> e) & 1u) ? (half_of(v, e) & 0x7FFFu) + 1u : 0u;
+            }
+            keep |= keep_of_group<M>(score, n) << (g * M);
+        }
+        mask[c] = (uint8_t)keep;
+        u32x4 out;
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+            out[w] = (((keep >> (2 * w)) & 1u) ? (v[w] & 0xFFFFu) : 0u) | (((keep >> (2 * w + 1)) & 1u) ? (v[w] & 0xFFFF0000u) : 0u);
+        if (masked) masked[c] = out;
+        if (masked_t) {
+            const size_t row = c / (size_t)(cols / 8), col0 = (c % (size_t)(cols / 8)) * 8;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) masked_t[(col0 + e) * (size_t)rows + row] = (bf16_t)half_of(out, e);
+        }
+    }
+}
+
+// groups of M consecutive elements inside a column; one lane = 8 consecutive columns x the M rows of a group
+template <int M>
+__global__ void __launch_bounds__(256) nm_mask_cols_kernel(const bf16_t* __restrict__ W, size_t units, int rows,
+                                                           int cols, int n, const uint8_t* __restrict__ cand,
+                                                           uint8_t* __restrict__ mask, bf16_t* __restrict__ masked,
+                                                           bf16_t* __restrict__ masked_t) {
+    const size_t cpr = (size_t)cols / 8;                      // 8-column chunks per row
+    for (size_t u = (size_t)blockIdx.x * 256 + threadIdx.x; u < units; u += (size_t)gridDim.x * 256) {
+        const size_t rg = u / cpr, cc = u % cpr, row0 = rg * M;
+        u32x4 v[M];
+        uint32_t cb[M], keep[M];
+#pragma unroll
+        for (int k = 0; k < M; ++k) {
+            v[k] = *(const u32x4*)(W + (row0 + k) * (size_t)cols + cc * 8);
+            cb[k] = cand ? cand[(row0 + k) * cpr + cc] : 0xFFu;
+            keep[k] = 0;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            uint32_t score[M];
+#pragma unroll
+            for (int k = 0; k < M; ++k) score[k] = ((cb[k] >> e) & 1u) ? (half_of(v[k], e) & 0x7FFFu) + 1u : 0u;
+            const uint32_t kg = keep_of_group<M>(score, n);
+#pragma unroll
+            for (int k = 0; k < M; ++k) keep[k] |= ((kg >> k) & 1u) << e;
+        }
+#pragma unroll
+        for (int k = 0; k < M; ++k) {
+            mask[(row0 + k) * cpr + cc] = (uint8_t)keep[k];
+            u32x4 out;
+#pragma unroll
+            for (int w = 0; w < 4; ++w)
+                out[w] = (((keep[k] >> (2 * w)) & 1u) ? (v[k][w] & 0xFFFFu) : 0u) |
+                         (((keep[k] >> (2 * w + 1)) & 1u) ? (v[k][w] & 0xFFFF0000u) : 0u);
+            v[k] = out;
+            if (masked) *(u32x4*)(masked + (row0 + k) * (size_t)cols + cc * 8) = out;
+        }
+        if (masked_t) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+#pragma unroll
+                for (int k = 0; k < M; ++k) masked_t[(cc * 8 + e) * (size_t)rows + row0 + k] = (bf16_t)half_of(v[k], e);
+        }
+    }
+}
+
+template <int M>
+hipError_t launch_m(const bf16_t* W, int64_t rows, int64_t cols, int n, int axis, const uint8_t* cand, uint8_t* mask,
+                    bf16_t* masked, bf16_t* masked_t, hipStream_t s) {
+    const size_t units = axis == 0 ? (size_t)rows * (size_t)(cols / 8) : (size_t)(rows / M) * (size_t)(cols / 8);
+    size_t blocks = (units + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    if (blocks == 0) blocks = 1;
+    if (axis == 0)
+        nm_mask_rows_kernel<M><<<dim3((unsigned)blocks), dim3(256), 0, s>>>((const u32x4*)W, units, (int)rows, (int)cols, n,
+                                                                          cand, mask, (u32x4*)masked, masked_t);
+    else
+        nm_mask_cols_kernel<M><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(W, units, (int)rows, (int)cols, n, cand, mask,
+                                                                          masked, masked_t);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_nm_mask(const bf16_t* W, int64_t rows, int64_t cols, int n, int m, int axis, const uint8_t* cand,
+                          uint8_t* mask, bf16_t* masked, bf16_t* masked_t, hipStream_t s) {
+    if (m == 2) return launch_m<2>(W, rows, cols, n, axis, cand, mask, masked, masked_t, s);
+    if (m == 4) return launch_m<4>(W, rows, cols, n, axis, cand, mask, masked, masked_t, s);
+    return launch_m<8>(W, rows, cols, n, axis, cand, mask, masked, masked_t, s);
+}

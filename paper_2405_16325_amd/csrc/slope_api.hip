@@ -222,6 +222,26 @@ slope_status slope_wgrad_adapter(const void* dY, const void* X, int64_t b, const
                                        (bf16_t*)dR, workspace, (hipStream_t)stream));
 }
 
+slope_status slope_prune_mask(const void* W, int64_t rows, int64_t cols, int n, int m, int axis,
+                              const void* candidates_or_null, void* mask_out, void* masked_out_or_null,
+                              void* masked_t_out_or_null, void* stream) {
+    if (!W || !mask_out) return SLOPE_ERR_NULL;
+    if ((m != 2 && m != 4 && m != 8) || n < 1 || n > m || (axis != 0 && axis != 1)) return SLOPE_ERR_UNSUPPORTED;
+    if (bad_extent(rows, axis == 1 ? m : 1) || bad_extent(cols, 8)) return SLOPE_ERR_SHAPE;
+    if (misaligned(W, 16) || misaligned(masked_out_or_null, 16) || misaligned(masked_t_out_or_null, 16))
+        return SLOPE_ERR_ALIGN;
+    return finish(launch_nm_mask((const bf16_t*)W, rows, cols, n, m, axis, (const uint8_t*)candidates_or_null,
+                                 (uint8_t*)mask_out, (bf16_t*)masked_out_or_null, (bf16_t*)masked_t_out_or_null,
+                                 (hipStream_t)stream));
+}
+
+slope_status slope_gemm_tn(const void* B, int64_t n, const void* A, int64_t m, int64_t K, void* C, void* stream) {
+    if (!B || !A || !C) return SLOPE_ERR_NULL;
+    if (bad_extent(n, 1) || bad_extent(m, 4) || bad_extent(K, 64)) return SLOPE_ERR_SHAPE;
+    if (misaligned(B, 16) || misaligned(A, 16) || misaligned(C, 16)) return SLOPE_ERR_ALIGN;
+    return finish(launch_dense_tn_any((const bf16_t*)B, n, (const bf16_t*)A, m, K, (bf16_t*)C, (hipStream_t)stream));
+}
+
 slope_status slope_sparse_add(const void* A_vals, const void* B_vals, int64_t rows, int64_t cols, float beta,
                               float gamma, void* out_vals, void* stream) {
     if (!A_vals || !B_vals || !out_vals) return SLOPE_ERR_NULL;

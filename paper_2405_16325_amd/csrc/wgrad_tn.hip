@@ -434,6 +434,26 @@ hipError_t launch_dense_tn_plain(const bf16_t* B, int64_t n, const bf16_t* A, in
     return launch_dense_tn<128, 64, EPI_PLAIN, 6>(A, m, B, n, K, nullptr, C, s);
 }
 
+// The same product for any shape (dense weights with a general N:M mask, where no sparse MFMA
+// applies): tile by the rounds x operand-rows estimate of the other tile kernels.
+hipError_t launch_dense_tn_any(const bf16_t* B, int64_t n, const bf16_t* A, int64_t m, int64_t K, bf16_t* C,
+                               hipStream_t s) {
+    const int bms[4] = {256, 256, 128, 128}, bns[4] = {256, 128, 128, 64};
+    int best = 0;
+    int64_t best_cost = INT64_MAX;
+    for (int c = 0; c < 4; ++c) {
+        int64_t tiles = ((m + bms[c] - 1) / bms[c]) * ((n + bns[c] - 1) / bns[c]);
+        int64_t cost = ((tiles + RESIDENT - 1) / RESIDENT) * (bms[c] + bns[c]);
+        if (cost < best_cost) { best_cost = cost; best = c; }
+    }
+    switch (best) {
+        case 0: return launch_dense_tn<256, 256, EPI_PLAIN, 2>(A, m, B, n, K, nullptr, C, s);
+        case 1: return launch_dense_tn<256, 128, EPI_PLAIN, 3>(A, m, B, n, K, nullptr, C, s);
+        case 2: return launch_dense_tn<128, 128, EPI_PLAIN, 4>(A, m, B, n, K, nullptr, C, s);
+        default: return launch_dense_tn<128, 64, EPI_PLAIN, 6>(A, m, B, n, K, nullptr, C, s);
+    }
+}
+
 // ------------------------------------------------------------------------------------------
 // Weight gradient of a layer with adapters: the packed dW as above plus the adapter gradients
 // (chain rule of Eq. 11)   dL = X^T (dY R^T)  [d_in, r],   dR = (X L)^T dY  [r, d_out],

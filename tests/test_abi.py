@@ -67,6 +67,13 @@ def test_argument_errors_are_reported_before_launch():
     assert lib.slope_wgrad_adapter(p, p, 8, p, 64, 72, p, p, 32, p, p, p, p, None) == binding.SLOPE_ERR_SHAPE
     assert lib.slope_wgrad_adapter(p, p, 8, p, 64, 64, p, p, 1024, p, p, p, p, None) == binding.SLOPE_ERR_UNSUPPORTED
     assert lib.slope_wgrad_adapter_workspace_bytes(100, 64, 128, 32) > lib.slope_wgrad_workspace_bytes(100, 64, 128)
+    assert lib.slope_prune_mask(p, 8, 64, 1, 3, 0, None, p, None, None, None) == binding.SLOPE_ERR_UNSUPPORTED
+    assert lib.slope_prune_mask(p, 8, 64, 5, 4, 0, None, p, None, None, None) == binding.SLOPE_ERR_UNSUPPORTED
+    assert lib.slope_prune_mask(p, 6, 64, 2, 4, 1, None, p, None, None, None) == binding.SLOPE_ERR_SHAPE
+    assert lib.slope_prune_mask(p, 8, 60, 2, 4, 0, None, p, None, None, None) == binding.SLOPE_ERR_SHAPE
+    assert lib.slope_prune_mask(p, 8, 64, 2, 4, 0, None, None, None, None, None) == binding.SLOPE_ERR_NULL
+    assert lib.slope_gemm_tn(p, 8, p, 64, 100, p, None) == binding.SLOPE_ERR_SHAPE
+    assert lib.slope_gemm_tn(p, 8, None, 64, 128, p, None) == binding.SLOPE_ERR_NULL
     assert lib.slope_sparse_add(p, None, 4, 64, 1.0, 1.0, p, None) == binding.SLOPE_ERR_NULL
     assert lib.slope_sparse_add(p, p, 4, 24, 1.0, 1.0, p, None) == binding.SLOPE_ERR_SHAPE
     assert lib.slope_sparse_add(p, p, 4, 64, 1.0, 1.0, odd, None) == binding.SLOPE_ERR_ALIGN
