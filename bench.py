@@ -41,6 +41,8 @@ def parse():
                     help="opt66b (headline) | opt13b | opt2.7b | opt125m_fc1 | opt66b_infer (forward at 1/16/128 tokens)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the step (and the dense comparison) replayed from a captured HIP graph")
     return ap.parse_args()
 
 
@@ -133,6 +135,27 @@ def main():
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
+    def graph_ms(fn):
+        """fn captured into a HIP graph on a side stream and replayed args.steps times (ms per replay)."""
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            fn()
+            side.synchronize()
+            with torch.cuda.graph(g, stream=side):
+                fn()
+        torch.cuda.current_stream().wait_stream(side)
+        g.replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for _ in range(args.steps):
+            g.replay()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - g0) * 1e3 / args.steps
+
+    graph = {"ms_per_step": graph_ms(step)} if args.graph else None
+
     flops_layer = [2.0 * b * l["d_in"] * l["d_out"] for l in layers]
     total_flops = 3.0 * sum(flops_layer)
     value = total_flops / (ms_per_step * 1e-3) / 1e12
@@ -200,6 +223,9 @@ def main():
             dense_step()
         torch.cuda.synchronize()
         dense_ms = (time.perf_counter() - d0) * 1e3 / nd
+        if graph is not None:
+            graph["dense_ms_per_step"] = graph_ms(dense_step)
+            graph["speedup_vs_dense"] = graph["dense_ms_per_step"] / graph["ms_per_step"]
         gemm_ms = per_call["spmm_fwd"] + per_call["spmm_bwd_x"] + per_call["wgrad_masked"]
         dense = {"ms_per_step": dense_ms, "tflops": total_flops / (dense_ms * 1e-3) / 1e12,
                  "speedup_products_only": dense_ms / gemm_ms, "speedup_with_reprune": dense_ms / ms_per_step,
@@ -273,7 +299,7 @@ def main():
         "measured_ceilings": MEASURED,
         "speedup_vs_dense": None if dense is None else dense["speedup_with_reprune"],
         "roofline": roofline, "kernels": kernels, "dense_gemm": dense, "cpu_baseline": cpu,
-        "per_call_ms": per_call, "optimizer_side": optimizer, "adapter_backward": adapter_bwd,
+        "per_call_ms": per_call, "hip_graph": graph, "optimizer_side": optimizer, "adapter_backward": adapter_bwd,
     }
     print(json.dumps(out))
 

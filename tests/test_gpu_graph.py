@@ -1,0 +1,62 @@
+"""The hot path under HIP graph capture: one captured step, replayed several times with eager work and
+synchronisations in between, must reproduce the eager results bit for bit on every replay (the library
+allocates nothing, keeps no state and launches only kernels, so a captured step is just its launches)."""
+import pytest
+import torch
+
+from paper_2405_16325_amd import binding as sl
+from paper_2405_16325_amd import inputs
+from tests.test_gpu_parity import dev, host, say
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("b,d_out,d_in,r", [(2048, 3072, 768, 64), (16, 512, 768, 64), (100, 768, 4096, 0)])
+def test_captured_step_replays_bit_identically(b, d_out, d_in, r):
+    say(f"graph b={b} d_out={d_out} d_in={d_in} r={r}")
+    t = inputs.layer_inputs(b, d_out, d_in, max(r, 32), seed=3)
+    d = {k: dev(v) for k, v in t.items()}
+    L, R = (d["L"][:, :r].contiguous(), d["R"][:r].contiguous()) if r else (None, None)
+    vals = torch.empty((d_out, d_in // 2), dtype=torch.bfloat16, device="cuda")
+    meta = torch.empty((d_out, d_in // 8), dtype=torch.uint8, device="cuda")
+    vals_t = torch.empty((d_in, d_out // 2), dtype=torch.bfloat16, device="cuda")
+    meta_t = torch.empty((d_in, d_out // 8), dtype=torch.uint8, device="cuda")
+    Y = torch.empty((b, d_out), dtype=torch.bfloat16, device="cuda")
+    dX = torch.empty((b, d_in), dtype=torch.bfloat16, device="cuda")
+    G = torch.empty((d_out, d_in // 2), dtype=torch.bfloat16, device="cuda")
+    ws_f = torch.empty(max(256, sl.slope_spmm_fwd_workspace_bytes(b, d_in, d_out, r)), dtype=torch.uint8, device="cuda")
+    ws_g = torch.empty(sl.slope_wgrad_workspace_bytes(b, d_in, d_out), dtype=torch.uint8, device="cuda")
+
+    def step():
+        sl.slope_prune_rows(d["W"], out=(vals, meta, None))
+        sl.slope_double_prune(vals, meta, out=(vals_t, meta_t, None))
+        sl.slope_spmm_fwd(d["X"], vals, meta, L, R, out=Y, workspace=ws_f)
+        sl.slope_spmm_bwd_x(d["dY"], vals_t, meta_t, out=dX)
+        sl.slope_wgrad_masked(d["dY"], d["X"], meta, out=G, workspace=ws_g)
+
+    step()
+    torch.cuda.synchronize()
+    want = [host(x).copy() for x in (vals, vals_t, Y, dX, G)] + [meta.cpu().numpy().copy(), meta_t.cpu().numpy().copy()]
+
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                             # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+
+    for replay in range(3):
+        for x in (vals, vals_t, Y, dX, G):
+            x.fill_(float("nan"))                          # eager work between the replays
+        meta.zero_()
+        meta_t.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [host(x) for x in (vals, vals_t, Y, dX, G)] + [meta.cpu().numpy(), meta_t.cpu().numpy()]
+        for g_, w_ in zip(got, want):
+            assert (g_ == w_).all(), f"replay {replay}"
