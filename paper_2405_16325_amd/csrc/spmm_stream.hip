@@ -2,236 +2,50 @@
 //     C[n, m] = sum_k B[n, k] * A[m, k]   (+ T[n, K2] * R[K2, m] for the adapters of Eq. 11)
 // With so few tokens the product is one pass over the packed weight (1.125 bytes per element) and
 // HBM bounds it, so the kernel is built to keep reads in flight rather than to share operands:
-//   - a workgroup owns 32 weight rows and all tokens; its 8 wavefronts take the k-steps of 64 in
-//     turn (wavefront w: the pairs of steps w, w + 8, ...), each accumulating a partial 32 x n tile, so even a
-//     9216-row weight gives 288 workgroups and every row of the weight is read in 128-byte pieces
-//     by neighbouring wavefronts at about the same time;
-//   - operands go from global memory into registers, several steps ahead, four lanes per row
-//     segment of 64 bytes, and reach the lane order of v_smfmac_f32_16x16x64_bf16 (lane = row
-//     l%16, chunk l/16) by ds_bpermute; no LDS buffers, no barriers in the main loop;
-//   - the 8 partial tiles are summed in a fixed order through LDS (bit-identical runs), and the
+//   - a workgroup owns 32 to 64 weight rows and all tokens; its wavefronts take the pairs of
+//     k-steps in turn (wavefront w: pairs w, w + W, ...), each accumulating a partial tile;
+//   - every operand goes through a ring in LDS that is private to the wavefront, fed by
+//     global -> LDS loads of full 128-byte lines and read back with ds_read_b128 in MFMA order:
+//     no barrier in the main loop, only the wavefront's own s_waitcnt;
+//   - the partial tiles are summed in a fixed order through LDS (bit-identical runs), and the
 //     adapter term is added there with plain fp32 FMAs on T = X L and the factor R as stored.
 // T itself comes from a split over d_in (xl_partial_kernel, fp32 partial sums in the workspace)
 // followed by a fixed-order reduction that rounds to bf16 (xl_reduce_kernel).
+// (A first version kept the operands in registers and moved them into MFMA order with ds_bpermute;
+// the permutes capped a compute unit near 23 B/ns, against 44 B/ns with the LDS rings.)
 #include "pipeline.h"
 
 namespace {
 
-constexpr int ST_BM = 32;           // weight rows per workgroup
-constexpr int ST_WAVES = 8;
-#ifndef ST_DEPTH_PAIRS
-#define ST_DEPTH_PAIRS 2
-#endif
-#ifdef ST_NONTEMPORAL
-#define ST_LOAD(p) __builtin_nontemporal_load(p)
-#else
-#define ST_LOAD(p) (*(p))
-#endif
-constexpr int ST_DEPTH = ST_DEPTH_PAIRS;   // pairs of k-steps each wavefront keeps in flight
-constexpr int XL_CHUNK = 64;        // rows of L per workgroup of xl_partial_kernel
+constexpr int XL_CHUNK = 64;        // rows of L per chunk of xl_partial_kernel
 
 union StB { u32x4 u[2]; bf16x16 v; };
 union StA { u32x4 u; bf16x8 v; };
 
-// One pair of k-steps as loaded: every load instruction fetches 8 rows x 128 contiguous bytes
-// (8 lanes per row), which for the packed weight is both steps of the pair and for the token
-// operand one step.
-template <int NF>
-struct StStage {
-    u32x4 a[2][2];          // [fragment][rows 0-7 | rows 8-15]: 128 bytes per row = 2 steps x 64
-    uint32_t mt[2];         // [fragment]: 16 bytes of metadata per row (4 lanes per row)
-    u32x4 b[2][NF][2];      // [step][fragment][tokens 0-7 | 8-15]: 128 bytes per token
-};
-
-template <int NF>
-__global__ void __launch_bounds__(ST_WAVES * 64) spmm_stream_kernel(const bf16_t* __restrict__ B, int n,
-                                                                  const bf16_t* __restrict__ Av,
-                                                                  const uint8_t* __restrict__ Am, int m, int K,
-                                                                  const bf16_t* __restrict__ T,
-                                                                  const bf16_t* __restrict__ R, int K2,
-                                                                  bf16_t* __restrict__ C) {
-    constexpr int MF = ST_BM / 16, NC = NF * 16, PITCH = NC + 1;
-    __shared__ float part[ST_WAVES][ST_BM][PITCH];
-
-    const int t = threadIdx.x, lane = t & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-    const int l16 = lane & 15, lq = lane >> 4;
-    const int m0 = blockIdx.x * ST_BM;
-    const int ksteps = K / 64, kpairs = (ksteps + 1) / 2;
-    const bool odd_tail = (ksteps & 1) != 0;                 // the last pair has one step only
-
-    // Loader lanes: lane = 8 * row + chunk.  The MFMA wants row l%16 and 16-byte chunk l/16 of the
-    // step in lane l: multiply() fetches them from the loader lanes with ds_bpermute.
-    const int ld_row = lane >> 3, ld_chunk = lane & 7;
-    const uint8_t* a_ptr[MF][2];
-    const uint8_t* m_ptr[MF];
-#pragma unroll
-    for (int i = 0; i < MF; ++i) {
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            int row = m0 + 16 * i + 8 * h + ld_row;
-            row = row < m ? row : m - 1;
-            a_ptr[i][h] = (const uint8_t*)Av + (size_t)row * K + 16 * ld_chunk;   // K bytes of packed values per row
-        }
-        int row = m0 + 16 * i + (lane >> 2);
-        row = row < m ? row : m - 1;
-        m_ptr[i] = Am + (size_t)row * (K / 8) + 4 * (lane & 3);
-    }
-    const uint8_t* b_ptr[NF][2];
-#pragma unroll
-    for (int j = 0; j < NF; ++j)
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            int tok = 16 * j + 8 * h + ld_row;
-            tok = tok < n ? tok : n - 1;
-            b_ptr[j][h] = (const uint8_t*)B + (size_t)tok * K * 2 + 16 * ld_chunk;
-        }
-    const int src_lo = ((l16 & 7) * 8 + lq) * 4;              // ds_bpermute byte address: chunk lq of row l16 % 8
-    const bool upper = l16 >= 8;                              // which of the two 8-row loads holds row l16
-    const int src_meta = (4 * l16 + (lq >> 1)) * 4;           // dword lq / 2 of row l16's metadata of a step
-
-    f32x4 acc[MF][NF];
-#pragma unroll
-    for (int i = 0; i < MF; ++i)
-#pragma unroll
-        for (int j = 0; j < NF; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
-
-    StStage<NF> st[ST_DEPTH];
-    auto load = [&](StStage<NF>& s, int kp) {                 // pair kp, clamped: a late load is never used
-        const size_t pc = kp < kpairs ? kp : kpairs - 1;
-        // an odd number of steps: the last pair is read as steps (ksteps - 2, ksteps - 1) and only
-        // its second half is used, so that no load runs past the row
-        const size_t s0 = (odd_tail && pc == (size_t)kpairs - 1) ? (size_t)ksteps - 2 : 2 * pc;
-#pragma unroll
-        for (int i = 0; i < MF; ++i) {
-            s.a[i][0] = ST_LOAD((const u32x4*)(a_ptr[i][0] + s0 * 64));
-            s.a[i][1] = ST_LOAD((const u32x4*)(a_ptr[i][1] + s0 * 64));
-            s.mt[i] = *(const uint32_t*)(m_ptr[i] + s0 * 8);
-        }
-#pragma unroll
-        for (int e = 0; e < 2; ++e)
-#pragma unroll
-            for (int j = 0; j < NF; ++j) {
-                s.b[e][j][0] = *(const u32x4*)(b_ptr[j][0] + (s0 + e) * 128);
-                s.b[e][j][1] = *(const u32x4*)(b_ptr[j][1] + (s0 + e) * 128);
-            }
-    };
-    // chunk c (0..7) of row l16 out of the pair of 8-row loads
-    auto gather = [&](const u32x4 (&v)[2], int c) {
-        u32x4 r;
-        const int addr = src_lo + c * 4;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            uint32_t lo = (uint32_t)__builtin_amdgcn_ds_bpermute(addr, (int)v[0][e]);
-            uint32_t hi = (uint32_t)__builtin_amdgcn_ds_bpermute(addr, (int)v[1][e]);
-            r[e] = upper ? hi : lo;
-        }
-        return r;
-    };
-    auto multiply = [&](const StStage<NF>& s, int e) {       // step e (0 or 1) of the pair
-        StB b[NF];
-#pragma unroll
-        for (int j = 0; j < NF; ++j) {
-            b[j].u[0] = gather(s.b[e][j], 0);
-            b[j].u[1] = gather(s.b[e][j], 4);
-        }
-#pragma unroll
-        for (int i = 0; i < MF; ++i) {
-            uint32_t w = (uint32_t)__builtin_amdgcn_ds_bpermute(src_meta + e * 8, (int)s.mt[i]);
-            int idx = (int)((w >> (16 * (lq & 1))) & 0xFFFFu);
-            StA a;
-            a.u = gather(s.a[i], 4 * e);
-#pragma unroll
-            for (int j = 0; j < NF; ++j)
-                acc[i][j] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a.v, b[j].v, acc[i][j], idx, 0, 0);
-        }
-    };
-
-    // Workgroups start at different places of the k range and wrap around, so that at any moment
-    // the chip reads many different column bands of the weight rather than one (all rows have the
-    // same pitch, and one band maps to few memory channels).
-    const int rot = (int)((blockIdx.x * 37u) % (unsigned)kpairs);
-    auto pair_of = [&](int q) { int p = q + rot; return p >= kpairs ? p - kpairs : p; };   // q < kpairs
-#pragma unroll
-    for (int d = 0; d < ST_DEPTH; ++d) {
-        const int q = wave + ST_WAVES * d;
-        load(st[d], q < kpairs ? pair_of(q) : kpairs - 1);
-    }
-    for (int kq = wave; kq < kpairs; kq += ST_WAVES * ST_DEPTH) {
-#pragma unroll
-        for (int d = 0; d < ST_DEPTH; ++d) {
-            const int q = kq + ST_WAVES * d;                  // wave-uniform
-            if (q < kpairs) {
-                const int p = pair_of(q);
-                if (!(odd_tail && p == kpairs - 1)) multiply(st[d], 0);
-                multiply(st[d], 1);
-            }
-            const int qn = q + ST_WAVES * ST_DEPTH;
-            load(st[d], qn < kpairs ? pair_of(qn) : kpairs - 1);
-        }
-    }
-
-    // partial tiles: lane (l16, lq) holds token 16 j + l16, rows 16 i + 4 lq .. + 3
-#pragma unroll
-    for (int i = 0; i < MF; ++i)
-#pragma unroll
-        for (int j = 0; j < NF; ++j)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) part[wave][16 * i + 4 * lq + e][16 * j + l16] = acc[i][j][e];
-    __syncthreads();
-
-    // fixed-order sum, adapter term, store: thread = (feature o, token tok)
-    const int o = t & 31;
-    for (int tok = t >> 5; tok < n; tok += ST_WAVES * 2) {
-        float v = 0.f;
-#pragma unroll
-        for (int w = 0; w < ST_WAVES; ++w) v += part[w][o][tok];
-        if (m0 + o < m) {
-            if (K2 > 0) {
-                float low = 0.f;
-                const bf16_t* tp = T + (size_t)tok * K2;
-                const bf16_t* rp = R + m0 + o;
-#pragma unroll 8
-                for (int k = 0; k < K2; ++k)
-                    low = __builtin_fmaf(__uint_as_float((uint32_t)tp[k] << 16),
-                                         __uint_as_float((uint32_t)rp[(size_t)k * m] << 16), low);
-                v += low;
-            }
-            union { __bf16 h; bf16_t u; } r;
-            r.h = (__bf16)v;
-            C[(size_t)tok * m + m0 + o] = r.u;
-        }
-    }
-}
-
-// ------------------------------------------------------------------------------------------
-// Up to 16 tokens: the same k-split, but every operand takes the route of the tile kernels,
-// global -> LDS loads of full 128-byte lines into a ring that is private to the wavefront (two
-// pairs of k-steps deep), then ds_read_b128 in MFMA order.  Nothing is shared between wavefronts,
-// so the main loop needs no barrier, only the wavefront's own s_waitcnt; the lane permutations of
-// the register variant, which cap a compute unit near 23 B/ns, are gone, and one workgroup per
-// compute unit is enough to saturate HBM.  Ring stage of one wavefront:
-//     A: MF fragments x (16 rows x 128 B: both steps of the pair) | B: 2 steps x (16 tokens x 128 B)
+// The ring is two pairs of k-steps deep.  One workgroup per compute unit is resident and about 140
+// of them saturate HBM.  NF token fragments of 16: one (up to 16 tokens, 8 to 4 wavefronts) or
+// two (up to 32 tokens, 4 wavefronts).  Ring stage of one wavefront:
+//     A: MF fragments x (16 rows x 128 B: both steps of the pair) | B: 2 steps x NF x (16 tokens x 128 B)
 //     | metadata: 16 MF rows x 16 B
-template <int MF, int WAVES>
+template <int MF, int WAVES, int NF>
 struct StreamLds {
     static constexpr int BM = 16 * MF;
-    static constexpr int A_BYTES = MF * 2048, B_BYTES = 2 * 2048, M_BYTES = MF * 256;
+    static constexpr int A_BYTES = MF * 2048, B_BYTES = 2 * NF * 2048, M_BYTES = MF * 256;
     static constexpr int STAGE = A_BYTES + B_BYTES + M_BYTES;
-    static constexpr int OPS = 2 * MF + 4 + 1;                // loads per wavefront and pair
+    static constexpr int OPS = 2 * MF + 4 * NF + 1;           // loads per wavefront and pair
     static constexpr int RING = WAVES * 2 * STAGE;
-    static constexpr int PART_PITCH = 17;
+    static constexpr int PART_PITCH = 16 * NF + 1;
     static constexpr int TOTAL = RING + WAVES * BM * PART_PITCH * 4;
 };
 
-template <int MF, int WAVES>
+template <int MF, int WAVES, int NF>
 __global__ void __launch_bounds__(WAVES * 64) spmm_stream_lds_kernel(const bf16_t* __restrict__ B, int n,
                                                                    const bf16_t* __restrict__ Av,
                                                                    const uint8_t* __restrict__ Am, int m, int K,
                                                                    const bf16_t* __restrict__ T,
                                                                    const bf16_t* __restrict__ R, int K2,
                                                                    bf16_t* __restrict__ C) {
-    using S = StreamLds<MF, WAVES>;
+    using S = StreamLds<MF, WAVES, NF>;
     extern __shared__ __align__(16) uint8_t smem[];
     float* part = (float*)(smem + S::RING);                   // [wave][row][PART_PITCH]
 
@@ -255,13 +69,15 @@ __global__ void __launch_bounds__(WAVES * 64) spmm_stream_lds_kernel(const bf16_
             row = row < m ? row : m - 1;
             a_src[i][h] = (const uint8_t*)Av + (size_t)row * K + ((ld_slot ^ ((rl >> 1) & 7)) * 16);
         }
-    const uint8_t* b_src[2];
+    const uint8_t* b_src[NF][2];
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        int rl = 8 * h + ld_row;
-        int tok = rl < n ? rl : n - 1;
-        b_src[h] = (const uint8_t*)B + (size_t)tok * K * 2 + ((ld_slot ^ ((rl >> 1) & 7)) * 16);
-    }
+    for (int j = 0; j < NF; ++j)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            int rl = 8 * h + ld_row;
+            int tok = 16 * j + rl < n ? 16 * j + rl : n - 1;
+            b_src[j][h] = (const uint8_t*)B + (size_t)tok * K * 2 + ((ld_slot ^ ((rl >> 1) & 7)) * 16);
+        }
     const bool meta_lane = lane < 16 * MF;
     const uint8_t* m_src;
     {
@@ -280,28 +96,37 @@ __global__ void __launch_bounds__(WAVES * 64) spmm_stream_lds_kernel(const bf16_
             dma16(a_src[i][1] + s0 * 64, st + i * 2048 + 1024);
         }
 #pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            dma16(b_src[0] + (s0 + e) * 128, st + S::A_BYTES + e * 2048);
-            dma16(b_src[1] + (s0 + e) * 128, st + S::A_BYTES + e * 2048 + 1024);
-        }
+        for (int e = 0; e < 2; ++e)
+#pragma unroll
+            for (int j = 0; j < NF; ++j) {
+                dma16(b_src[j][0] + (s0 + e) * 128, st + S::A_BYTES + (e * NF + j) * 2048);
+                dma16(b_src[j][1] + (s0 + e) * 128, st + S::A_BYTES + (e * NF + j) * 2048 + 1024);
+            }
         if (meta_lane) dma16(m_src + s0 * 8, st + S::A_BYTES + S::B_BYTES);
     };
 
     const int sw = (l16 >> 1) & 7;
-    f32x4 acc[MF];
+    f32x4 acc[MF][NF];
 #pragma unroll
-    for (int i = 0; i < MF; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < MF; ++i)
+#pragma unroll
+        for (int j = 0; j < NF; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
     auto multiply = [&](int stage, int e) {                   // step e (0 or 1) of the pair in `stage`
         const uint8_t* st = ring + stage * S::STAGE;
-        StB b;
-        b.u[0] = *(const u32x4*)(st + S::A_BYTES + e * 2048 + l16 * 128 + ((lq ^ sw) * 16));
-        b.u[1] = *(const u32x4*)(st + S::A_BYTES + e * 2048 + l16 * 128 + (((4 + lq) ^ sw) * 16));
+        StB b[NF];
+#pragma unroll
+        for (int j = 0; j < NF; ++j) {
+            b[j].u[0] = *(const u32x4*)(st + S::A_BYTES + (e * NF + j) * 2048 + l16 * 128 + ((lq ^ sw) * 16));
+            b[j].u[1] = *(const u32x4*)(st + S::A_BYTES + (e * NF + j) * 2048 + l16 * 128 + (((4 + lq) ^ sw) * 16));
+        }
 #pragma unroll
         for (int i = 0; i < MF; ++i) {
             StA a;
             a.u = *(const u32x4*)(st + i * 2048 + l16 * 128 + (((4 * e + lq) ^ sw) * 16));
             int idx = *(const uint16_t*)(st + S::A_BYTES + S::B_BYTES + (16 * i + l16) * 16 + 8 * e + 2 * lq);
-            acc[i] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a.v, b.v, acc[i], idx, 0, 0);
+#pragma unroll
+            for (int j = 0; j < NF; ++j)
+                acc[i][j] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a.v, b[j].v, acc[i][j], idx, 0, 0);
         }
     };
 
@@ -332,17 +157,19 @@ __global__ void __launch_bounds__(WAVES * 64) spmm_stream_lds_kernel(const bf16_
     }
     WAIT_HERE(waitcnt_imm(0, 15));                            // drain the clamped look-ahead loads
 
-    // partial tiles: lane (l16, lq) holds token l16, rows 16 i + 4 lq .. + 3
+    // partial tiles: lane (l16, lq) holds token 16 j + l16, rows 16 i + 4 lq .. + 3
 #pragma unroll
     for (int i = 0; i < MF; ++i)
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-            part[(wave * S::BM + 16 * i + 4 * lq + e) * S::PART_PITCH + l16] = acc[i][e];
+        for (int j = 0; j < NF; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                part[(wave * S::BM + 16 * i + 4 * lq + e) * S::PART_PITCH + 16 * j + l16] = acc[i][j][e];
     __syncthreads();
 
     // adapter operands into the ring, which is free now: T[n][K2] and the tile R[K2][BM] of the factor
     bf16_t* const t_lds = (bf16_t*)smem;                      // [tok][K2]
-    bf16_t* const r_lds = t_lds + 16 * K2;                    // [k][BM]
+    bf16_t* const r_lds = t_lds + 16 * NF * K2;               // [k][BM]
     if (K2 > 0) {
         for (int idx = t; idx < n * K2 / 8; idx += WAVES * 64)
             ((u32x4*)t_lds)[idx] = ((const u32x4*)T)[idx];
@@ -357,8 +184,9 @@ __global__ void __launch_bounds__(WAVES * 64) spmm_stream_lds_kernel(const bf16_
     }
 
     // fixed-order sum, adapter term, store: thread = (feature o, token tok)
+    constexpr int TOK_GROUPS = WAVES * 64 / S::BM;            // whole groups of BM threads
     const int o = t % S::BM;
-    for (int tok = t / S::BM; tok < n; tok += WAVES * 64 / S::BM) {
+    for (int tok = t < TOK_GROUPS * S::BM ? t / S::BM : n; tok < n; tok += TOK_GROUPS) {
         float v = 0.f;
 #pragma unroll
         for (int w = 0; w < WAVES; ++w) v += part[(w * S::BM + o) * S::PART_PITCH + tok];
@@ -378,12 +206,12 @@ __global__ void __launch_bounds__(WAVES * 64) spmm_stream_lds_kernel(const bf16_
     }
 }
 
-template <int MF, int WAVES>
+template <int MF, int WAVES, int NF>
 hipError_t launch_stream_lds(const bf16_t* B, int64_t n, const bf16_t* Av, const uint8_t* Am, int64_t m, int64_t K,
                              const bf16_t* T, const bf16_t* R, int64_t K2, bf16_t* C, hipStream_t s) {
-    using S = StreamLds<MF, WAVES>;
+    using S = StreamLds<MF, WAVES, NF>;
     static_assert(S::TOTAL <= 160 * 1024, "LDS budget");
-    auto kern = spmm_stream_lds_kernel<MF, WAVES>;
+    auto kern = spmm_stream_lds_kernel<MF, WAVES, NF>;
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, S::TOTAL);
     if (e != hipSuccess) return e;
     kern<<<dim3((unsigned)((m + S::BM - 1) / S::BM)), dim3(WAVES * 64), S::TOTAL, s>>>(B, (int)n, Av, Am, (int)m, (int)K,
@@ -511,13 +339,16 @@ hipError_t launch_spmm_stream(const bf16_t* B, int64_t n, const bf16_t* A_vals, 
             const double est = full * round_ns(RESIDENT) + (rest ? round_ns(rest) : 0.0);
             if (est < best_t) { best_t = est; best = c; }
         }
-        if (best == 0) return launch_stream_lds<2, 8>(B, n, A_vals, A_meta, m, K, T, R, K2, C, s);
-        if (best == 1) return launch_stream_lds<3, 6>(B, n, A_vals, A_meta, m, K, T, R, K2, C, s);
-        return launch_stream_lds<4, 4>(B, n, A_vals, A_meta, m, K, T, R, K2, C, s);
+        if (best == 0) return launch_stream_lds<2, 8, 1>(B, n, A_vals, A_meta, m, K, T, R, K2, C, s);
+        if (best == 1) return launch_stream_lds<3, 6, 1>(B, n, A_vals, A_meta, m, K, T, R, K2, C, s);
+        return launch_stream_lds<4, 4, 1>(B, n, A_vals, A_meta, m, K, T, R, K2, C, s);
     }
-    dim3 grid((unsigned)((m + ST_BM - 1) / ST_BM)), block(ST_WAVES * 64);
-    spmm_stream_kernel<2><<<grid, block, 0, s>>>(B, (int)n, A_vals, A_meta, (int)m, (int)K, T, R, (int)K2, C);
-    return hipGetLastError();
+    // 17 to 32 tokens: two token fragments per wavefront leave room for four wavefronts only
+    const int64_t b32 = (m + 31) / 32, b48 = (m + 47) / 48;
+    auto last_round = [](int64_t blocks) { int64_t r = blocks % RESIDENT; return r == 0 ? RESIDENT : r; };
+    if (last_round(b48) > last_round(b32) || b48 % RESIDENT == 0)
+        return launch_stream_lds<3, 4, 2>(B, n, A_vals, A_meta, m, K, T, R, K2, C, s);
+    return launch_stream_lds<2, 4, 2>(B, n, A_vals, A_meta, m, K, T, R, K2, C, s);
 }
 
 // T = X L for few tokens (up to 128), split over d_in; scratch holds xl_small_scratch_bytes

@@ -118,6 +118,7 @@ PRODUCT_SHAPES = [
 SKINNY_SHAPES = [(1, 512, 512), (7, 25600, 256), (100, 512, 768), (128, 25600, 256), (16, 256, 25600),
                  (32, 2112, 4160), (17, 4160, 2112), (33, 512, 512),
                  (8, 8320, 256), (16, 13696, 256), (3, 256, 8320),   # 48- and 64-row workgroups of the small-batch kernel
+                 (24, 8320, 256),                                      # 17-32 tokens, 48-row workgroups
                  (100, 768, 4096), (200, 4160, 2048), (48, 512, 8192)]   # split over K with partial sums (forward)
 
 
@@ -166,7 +167,7 @@ def test_wgrad_masked(b, d_out, d_in, ws):
 @pytest.mark.parametrize("b,d_out,d_in,r", [(2048, 3072, 768, 64), (300, 448, 320, 32), (4100, 4160, 256, 128), (4000, 4032, 256, 128),
                                             (16, 512, 768, 64), (1, 1280, 256, 32), (32, 4160, 1024, 128), (7, 448, 320, 288),
                                             (16, 8320, 256, 64), (5, 13696, 256, 512),
-                                            (200, 4160, 2048, 64), (100, 768, 4096, 128), (48, 512, 8192, 32),
+                                            (200, 4160, 2048, 64), (100, 768, 4096, 128), (48, 512, 8192, 32), (32, 8320, 256, 64),
                                             (50, 128, 192, 160)])
 def test_spmm_fwd_with_adapter(b, d_out, d_in, r):
     say(f"spmm_fwd adapter b={b} d_out={d_out} d_in={d_in} r={r}")
