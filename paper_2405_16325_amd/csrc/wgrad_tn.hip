@@ -278,18 +278,18 @@ __global__ void __launch_bounds__(TN_THREADS) dense_tn_split_kernel(const bf16_t
         b_src[q] = (const uint8_t*)Bt + (size_t)rb * kp * 2 + sw16;
     }
     const int ksteps = kp / 64;
-    auto issue_a = [&](int half, int ks) {                   // rows 128 half .. +127 of A(ks), ks clamped
+    // the four loads a wavefront queues per phase, one at a time (ks clamped: the look-ahead of the
+    // last steps re-reads the last one)
+    auto issue_a = [&](int half, int ks, int i) {            // 8 rows of rows 128 half .. +127 of A(ks)
         int kc = ks < ksteps ? ks : ksteps - 1;
-        uint8_t* st = smem + (ks % 3) * S::A_STAGE + (half * 16 + wave * 2) * 1024;
-        dma16(a_src[half * 2] + (size_t)kc * 128, st);
-        dma16(a_src[half * 2 + 1] + (size_t)kc * 128, st + 1024);
+        dma16(a_src[half * 2 + i] + (size_t)kc * 128, smem + (ks % 3) * S::A_STAGE + (half * 16 + wave * 2 + i) * 1024);
     };
-    auto issue_b = [&](int g, int ks) {                      // B half of group g, step ks (clamped)
+    auto issue_b = [&](int g, int ks, int i) {               // 8 rows of the B half of group g, step ks
         int kc = ks < ksteps ? ks : ksteps - 1;
-        uint8_t* st = smem + S::B_OFF + (g * 2 + (ks & 1)) * S::B_HALF + (wave * 2) * 1024;
-        dma16(b_src[g * 2] + (size_t)kc * 128, st);
-        dma16(b_src[g * 2 + 1] + (size_t)kc * 128, st + 1024);
+        dma16(b_src[g * 2 + i] + (size_t)kc * 128, smem + S::B_OFF + (g * 2 + (ks & 1)) * S::B_HALF + (wave * 2 + i) * 1024);
     };
+    auto even_load = [&](int k, int idx) { if (idx < 2) issue_b(1, k + 1, idx); else issue_a(0, k + 2, idx - 2); };
+    auto odd_load = [&](int k, int idx) { if (idx < 2) issue_a(1, k + 2, idx); else issue_b(0, k + 2, idx - 2); };
 
     // reader lanes: fragment f = rows 16f .. 16f+15 = 2 KiB; lane (l16, lq) wants chunk 4h + lq
     const int sw = (l16 >> 1) & 7;
@@ -317,20 +317,26 @@ __global__ void __launch_bounds__(TN_THREADS) dense_tn_split_kernel(const bf16_t
             bf[j].u[0] = *(const u32x4*)(sb + j * 2048 + rd0);                                         \
             bf[j].u[1] = *(const u32x4*)(sb + j * 2048 + rd1);                                         \
         }
-#define SPLIT_MFMA                                                                                     \
+// the compute phase: 64 MFMAs with the phase's four loads spread between them (queued in one burst
+// at the start of the phase they cost 2 % more)
+#define SPLIT_MFMA(LOAD, k)                                                                            \
         _Pragma("unroll") for (int h = 0; h < 2; ++h)                                                  \
-        _Pragma("unroll") for (int i = 0; i < MF; ++i) _Pragma("unroll") for (int j = 0; j < NF; ++j) { \
-            AFrag a, b;                                                                                \
-            a.u = af[i].u[h]; b.u = bf[j].u[h];                                                        \
-            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, acc[i][j], 0, 0, 0);         \
+        _Pragma("unroll") for (int i = 0; i < MF; ++i) {                                               \
+            _Pragma("unroll") for (int j = 0; j < NF; ++j) {                                           \
+                AFrag a, b;                                                                            \
+                a.u = af[i].u[h]; b.u = bf[j].u[h];                                                    \
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, acc[i][j], 0, 0, 0);     \
+            }                                                                                          \
+            if (h == 0 && (i & 1) == 1) LOAD(k, i >> 1);                                               \
+            __builtin_amdgcn_sched_barrier(0);                                                         \
         }
-#define EVEN_LOADS(k) { issue_b(1, (k) + 1); issue_a(0, (k) + 2); }
-#define ODD_LOADS(k)  { issue_a(1, (k) + 2); issue_b(0, (k) + 2); }
+#define EVEN_LOADS(k) { even_load(k, 0); even_load(k, 1); even_load(k, 2); even_load(k, 3); }
+#define ODD_LOADS(k)  { odd_load(k, 0); odd_load(k, 1); odd_load(k, 2); odd_load(k, 3); }
 
     // steps 0 and 1 as far as the schedule would have queued them before phase 0
-    issue_a(0, 0); issue_a(1, 0); issue_b(0, 0);
-    issue_b(1, 0); issue_a(0, 1);
-    issue_a(1, 1); issue_b(0, 1);
+    issue_a(0, 0, 0); issue_a(0, 0, 1); issue_a(1, 0, 0); issue_a(1, 0, 1); issue_b(0, 0, 0); issue_b(0, 0, 1);
+    issue_b(1, 0, 0); issue_b(1, 0, 1); issue_a(0, 1, 0); issue_a(0, 1, 1);
+    issue_a(1, 1, 0); issue_a(1, 1, 1); issue_b(0, 1, 0); issue_b(0, 1, 1);
     WAIT_HERE(waitcnt_imm(KEEP, 15));                         // A(0) and B0(0) have landed
     wg_barrier();
     if (group == 0) {
@@ -339,8 +345,7 @@ __global__ void __launch_bounds__(TN_THREADS) dense_tn_split_kernel(const bf16_t
             EVEN_LOADS(ks)
             WAIT_HERE(waitcnt_imm(KEEP, 0));
             wg_barrier();
-            ODD_LOADS(ks)                                     // phase 2 ks + 1
-            SPLIT_MFMA
+            SPLIT_MFMA(odd_load, ks)                          // phase 2 ks + 1
             WAIT_HERE(waitcnt_imm(KEEP, 15));
             wg_barrier();
         }
@@ -354,8 +359,7 @@ __global__ void __launch_bounds__(TN_THREADS) dense_tn_split_kernel(const bf16_t
             ODD_LOADS(ks)
             WAIT_HERE(waitcnt_imm(KEEP, 0));
             wg_barrier();
-            EVEN_LOADS(ks + 1)                                // phase 2 ks + 2
-            SPLIT_MFMA
+            SPLIT_MFMA(even_load, ks + 1)                     // phase 2 ks + 2
             WAIT_HERE(waitcnt_imm(KEEP, 15));
             wg_barrier();
         }
