@@ -5,7 +5,9 @@
 // MFMA straight from [token][feature] slabs needs the transposing LDS read, which delivers only a
 // quarter of the LDS bandwidth of ds_read_b128 and caps the kernel near half the MFMA peak.  So
 // the operands are first copied once into token-contiguous form in the caller's workspace
-//     Xt [d_in ][bp],  dYt[d_out][bp],   bp = b rounded up to 64, the tail zero-filled
+//     Xt [d_in ][ld],  dYt[d_out][ld],   bp = b rounded up to 64, the tail zero-filled,
+//     ld = row pitch: bp, plus one 128-byte line where bp * 2 is a multiple of 4 KiB (rows that
+//     far apart crowd the same L2 channels: the padded pitch is 2-3 % faster at b = 16384)
 // (two HBM streams, a few percent of the product's time at LLM layer sizes), and the product
 //     D[i, j] = sum_t Xt[i, t] * dYt[j, t]
 // runs with the same machinery as the sparse kernels: 8 wavefronts in two groups half a k-step
@@ -19,10 +21,10 @@
 namespace {
 
 // out[c][r] = in[r][c] for r < rows, zero for rows <= r < rows_pad; in is [rows][cols] bf16 with
-// cols % 8 == 0, out is [cols][rows_pad] with rows_pad % 64 == 0.  64 x 64 tiles through LDS,
-// 16-byte global accesses on both sides.
+// cols % 8 == 0, out is [cols] rows of pitch ld >= rows_pad, rows_pad % 64 == 0, ld % 8 == 0.
+// 64 x 64 tiles through LDS, 16-byte global accesses on both sides.
 __global__ void __launch_bounds__(256) transpose_pad_kernel(const bf16_t* __restrict__ in, int rows, int cols,
-                                                            int rows_pad, bf16_t* __restrict__ out) {
+                                                            int rows_pad, int ld, bf16_t* __restrict__ out) {
     __shared__ bf16_t tile[64][66];
     const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64, t = threadIdx.x;
 #pragma unroll
@@ -40,15 +42,18 @@ __global__ void __launch_bounds__(256) transpose_pad_kernel(const bf16_t* __rest
         if (c0 + c >= cols) continue;
         const uint32_t* src = (const uint32_t*)&tile[c][r8];
         u32x4 v = {src[0], src[1], src[2], src[3]};
-        *(u32x4*)(out + (size_t)(c0 + c) * rows_pad + r0 + r8) = v;
+        *(u32x4*)(out + (size_t)(c0 + c) * ld + r0 + r8) = v;
     }
 }
 
-inline void launch_transpose_pad(const bf16_t* in, int64_t rows, int64_t cols, int64_t rows_pad, bf16_t* out,
-                                 hipStream_t s) {
+inline void launch_transpose_pad(const bf16_t* in, int64_t rows, int64_t cols, int64_t rows_pad, int64_t ld,
+                                 bf16_t* out, hipStream_t s) {
     transpose_pad_kernel<<<dim3((unsigned)(rows_pad / 64), (unsigned)((cols + 63) / 64)), dim3(256), 0, s>>>(
-        in, (int)rows, (int)cols, (int)rows_pad, out);
+        in, (int)rows, (int)cols, (int)rows_pad, (int)ld, out);
 }
+
+// pitch (elements) of a token-contiguous copy with bp tokens per row
+inline int64_t token_pitch(int64_t bp) { return (bp * 2) % 4096 == 0 ? bp + 64 : bp; }
 
 template <int BM, int BN, int NS>
 struct TnSmem {
@@ -96,7 +101,7 @@ __device__ __forceinline__ void store_masked_packed(const f32x4 (&acc)[MF][NF], 
     }
 }
 
-// D[i, j] = sum_k At[i, k] * Bt[j, k];  At: [m][kp], Bt: [n][kp], kp % 64 == 0.
+// D[i, j] = sum_k At[i, k] * Bt[j, k];  At: m rows, Bt: n rows, both of pitch ld elements; kp % 64 == 0.
 //   EPI_MASKED_PACKED: out = packed gradient [n][m/2] selected by meta (u8[n][m/8])
 //   EPI_PLAIN        : out = bf16 [n][m]  (row j, four consecutive i per lane)
 // NS = ring depth: loads run NS - 1 k-steps ahead.  Two stages are all that fits beside a 256 x 256
@@ -104,7 +109,7 @@ __device__ __forceinline__ void store_masked_packed(const f32x4 (&acc)[MF][NF], 
 template <int BM, int BN, int EPI, int NS>
 __global__ void __launch_bounds__(TN_THREADS) dense_tn_kernel(const bf16_t* __restrict__ At, int m,
                                                               const bf16_t* __restrict__ Bt, int n, int kp,
-                                                              const uint8_t* __restrict__ meta,
+                                                              int ld, const uint8_t* __restrict__ meta,
                                                               bf16_t* __restrict__ out, int tiles_m, int tiles_n) {
     using S = TnSmem<BM, BN, NS>;
     constexpr int MF = BM / 32, NF = BN / 64;                // 16 x 16 fragments per wavefront (2 x 4 waves)
@@ -129,13 +134,13 @@ __global__ void __launch_bounds__(TN_THREADS) dense_tn_kernel(const bf16_t* __re
     for (int i = 0; i < LD_A; ++i) {
         int rl = (wave * LD_A + i) * 8 + (lane >> 3);
         int ra = m0 + rl < m ? m0 + rl : m - 1;
-        a_src[i] = (const uint8_t*)At + (size_t)ra * kp * 2 + (((lane & 7) ^ ((rl >> 1) & 7)) * 16);
+        a_src[i] = (const uint8_t*)At + (size_t)ra * ld * 2 + (((lane & 7) ^ ((rl >> 1) & 7)) * 16);
     }
 #pragma unroll
     for (int i = 0; i < LD_B; ++i) {
         int rl = (wave * LD_B + i) * 8 + (lane >> 3);
         int rb = n0 + rl < n ? n0 + rl : n - 1;
-        b_src[i] = (const uint8_t*)Bt + (size_t)rb * kp * 2 + (((lane & 7) ^ ((rl >> 1) & 7)) * 16);
+        b_src[i] = (const uint8_t*)Bt + (size_t)rb * ld * 2 + (((lane & 7) ^ ((rl >> 1) & 7)) * 16);
     }
     const int ksteps = kp / 64;
     auto issue = [&](int ks) {                               // k-step ks (clamped) into stage ks % NS
@@ -248,7 +253,7 @@ struct SplitSmem {
 
 __global__ void __launch_bounds__(TN_THREADS) dense_tn_split_kernel(const bf16_t* __restrict__ At, int m,
                                                                     const bf16_t* __restrict__ Bt, int n, int kp,
-                                                                    const uint8_t* __restrict__ meta,
+                                                                    int ld, const uint8_t* __restrict__ meta,
                                                                     bf16_t* __restrict__ out, int tiles_m,
                                                                     int tiles_n) {
     using S = SplitSmem;
@@ -274,8 +279,8 @@ __global__ void __launch_bounds__(TN_THREADS) dense_tn_split_kernel(const bf16_t
         int sw16 = ((lane & 7) ^ ((rl >> 1) & 7)) * 16;
         int ra = m0 + rl < m ? m0 + rl : m - 1;
         int rb = n0 + rl < n ? n0 + rl : n - 1;
-        a_src[q] = (const uint8_t*)At + (size_t)ra * kp * 2 + sw16;
-        b_src[q] = (const uint8_t*)Bt + (size_t)rb * kp * 2 + sw16;
+        a_src[q] = (const uint8_t*)At + (size_t)ra * ld * 2 + sw16;
+        b_src[q] = (const uint8_t*)Bt + (size_t)rb * ld * 2 + sw16;
     }
     const int ksteps = kp / 64;
     // the four loads a wavefront queues per phase, one at a time (ks clamped: the look-ahead of the
@@ -373,8 +378,8 @@ __global__ void __launch_bounds__(TN_THREADS) dense_tn_split_kernel(const bf16_t
 }
 
 template <int BM, int BN, int EPI, int NS>
-hipError_t launch_dense_tn(const bf16_t* At, int64_t m, const bf16_t* Bt, int64_t n, int64_t kp, const uint8_t* meta,
-                           bf16_t* out, hipStream_t s) {
+hipError_t launch_dense_tn(const bf16_t* At, int64_t m, const bf16_t* Bt, int64_t n, int64_t kp, int64_t ld,
+                           const uint8_t* meta, bf16_t* out, hipStream_t s) {
     using S = TnSmem<BM, BN, NS>;
     static_assert(S::TOTAL <= 160 * 1024, "LDS budget");
     int tiles_m = (int)((m + BM - 1) / BM), tiles_n = (int)((n + BN - 1) / BN);
@@ -382,11 +387,11 @@ hipError_t launch_dense_tn(const bf16_t* At, int64_t m, const bf16_t* Bt, int64_
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, S::TOTAL);
     if (e != hipSuccess) return e;
     kern<<<dim3((unsigned)super_grid(tiles_m, tiles_n)), dim3(TN_THREADS), S::TOTAL, s>>>(
-        At, (int)m, Bt, (int)n, (int)kp, meta, out, tiles_m, tiles_n);
+        At, (int)m, Bt, (int)n, (int)kp, (int)ld, meta, out, tiles_m, tiles_n);
     return hipGetLastError();
 }
 
-hipError_t launch_dense_tn_split(const bf16_t* At, int64_t m, const bf16_t* Bt, int64_t n, int64_t kp,
+hipError_t launch_dense_tn_split(const bf16_t* At, int64_t m, const bf16_t* Bt, int64_t n, int64_t kp, int64_t ld,
                                  const uint8_t* meta, bf16_t* out, hipStream_t s) {
     using S = SplitSmem;
     static_assert(S::TOTAL <= 160 * 1024, "LDS budget");
@@ -395,24 +400,23 @@ hipError_t launch_dense_tn_split(const bf16_t* At, int64_t m, const bf16_t* Bt, 
                                        hipFuncAttributeMaxDynamicSharedMemorySize, S::TOTAL);
     if (e != hipSuccess) return e;
     dense_tn_split_kernel<<<dim3((unsigned)super_grid(tiles_m, tiles_n)), dim3(TN_THREADS), S::TOTAL, s>>>(
-        At, (int)m, Bt, (int)n, (int)kp, meta, out, tiles_m, tiles_n);
+        At, (int)m, Bt, (int)n, (int)kp, (int)ld, meta, out, tiles_m, tiles_n);
     return hipGetLastError();
 }
 
 }  // namespace
 
 size_t wgrad_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out) {
-    size_t bp = ((size_t)b + 63) / 64 * 64;
-    return (size_t)(d_in + d_out) * bp * 2;
+    return (size_t)(d_in + d_out) * (size_t)token_pitch((b + 63) / 64 * 64) * 2;
 }
 
 hipError_t launch_wgrad_masked_ws(const bf16_t* dY, const bf16_t* X, int64_t b, const uint8_t* meta, int64_t d_out,
                                   int64_t d_in, bf16_t* gvals, void* workspace, hipStream_t s) {
-    int bp = (int)((b + 63) / 64 * 64);
+    const int64_t bp = (b + 63) / 64 * 64, ld = token_pitch(bp);
     bf16_t* Xt = (bf16_t*)workspace;
-    bf16_t* dYt = Xt + (size_t)d_in * bp;
-    launch_transpose_pad(X, b, d_in, bp, Xt, s);
-    launch_transpose_pad(dY, b, d_out, bp, dYt, s);
+    bf16_t* dYt = Xt + (size_t)d_in * ld;
+    launch_transpose_pad(X, b, d_in, bp, ld, Xt, s);
+    launch_transpose_pad(dY, b, d_out, bp, ld, dYt, s);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     // The kernel runs at the rate its compute units pull operands from L2: a launch costs about
@@ -425,9 +429,9 @@ hipError_t launch_wgrad_masked_ws(const bf16_t* dY, const bf16_t* X, int64_t b, 
         int64_t cost = ((tiles + RESIDENT - 1) / RESIDENT) * (bms[c] + bns[c]);
         if (cost < best_cost) { best_cost = cost; best = c; }
     }
-    if (best == 0) return launch_dense_tn_split(Xt, d_in, dYt, d_out, bp, meta, gvals, s);
-    if (best == 1) return launch_dense_tn<256, 128, EPI_MASKED_PACKED, 3>(Xt, d_in, dYt, d_out, bp, meta, gvals, s);
-    return launch_dense_tn<128, 128, EPI_MASKED_PACKED, 4>(Xt, d_in, dYt, d_out, bp, meta, gvals, s);
+    if (best == 0) return launch_dense_tn_split(Xt, d_in, dYt, d_out, bp, ld, meta, gvals, s);
+    if (best == 1) return launch_dense_tn<256, 128, EPI_MASKED_PACKED, 3>(Xt, d_in, dYt, d_out, bp, ld, meta, gvals, s);
+    return launch_dense_tn<128, 128, EPI_MASKED_PACKED, 4>(Xt, d_in, dYt, d_out, bp, ld, meta, gvals, s);
 }
 
 // C[n, m] = B[n, K] * A[m, K]^T, all bf16 row-major, K % 64 == 0 (the skinny product T = X L of the
@@ -435,7 +439,7 @@ hipError_t launch_wgrad_masked_ws(const bf16_t* dY, const bf16_t* X, int64_t b, 
 // m = 128 gives every compute unit a tile, and a six-deep ring to keep enough reads in flight.
 hipError_t launch_dense_tn_plain(const bf16_t* B, int64_t n, const bf16_t* A, int64_t m, int64_t K, bf16_t* C,
                                  hipStream_t s) {
-    return launch_dense_tn<128, 64, EPI_PLAIN, 6>(A, m, B, n, K, nullptr, C, s);
+    return launch_dense_tn<128, 64, EPI_PLAIN, 6>(A, m, B, n, K, K, nullptr, C, s);
 }
 
 // The same product for any shape (dense weights with a general N:M mask, where no sparse MFMA
@@ -451,10 +455,10 @@ hipError_t launch_dense_tn_any(const bf16_t* B, int64_t n, const bf16_t* A, int6
         if (cost < best_cost) { best_cost = cost; best = c; }
     }
     switch (best) {
-        case 0: return launch_dense_tn<256, 256, EPI_PLAIN, 2>(A, m, B, n, K, nullptr, C, s);
-        case 1: return launch_dense_tn<256, 128, EPI_PLAIN, 3>(A, m, B, n, K, nullptr, C, s);
-        case 2: return launch_dense_tn<128, 128, EPI_PLAIN, 4>(A, m, B, n, K, nullptr, C, s);
-        default: return launch_dense_tn<128, 64, EPI_PLAIN, 6>(A, m, B, n, K, nullptr, C, s);
+        case 0: return launch_dense_tn<256, 256, EPI_PLAIN, 2>(A, m, B, n, K, K, nullptr, C, s);
+        case 1: return launch_dense_tn<256, 128, EPI_PLAIN, 3>(A, m, B, n, K, K, nullptr, C, s);
+        case 2: return launch_dense_tn<128, 128, EPI_PLAIN, 4>(A, m, B, n, K, K, nullptr, C, s);
+        default: return launch_dense_tn<128, 64, EPI_PLAIN, 6>(A, m, B, n, K, K, nullptr, C, s);
     }
 }
 
@@ -462,40 +466,41 @@ hipError_t launch_dense_tn_any(const bf16_t* B, int64_t n, const bf16_t* A, int6
 // Weight gradient of a layer with adapters: the packed dW as above plus the adapter gradients
 // (chain rule of Eq. 11)   dL = X^T (dY R^T)  [d_in, r],   dR = (X L)^T dY  [r, d_out],
 // all three contractions over the tokens sharing the token-contiguous copies of X and dY.
-// Workspace: Xt | dYt | Lt [r][d_in] | T = X L [b][r] | T2 = dY R^T [b][r] | Tt [r][bp] | T2t [r][bp].
+// Workspace: Xt | dYt | Lt [r][d_in] | T = X L [b][r] | T2 = dY R^T [b][r] | Tt [r][ld] | T2t [r][ld].
 namespace {
 inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
 }  // namespace
 
 size_t wgrad_adapter_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out, int64_t r) {
-    size_t bp = ((size_t)b + 63) / 64 * 64;
+    size_t ld = (size_t)token_pitch((b + 63) / 64 * 64);
     return round256(wgrad_workspace_bytes(b, d_in, d_out)) + round256((size_t)r * d_in * 2) +
-           2 * round256((size_t)b * r * 2) + 2 * round256((size_t)r * bp * 2);
+           2 * round256((size_t)b * r * 2) + 2 * round256((size_t)r * ld * 2);
 }
 
 hipError_t launch_wgrad_adapter(const bf16_t* dY, const bf16_t* X, int64_t b, const uint8_t* meta, int64_t d_out,
                                 int64_t d_in, const bf16_t* L, const bf16_t* R, int64_t r, bf16_t* gvals, bf16_t* dL,
                                 bf16_t* dR, void* workspace, hipStream_t s) {
-    const int64_t bp = (b + 63) / 64 * 64;
+    const int64_t bp = (b + 63) / 64 * 64, ld = token_pitch(bp);
     uint8_t* w = (uint8_t*)workspace;
     bf16_t* Xt = (bf16_t*)w;
-    bf16_t* dYt = Xt + (size_t)d_in * bp;
+    bf16_t* dYt = Xt + (size_t)d_in * ld;
     w += round256(wgrad_workspace_bytes(b, d_in, d_out));
     bf16_t* Lt = (bf16_t*)w;   w += round256((size_t)r * d_in * 2);
     bf16_t* T = (bf16_t*)w;    w += round256((size_t)b * r * 2);
     bf16_t* T2 = (bf16_t*)w;   w += round256((size_t)b * r * 2);
-    bf16_t* Tt = (bf16_t*)w;   w += round256((size_t)r * bp * 2);
+    bf16_t* Tt = (bf16_t*)w;   w += round256((size_t)r * ld * 2);
     bf16_t* T2t = (bf16_t*)w;
 
     hipError_t e = launch_wgrad_masked_ws(dY, X, b, meta, d_out, d_in, gvals, workspace, s);   // fills Xt, dYt
     if (e != hipSuccess) return e;
-    launch_transpose_pad(L, d_in, r, d_in, Lt, s);                                // Lt[r][d_in]
+    launch_transpose_pad(L, d_in, r, d_in, d_in, Lt, s);                          // Lt[r][d_in]
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if ((e = launch_dense_tn_plain(X, b, Lt, r, d_in, T, s)) != hipSuccess) return e;      // T  = X L
     if ((e = launch_dense_tn_plain(dY, b, R, r, d_out, T2, s)) != hipSuccess) return e;    // T2 = dY R^T
-    launch_transpose_pad(T, b, r, bp, Tt, s);
-    launch_transpose_pad(T2, b, r, bp, T2t, s);
+    launch_transpose_pad(T, b, r, bp, ld, Tt, s);
+    launch_transpose_pad(T2, b, r, bp, ld, T2t, s);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    if ((e = launch_dense_tn_plain(Xt, d_in, T2t, r, bp, dL, s)) != hipSuccess) return e;  // dL[d_in][r]
-    return launch_dense_tn_plain(Tt, r, dYt, d_out, bp, dR, s);                            // dR[r][d_out]
+    e = launch_dense_tn<128, 64, EPI_PLAIN, 6>(T2t, r, Xt, d_in, bp, ld, nullptr, dL, s);   // dL[d_in][r]
+    if (e != hipSuccess) return e;
+    return launch_dense_tn<128, 64, EPI_PLAIN, 6>(dYt, d_out, Tt, r, bp, ld, nullptr, dR, s);   // dR[r][d_out]
 }
