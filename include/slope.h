@@ -227,6 +227,17 @@ slope_status slope_sparse_add(const void* A_vals, const void* B_vals, int64_t ro
 slope_status slope_update_sparse(const void* Wnew_vals, const void* Wr_meta, int64_t d_out, int64_t d_in,
                                  void* Wr_vals, const void* WrcT_meta, void* WrcT_vals, void* stream);
 
+/*
+ * slope_tile_order - diagnostics, host only (no GPU call): the workgroup -> tile assignment the
+ * MFMA tile kernels use for a grid of tiles_m x tiles_n tiles (the XCD-aware order behind the
+ * products of Eq. 1, 4-6).  Workgroup w of the launch computes tile (tm[w], tn[w]); -1 in both
+ * marks a workgroup that exits at once (ragged chunks).
+ *   tm, tn    out  host int32[capacity]
+ *   returns the number of workgroups of the launch (entries written), or -1 if capacity is
+ *   smaller than that or an extent is not positive.
+ */
+int64_t slope_tile_order(int64_t tiles_m, int64_t tiles_n, int32_t* tm, int32_t* tn, int64_t capacity);
+
 #ifdef __cplusplus
 }
 #endif

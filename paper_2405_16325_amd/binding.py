@@ -46,6 +46,7 @@ SIGNATURES = {
     "slope_gemm_tn": (_INT, [_P, _I64, _P, _I64, _I64, _P, _P]),
     "slope_sparse_add": (_INT, [_P, _P, _I64, _I64, ctypes.c_float, ctypes.c_float, _P, _P]),
     "slope_update_sparse": (_INT, [_P, _P, _I64, _I64, _P, _P, _P, _P]),
+    "slope_tile_order": (_I64, [_I64, _I64, _P, _P, _I64]),
 }
 
 _lib = None
@@ -266,3 +267,15 @@ def bf16_to_host(t):
     """bf16 tensor -> numpy uint16 bit patterns."""
     import numpy as np
     return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def slope_tile_order(tiles_m: int, tiles_n: int):
+    """Workgroup -> tile assignment of the tile kernels (host only): two int32 arrays, -1 = idle."""
+    import numpy as np
+    cap = (tiles_m * tiles_n + 255) // 256 * 256 + 8 * 256 * ((tiles_m + 7) // 8 + (tiles_n + 3) // 4 + 1)
+    tm = np.empty(cap, dtype=np.int32)
+    tn = np.empty(cap, dtype=np.int32)
+    grid = lib().slope_tile_order(tiles_m, tiles_n, tm.ctypes.data, tn.ctypes.data, cap)
+    if grid < 0:
+        raise ValueError("slope_tile_order: extents must be positive")
+    return tm[:grid].copy(), tn[:grid].copy()

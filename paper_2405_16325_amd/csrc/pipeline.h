@@ -25,8 +25,7 @@ __host__ __device__ inline int narrow_run(int tiles) {
     return (tiles + XCDS * rounds - 1) / (XCDS * rounds);
 }
 
-__device__ __forceinline__ bool tile_of_block(int tiles_m, int tiles_n, int& tm, int& tn) {
-    int b = blockIdx.x;
+__host__ __device__ inline bool tile_of_index(int b, int tiles_m, int tiles_n, int& tm, int& tn) {
     int xcd = b % XCDS, slot = b / XCDS;
     if (tiles_m >= SUPER && tiles_n >= SUPER) {
         int round = slot / 32, w = slot % 32;
@@ -46,6 +45,10 @@ __device__ __forceinline__ bool tile_of_block(int tiles_m, int tiles_n, int& tm,
     if (tiles_m <= tiles_n) { tm = t % tiles_m; tn = t / tiles_m; }
     else { tn = t % tiles_n; tm = t / tiles_n; }
     return tm < tiles_m && tn < tiles_n;
+}
+
+__device__ __forceinline__ bool tile_of_block(int tiles_m, int tiles_n, int& tm, int& tn) {
+    return tile_of_index((int)blockIdx.x, tiles_m, tiles_n, tm, tn);
 }
 
 inline int super_grid(int tiles_m, int tiles_n) {

@@ -1,6 +1,6 @@
 // C ABI of the double-pruned 2:4 sparse linear layer (declared in include/slope.h):
 // argument checks on the host, then the launchers.  No allocation, no synchronisation, no state.
-#include "common.h"
+#include "pipeline.h"
 
 namespace {
 
@@ -266,6 +266,19 @@ slope_status slope_update_sparse(const void* Wnew_vals, const void* Wr_meta, int
     }
     return finish(launch_update_transposed((const bf16_t*)Wnew_vals, (const uint8_t*)Wr_meta, d_out, d_in,
                                            (const uint8_t*)WrcT_meta, (bf16_t*)WrcT_vals, s));
+}
+
+int64_t slope_tile_order(int64_t tiles_m, int64_t tiles_n, int32_t* tm, int32_t* tn, int64_t capacity) {
+    if (tiles_m <= 0 || tiles_n <= 0 || tiles_m > (1 << 20) || tiles_n > (1 << 20) || !tm || !tn) return -1;
+    const int64_t grid = super_grid((int)tiles_m, (int)tiles_n);
+    if (capacity < grid) return -1;
+    for (int64_t w = 0; w < grid; ++w) {
+        int a = -1, b = -1;
+        if (!tile_of_index((int)w, (int)tiles_m, (int)tiles_n, a, b)) a = b = -1;
+        tm[w] = a;
+        tn[w] = b;
+    }
+    return grid;
 }
 
 }  // extern "C"

@@ -1,12 +1,15 @@
 """The C-ABI library loads, exports every symbol the header declares, and rejects bad arguments
-on the host (no GPU needed: argument errors are found before anything is launched)."""
+on the host (no GPU needed: argument errors are found before anything is launched); host logic:
+the workgroup -> tile order of the tile kernels covers every tile once and balances the XCDs."""
 import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 from paper_2405_16325_amd import binding
+from paper_2405_16325_amd import binding as sl
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -88,3 +91,39 @@ def test_binding_refuses_host_tensors():
     import torch
     with pytest.raises(ValueError):
         binding.slope_prune_rows(torch.zeros((8, 8), dtype=torch.bfloat16))
+
+
+# ---- host logic: the XCD-aware workgroup -> tile order of the tile kernels -----------------------
+TILE_GRIDS = [(1, 1), (1, 128), (128, 1), (3, 7), (15, 400), (16, 16), (17, 16), (16, 19), (36, 36), (36, 144),
+              (144, 36), (64, 144), (64, 36), (100, 100), (33, 47), (2, 2000), (250, 15)]
+
+
+@pytest.mark.parametrize("tiles_m,tiles_n", TILE_GRIDS)
+def test_tile_order_covers_every_tile_once(tiles_m, tiles_n):
+    tm, tn = sl.slope_tile_order(tiles_m, tiles_n)
+    live = tm >= 0
+    assert np.array_equal(live, tn >= 0)
+    assert (tm[live] < tiles_m).all() and (tn[live] < tiles_n).all()
+    flat = tm[live].astype(np.int64) * tiles_n + tn[live]
+    assert flat.size == tiles_m * tiles_n
+    assert np.array_equal(np.sort(flat), np.arange(tiles_m * tiles_n))
+
+
+@pytest.mark.parametrize("tiles_m,tiles_n", [g for g in TILE_GRIDS if g[0] * g[1] >= 256])
+def test_tile_order_balances_the_xcds(tiles_m, tiles_n):
+    # workgroups are dealt round-robin to 8 XCDs: no XCD may get much more than its share
+    tm, _ = sl.slope_tile_order(tiles_m, tiles_n)
+    per_xcd = np.array([(tm[x::8] >= 0).sum() for x in range(8)])
+    assert per_xcd.sum() == tiles_m * tiles_n
+    assert per_xcd.max() - per_xcd.min() <= 32          # one chunk of 8 x 4 tiles
+
+
+def test_tile_order_keeps_chunks_together():
+    # wide grids: the 32 tiles an XCD holds at a time form one 8 x 4 chunk
+    tm, tn = sl.slope_tile_order(36, 144)
+    for start in range(0, tm.size, 256):
+        for x in range(8):
+            a, b = tm[start + x:start + 256:8], tn[start + x:start + 256:8]
+            a, b = a[a >= 0], b[b >= 0]
+            if a.size:
+                assert a.max() - a.min() < 8 and b.max() - b.min() < 4 and a.min() % 8 == 0 and b.min() % 4 == 0
