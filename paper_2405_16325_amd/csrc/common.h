@@ -40,11 +40,12 @@ hipError_t launch_spmm_stream(const bf16_t* B, int64_t n, const bf16_t* A_vals, 
 constexpr int64_t XL_SMALL_MAX_TOKENS = 128;
 size_t xl_small_scratch_bytes(int64_t n, int64_t d_in, int64_t r);
 hipError_t launch_xl_small(const bf16_t* X, int64_t n, int64_t d_in, const bf16_t* L, int64_t r, float* scratch,
-                           bf16_t* T, hipStream_t s);
+                           bf16_t* T, hipStream_t s, const bf16_t* R = nullptr, int64_t d_out = 0,
+                           bf16_t* Rt = nullptr);
 // T[n, r] = X[n, K] * Lt[r, K]^T (dense), plus transposes of the adapter factors
 hipError_t launch_lowrank_prepare(const bf16_t* X, int64_t n, int64_t d_in, int64_t d_out, const bf16_t* L,
-                                  const bf16_t* R, int64_t r, bf16_t* T, bf16_t* Lt, bf16_t* Rt, hipStream_t s);
-hipError_t launch_transpose_factor(const bf16_t* in, int64_t rows, int64_t cols, bf16_t* out, hipStream_t s);
+                                  const bf16_t* R, int64_t r, bf16_t* T, bf16_t* Lt, bf16_t* Rt, float* partial_or_null,
+                                  hipStream_t s);
 hipError_t launch_wgrad_masked(const bf16_t* dY, const bf16_t* X, int64_t b, const uint8_t* meta, int64_t d_out,
                                int64_t d_in, bf16_t* gvals, hipStream_t s);
 // same result through token-contiguous copies of dY and X in `workspace`
@@ -53,8 +54,9 @@ hipError_t launch_wgrad_masked_ws(const bf16_t* dY, const bf16_t* X, int64_t b, 
                                   int64_t d_in, bf16_t* gvals, void* workspace, hipStream_t s);
 
 // C[n, m] = B[n, K] * A[m, K]^T (dense bf16, fp32 accumulation), K % 64 == 0
+size_t dense_tn_plain_partial_bytes(int64_t n, int64_t m);
 hipError_t launch_dense_tn_plain(const bf16_t* B, int64_t n, const bf16_t* A, int64_t m, int64_t K, bf16_t* C,
-                                 hipStream_t s);
+                                 float* partial_or_null, hipStream_t s);
 hipError_t launch_dense_tn_any(const bf16_t* B, int64_t n, const bf16_t* A, int64_t m, int64_t K, bf16_t* C,
                                hipStream_t s);
 // general N:M magnitude mask (M in {2, 4, 8}); axis 0: groups inside a row, axis 1: inside a column

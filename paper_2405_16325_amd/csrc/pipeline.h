@@ -60,6 +60,12 @@ inline int super_grid(int tiles_m, int tiles_n) {
     return (tiles + chunk - 1) / chunk * chunk;
 }
 
+// Row that a loader lane reads for tile row `row` of an operand with `rows` rows.  Rows past the
+// end only feed accumulators that are never stored, so any valid row will do; they are spread over
+// the operand (row % rows) rather than clamped to the last row, which would make that one row's
+// lines a hot spot of the L2 channel they live in (a ragged token tile ran 25 % slower that way).
+__device__ __forceinline__ int wrap_row(int row, int rows) { return row < rows ? row : row % rows; }
+
 // 64 lanes x 16 bytes: lane l's bytes land at lds_dst + 16 * l; lds_dst is wave-uniform
 __device__ __forceinline__ void dma16(const void* gsrc, uint8_t* lds_dst) {
     __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gsrc,

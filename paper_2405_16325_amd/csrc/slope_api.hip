@@ -56,8 +56,9 @@ static size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
 static size_t adapter_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out, int64_t r) {
     if (r <= 0) return 0;
     size_t tiles = round256((size_t)b * r * 2) + round256((size_t)d_in * r * 2) + round256((size_t)d_out * r * 2);
-    // few tokens: T = X L comes from a split over d_in whose partial sums also live here
-    return b <= XL_SMALL_MAX_TOKENS ? tiles + round256(xl_small_scratch_bytes(b, d_in, r)) : tiles;
+    // T = X L comes from a split over d_in whose partial sums also live here (none for many tokens)
+    return tiles + round256(b <= XL_SMALL_MAX_TOKENS ? xl_small_scratch_bytes(b, d_in, r)
+                                                     : dense_tn_plain_partial_bytes(b, r));
 }
 
 size_t slope_spmm_fwd_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out, int64_t r) {
@@ -126,14 +127,13 @@ slope_status slope_spmm_fwd(const void* X, int64_t b, const void* Wr_vals, const
     if (adapter) {
         bf16_t* Lt = (bf16_t*)(ws + round256((size_t)b * r * 2));
         bf16_t* Rt = (bf16_t*)((uint8_t*)Lt + round256((size_t)d_in * r * 2));
+        float* scratch = (float*)((uint8_t*)Rt + round256((size_t)d_out * r * 2));
         hipError_t e;
         if (b <= XL_SMALL_MAX_TOKENS) {   // too few tokens for the tile kernel to spread X L over the chip
-            float* scratch = (float*)((uint8_t*)Rt + round256((size_t)d_out * r * 2));
-            e = launch_xl_small(x, b, d_in, (const bf16_t*)L_or_null, r, scratch, T, s);
-            if (e == hipSuccess) e = launch_transpose_factor((const bf16_t*)R_or_null, r, d_out, Rt, s);
+            e = launch_xl_small(x, b, d_in, (const bf16_t*)L_or_null, r, scratch, T, s, (const bf16_t*)R_or_null, d_out, Rt);
         } else {
             e = launch_lowrank_prepare(x, b, d_in, d_out, (const bf16_t*)L_or_null, (const bf16_t*)R_or_null, r, T, Lt,
-                                       Rt, s);
+                                       Rt, dense_tn_plain_partial_bytes(b, r) ? scratch : nullptr, s);
         }
         if (e != hipSuccess) return finish(e);
         B2 = T;
@@ -181,7 +181,7 @@ slope_status slope_wgrad_masked(const void* dY, const void* X, int64_t b, const 
 
 size_t slope_spmm_bwd_x_adapter_workspace_bytes(int64_t b, int64_t r) {
     if (b <= 0 || r <= 0) return 0;
-    return round256((size_t)b * r * 2);
+    return round256((size_t)b * r * 2) + round256(dense_tn_plain_partial_bytes(b, r));
 }
 
 slope_status slope_spmm_bwd_x_adapter(const void* dY, int64_t b, const void* WrcT_vals, const void* WrcT_meta,
@@ -195,7 +195,9 @@ slope_status slope_spmm_bwd_x_adapter(const void* dY, int64_t b, const void* Wrc
         return SLOPE_ERR_ALIGN;
     hipStream_t s = (hipStream_t)stream;
     bf16_t* T2 = (bf16_t*)workspace;                          // dY R^T, bf16[b, r]
-    hipError_t e = launch_dense_tn_plain((const bf16_t*)dY, b, (const bf16_t*)R, r, d_out, T2, s);
+    float* partial = dense_tn_plain_partial_bytes(b, r)
+                         ? (float*)((uint8_t*)workspace + round256((size_t)b * r * 2)) : nullptr;
+    hipError_t e = launch_dense_tn_plain((const bf16_t*)dY, b, (const bf16_t*)R, r, d_out, T2, partial, s);
     if (e != hipSuccess) return finish(e);
     // sparse rows = d_in, contraction over d_out, then r more k-steps on T2 and L (K-contiguous as stored)
     return finish(launch_spmm((const bf16_t*)dY, b, (const bf16_t*)WrcT_vals, (const uint8_t*)WrcT_meta, d_in, d_out,

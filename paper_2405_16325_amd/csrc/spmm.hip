@@ -55,12 +55,12 @@ __device__ __forceinline__ void extend_and_store(f32x4 (&acc)[MF][NF], int f0, i
 #pragma unroll
         for (int i = 0; i < MF; ++i) {
             int row = f0 + i * 16 + l16;
-            a_row[i] = A2 + (size_t)(row < m ? row : m - 1) * K2 + lq * 8;
+            a_row[i] = A2 + (size_t)wrap_row(row, m) * K2 + lq * 8;
         }
 #pragma unroll
         for (int j = 0; j < NF; ++j) {
             int row = t0 + j * 16 + l16;
-            b_row[j] = B2 + (size_t)(row < n ? row : n - 1) * K2 + lq * 8;
+            b_row[j] = B2 + (size_t)wrap_row(row, n) * K2 + lq * 8;
         }
         AFrag a2[2][MF], b2[2][NF];
 #pragma unroll
@@ -146,21 +146,21 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_kernel(const bf16_t* __rest
 #pragma unroll
     for (int i = 0; i < A_LD; ++i) {
         int rl = (wave * A_LD + i) * 8 + (lane >> 3);         // row inside the tile
-        int row = m0 + rl < m ? m0 + rl : m - 1;
+        int row = wrap_row(m0 + rl, m);
         a_src[i] = (const uint8_t*)Av + (size_t)row * K + (((lane & 7) ^ ((rl >> 1) & 7)) * 16);
     }
     const uint8_t* b_src[B_LD];
 #pragma unroll
     for (int i = 0; i < B_LD; ++i) {
         int rl = (wave * B_LD + i) * 8 + (lane >> 3);
-        int row = n0 + rl < n ? n0 + rl : n - 1;
+        int row = wrap_row(n0 + rl, n);
         b_src[i] = (const uint8_t*)B + (size_t)row * K * 2 + (((lane & 7) ^ ((rl >> 1) & 7)) * 16);
     }
     const bool meta_wave = wave < M_WAVES;                    // wave-uniform
     const uint8_t* m_src;
     {
         int rl = (meta_wave ? wave : 0) * 32 + (lane >> 1);   // two lanes (16 bytes each) per row
-        int row = m0 + rl < m ? m0 + rl : m - 1;
+        int row = wrap_row(m0 + rl, m);
         m_src = Am + (size_t)row * (K / 8) + (lane & 1) * 16;
     }
     uint8_t* const m_dst0 = smem + (meta_wave ? S::M_OFF + wave * 1024 : S::DUMMY);
@@ -318,15 +318,15 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_split_kernel(const bf16_t* 
     for (int q = 0; q < 4; ++q) {
         int rl = ((q >> 1) * 16 + wave * 2 + (q & 1)) * 8 + (lane >> 3);     // row inside the tile
         int sw16 = ((lane & 7) ^ ((rl >> 1) & 7)) * 16;
-        int ra = m0 + rl < m ? m0 + rl : m - 1;
-        int rb = n0 + rl < n ? n0 + rl : n - 1;
+        int ra = wrap_row(m0 + rl, m);
+        int rb = wrap_row(n0 + rl, n);
         a_src[q] = (const uint8_t*)Av + (size_t)ra * K + sw16;
         b_src[q] = (const uint8_t*)B + (size_t)rb * K * 2 + sw16;
     }
     const uint8_t* m_src;                                    // 32 rows per wavefront, two lanes per row
     {
         int rl = wave * 32 + (lane >> 1);
-        int row = m0 + rl < m ? m0 + rl : m - 1;
+        int row = wrap_row(m0 + rl, m);
         m_src = Am + (size_t)row * (K / 8) + (lane & 1) * 16;
     }
 
@@ -472,7 +472,7 @@ __global__ void __launch_bounds__(256) spmm_generic_kernel(const bf16_t* __restr
 #pragma unroll
     for (int i = 0; i < A_LD; ++i) {
         int row = m0 + (wave * A_LD + i) * 16 + l16;
-        row = row < m ? row : m - 1;
+        row = wrap_row(row, m);
         a_src[i] = Av + (size_t)row * a_pitch + lq * 8;
     }
     const bf16_t* b_src[B_LD];
@@ -480,13 +480,13 @@ __global__ void __launch_bounds__(256) spmm_generic_kernel(const bf16_t* __restr
     for (int i = 0; i < B_LD; ++i) {
         int slot = wave * B_LD + i;
         int row = n0 + (slot >> 1) * 16 + l16;
-        row = row < n ? row : n - 1;
+        row = wrap_row(row, n);
         b_src[i] = B + (size_t)row * b_pitch + (slot & 1) * 32 + lq * 8;
     }
     const uint8_t* m_src;
     {
         int row = m0 + (t & 127);
-        row = row < m ? row : m - 1;
+        row = wrap_row(row, m);
         m_src = Am + (size_t)row * m_pitch;
     }
     f32x4 acc[MF][NF];
@@ -591,16 +591,17 @@ hipError_t launch_split(const bf16_t* B, int64_t n, const bf16_t* Av, const uint
 
 }  // namespace
 
-// A few dozen to a few hundred tokens: the token tile is so narrow that small weight tiles would
+// A few dozen to a thousand tokens: the token tile is so narrow that small weight tiles would
 // re-read it from L2 for every few weight rows (the tile kernels run at the L2 -> LDS rate), and
 // tall weight tiles alone are too few to fill the chip.  So: 256-row weight tiles, the k range
 // cut into slabs that run as separate workgroups and leave fp32 partial sums in `slabs`, and a
 // short reduction kernel (fixed order: bit-identical runs) that rounds to bf16.
-constexpr int64_t SLAB_MAX_TOKENS = 256;
+constexpr int64_t SLAB_MAX_TOKENS = 1024;
 
 int spmm_slab_count(int64_t n, int64_t m, int64_t K) {
     if (n <= STREAM_MAX_TOKENS || n > SLAB_MAX_TOKENS || K % 256 != 0) return 0;
     const int64_t tiles = ((m + 255) / 256) * ((n + 127) / 128);
+    if (tiles >= RESIDENT) return 0;                          // the chip is full without a split (measured: slabs lose)
     const int64_t quads = K / 256;                            // slabs are whole quads of k-steps
     // Estimate per slab count: the rounds of 256 workgroups, each pulling its share of the packed
     // weight at what one compute unit sustains with this tile (about 24 B/ns of weight bytes), plus

@@ -7,8 +7,8 @@
 //   - every operand goes through a ring in LDS that is private to the wavefront, fed by
 //     global -> LDS loads of full 128-byte lines and read back with ds_read_b128 in MFMA order:
 //     no barrier in the main loop, only the wavefront's own s_waitcnt;
-//   - the partial tiles are summed in a fixed order through LDS (bit-identical runs), and the
-//     adapter term is added there with plain fp32 FMAs on T = X L and the factor R as stored.
+//   - the partial tiles are summed in a fixed order through LDS (bit-identical runs); before that
+//     the adapter term is added on dense MFMA from T = X L and the factor R as stored.
 // T itself comes from a split over d_in (xl_partial_kernel, fp32 partial sums in the workspace)
 // followed by a fixed-order reduction that rounds to bf16 (xl_reduce_kernel).
 // (A first version kept the operands in registers and moved them into MFMA order with ds_bpermute;
@@ -167,23 +167,71 @@ __global__ void __launch_bounds__(WAVES * 64) spmm_stream_lds_kernel(const bf16_
                 part[(wave * S::BM + 16 * i + 4 * lq + e) * S::PART_PITCH + 16 * j + l16] = acc[i][j][e];
     __syncthreads();
 
-    // adapter operands into the ring, which is free now: T[n][K2] and the tile R[K2][BM] of the factor
-    bf16_t* const t_lds = (bf16_t*)smem;                      // [tok][K2]
-    bf16_t* const r_lds = t_lds + 16 * NF * K2;               // [k][BM]
+    // Adapter term T R on dense MFMA, in chunks of 128 of the rank, from operands staged in the ring
+    // (free now).  T[tok][k] is k-contiguous as stored; the tile of R[k][m0 .. m0 + BM) is k-major
+    // and is read with the transposing LDS read (lane s of a 16-lane block gets four consecutive k of
+    // column s; a row pitch of 160 bytes keeps its four rows on distinct banks).  Every wavefront
+    // adds the fragments it owns to its own partial tile, so the sum below stays in a fixed order.
     if (K2 > 0) {
-        for (int idx = t; idx < n * K2 / 8; idx += WAVES * 64)
-            ((u32x4*)t_lds)[idx] = ((const u32x4*)T)[idx];
-        constexpr int SEG = S::BM / 8;                        // 16-byte segments per row of the tile
-        for (int idx = t; idx < K2 * SEG; idx += WAVES * 64) {
-            int k = idx / SEG, sg = idx % SEG;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (m0 + 8 * sg < m) v = *(const u32x4*)(R + (size_t)k * m + m0 + 8 * sg);
-            *(u32x4*)(r_lds + k * S::BM + 8 * sg) = v;
+        constexpr int TP = 128 * 2 + 16, RP = 160;            // bytes per staged row of T and of R's tile
+        constexpr int FR = (MF * NF + WAVES - 1) / WAVES;     // fragments per wavefront
+        constexpr int SEG = S::BM / 8;                        // 16-byte segments per row of R's tile
+        static_assert(16 * NF * TP + 128 * RP <= S::RING, "adapter operands fit in the ring");
+        uint8_t* const t_lds = smem;                          // [16 NF tokens][TP]
+        uint8_t* const r_lds = smem + 16 * NF * TP;           // [128 k][RP]
+        f32x4 low[FR];
+#pragma unroll
+        for (int q = 0; q < FR; ++q) low[q] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int kc = 0; kc < K2; kc += 128) {
+            const int kn = K2 - kc < 128 ? K2 - kc : 128;     // a multiple of 32
+            for (int idx = t; idx < 16 * NF * 16; idx += WAVES * 64) {
+                int tok = idx >> 4, pc = idx & 15;
+                u32x4 v = {0u, 0u, 0u, 0u};
+                if (tok < n && pc * 8 < kn) v = *(const u32x4*)(T + (size_t)tok * K2 + kc + pc * 8);
+                *(u32x4*)(t_lds + tok * TP + pc * 16) = v;
+            }
+            for (int idx = t; idx < 128 * SEG; idx += WAVES * 64) {
+                int k = idx / SEG, sg = idx % SEG;
+                u32x4 v = {0u, 0u, 0u, 0u};
+                if (k < kn && m0 + 8 * sg < m) v = *(const u32x4*)(R + (size_t)(kc + k) * m + m0 + 8 * sg);
+                *(u32x4*)(r_lds + k * RP + sg * 16) = v;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int q = 0; q < FR; ++q) {
+                const int fi = wave + WAVES * q;              // wave-uniform
+                if (fi < MF * NF) {
+                    const int i = fi / NF, j = fi % NF;
+                    const uint8_t* ra = r_lds + (8 * lq + (l16 >> 2)) * RP + 2 * (16 * i + 4 * (l16 & 3));
+                    const uint8_t* tb = t_lds + (16 * j + l16) * TP + lq * 16;
+                    for (int ks = 0; ks * 32 < kn; ++ks) {
+                        union { s16x4 h[2]; bf16x8 v; } a;
+                        a.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (s16x4 __attribute__((address_space(3)))*)(ra + ks * 32 * RP));
+                        a.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (s16x4 __attribute__((address_space(3)))*)(ra + (ks * 32 + 4) * RP));
+                        StA b;
+                        b.u = *(const u32x4*)(tb + ks * 64);
+                        low[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, low[q], 0, 0, 0);
+                    }
+                }
+            }
+            __syncthreads();                                  // before the next chunk overwrites the operands
+        }
+#pragma unroll
+        for (int q = 0; q < FR; ++q) {
+            const int fi = wave + WAVES * q;
+            if (fi < MF * NF) {
+                const int i = fi / NF, j = fi % NF;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    part[(wave * S::BM + 16 * i + 4 * lq + e) * S::PART_PITCH + 16 * j + l16] += low[q][e];
+            }
         }
         __syncthreads();
     }
 
-    // fixed-order sum, adapter term, store: thread = (feature o, token tok)
+    // fixed-order sum and store: thread = (feature o, token tok)
     constexpr int TOK_GROUPS = WAVES * 64 / S::BM;            // whole groups of BM threads
     const int o = t % S::BM;
     for (int tok = t < TOK_GROUPS * S::BM ? t / S::BM : n; tok < n; tok += TOK_GROUPS) {
@@ -191,14 +239,6 @@ __global__ void __launch_bounds__(WAVES * 64) spmm_stream_lds_kernel(const bf16_
 #pragma unroll
         for (int w = 0; w < WAVES; ++w) v += part[(w * S::BM + o) * S::PART_PITCH + tok];
         if (m0 + o < m) {
-            if (K2 > 0) {
-                float low = 0.f;
-#pragma unroll 8
-                for (int k = 0; k < K2; ++k)
-                    low = __builtin_fmaf(__uint_as_float((uint32_t)t_lds[tok * K2 + k] << 16),
-                                         __uint_as_float((uint32_t)r_lds[k * S::BM + o] << 16), low);
-                v += low;
-            }
             union { __bf16 h; bf16_t u; } r;
             r.h = (__bf16)v;
             C[(size_t)tok * m + m0 + o] = r.u;
@@ -286,11 +326,127 @@ __global__ void __launch_bounds__(256) xl_partial_kernel(const bf16_t* __restric
     }
 }
 
+// The same partial sums on MFMA, for 17 to 128 tokens (where the multiply-adds above become the
+// bottleneck).  L is k-major (rows = d_in), the wrong way round for an MFMA operand, so a slab of
+// it is staged in LDS as stored and read back with the transposing read ds_read_b64_tr_b16: in
+// each block of 16 lanes, lane s receives four consecutive rows (k) of column s.  D rows are the
+// columns of L, D columns the tokens: a lane ends up with four consecutive columns of one token.
+//   workgroup = slab c of 64 * subs rows x 128 columns (blockIdx.y) x all tokens; wavefront w
+//   takes columns 32 w .. 32 w + 31; token rows come straight from global memory (k-contiguous).
+constexpr int XLM_PITCH = 128 * 2 + 32;      // bytes per staged row of L: pitch % 128 == 32 keeps the
+                                             // four rows of a transposing read on distinct banks
+__global__ void __launch_bounds__(256) xl_mfma_kernel(const bf16_t* __restrict__ X, int n, int d_in,
+                                                      const bf16_t* __restrict__ L, int r, int subs,
+                                                      float* __restrict__ P) {
+    extern __shared__ __align__(16) uint8_t smem[];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int l16 = lane & 15, lq = lane >> 4;
+    const int c = blockIdx.x, j0 = blockIdx.y * 128;
+    const int k0 = c * XL_CHUNK * subs;
+    int rows = d_in - k0;                                    // d_in % 64 == 0: whole chunks
+    if (rows > XL_CHUNK * subs) rows = XL_CHUNK * subs;
+    if (rows <= 0) return;                                   // uniform
+
+    // stage the slab: 16 pieces of 16 bytes per row, 16 rows per pass of the workgroup
+    {
+        const int pc = t & 15, col = j0 + pc * 8;
+        u32x4 v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            int row = u * 16 + (t >> 4);
+            v[u] = (u32x4){0u, 0u, 0u, 0u};
+            if (row < rows && col < r) v[u] = *(const u32x4*)(L + (size_t)(k0 + row) * r + col);
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            int row = u * 16 + (t >> 4);
+            if (row < rows) *(u32x4*)(smem + row * XLM_PITCH + pc * 16) = v[u];
+        }
+    }
+    __syncthreads();
+
+    const int ntf = (n + 15) / 16;                           // token fragments, at most 8
+    const bf16_t* x_row[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        int tok = 16 * j + l16;
+        x_row[j] = X + (size_t)(tok < n ? tok : tok % n) * d_in + k0 + lq * 8;
+    }
+    f32x4 acc[2][8];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    // lane (s = l16, q = lq) points at slab row 8 q + 4 h + s / 4, column 4 (s % 4) of a 16-column
+    // fragment; it receives k = 8 q + 4 h .. + 3 of column s
+    const uint8_t* tr = smem + (8 * lq + (l16 >> 2)) * XLM_PITCH + 2 * (32 * wave + 4 * (l16 & 3));
+    const int steps = rows / 32;
+    u32x4 xb[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+        if (j < ntf) xb[j] = *(const u32x4*)x_row[j];
+    for (int st = 0; st < steps; ++st) {
+        StA af[2], bf[8];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            union { s16x4 h[2]; bf16x8 v; } x;
+            x.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (s16x4 __attribute__((address_space(3)))*)(tr + st * 32 * XLM_PITCH + 32 * i));
+            x.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (s16x4 __attribute__((address_space(3)))*)(tr + (st * 32 + 4) * XLM_PITCH + 32 * i));
+            af[i].v = x.v;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) bf[j].u = xb[j];
+        if (st + 1 < steps) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (j < ntf) xb[j] = *(const u32x4*)(x_row[j] + (st + 1) * 32);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (j < ntf) {
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i].v, bf[j].v, acc[i][j], 0, 0, 0);
+            }
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        int tok = 16 * j + l16;
+        if (tok >= n) continue;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            int col = j0 + 32 * wave + 16 * i + 4 * lq;
+            if (col < r) *(f32x4*)(P + ((size_t)c * n + tok) * r + col) = acc[i][j];
+        }
+    }
+}
+
 // T[idx] = bf16( sum over chunks of P[c][idx] ), idx = t * r + k, in a fixed order: a workgroup
 // takes 32 outputs; its 8 wavefront-halves each sum every 8th chunk, then the 8 sums are added
 // in order through LDS.
+// Workgroups past the first red_blocks copy the other factor into k-contiguous form instead,
+// Rt[c][k] = R[k][c] in 64 x 64 tiles (saves the tile kernels' caller a launch of its own).
 __global__ void __launch_bounds__(256) xl_reduce_kernel(const float* __restrict__ P, int chunks, int count,
-                                                        bf16_t* __restrict__ T) {
+                                                        bf16_t* __restrict__ T, int red_blocks,
+                                                        const bf16_t* __restrict__ R, int r_rows, int r_cols,
+                                                        bf16_t* __restrict__ Rt) {
+    if ((int)blockIdx.x >= red_blocks) {
+        __shared__ bf16_t tile[64][66];
+        const int tb = blockIdx.x - red_blocks, tiles_c = (r_cols + 63) / 64;
+        const int r0 = (tb / tiles_c) * 64, c0 = (tb % tiles_c) * 64;
+        for (int idx = threadIdx.x; idx < 64 * 64; idx += 256) {
+            int rr = idx >> 6, c = idx & 63;
+            tile[rr][c] = (r0 + rr < r_rows && c0 + c < r_cols) ? R[(size_t)(r0 + rr) * r_cols + c0 + c] : (bf16_t)0;
+        }
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < 64 * 64; idx += 256) {
+            int c = idx >> 6, rr = idx & 63;
+            if (r0 + rr < r_rows && c0 + c < r_cols) Rt[(size_t)(c0 + c) * r_rows + r0 + rr] = tile[rr][c];
+        }
+        return;
+    }
     __shared__ float red[8][33];
     const int o = threadIdx.x & 31, cl = threadIdx.x >> 5;
     const int idx = blockIdx.x * 32 + o;
@@ -351,30 +507,43 @@ hipError_t launch_spmm_stream(const bf16_t* B, int64_t n, const bf16_t* A_vals, 
     return launch_stream_lds<2, 4, 2>(B, n, A_vals, A_meta, m, K, T, R, K2, C, s);
 }
 
-// T = X L for few tokens (up to 128), split over d_in; scratch holds xl_small_scratch_bytes
-// slabs of L per launch: single chunks of 64 rows for up to 32 tokens, four chunks beyond (the
-// partial sums then stay a few MB)
-static int xl_subs(int64_t n) { return n <= 32 ? 1 : 4; }
+// T = X L for few tokens (up to 128), split over d_in; scratch holds xl_small_scratch_bytes.
+// Slabs of L per workgroup: single chunks of 64 rows for up to 32 tokens; beyond, up to four
+// chunks (smaller partial sums) as long as the launch still has a workgroup for every compute
+// unit.  Up to 16 tokens run on fp32 multiply-adds (xl_partial_kernel), more on MFMA.
+static int xl_subs(int64_t n, int64_t d_in, int64_t r) {
+    if (n <= 32) return 1;
+    const int64_t per_slab = (r + 127) / 128;                // workgroups per slab
+    for (int subs = 4; subs > 1; subs /= 2)
+        if ((d_in + XL_CHUNK * subs - 1) / (XL_CHUNK * subs) * per_slab >= RESIDENT) return subs;
+    return 1;
+}
 
 size_t xl_small_scratch_bytes(int64_t n, int64_t d_in, int64_t r) {
-    const int64_t rows = (int64_t)XL_CHUNK * xl_subs(n);
+    const int64_t rows = (int64_t)XL_CHUNK * xl_subs(n, d_in, r);
     return (size_t)((d_in + rows - 1) / rows) * (size_t)n * (size_t)r * 4;
 }
 
+// With Rt the launch of the reduction also writes Rt[d_out][r] = R[r][d_out]^T.
 hipError_t launch_xl_small(const bf16_t* X, int64_t n, int64_t d_in, const bf16_t* L, int64_t r, float* scratch,
-                           bf16_t* T, hipStream_t s) {
-    const int subs = xl_subs(n);
+                           bf16_t* T, hipStream_t s, const bf16_t* R, int64_t d_out, bf16_t* Rt) {
+    const int subs = xl_subs(n, d_in, r);
     const int slabs = (int)((d_in + XL_CHUNK * subs - 1) / (XL_CHUNK * subs));
     if (n <= 16) {
         dim3 grid((unsigned)slabs, (unsigned)((r + 127) / 128), 1);
         xl_partial_kernel<16><<<grid, dim3(256), 0, s>>>(X, (int)n, (int)d_in, L, (int)r, subs, scratch);
     } else {
-        dim3 grid((unsigned)slabs, (unsigned)((r + 127) / 128), (unsigned)((n + 31) / 32));
-        xl_partial_kernel<32><<<grid, dim3(256), 0, s>>>(X, (int)n, (int)d_in, L, (int)r, subs, scratch);
+        const int lds = XL_CHUNK * subs * XLM_PITCH;
+        hipError_t e = hipFuncSetAttribute((const void*)xl_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        dim3 grid((unsigned)slabs, (unsigned)((r + 127) / 128), 1);
+        xl_mfma_kernel<<<grid, dim3(256), lds, s>>>(X, (int)n, (int)d_in, L, (int)r, subs, scratch);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const int count = (int)(n * r);
-    xl_reduce_kernel<<<dim3((unsigned)((count + 31) / 32)), dim3(256), 0, s>>>(scratch, slabs, count, T);
+    const int count = (int)(n * r), red_blocks = (count + 31) / 32;
+    const int tr_blocks = Rt ? (int)(((r + 63) / 64) * ((d_out + 63) / 64)) : 0;
+    xl_reduce_kernel<<<dim3((unsigned)(red_blocks + tr_blocks)), dim3(256), 0, s>>>(scratch, slabs, count, T, red_blocks,
+                                                                                   R, (int)r, (int)d_out, Rt);
     return hipGetLastError();
 }

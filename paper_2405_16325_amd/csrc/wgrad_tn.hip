@@ -110,7 +110,8 @@ template <int BM, int BN, int EPI, int NS>
 __global__ void __launch_bounds__(TN_THREADS) dense_tn_kernel(const bf16_t* __restrict__ At, int m,
                                                               const bf16_t* __restrict__ Bt, int n, int kp,
                                                               int ld, const uint8_t* __restrict__ meta,
-                                                              bf16_t* __restrict__ out, int tiles_m, int tiles_n) {
+                                                              bf16_t* __restrict__ out, int tiles_m, int tiles_n,
+                                                              int slab_steps, float* __restrict__ partial) {
     using S = TnSmem<BM, BN, NS>;
     constexpr int MF = BM / 32, NF = BN / 64;                // 16 x 16 fragments per wavefront (2 x 4 waves)
     constexpr int LD_A = BM / 64, LD_B = BN / 64;            // 1 KiB loads per wavefront per step
@@ -127,22 +128,26 @@ __global__ void __launch_bounds__(TN_THREADS) dense_tn_kernel(const bf16_t* __re
     const int wm = wave & 1, wn = wave >> 1;
     const int l16 = lane & 15, lq = lane >> 4;
 
-    // loader lanes: 8 lanes per row, chunk rotated by (row / 2) % 8 (rows clamped, never stored)
+    // loader lanes: 8 lanes per row, chunk rotated by (row / 2) % 8 (rows past the end wrapped, never stored)
     const uint8_t* a_src[LD_A];
     const uint8_t* b_src[LD_B];
 #pragma unroll
     for (int i = 0; i < LD_A; ++i) {
         int rl = (wave * LD_A + i) * 8 + (lane >> 3);
-        int ra = m0 + rl < m ? m0 + rl : m - 1;
+        int ra = wrap_row(m0 + rl, m);
         a_src[i] = (const uint8_t*)At + (size_t)ra * ld * 2 + (((lane & 7) ^ ((rl >> 1) & 7)) * 16);
     }
 #pragma unroll
     for (int i = 0; i < LD_B; ++i) {
         int rl = (wave * LD_B + i) * 8 + (lane >> 3);
-        int rb = n0 + rl < n ? n0 + rl : n - 1;
+        int rb = wrap_row(n0 + rl, n);
         b_src[i] = (const uint8_t*)Bt + (size_t)rb * ld * 2 + (((lane & 7) ^ ((rl >> 1) & 7)) * 16);
     }
     const int ksteps = kp / 64;
+    // with `partial` the k range is cut into slabs of slab_steps k-steps, one per blockIdx.y, each
+    // leaving fp32 sums; the look-ahead past a slab's end reads real (unused) data
+    const int k_begin = partial ? (int)blockIdx.y * slab_steps : 0;
+    const int k_end = partial && k_begin + slab_steps < ksteps ? k_begin + slab_steps : ksteps;
     auto issue = [&](int ks) {                               // k-step ks (clamped) into stage ks % NS
         int kc = ks < ksteps ? ks : ksteps - 1;
         uint8_t* st = smem + (ks % NS) * S::STAGE;
@@ -198,16 +203,16 @@ __global__ void __launch_bounds__(TN_THREADS) dense_tn_kernel(const bf16_t* __re
         wg_barrier();                                                                                  \
     }
 #pragma unroll
-    for (int p = 0; p < NS - 1; ++p) issue(p);
-    WAIT_HERE(waitcnt_imm(AHEAD, 15));                        // step 0 has landed (this wave's share)
+    for (int p = 0; p < NS - 1; ++p) issue(k_begin + p);
+    WAIT_HERE(waitcnt_imm(AHEAD, 15));                        // the first step has landed (this wave's share)
     wg_barrier();
     if (group == 0) {
-        for (int ks = 0; ks < ksteps; ++ks) TN_STEP(0)
+        for (int ks = k_begin; ks < k_end; ++ks) TN_STEP(0)
         wg_barrier();
     } else {
-        issue(NS - 1);
+        issue(k_begin + NS - 1);
         wg_barrier();
-        for (int ks = 0; ks < ksteps; ++ks) TN_STEP(1)
+        for (int ks = k_begin; ks < k_end; ++ks) TN_STEP(1)
     }
 #undef TN_STEP
     WAIT_HERE(waitcnt_imm(0, 15));                            // drain the clamped look-ahead loads
@@ -222,6 +227,10 @@ __global__ void __launch_bounds__(TN_THREADS) dense_tn_kernel(const bf16_t* __re
                 int col = m0 + wm * WM + i * 16 + lq * 4;
                 if (col >= m) continue;
                 f32x4 v = acc[i][j];
+                if (partial) {
+                    *(f32x4*)(partial + ((size_t)blockIdx.y * n + row) * m + col) = v;
+                    continue;
+                }
                 union { __bf16 h[4]; u32x2 u; } o;
                 o.h[0] = (__bf16)v[0]; o.h[1] = (__bf16)v[1]; o.h[2] = (__bf16)v[2]; o.h[3] = (__bf16)v[3];
                 *(u32x2*)(out + (size_t)row * m + col) = o.u;
@@ -230,6 +239,21 @@ __global__ void __launch_bounds__(TN_THREADS) dense_tn_kernel(const bf16_t* __re
         return;
     }
     store_masked_packed<MF, NF>(acc, m, n, m0 + wm * WM, n0 + wn * NF * 16, l16, lq, meta, out);
+}
+
+// out = sum over the slabs (in slab order: runs are bit-identical), rounded to bf16; four elements per lane
+__global__ void __launch_bounds__(256) partial_reduce_kernel(const f32x4* __restrict__ P, int nslabs, size_t count4,
+                                                             u32x2* __restrict__ out) {
+    size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= count4) return;
+    f32x4 v = P[idx];
+    for (int sl = 1; sl < nslabs; ++sl) {
+        f32x4 w = P[(size_t)sl * count4 + idx];
+        v[0] += w[0]; v[1] += w[1]; v[2] += w[2]; v[3] += w[3];
+    }
+    union { __bf16 h[4]; u32x2 u; } o;
+    o.h[0] = (__bf16)v[0]; o.h[1] = (__bf16)v[1]; o.h[2] = (__bf16)v[2]; o.h[3] = (__bf16)v[3];
+    out[idx] = o.u;
 }
 
 // The 256 x 256 tile of the weight gradient with split rings.  A plain two-stage ring (all that
@@ -269,7 +293,7 @@ __global__ void __launch_bounds__(TN_THREADS) dense_tn_split_kernel(const bf16_t
     const int wm = wave & 1, wn = wave >> 1;
     const int l16 = lane & 15, lq = lane >> 4;
 
-    // loader lanes: 8 lanes per row, chunk rotated by (row / 2) % 8 (rows clamped, never stored).
+    // loader lanes: 8 lanes per row, chunk rotated by (row / 2) % 8 (rows past the end wrapped, never stored).
     // Each load set (half of A, half of B) is 16 loads of 8 rows: two per wavefront.
     const uint8_t* a_src[4];                                 // [half * 2 + i]
     const uint8_t* b_src[4];                                 // [group * 2 + i]
@@ -277,8 +301,8 @@ __global__ void __launch_bounds__(TN_THREADS) dense_tn_split_kernel(const bf16_t
     for (int q = 0; q < 4; ++q) {
         int rl = ((q >> 1) * 16 + wave * 2 + (q & 1)) * 8 + (lane >> 3);     // row inside the tile
         int sw16 = ((lane & 7) ^ ((rl >> 1) & 7)) * 16;
-        int ra = m0 + rl < m ? m0 + rl : m - 1;
-        int rb = n0 + rl < n ? n0 + rl : n - 1;
+        int ra = wrap_row(m0 + rl, m);
+        int rb = wrap_row(n0 + rl, n);
         a_src[q] = (const uint8_t*)At + (size_t)ra * ld * 2 + sw16;
         b_src[q] = (const uint8_t*)Bt + (size_t)rb * ld * 2 + sw16;
     }
@@ -379,15 +403,16 @@ __global__ void __launch_bounds__(TN_THREADS) dense_tn_split_kernel(const bf16_t
 
 template <int BM, int BN, int EPI, int NS>
 hipError_t launch_dense_tn(const bf16_t* At, int64_t m, const bf16_t* Bt, int64_t n, int64_t kp, int64_t ld,
-                           const uint8_t* meta, bf16_t* out, hipStream_t s) {
+                           const uint8_t* meta, bf16_t* out, hipStream_t s, int nslabs = 1, int slab_steps = 0,
+                           float* partial = nullptr) {
     using S = TnSmem<BM, BN, NS>;
     static_assert(S::TOTAL <= 160 * 1024, "LDS budget");
     int tiles_m = (int)((m + BM - 1) / BM), tiles_n = (int)((n + BN - 1) / BN);
     auto kern = dense_tn_kernel<BM, BN, EPI, NS>;
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, S::TOTAL);
     if (e != hipSuccess) return e;
-    kern<<<dim3((unsigned)super_grid(tiles_m, tiles_n)), dim3(TN_THREADS), S::TOTAL, s>>>(
-        At, (int)m, Bt, (int)n, (int)kp, (int)ld, meta, out, tiles_m, tiles_n);
+    kern<<<dim3((unsigned)super_grid(tiles_m, tiles_n), (unsigned)nslabs), dim3(TN_THREADS), S::TOTAL, s>>>(
+        At, (int)m, Bt, (int)n, (int)kp, (int)ld, meta, out, tiles_m, tiles_n, slab_steps, partial);
     return hipGetLastError();
 }
 
@@ -437,9 +462,32 @@ hipError_t launch_wgrad_masked_ws(const bf16_t* dY, const bf16_t* X, int64_t b, 
 // C[n, m] = B[n, K] * A[m, K]^T, all bf16 row-major, K % 64 == 0 (the skinny product T = X L of the
 // adapter: m = rank).  The product is bound by streaming B once: narrow token tiles so that even
 // m = 128 gives every compute unit a tile, and a six-deep ring to keep enough reads in flight.
+//
+// A few hundred to a few thousand tokens give that product only a handful of tiles with a long
+// contraction each.  With scratch memory (`partial`, dense_tn_plain_partial_bytes(n, m) bytes) the
+// contraction is then cut into slabs that run as separate workgroups, about 256 in all, and leave
+// fp32 sums that a second kernel adds in slab order.
+size_t dense_tn_plain_partial_bytes(int64_t n, int64_t m) {
+    const int64_t tiles = ((m + 127) / 128) * ((n + 63) / 64);
+    if (tiles >= RESIDENT / 2) return 0;
+    return (size_t)((RESIDENT + tiles - 1) / tiles) * (size_t)n * (size_t)m * 4;
+}
+
 hipError_t launch_dense_tn_plain(const bf16_t* B, int64_t n, const bf16_t* A, int64_t m, int64_t K, bf16_t* C,
-                                 hipStream_t s) {
-    return launch_dense_tn<128, 64, EPI_PLAIN, 6>(A, m, B, n, K, K, nullptr, C, s);
+                                 float* partial, hipStream_t s) {
+    const int64_t tiles = ((m + 127) / 128) * ((n + 63) / 64), ksteps = K / 64;
+    int64_t nslabs = partial && tiles < RESIDENT / 2 ? (RESIDENT + tiles - 1) / tiles : 1;
+    if (nslabs > ksteps / 8) nslabs = ksteps / 8;            // at least eight k-steps per slab
+    if (nslabs <= 1) return launch_dense_tn<128, 64, EPI_PLAIN, 6>(A, m, B, n, K, K, nullptr, C, s);
+    const int64_t slab_steps = (ksteps + nslabs - 1) / nslabs;
+    nslabs = (ksteps + slab_steps - 1) / slab_steps;
+    hipError_t e = launch_dense_tn<128, 64, EPI_PLAIN, 6>(A, m, B, n, K, K, nullptr, C, s, (int)nslabs, (int)slab_steps,
+                                                          partial);
+    if (e != hipSuccess) return e;
+    const size_t count4 = (size_t)n * (size_t)m / 4;
+    partial_reduce_kernel<<<dim3((unsigned)((count4 + 255) / 256)), dim3(256), 0, s>>>((const f32x4*)partial, (int)nslabs,
+                                                                                     count4, (u32x2*)C);
+    return hipGetLastError();
 }
 
 // The same product for any shape (dense weights with a general N:M mask, where no sparse MFMA
@@ -495,8 +543,8 @@ hipError_t launch_wgrad_adapter(const bf16_t* dY, const bf16_t* X, int64_t b, co
     if (e != hipSuccess) return e;
     launch_transpose_pad(L, d_in, r, d_in, d_in, Lt, s);                          // Lt[r][d_in]
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    if ((e = launch_dense_tn_plain(X, b, Lt, r, d_in, T, s)) != hipSuccess) return e;      // T  = X L
-    if ((e = launch_dense_tn_plain(dY, b, R, r, d_out, T2, s)) != hipSuccess) return e;    // T2 = dY R^T
+    if ((e = launch_dense_tn_plain(X, b, Lt, r, d_in, T, nullptr, s)) != hipSuccess) return e;      // T  = X L
+    if ((e = launch_dense_tn_plain(dY, b, R, r, d_out, T2, nullptr, s)) != hipSuccess) return e;    // T2 = dY R^T
     launch_transpose_pad(T, b, r, bp, ld, Tt, s);
     launch_transpose_pad(T2, b, r, bp, ld, T2t, s);
     if ((e = hipGetLastError()) != hipSuccess) return e;
