@@ -407,7 +407,7 @@ def cpu_baseline(lay, b, rank):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         cores = os.cpu_count() or 1
-    rows, toks = min(4096, lay["d_out"]), min(1024, b)                # about 10 s of host work
+    rows, toks = min(8192, lay["d_out"]), min(1024, b)                # about 10 s of host work
     d_in = lay["d_in"]
     w = sl.bf16_to_host(lay["W"][:rows])
     x = sl.bf16_to_host(lay["X"][:toks])
