@@ -37,7 +37,7 @@ constexpr int64_t STREAM_MAX_TOKENS = 32;
 hipError_t launch_spmm_stream(const bf16_t* B, int64_t n, const bf16_t* A_vals, const uint8_t* A_meta, int64_t m,
                               int64_t K, const bf16_t* T, const bf16_t* R, int64_t K2, bf16_t* C, hipStream_t s);
 // T = X L for few tokens (n <= XL_SMALL_MAX_TOKENS), split over d_in with fp32 partial sums in `scratch`
-constexpr int64_t XL_SMALL_MAX_TOKENS = 128;
+constexpr int64_t XL_SMALL_MAX_TOKENS = 512;
 size_t xl_small_scratch_bytes(int64_t n, int64_t d_in, int64_t r);
 hipError_t launch_xl_small(const bf16_t* X, int64_t n, int64_t d_in, const bf16_t* L, int64_t r, float* scratch,
                            bf16_t* T, hipStream_t s, const bf16_t* R = nullptr, int64_t d_out = 0,

@@ -326,13 +326,15 @@ __global__ void __launch_bounds__(256) xl_partial_kernel(const bf16_t* __restric
     }
 }
 
-// The same partial sums on MFMA, for 17 to 128 tokens (where the multiply-adds above become the
-// bottleneck).  L is k-major (rows = d_in), the wrong way round for an MFMA operand, so a slab of
-// it is staged in LDS as stored and read back with the transposing read ds_read_b64_tr_b16: in
-// each block of 16 lanes, lane s receives four consecutive rows (k) of column s.  D rows are the
+// The same partial sums on MFMA, from 17 tokens (where the multiply-adds above become the
+// bottleneck) to XL_SMALL_MAX_TOKENS.  L is k-major (rows = d_in), the wrong way round for an
+// MFMA operand, so a slab of it is staged in LDS as stored and read back with the transposing read
+// ds_read_b64_tr_b16: in each block of 16 lanes, lane s receives four consecutive rows (k) of
+// column s.  D rows are the
 // columns of L, D columns the tokens: a lane ends up with four consecutive columns of one token.
-//   workgroup = slab c of 64 * subs rows x 128 columns (blockIdx.y) x all tokens; wavefront w
-//   takes columns 32 w .. 32 w + 31; token rows come straight from global memory (k-contiguous).
+//   workgroup = slab c of 64 * subs rows x 128 columns (blockIdx.y) x 128 tokens (blockIdx.z);
+//   wavefront w takes columns 32 w .. 32 w + 31; token rows come straight from global memory
+//   (k-contiguous).
 constexpr int XLM_PITCH = 128 * 2 + 32;      // bytes per staged row of L: pitch % 128 == 32 keeps the
                                              // four rows of a transposing read on distinct banks
 __global__ void __launch_bounds__(256) xl_mfma_kernel(const bf16_t* __restrict__ X, int n, int d_in,
@@ -365,12 +367,13 @@ __global__ void __launch_bounds__(256) xl_mfma_kernel(const bf16_t* __restrict__
     }
     __syncthreads();
 
-    const int ntf = (n + 15) / 16;                           // token fragments, at most 8
+    const int t0 = blockIdx.z * 128;
+    const int ntf = ((n - t0 < 128 ? n - t0 : 128) + 15) / 16;   // token fragments of this workgroup, at most 8
     const bf16_t* x_row[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        int tok = 16 * j + l16;
-        x_row[j] = X + (size_t)(tok < n ? tok : tok % n) * d_in + k0 + lq * 8;
+        int tok = t0 + 16 * j + l16;
+        x_row[j] = X + (size_t)(tok < n ? tok : t0) * d_in + k0 + lq * 8;
     }
     f32x4 acc[2][8];
 #pragma unroll
@@ -413,7 +416,7 @@ __global__ void __launch_bounds__(256) xl_mfma_kernel(const bf16_t* __restrict__
     }
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        int tok = 16 * j + l16;
+        int tok = t0 + 16 * j + l16;
         if (tok >= n) continue;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
@@ -507,13 +510,13 @@ hipError_t launch_spmm_stream(const bf16_t* B, int64_t n, const bf16_t* A_vals, 
     return launch_stream_lds<2, 4, 2>(B, n, A_vals, A_meta, m, K, T, R, K2, C, s);
 }
 
-// T = X L for few tokens (up to 128), split over d_in; scratch holds xl_small_scratch_bytes.
+// T = X L for few tokens (up to XL_SMALL_MAX_TOKENS), split over d_in; scratch holds xl_small_scratch_bytes.
 // Slabs of L per workgroup: single chunks of 64 rows for up to 32 tokens; beyond, up to four
 // chunks (smaller partial sums) as long as the launch still has a workgroup for every compute
 // unit.  Up to 16 tokens run on fp32 multiply-adds (xl_partial_kernel), more on MFMA.
 static int xl_subs(int64_t n, int64_t d_in, int64_t r) {
     if (n <= 32) return 1;
-    const int64_t per_slab = (r + 127) / 128;                // workgroups per slab
+    const int64_t per_slab = ((r + 127) / 128) * ((n + 127) / 128);   // workgroups per slab
     for (int subs = 4; subs > 1; subs /= 2)
         if ((d_in + XL_CHUNK * subs - 1) / (XL_CHUNK * subs) * per_slab >= RESIDENT) return subs;
     return 1;
@@ -536,7 +539,7 @@ hipError_t launch_xl_small(const bf16_t* X, int64_t n, int64_t d_in, const bf16_
         const int lds = XL_CHUNK * subs * XLM_PITCH;
         hipError_t e = hipFuncSetAttribute((const void*)xl_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
-        dim3 grid((unsigned)slabs, (unsigned)((r + 127) / 128), 1);
+        dim3 grid((unsigned)slabs, (unsigned)((r + 127) / 128), (unsigned)((n + 127) / 128));
         xl_mfma_kernel<<<grid, dim3(256), lds, s>>>(X, (int)n, (int)d_in, L, (int)r, subs, scratch);
     }
     hipError_t e = hipGetLastError();
