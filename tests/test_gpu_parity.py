@@ -168,7 +168,9 @@ def test_wgrad_masked(b, d_out, d_in, ws):
                                             (16, 512, 768, 64), (1, 1280, 256, 32), (32, 4160, 1024, 128), (7, 448, 320, 288),
                                             (16, 8320, 256, 64), (5, 13696, 256, 512),
                                             (200, 4160, 2048, 64), (100, 768, 4096, 128), (48, 512, 8192, 32), (32, 8320, 256, 64),
-                                            (50, 128, 192, 160)])
+                                            (50, 128, 192, 160),
+                                            # the MFMA split of X L: several column groups of the rank, token groups of 128
+                                            (130, 512, 768, 288), (500, 1024, 1024, 512), (40, 768, 512, 160), (20, 4160, 640, 96)])
 def test_spmm_fwd_with_adapter(b, d_out, d_in, r):
     say(f"spmm_fwd adapter b={b} d_out={d_out} d_in={d_in} r={r}")
     t, d, mask_r, _ = layer_on_device(b, d_out, d_in, r, seed=r + b)
