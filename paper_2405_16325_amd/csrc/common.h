@@ -22,7 +22,8 @@ hipError_t launch_update_transposed(const bf16_t* vals, const uint8_t* meta, int
                                     const uint8_t* metaT, bf16_t* valsT, hipStream_t s);
 hipError_t launch_sparse_add(const bf16_t* a, const bf16_t* b, size_t count, float beta, float gamma, bf16_t* out,
                              hipStream_t s);
-// C[n, m] = B[n, K] * Asparse[m, K]^T  (+ B2[n, K2] * A2[m, K2]^T dense when K2 > 0)
+// C[n, m] = B[n, K] * Asparse[m, K]^T  (+ B2[n, |K2|] * A2^T dense: K2 > 0 with A2 = [m][K2], k-contiguous;
+// K2 < 0 with A2 = [-K2][m], k-major, the way the adapter factor R is stored)
 hipError_t launch_spmm(const bf16_t* B, int64_t n, const bf16_t* A_vals, const uint8_t* A_meta, int64_t m,
                        int64_t K, const bf16_t* B2, const bf16_t* A2, int64_t K2, bf16_t* C, hipStream_t s);
 // the same product for a few dozen to a few hundred tokens, split over K with fp32 partial sums in `slabs`
@@ -40,12 +41,10 @@ hipError_t launch_spmm_stream(const bf16_t* B, int64_t n, const bf16_t* A_vals, 
 constexpr int64_t XL_SMALL_MAX_TOKENS = 512;
 size_t xl_small_scratch_bytes(int64_t n, int64_t d_in, int64_t r);
 hipError_t launch_xl_small(const bf16_t* X, int64_t n, int64_t d_in, const bf16_t* L, int64_t r, float* scratch,
-                           bf16_t* T, hipStream_t s, const bf16_t* R = nullptr, int64_t d_out = 0,
-                           bf16_t* Rt = nullptr);
+                           bf16_t* T, hipStream_t s);
 // T[n, r] = X[n, K] * Lt[r, K]^T (dense), plus transposes of the adapter factors
-hipError_t launch_lowrank_prepare(const bf16_t* X, int64_t n, int64_t d_in, int64_t d_out, const bf16_t* L,
-                                  const bf16_t* R, int64_t r, bf16_t* T, bf16_t* Lt, bf16_t* Rt, float* partial_or_null,
-                                  hipStream_t s);
+hipError_t launch_lowrank_prepare(const bf16_t* X, int64_t n, int64_t d_in, const bf16_t* L, int64_t r, bf16_t* T,
+                                  bf16_t* Lt, float* partial_or_null, hipStream_t s);
 hipError_t launch_wgrad_masked(const bf16_t* dY, const bf16_t* X, int64_t b, const uint8_t* meta, int64_t d_out,
                                int64_t d_in, bf16_t* gvals, hipStream_t s);
 // same result through token-contiguous copies of dY and X in `workspace`

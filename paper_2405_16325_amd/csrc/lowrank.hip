@@ -1,11 +1,12 @@
-// Adapter preparation for slope_spmm_fwd (Eq. 11): T = X L, and K-contiguous copies of L and R.
+// Adapter preparation for slope_spmm_fwd (Eq. 11) with many tokens: T = X L.
 //
 // The paper concatenates L to the sparse weight so that one vendor SpMM call yields [Y1 | Y2] and
-// a second fused GEMM adds Y2 R.  Here the sparse kernel's main loop is simply extended by r more
-// k-steps on dense MFMA (operands T and R^T), so only the skinny product T = X L is a kernel of
-// its own (the dense tile kernel with a plain epilogue, split over d_in while its tiles are too few
-// to fill the chip); it is bound by reading X once.  With up to 128 tokens the FMA split over d_in
-// in spmm_stream.hip computes T instead, and its reduction launch also makes the copy of R.
+// a second fused GEMM adds Y2 R.  Here the sparse kernel is simply extended by r more k-steps on
+// dense MFMA (operands T and R as stored), so only the skinny product T = X L is a kernel of its
+// own: the dense tile kernel with a plain epilogue on a k-contiguous copy of L, split over d_in
+// while its tiles are too few to fill the chip; it is bound by reading X once.  With up to
+// XL_SMALL_MAX_TOKENS tokens the split over d_in in spmm_stream.hip computes T instead, from L as
+// stored.
 #include "common.h"
 
 namespace {
@@ -28,14 +29,11 @@ __global__ void __launch_bounds__(256) transpose_kernel(const bf16_t* __restrict
 
 }  // namespace
 
-hipError_t launch_lowrank_prepare(const bf16_t* X, int64_t n, int64_t d_in, int64_t d_out, const bf16_t* L,
-                                  const bf16_t* R, int64_t r, bf16_t* T, bf16_t* Lt, bf16_t* Rt, float* partial_or_null,
-                                  hipStream_t s) {
-    // L[d_in, r] -> Lt[r, d_in];  R[r, d_out] -> Rt[d_out, r]
+hipError_t launch_lowrank_prepare(const bf16_t* X, int64_t n, int64_t d_in, const bf16_t* L, int64_t r, bf16_t* T,
+                                  bf16_t* Lt, float* partial_or_null, hipStream_t s) {
+    // L[d_in, r] -> Lt[r, d_in]
     transpose_kernel<<<dim3((unsigned)((r + 63) / 64), (unsigned)((d_in + 63) / 64)), dim3(256), 0, s>>>(
         L, (int)d_in, (int)r, Lt);
-    transpose_kernel<<<dim3((unsigned)((d_out + 63) / 64), (unsigned)((r + 63) / 64)), dim3(256), 0, s>>>(
-        R, (int)r, (int)d_out, Rt);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return launch_dense_tn_plain(X, n, Lt, r, d_in, T, partial_or_null, s);   // T[n, r] = X[n, d_in] * Lt[r, d_in]^T

@@ -52,10 +52,11 @@ size_t slope_mask_bytes(int64_t rows, int64_t cols) { return slope_packed_meta_b
 
 static size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
 
-// [ T | Lt | Rt | partial sums of X L ] when adapters are active, then the slab buffer of the split over K
+// [ T | Lt | partial sums of X L ] when adapters are active, then the slab buffer of the split over K
 static size_t adapter_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out, int64_t r) {
+    (void)d_out;
     if (r <= 0) return 0;
-    size_t tiles = round256((size_t)b * r * 2) + round256((size_t)d_in * r * 2) + round256((size_t)d_out * r * 2);
+    size_t tiles = round256((size_t)b * r * 2) + round256((size_t)d_in * r * 2);
     // T = X L comes from a split over d_in whose partial sums also live here (none for many tokens)
     return tiles + round256(b <= XL_SMALL_MAX_TOKENS ? xl_small_scratch_bytes(b, d_in, r)
                                                      : dense_tn_plain_partial_bytes(b, r));
@@ -126,21 +127,21 @@ slope_status slope_spmm_fwd(const void* X, int64_t b, const void* Wr_vals, const
     const bf16_t* A2 = nullptr;
     if (adapter) {
         bf16_t* Lt = (bf16_t*)(ws + round256((size_t)b * r * 2));
-        bf16_t* Rt = (bf16_t*)((uint8_t*)Lt + round256((size_t)d_in * r * 2));
-        float* scratch = (float*)((uint8_t*)Rt + round256((size_t)d_out * r * 2));
+        float* scratch = (float*)((uint8_t*)Lt + round256((size_t)d_in * r * 2));
         hipError_t e;
         if (b <= XL_SMALL_MAX_TOKENS) {   // too few tokens for the tile kernel to spread X L over the chip
-            e = launch_xl_small(x, b, d_in, (const bf16_t*)L_or_null, r, scratch, T, s, (const bf16_t*)R_or_null, d_out, Rt);
+            e = launch_xl_small(x, b, d_in, (const bf16_t*)L_or_null, r, scratch, T, s);
         } else {
-            e = launch_lowrank_prepare(x, b, d_in, d_out, (const bf16_t*)L_or_null, (const bf16_t*)R_or_null, r, T, Lt,
-                                       Rt, dense_tn_plain_partial_bytes(b, r) ? scratch : nullptr, s);
+            e = launch_lowrank_prepare(x, b, d_in, (const bf16_t*)L_or_null, r, T, Lt,
+                                       dense_tn_plain_partial_bytes(b, r) ? scratch : nullptr, s);
         }
         if (e != hipSuccess) return finish(e);
         B2 = T;
-        A2 = Rt;
+        A2 = (const bf16_t*)R_or_null;                        // as stored, [r][d_out]: the kernels take it k-major
     }
-    if (slabs) return finish(launch_spmm_slabs(x, b, wv, wm, d_out, d_in, B2, A2, adapter ? r : 0, (bf16_t*)Y, slabs, s));
-    return finish(launch_spmm(x, b, wv, wm, d_out, d_in, B2, A2, adapter ? r : 0, (bf16_t*)Y, s));
+    const int64_t K2 = adapter ? -r : 0;
+    if (slabs) return finish(launch_spmm_slabs(x, b, wv, wm, d_out, d_in, B2, A2, K2, (bf16_t*)Y, slabs, s));
+    return finish(launch_spmm(x, b, wv, wm, d_out, d_in, B2, A2, K2, (bf16_t*)Y, s));
 }
 
 slope_status slope_spmm_bwd_x(const void* dY, int64_t b, const void* WrcT_vals, const void* WrcT_meta, int64_t d_out,

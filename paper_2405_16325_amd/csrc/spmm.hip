@@ -39,15 +39,66 @@ namespace {
 
 // Tail shared by the tile kernels, for one wavefront whose acc[i][j] is the 16 x 16 fragment at
 // features f0 + 16 i, tokens t0 + 16 j.
-//  - dense K-extension: C += B2 * A2^T with v_mfma_f32_16x16x32_bf16, operands straight from
-//    global memory (lane l: row l%16, k = 8*(l/16) .. +7, for A and B alike);
+//  - dense K-extension: C += B2 * A2^T with v_mfma_f32_16x16x32_bf16.  K2 > 0: A2 is [m][K2],
+//    k-contiguous like B2, and both operands come straight from global memory (lane l: row l%16,
+//    k = 8*(l/16) .. +7).  K2 < 0: A2 is k-major, [-K2][m] (the adapter factor R as stored): the
+//    workgroup stages the tile's BMT columns of 128 rows at a time in LDS (the rings are idle by
+//    then) and the wavefronts read their fragments back with the transposing LDS read; every
+//    thread of the workgroup must make the call (it contains barriers);
 //  - epilogue: four consecutive features of one token per lane, one 8-byte store.
 //  - with a slab buffer (a split over k, see launch_spmm_slabs): the fp32 accumulators go to
 //    partial[token][feature] instead, 16 bytes per lane, and a reduction kernel finishes.
-template <int MF, int NF>
+template <int MF, int NF, int BMT>
 __device__ __forceinline__ void extend_and_store(f32x4 (&acc)[MF][NF], int f0, int t0, int m, int n, int l16, int lq,
                                                  const bf16_t* __restrict__ B2, const bf16_t* __restrict__ A2,
-                                                 int K2, bf16_t* __restrict__ C, float* __restrict__ partial = nullptr) {
+                                                 int K2, bf16_t* __restrict__ C, uint8_t* smem, int tile_f0,
+                                                 float* __restrict__ partial = nullptr) {
+    if (K2 < 0) {
+        constexpr int PITCH = BMT * 2 + 32;                   // pitch % 128 == 32: the four rows of a transposing
+                                                              // read fall on distinct banks
+        constexpr int SEG = BMT / 8;                          // 16-byte pieces per staged row
+        const int KR = -K2, nthreads = (int)blockDim.x, tid = (int)threadIdx.x;
+        const bf16_t* b_row[NF];
+#pragma unroll
+        for (int j = 0; j < NF; ++j) b_row[j] = B2 + (size_t)wrap_row(t0 + j * 16 + l16, n) * KR + lq * 8;
+        // lane (s = l16, q = lq) points at staged row 8 q + 4 h + s / 4, column 4 (s % 4) of a fragment
+        const uint8_t* tr = smem + (8 * lq + (l16 >> 2)) * PITCH + 2 * (f0 - tile_f0 + 4 * (l16 & 3));
+        for (int kc = 0; kc < KR; kc += 128) {
+            const int kn = KR - kc < 128 ? KR - kc : 128;     // a multiple of 32
+            __syncthreads();                                  // the rings are drained / the last chunk is consumed
+            for (int idx = tid; idx < kn * SEG; idx += nthreads) {
+                int k = idx / SEG, sg = idx % SEG, col = tile_f0 + 8 * sg;
+                u32x4 v = {0u, 0u, 0u, 0u};
+                if (col < m) v = *(const u32x4*)(A2 + (size_t)(kc + k) * m + col);
+                *(u32x4*)(smem + k * PITCH + sg * 16) = v;
+            }
+            AFrag b2[2][NF];
+#pragma unroll
+            for (int j = 0; j < NF; ++j) b2[0][j].u = *(const u32x4*)(b_row[j] + kc);
+            __syncthreads();
+            for (int k0 = 0; k0 < kn; k0 += 64) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int kk = k0 + 32 * h;               // uniform
+                    if (kk >= kn) break;
+                    const int knx = kk + 32 < kn ? kk + 32 : kk;
+#pragma unroll
+                    for (int j = 0; j < NF; ++j) b2[h ^ 1][j].u = *(const u32x4*)(b_row[j] + kc + knx);
+#pragma unroll
+                    for (int i = 0; i < MF; ++i) {
+                        union { s16x4 hh[2]; bf16x8 v; } a;
+                        a.hh[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (s16x4 __attribute__((address_space(3)))*)(tr + kk * PITCH + 32 * i));
+                        a.hh[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                            (s16x4 __attribute__((address_space(3)))*)(tr + (kk + 4) * PITCH + 32 * i));
+#pragma unroll
+                        for (int j = 0; j < NF; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b2[h][j].v, acc[i][j], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
     if (K2 > 0) {
         // operands of step k0 + 32 are requested before the MFMAs of step k0 are issued
         const bf16_t* a_row[MF];
@@ -261,9 +312,9 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_kernel(const bf16_t* __rest
     WAIT_HERE(waitcnt_imm(0, 15));           // drain the clamped look-ahead loads
 
     // the dense extension is added once, by the first slab
-    extend_and_store<MF, NF>(acc, m0 + wm * MF * 16, n0 + wn * NF * 16, m, n, l16, lq, B2, A2,
-                             blockIdx.y == 0 ? K2 : 0, C,
-                             slabs ? slabs + (size_t)blockIdx.y * (size_t)n * (size_t)m : nullptr);
+    extend_and_store<MF, NF, BM>(acc, m0 + wm * MF * 16, n0 + wn * NF * 16, m, n, l16, lq, B2, A2,
+                                 blockIdx.y == 0 ? K2 : 0, C, smem, m0,
+                                 slabs ? slabs + (size_t)blockIdx.y * (size_t)n * (size_t)m : nullptr);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -442,7 +493,7 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_split_kernel(const bf16_t* 
 #undef SPLIT_STEP0
 #undef SPLIT_STEP1
     WAIT_HERE(waitcnt_imm(0, 15));                            // drain the clamped look-ahead loads
-    extend_and_store<MF, NF>(acc, m0 + wm * MF * 16, n0 + wn * NF * 16, m, n, l16, lq, B2, A2, K2, C);
+    extend_and_store<MF, NF, S::BM>(acc, m0 + wm * MF * 16, n0 + wn * NF * 16, m, n, l16, lq, B2, A2, K2, C, smem, m0);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -542,7 +593,7 @@ __global__ void __launch_bounds__(256) spmm_generic_kernel(const bf16_t* __restr
     }
 #undef GEN_LOAD
 #undef GEN_STORE
-    extend_and_store<MF, NF>(acc, m0 + wm * MF * 16, n0 + wn * NF * 16, m, n, l16, lq, B2, A2, K2, C);
+    extend_and_store<MF, NF, 128>(acc, m0 + wm * MF * 16, n0 + wn * NF * 16, m, n, l16, lq, B2, A2, K2, C, smem, m0);
 }
 
 template <int BM, int BN>

@@ -429,27 +429,8 @@ __global__ void __launch_bounds__(256) xl_mfma_kernel(const bf16_t* __restrict__
 // T[idx] = bf16( sum over chunks of P[c][idx] ), idx = t * r + k, in a fixed order: a workgroup
 // takes 32 outputs; its 8 wavefront-halves each sum every 8th chunk, then the 8 sums are added
 // in order through LDS.
-// Workgroups past the first red_blocks copy the other factor into k-contiguous form instead,
-// Rt[c][k] = R[k][c] in 64 x 64 tiles (saves the tile kernels' caller a launch of its own).
 __global__ void __launch_bounds__(256) xl_reduce_kernel(const float* __restrict__ P, int chunks, int count,
-                                                        bf16_t* __restrict__ T, int red_blocks,
-                                                        const bf16_t* __restrict__ R, int r_rows, int r_cols,
-                                                        bf16_t* __restrict__ Rt) {
-    if ((int)blockIdx.x >= red_blocks) {
-        __shared__ bf16_t tile[64][66];
-        const int tb = blockIdx.x - red_blocks, tiles_c = (r_cols + 63) / 64;
-        const int r0 = (tb / tiles_c) * 64, c0 = (tb % tiles_c) * 64;
-        for (int idx = threadIdx.x; idx < 64 * 64; idx += 256) {
-            int rr = idx >> 6, c = idx & 63;
-            tile[rr][c] = (r0 + rr < r_rows && c0 + c < r_cols) ? R[(size_t)(r0 + rr) * r_cols + c0 + c] : (bf16_t)0;
-        }
-        __syncthreads();
-        for (int idx = threadIdx.x; idx < 64 * 64; idx += 256) {
-            int c = idx >> 6, rr = idx & 63;
-            if (r0 + rr < r_rows && c0 + c < r_cols) Rt[(size_t)(c0 + c) * r_rows + r0 + rr] = tile[rr][c];
-        }
-        return;
-    }
+                                                        bf16_t* __restrict__ T) {
     __shared__ float red[8][33];
     const int o = threadIdx.x & 31, cl = threadIdx.x >> 5;
     const int idx = blockIdx.x * 32 + o;
@@ -527,9 +508,8 @@ size_t xl_small_scratch_bytes(int64_t n, int64_t d_in, int64_t r) {
     return (size_t)((d_in + rows - 1) / rows) * (size_t)n * (size_t)r * 4;
 }
 
-// With Rt the launch of the reduction also writes Rt[d_out][r] = R[r][d_out]^T.
 hipError_t launch_xl_small(const bf16_t* X, int64_t n, int64_t d_in, const bf16_t* L, int64_t r, float* scratch,
-                           bf16_t* T, hipStream_t s, const bf16_t* R, int64_t d_out, bf16_t* Rt) {
+                           bf16_t* T, hipStream_t s) {
     const int subs = xl_subs(n, d_in, r);
     const int slabs = (int)((d_in + XL_CHUNK * subs - 1) / (XL_CHUNK * subs));
     if (n <= 16) {
@@ -544,9 +524,7 @@ hipError_t launch_xl_small(const bf16_t* X, int64_t n, int64_t d_in, const bf16_
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const int count = (int)(n * r), red_blocks = (count + 31) / 32;
-    const int tr_blocks = Rt ? (int)(((r + 63) / 64) * ((d_out + 63) / 64)) : 0;
-    xl_reduce_kernel<<<dim3((unsigned)(red_blocks + tr_blocks)), dim3(256), 0, s>>>(scratch, slabs, count, T, red_blocks,
-                                                                                   R, (int)r, (int)d_out, Rt);
+    const int count = (int)(n * r);
+    xl_reduce_kernel<<<dim3((unsigned)((count + 31) / 32)), dim3(256), 0, s>>>(scratch, slabs, count, T);
     return hipGetLastError();
 }
