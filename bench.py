@@ -27,6 +27,7 @@ sys.path.insert(0, ROOT)
 PEAK_DENSE_BF16 = 2500.0     # TFLOP/s, MI355X dense bf16 MFMA
 PEAK_SPARSE_BF16 = 5000.0    # TFLOP/s dense-equivalent, structured-sparse bf16 MFMA
 PEAK_HBM = 8000.0            # GB/s
+NOMINAL_MHZ = 2400.0         # shader clock the published MFMA peaks assume
 # What register-resident loops and plain streams reached on this machine's MI355X (the ceilings a kernel can
 # actually touch): v_smfmac_f32_16x16x64_bf16, v_mfma_f32_32x32x16_bf16, a read-only stream, a copy.
 MEASURED = {"sparse_bf16_tflops": 4390.0, "dense_bf16_tflops": 2390.0, "hbm_read_gbs": 6900.0, "hbm_copy_gbs": 4700.0}
@@ -278,6 +279,23 @@ def main():
         adapter_bwd = {"ms_per_step": ab_ms, "plain_backward_ms": per_call["spmm_bwd_x"] + per_call["wgrad_masked"],
                        "calls": "slope_spmm_bwd_x_adapter + slope_wgrad_adapter per layer"}
 
+    # Shader clock under load (outside the timed region): the published MFMA peaks assume 2.4 GHz, but the
+    # power management lowers the clock while MFMA-bound kernels run.  rocm-smi is sampled while one kind of
+    # call loops for about a second.
+    big = max(layers, key=lambda l: l["d_in"] * l["d_out"])
+    sclk = {
+        "idle": sample_sclk(torch, None),
+        "slope_spmm_bwd_x": sample_sclk(torch, lambda: sl.slope_spmm_bwd_x(big["dY"], big["vals_t"], big["meta_t"],
+                                                                         out=big["dX"])),
+        "slope_wgrad_masked": sample_sclk(torch, lambda: sl.slope_wgrad_masked(big["dY"], big["X"], big["meta"],
+                                                                             out=big["G"], workspace=wg_ws)),
+        "dense_gemm": None if args.no_dense else sample_sclk(torch, lambda: torch.matmul(big["X"], big["W"].t(),
+                                                                                        out=big["Y"])),
+    }
+    if sclk["slope_spmm_bwd_x"]:
+        roofline["sclk_mhz_under_load"] = sclk["slope_spmm_bwd_x"]
+        roofline["frac_at_that_clock"] = roofline["frac"] * NOMINAL_MHZ / sclk["slope_spmm_bwd_x"]
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(layers[-2] if len(layers) > 1 else layers[0], b, rank)
@@ -300,6 +318,7 @@ def main():
         "speedup_vs_dense": None if dense is None else dense["speedup_with_reprune"],
         "roofline": roofline, "kernels": kernels, "dense_gemm": dense, "cpu_baseline": cpu,
         "per_call_ms": per_call, "hip_graph": graph, "optimizer_side": optimizer, "adapter_backward": adapter_bwd,
+        "sclk_mhz": sclk,
     }
     print(json.dumps(out))
 
@@ -394,6 +413,40 @@ def read_traffic(kernel):
     except OSError:
         pass
     return None
+
+
+def sample_sclk(torch, fn, seconds=1.2):
+    """Median shader clock (MHz) that rocm-smi reports while fn loops (None: idle); None if it cannot be read."""
+    import re
+    import subprocess
+    import threading
+    vals, stop = [], [False]
+
+    def sampler():
+        while not stop[0]:
+            try:
+                txt = subprocess.run(["rocm-smi", "--showclocks", "--csv"], capture_output=True, text=True,
+                                     timeout=10).stdout
+                head, row = [ln.split(",") for ln in txt.strip().splitlines()[:2]]
+                idx = [i for i, h in enumerate(head) if h.startswith("sclk clock speed")][0]
+                vals.append(float(re.sub(r"[^0-9.]", "", row[idx])))
+            except Exception:
+                pass
+            time.sleep(0.1)
+    th = threading.Thread(target=sampler)
+    th.start()
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        if fn is None:
+            time.sleep(0.05)
+        else:
+            for _ in range(10):
+                fn()
+            torch.cuda.synchronize()
+    stop[0] = True
+    th.join()
+    vals = sorted(vals[len(vals) // 3:])                 # drop the ramp at the start
+    return vals[len(vals) // 2] if vals else None
 
 
 def cpu_baseline(lay, b, rank):
