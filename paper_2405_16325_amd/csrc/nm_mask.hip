@@ -61,16 +61,25 @@ __global__ void __launch_bounds__(256) nm_mask_rows_kernel(const u32x4* __restri
     }
 }
 
-// groups of M consecutive elements inside a column; one lane = 8 consecutive columns x the M rows of a group
+// groups of M consecutive elements inside a column; one lane = 8 consecutive columns x the M rows of a group.
+// A workgroup takes a tile of 64 columns x 32 row groups (thread = chunk tx of 8 columns, row group ty),
+// so that the transposed masked weight leaves through LDS in runs of 32 M consecutive rows per column
+// (lane-sized pieces of 2 M bytes scattered over eight rows of the output made this kernel 3-8 x slower).
 template <int M>
-__global__ void __launch_bounds__(256) nm_mask_cols_kernel(const bf16_t* __restrict__ W, size_t units, int rows,
-                                                           int cols, int n, const uint8_t* __restrict__ cand,
+__global__ void __launch_bounds__(256) nm_mask_cols_kernel(const bf16_t* __restrict__ W, int rows, int cols, int n,
+                                                           const uint8_t* __restrict__ cand,
                                                            uint8_t* __restrict__ mask, bf16_t* __restrict__ masked,
                                                            bf16_t* __restrict__ masked_t) {
+    constexpr int TR = 32 * M;                                // rows of a tile
+    constexpr int PITCH = TR + 2;                             // elements per column of the transposed tile
+    __shared__ bf16_t tile[64 * PITCH];
     const size_t cpr = (size_t)cols / 8;                      // 8-column chunks per row
-    for (size_t u = (size_t)blockIdx.x * 256 + threadIdx.x; u < units; u += (size_t)gridDim.x * 256) {
-        const size_t rg = u / cpr, cc = u % cpr, row0 = rg * M;
-        u32x4 v[M];
+    const int tx = threadIdx.x & 7, ty = threadIdx.x >> 3;
+    const size_t cc = (size_t)blockIdx.x * 8 + tx;            // chunk of 8 columns
+    const size_t row0 = ((size_t)blockIdx.y * 32 + ty) * M;   // first row of the group
+    const bool live = cc < cpr && row0 < (size_t)rows;        // rows % M == 0: a group is whole or absent
+    u32x4 v[M];
+    if (live) {
         uint32_t cb[M], keep[M];
 #pragma unroll
         for (int k = 0; k < M; ++k) {
@@ -98,12 +107,22 @@ __global__ void __launch_bounds__(256) nm_mask_cols_kernel(const bf16_t* __restr
             v[k] = out;
             if (masked) *(u32x4*)(masked + (row0 + k) * (size_t)cols + cc * 8) = out;
         }
-        if (masked_t) {
+    }
+    if (!masked_t) return;                                    // uniform
+    if (live) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
+        for (int e = 0; e < 8; ++e)
 #pragma unroll
-                for (int k = 0; k < M; ++k) masked_t[(cc * 8 + e) * (size_t)rows + row0 + k] = (bf16_t)half_of(v[k], e);
-        }
+            for (int k = 0; k < M; ++k) tile[(tx * 8 + e) * PITCH + ty * M + k] = (bf16_t)half_of(v[k], e);
+    }
+    __syncthreads();
+    // column c of the tile = TR consecutive elements of row (c0 + c) of the transposed output, two per lane
+    const size_t c0 = (size_t)blockIdx.x * 64, r0 = (size_t)blockIdx.y * TR;
+    for (int idx = threadIdx.x; idx < 64 * (TR / 2); idx += 256) {
+        const int c = idx / (TR / 2), p = idx % (TR / 2);
+        if (c0 + c >= (size_t)cols || r0 + 2 * p >= (size_t)rows) continue;      // rows is even
+        const uint32_t pair = (uint32_t)tile[c * PITCH + 2 * p] | ((uint32_t)tile[c * PITCH + 2 * p + 1] << 16);
+        *(uint32_t*)(masked_t + (c0 + c) * (size_t)rows + r0 + 2 * p) = pair;
     }
 }
 
@@ -118,8 +137,8 @@ hipError_t launch_m(const bf16_t* W, int64_t rows, int64_t cols, int n, int axis
         nm_mask_rows_kernel<M><<<dim3((unsigned)blocks), dim3(256), 0, s>>>((const u32x4*)W, units, (int)rows, (int)cols, n,
                                                                           cand, mask, (u32x4*)masked, masked_t);
     else
-        nm_mask_cols_kernel<M><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(W, units, (int)rows, (int)cols, n, cand, mask,
-                                                                          masked, masked_t);
+        nm_mask_cols_kernel<M><<<dim3((unsigned)((cols + 63) / 64), (unsigned)((rows / M + 31) / 32)), dim3(256), 0, s>>>(
+            W, (int)rows, (int)cols, n, cand, mask, masked, masked_t);
     return hipGetLastError();
 }
 
