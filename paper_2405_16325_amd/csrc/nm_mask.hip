@@ -27,12 +27,12 @@ __device__ __forceinline__ uint32_t keep_of_group(const uint32_t (&score)[M], in
 
 __device__ __forceinline__ uint32_t half_of(const u32x4& v, int e) { return (v[e >> 1] >> (16 * (e & 1))) & 0xFFFFu; }
 
-// groups of M consecutive elements inside a row; one lane = 8 consecutive elements of a row
+// groups of M consecutive elements inside a row; one lane = 8 consecutive elements of a row, the lanes of
+// a workgroup on consecutive chunks (mask and masked weight only: fully contiguous accesses)
 template <int M>
-__global__ void __launch_bounds__(256) nm_mask_rows_kernel(const u32x4* __restrict__ W, size_t chunks, int rows,
-                                                           int cols, int n, const uint8_t* __restrict__ cand,
-                                                           uint8_t* __restrict__ mask, u32x4* __restrict__ masked,
-                                                           bf16_t* __restrict__ masked_t) {
+__global__ void __launch_bounds__(256) nm_mask_rows_kernel(const u32x4* __restrict__ W, size_t chunks, int n,
+                                                           const uint8_t* __restrict__ cand,
+                                                           uint8_t* __restrict__ mask, u32x4* __restrict__ masked) {
     for (size_t c = (size_t)blockIdx.x * 256 + threadIdx.x; c < chunks; c += (size_t)gridDim.x * 256) {
         const u32x4 v = W[c];
         const uint32_t cb = cand ? cand[c] : 0xFFu;
@@ -53,11 +53,55 @@ __global__ void __launch_bounds__(256) nm_mask_rows_kernel(const u32x4* __restri
         for (int w = 0; w < 4; ++w)
             out[w] = (((keep >> (2 * w)) & 1u) ? (v[w] & 0xFFFFu) : 0u) | (((keep >> (2 * w + 1)) & 1u) ? (v[w] & 0xFFFF0000u) : 0u);
         if (masked) masked[c] = out;
-        if (masked_t) {
-            const size_t row = c / (size_t)(cols / 8), col0 = (c % (size_t)(cols / 8)) * 8;
+    }
+}
+
+// The same with the transposed masked weight as a further output.
+// A workgroup takes a tile of 64 columns x 128 rows (thread = chunk tx of 8 columns, rows ty + 32 i);
+// the transposed masked weight, if asked for, leaves through LDS in runs of 128 rows per column.
+template <int M>
+__global__ void __launch_bounds__(256) nm_mask_rows_t_kernel(const bf16_t* __restrict__ W, int rows, int cols, int n,
+                                                           const uint8_t* __restrict__ cand,
+                                                           uint8_t* __restrict__ mask, bf16_t* __restrict__ masked,
+                                                           bf16_t* __restrict__ masked_t) {
+    constexpr int TR = 128, PITCH = TR + 2;
+    __shared__ bf16_t tile[64 * PITCH];
+    const size_t cpr = (size_t)cols / 8;
+    const int tx = threadIdx.x & 7, ty = threadIdx.x >> 3;
+    const size_t cc = (size_t)blockIdx.x * 8 + tx, r0 = (size_t)blockIdx.y * TR;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) masked_t[(col0 + e) * (size_t)rows + row] = (bf16_t)half_of(out, e);
+    for (int i = 0; i < TR / 32; ++i) {
+        const size_t row = r0 + ty + 32 * i;
+        if (cc >= cpr || row >= (size_t)rows) continue;
+        const size_t c = row * cpr + cc;
+        const u32x4 v = *(const u32x4*)(W + c * 8);
+        const uint32_t cb = cand ? cand[c] : 0xFFu;
+        uint32_t keep = 0;
+#pragma unroll
+        for (int g = 0; g < 8 / M; ++g) {
+            uint32_t score[M];
+#pragma unroll
+            for (int q = 0; q < M; ++q) {
+                int e = g * M + q;
+                score[q] = ((cb >> e) & 1u) ? (half_of(v, e) & 0x7FFFu) + 1u : 0u;
+            }
+            keep |= keep_of_group<M>(score, n) << (g * M);
         }
+        mask[c] = (uint8_t)keep;
+        u32x4 out;
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+            out[w] = (((keep >> (2 * w)) & 1u) ? (v[w] & 0xFFFFu) : 0u) | (((keep >> (2 * w + 1)) & 1u) ? (v[w] & 0xFFFF0000u) : 0u);
+        if (masked) *(u32x4*)(masked + c * 8) = out;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) tile[(tx * 8 + e) * PITCH + ty + 32 * i] = (bf16_t)half_of(out, e);
+    }
+    __syncthreads();
+    const size_t c0 = (size_t)blockIdx.x * 64;
+    for (int idx = threadIdx.x; idx < 64 * TR; idx += 256) {
+        const int c = idx / TR, r = idx % TR;
+        if (c0 + c >= (size_t)cols || r0 + r >= (size_t)rows) continue;
+        masked_t[(c0 + c) * (size_t)rows + r0 + r] = tile[c * PITCH + r];
     }
 }
 
@@ -129,14 +173,16 @@ __global__ void __launch_bounds__(256) nm_mask_cols_kernel(const bf16_t* __restr
 template <int M>
 hipError_t launch_m(const bf16_t* W, int64_t rows, int64_t cols, int n, int axis, const uint8_t* cand, uint8_t* mask,
                     bf16_t* masked, bf16_t* masked_t, hipStream_t s) {
-    const size_t units = axis == 0 ? (size_t)rows * (size_t)(cols / 8) : (size_t)(rows / M) * (size_t)(cols / 8);
-    size_t blocks = (units + 255) / 256;
-    if (blocks > 256 * 32) blocks = 256 * 32;
-    if (blocks == 0) blocks = 1;
-    if (axis == 0)
-        nm_mask_rows_kernel<M><<<dim3((unsigned)blocks), dim3(256), 0, s>>>((const u32x4*)W, units, (int)rows, (int)cols, n,
-                                                                          cand, mask, (u32x4*)masked, masked_t);
-    else
+    if (axis == 0 && masked_t)
+        nm_mask_rows_t_kernel<M><<<dim3((unsigned)((cols + 63) / 64), (unsigned)((rows + 127) / 128)), dim3(256), 0, s>>>(
+            W, (int)rows, (int)cols, n, cand, mask, masked, masked_t);
+    else if (axis == 0) {
+        const size_t chunks = (size_t)rows * (size_t)(cols / 8);
+        size_t blocks = (chunks + 255) / 256;
+        if (blocks > 256 * 32) blocks = 256 * 32;
+        nm_mask_rows_kernel<M><<<dim3((unsigned)blocks), dim3(256), 0, s>>>((const u32x4*)W, chunks, n, cand, mask,
+                                                                          (u32x4*)masked);
+    } else
         nm_mask_cols_kernel<M><<<dim3((unsigned)((cols + 63) / 64), (unsigned)((rows / M + 31) / 32)), dim3(256), 0, s>>>(
             W, (int)rows, (int)cols, n, cand, mask, masked, masked_t);
     return hipGetLastError();
