@@ -101,6 +101,31 @@ __device__ __forceinline__ void store_masked_packed(const f32x4 (&acc)[MF][NF], 
     }
 }
 
+// Plain epilogue of one wavefront: out[j][i] bf16 row-major [n][m] (row j, four consecutive i per lane), or
+// the fp32 accumulators into partial[n][m] for a later reduction.
+template <int MF, int NF>
+__device__ __forceinline__ void store_plain(const f32x4 (&acc)[MF][NF], int m, int n, int c0, int o0, int l16, int lq,
+                                            bf16_t* __restrict__ out, float* __restrict__ partial) {
+#pragma unroll
+    for (int j = 0; j < NF; ++j) {
+        int row = o0 + j * 16 + l16;
+        if (row >= n) continue;
+#pragma unroll
+        for (int i = 0; i < MF; ++i) {
+            int col = c0 + i * 16 + lq * 4;
+            if (col >= m) continue;
+            f32x4 v = acc[i][j];
+            if (partial) {
+                *(f32x4*)(partial + (size_t)row * m + col) = v;
+                continue;
+            }
+            union { __bf16 h[4]; u32x2 u; } o;
+            o.h[0] = (__bf16)v[0]; o.h[1] = (__bf16)v[1]; o.h[2] = (__bf16)v[2]; o.h[3] = (__bf16)v[3];
+            *(u32x2*)(out + (size_t)row * m + col) = o.u;
+        }
+    }
+}
+
 // D[i, j] = sum_k At[i, k] * Bt[j, k];  At: m rows, Bt: n rows, both of pitch ld elements; kp % 64 == 0.
 //   EPI_MASKED_PACKED: out = packed gradient [n][m/2] selected by meta (u8[n][m/8])
 //   EPI_PLAIN        : out = bf16 [n][m]  (row j, four consecutive i per lane)
@@ -218,24 +243,8 @@ __global__ void __launch_bounds__(TN_THREADS) dense_tn_kernel(const bf16_t* __re
     WAIT_HERE(waitcnt_imm(0, 15));                            // drain the clamped look-ahead loads
 
     if (EPI == EPI_PLAIN) {
-#pragma unroll
-        for (int j = 0; j < NF; ++j) {
-            int row = n0 + (wn * NF + j) * 16 + l16;
-            if (row >= n) continue;
-#pragma unroll
-            for (int i = 0; i < MF; ++i) {
-                int col = m0 + wm * WM + i * 16 + lq * 4;
-                if (col >= m) continue;
-                f32x4 v = acc[i][j];
-                if (partial) {
-                    *(f32x4*)(partial + ((size_t)blockIdx.y * n + row) * m + col) = v;
-                    continue;
-                }
-                union { __bf16 h[4]; u32x2 u; } o;
-                o.h[0] = (__bf16)v[0]; o.h[1] = (__bf16)v[1]; o.h[2] = (__bf16)v[2]; o.h[3] = (__bf16)v[3];
-                *(u32x2*)(out + (size_t)row * m + col) = o.u;
-            }
-        }
+        store_plain<MF, NF>(acc, m, n, m0 + wm * WM, n0 + wn * NF * 16, l16, lq, out,
+                            partial ? partial + (size_t)blockIdx.y * n * m : nullptr);
         return;
     }
     store_masked_packed<MF, NF>(acc, m, n, m0 + wm * WM, n0 + wn * NF * 16, l16, lq, meta, out);
@@ -275,6 +284,7 @@ struct SplitSmem {
     static constexpr int TOTAL = 3 * A_STAGE + 4 * B_HALF;
 };
 
+template <int EPI>
 __global__ void __launch_bounds__(TN_THREADS) dense_tn_split_kernel(const bf16_t* __restrict__ At, int m,
                                                                     const bf16_t* __restrict__ Bt, int n, int kp,
                                                                     int ld, const uint8_t* __restrict__ meta,
@@ -398,7 +408,8 @@ __global__ void __launch_bounds__(TN_THREADS) dense_tn_split_kernel(const bf16_t
 #undef EVEN_LOADS
 #undef ODD_LOADS
     WAIT_HERE(waitcnt_imm(0, 15));                            // drain the clamped look-ahead loads
-    store_masked_packed<MF, NF>(acc, m, n, m0 + wm * WM, n0 + wn * NF * 16, l16, lq, meta, out);
+    if (EPI == EPI_PLAIN) store_plain<MF, NF>(acc, m, n, m0 + wm * WM, n0 + wn * NF * 16, l16, lq, out, nullptr);
+    else store_masked_packed<MF, NF>(acc, m, n, m0 + wm * WM, n0 + wn * NF * 16, l16, lq, meta, out);
 }
 
 template <int BM, int BN, int EPI, int NS>
@@ -416,15 +427,16 @@ hipError_t launch_dense_tn(const bf16_t* At, int64_t m, const bf16_t* Bt, int64_
     return hipGetLastError();
 }
 
+template <int EPI>
 hipError_t launch_dense_tn_split(const bf16_t* At, int64_t m, const bf16_t* Bt, int64_t n, int64_t kp, int64_t ld,
                                  const uint8_t* meta, bf16_t* out, hipStream_t s) {
     using S = SplitSmem;
     static_assert(S::TOTAL <= 160 * 1024, "LDS budget");
     int tiles_m = (int)((m + S::BM - 1) / S::BM), tiles_n = (int)((n + S::BN - 1) / S::BN);
-    hipError_t e = hipFuncSetAttribute((const void*)dense_tn_split_kernel,
+    hipError_t e = hipFuncSetAttribute((const void*)dense_tn_split_kernel<EPI>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, S::TOTAL);
     if (e != hipSuccess) return e;
-    dense_tn_split_kernel<<<dim3((unsigned)super_grid(tiles_m, tiles_n)), dim3(TN_THREADS), S::TOTAL, s>>>(
+    dense_tn_split_kernel<EPI><<<dim3((unsigned)super_grid(tiles_m, tiles_n)), dim3(TN_THREADS), S::TOTAL, s>>>(
         At, (int)m, Bt, (int)n, (int)kp, (int)ld, meta, out, tiles_m, tiles_n);
     return hipGetLastError();
 }
@@ -454,7 +466,7 @@ hipError_t launch_wgrad_masked_ws(const bf16_t* dY, const bf16_t* X, int64_t b, 
         int64_t cost = ((tiles + RESIDENT - 1) / RESIDENT) * (bms[c] + bns[c]);
         if (cost < best_cost) { best_cost = cost; best = c; }
     }
-    if (best == 0) return launch_dense_tn_split(Xt, d_in, dYt, d_out, bp, ld, meta, gvals, s);
+    if (best == 0) return launch_dense_tn_split<EPI_MASKED_PACKED>(Xt, d_in, dYt, d_out, bp, ld, meta, gvals, s);
     if (best == 1) return launch_dense_tn<256, 128, EPI_MASKED_PACKED, 3>(Xt, d_in, dYt, d_out, bp, ld, meta, gvals, s);
     return launch_dense_tn<128, 128, EPI_MASKED_PACKED, 4>(Xt, d_in, dYt, d_out, bp, ld, meta, gvals, s);
 }
@@ -503,7 +515,7 @@ hipError_t launch_dense_tn_any(const bf16_t* B, int64_t n, const bf16_t* A, int6
         if (cost < best_cost) { best_cost = cost; best = c; }
     }
     switch (best) {
-        case 0: return launch_dense_tn<256, 256, EPI_PLAIN, 2>(A, m, B, n, K, K, nullptr, C, s);
+        case 0: return launch_dense_tn_split<EPI_PLAIN>(A, m, B, n, K, K, nullptr, C, s);
         case 1: return launch_dense_tn<256, 128, EPI_PLAIN, 3>(A, m, B, n, K, K, nullptr, C, s);
         case 2: return launch_dense_tn<128, 128, EPI_PLAIN, 4>(A, m, B, n, K, K, nullptr, C, s);
         default: return launch_dense_tn<128, 64, EPI_PLAIN, 6>(A, m, B, n, K, K, nullptr, C, s);
