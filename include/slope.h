@@ -63,10 +63,10 @@ size_t slope_packed_vals_bytes(int64_t rows, int64_t cols);
 size_t slope_packed_meta_bytes(int64_t rows, int64_t cols);
 size_t slope_mask_bytes(int64_t rows, int64_t cols);
 
-/* Scratch of slope_spmm_fwd.  Required when adapters are active (T = X L as bf16[b, r],
- * K-contiguous copies of L and R, partial sums); optional otherwise: for a few dozen to a few
- * hundred tokens the call, given this many bytes, also splits the contraction over d_in and keeps
- * fp32 partial sums there, which is much faster at those sizes.  0 = no scratch is of use. */
+/* Scratch of slope_spmm_fwd.  Required when adapters are active (T = X L as bf16[b, r], a
+ * K-contiguous copy of L for many tokens, partial sums); optional otherwise: for a few dozen to
+ * about a thousand tokens the call, given this many bytes, also splits the contraction over d_in
+ * and keeps fp32 partial sums there, which is much faster at those sizes.  0 = no scratch is of use. */
 size_t slope_spmm_fwd_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out, int64_t r);
 
 /*
