@@ -228,6 +228,21 @@ slope_status slope_update_sparse(const void* Wnew_vals, const void* Wr_meta, int
                                  void* Wr_vals, const void* WrcT_meta, void* WrcT_vals, void* stream);
 
 /*
+ * slope_spmm_fwd_plan - diagnostics, host only (no GPU call): which kernels slope_spmm_fwd (Eq. 4, 11)
+ * would launch for a shape.  The choices are cost estimates over the shape alone, so that tests can
+ * pin the regimes.  plan: host int32[6]
+ *   [0] product: 0 small-batch kernel (one pass over the packed weight), 1 tile kernel with the
+ *       contraction split into slabs (needs the workspace), 2 tile kernel, 3 generic kernel
+ *       (d_in not a multiple of 256)
+ *   [1], [2] weight rows and tokens per workgroup      [3] slabs (1 = no split)
+ *   [4] T = X L: 0 no adapter, 1 split over d_in on fp32 FMAs, 2 the same on MFMA,
+ *       3 dense tile kernel, 4 dense tile kernel split over d_in
+ *   [5] chunks of 64 rows of L per workgroup for [4] in {1, 2}
+ * with_workspace: whether the call would be given its scratch.  Errors as slope_spmm_fwd.
+ */
+slope_status slope_spmm_fwd_plan(int64_t b, int64_t d_in, int64_t d_out, int64_t r, int with_workspace, int32_t* plan);
+
+/*
  * slope_tile_order - diagnostics, host only (no GPU call): the workgroup -> tile assignment the
  * MFMA tile kernels use for a grid of tiles_m x tiles_n tiles (the XCD-aware order behind the
  * products of Eq. 1, 4-6).  Workgroup w of the launch computes tile (tm[w], tn[w]); -1 in both

@@ -47,6 +47,7 @@ SIGNATURES = {
     "slope_sparse_add": (_INT, [_P, _P, _I64, _I64, ctypes.c_float, ctypes.c_float, _P, _P]),
     "slope_update_sparse": (_INT, [_P, _P, _I64, _I64, _P, _P, _P, _P]),
     "slope_tile_order": (_I64, [_I64, _I64, _P, _P, _I64]),
+    "slope_spmm_fwd_plan": (_INT, [_I64, _I64, _I64, _I64, _INT, _P]),
 }
 
 _lib = None
@@ -279,3 +280,12 @@ def slope_tile_order(tiles_m: int, tiles_n: int):
     if grid < 0:
         raise ValueError("slope_tile_order: extents must be positive")
     return tm[:grid].copy(), tn[:grid].copy()
+
+
+def slope_spmm_fwd_plan(b: int, d_in: int, d_out: int, r: int = 0, with_workspace: bool = True):
+    """Kernels slope_spmm_fwd would launch for a shape (host only): dict of the six plan fields."""
+    import numpy as np
+    plan = np.zeros(6, dtype=np.int32)
+    _check("slope_spmm_fwd_plan", lib().slope_spmm_fwd_plan(b, d_in, d_out, r, int(with_workspace), plan.ctypes.data))
+    names = ["product", "rows", "tokens", "slabs", "xl", "xl_chunks"]
+    return dict(zip(names, (int(v) for v in plan)))

@@ -26,6 +26,11 @@ hipError_t launch_sparse_add(const bf16_t* a, const bf16_t* b, size_t count, flo
 // K2 < 0 with A2 = [-K2][m], k-major, the way the adapter factor R is stored)
 hipError_t launch_spmm(const bf16_t* B, int64_t n, const bf16_t* A_vals, const uint8_t* A_meta, int64_t m,
                        int64_t K, const bf16_t* B2, const bf16_t* A2, int64_t K2, bf16_t* C, hipStream_t s);
+// the choices behind it (pure functions of the shape): tile of the tile kernels (0 x 0 = the generic kernel),
+// weight rows per workgroup of the small-batch kernel, chunks of 64 rows of L per workgroup of the X L split
+void spmm_tile_choice(int64_t n, int64_t m, int64_t K, int& bm, int& bn);
+int spmm_stream_rows(int64_t n, int64_t m, int64_t K);
+int xl_subs(int64_t n, int64_t d_in, int64_t r);
 // the same product for a few dozen to a few hundred tokens, split over K with fp32 partial sums in `slabs`
 // (spmm_slab_bytes of them; 0 = this shape does not take the path)
 int spmm_slab_count(int64_t n, int64_t m, int64_t K);

@@ -271,6 +271,35 @@ slope_status slope_update_sparse(const void* Wnew_vals, const void* Wr_meta, int
                                            (const uint8_t*)WrcT_meta, (bf16_t*)WrcT_vals, s));
 }
 
+slope_status slope_spmm_fwd_plan(int64_t b, int64_t d_in, int64_t d_out, int64_t r, int with_workspace, int32_t* plan) {
+    if (!plan) return SLOPE_ERR_NULL;
+    if (bad_extent(b, 1) || bad_extent(d_out, 64) || bad_extent(d_in, 64) || r < 0) return SLOPE_ERR_SHAPE;
+    if (r > 0 && (r % 32 != 0 || r > 512)) return SLOPE_ERR_UNSUPPORTED;
+    for (int i = 0; i < 6; ++i) plan[i] = 0;
+    plan[3] = 1;
+    if (b <= STREAM_MAX_TOKENS && d_in >= 128) {
+        plan[0] = 0;
+        plan[1] = spmm_stream_rows(b, d_out, d_in);
+        plan[2] = b <= 16 ? 16 : 32;
+    } else {
+        const int slabs = with_workspace ? spmm_slab_count(b, d_out, d_in) : 0;
+        int bm, bn;
+        spmm_tile_choice(b, d_out, d_in, bm, bn);
+        if (slabs > 0) { plan[0] = 1; plan[1] = 256; plan[2] = b <= 64 ? 64 : 128; plan[3] = slabs; }
+        else if (bm == 0) { plan[0] = 3; plan[1] = plan[2] = 128; }
+        else { plan[0] = 2; plan[1] = bm; plan[2] = bn; }
+    }
+    if (r > 0) {
+        if (b <= XL_SMALL_MAX_TOKENS) {
+            plan[4] = b <= 16 ? 1 : 2;
+            plan[5] = xl_subs(b, d_in, r);
+        } else {
+            plan[4] = dense_tn_plain_partial_bytes(b, r) ? 4 : 3;
+        }
+    }
+    return SLOPE_OK;
+}
+
 int64_t slope_tile_order(int64_t tiles_m, int64_t tiles_n, int32_t* tm, int32_t* tn, int64_t capacity) {
     if (tiles_m <= 0 || tiles_n <= 0 || tiles_m > (1 << 20) || tiles_n > (1 << 20) || !tm || !tn) return -1;
     const int64_t grid = super_grid((int)tiles_m, (int)tiles_n);

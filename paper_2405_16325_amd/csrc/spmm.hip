@@ -689,42 +689,47 @@ hipError_t launch_spmm_slabs(const bf16_t* B, int64_t n, const bf16_t* A_vals, c
     return hipGetLastError();
 }
 
+// Tile of the product for n tokens, m sparse rows, contraction K: bm = bn = 0 means the generic kernel.
+void spmm_tile_choice(int64_t n, int64_t m, int64_t K, int& bm, int& bn) {
+    bm = bn = 0;
+    if (K % 256 != 0) return;
+    // Few tokens (inference): the product is a single pass over the packed weight, bound by HBM.
+    // Narrow token tiles, and weight tiles small enough that every compute unit streams its share.
+    if (n <= 128) {
+        const bool many = (m + 127) / 128 >= 200;
+        bm = many ? 128 : 64;
+        bn = n <= 64 ? 64 : 128;
+        return;
+    }
+    // The tile kernels run at the rate their compute units pull operands from L2, so a launch costs
+    // about (rounds of 256 resident tiles) x (operand bytes per tile and k-step: 72 per weight row,
+    // 128 per token row).  Take the tile shape for which that is least; ties go to the larger tile.
+    const int bms[6] = {256, 192, 256, 128, 128, 64}, bns[6] = {256, 256, 128, 128, 64, 128};
+    int64_t best_cost = INT64_MAX;
+    for (int c = 0; c < 6; ++c) {
+        int64_t tiles = ((m + bms[c] - 1) / bms[c]) * ((n + bns[c] - 1) / bns[c]);
+        int64_t cost = ((tiles + RESIDENT - 1) / RESIDENT) * (72 * bms[c] + 128 * bns[c]);
+        if (cost < best_cost) { best_cost = cost; bm = bms[c]; bn = bns[c]; }
+    }
+}
+
 hipError_t launch_spmm(const bf16_t* B, int64_t n, const bf16_t* A_vals, const uint8_t* A_meta, int64_t m, int64_t K,
                        const bf16_t* B2, const bf16_t* A2, int64_t K2, bf16_t* C, hipStream_t s) {
-    if (K % 256 != 0) {
+    int bm, bn;
+    spmm_tile_choice(n, m, K, bm, bn);
+    if (bm == 0) {
         int tiles_m = (int)((m + 127) / 128), tiles_n = (int)((n + 127) / 128);
         spmm_generic_kernel<<<dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 0, s>>>(
             B, (int)n, A_vals, A_meta, (int)m, (int)K, B2, A2, (int)K2, C, tiles_m);
         return hipGetLastError();
     }
-    // Few tokens (inference): the product is a single pass over the packed weight, bound by HBM.
-    // Narrow token tiles, and weight tiles small enough that every compute unit streams its share.
-    if (n <= 128) {
-        const bool many = (m + 127) / 128 >= 200;
-        if (n <= 64)
-            return many ? launch_tile<128, 64>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s)
-                        : launch_tile<64, 64>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s);
-        return many ? launch_tile<128, 128>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s)
-                    : launch_tile<64, 128>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s);
-    }
-    // The tile kernels run at the rate their compute units pull operands from L2, so a launch costs
-    // about (rounds of 256 resident tiles) x (operand bytes per tile and k-step: 72 per weight row,
-    // 128 per token row).  Take the tile shape for which that is least; ties go to the larger tile.
-    struct Cand { int bm, bn; };
-    const Cand cands[6] = {{256, 256}, {192, 256}, {256, 128}, {128, 128}, {128, 64}, {64, 128}};
-    int best = 0;
-    int64_t best_cost = INT64_MAX;
-    for (int c = 0; c < 6; ++c) {
-        int64_t tiles = ((m + cands[c].bm - 1) / cands[c].bm) * ((n + cands[c].bn - 1) / cands[c].bn);
-        int64_t cost = ((tiles + RESIDENT - 1) / RESIDENT) * (72 * cands[c].bm + 128 * cands[c].bn);
-        if (cost < best_cost) { best_cost = cost; best = c; }
-    }
-    switch (best) {
-        case 0: return launch_split(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s);
-        case 1: return launch_tile<192, 256>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s);
-        case 2: return launch_tile<256, 128>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s);
-        case 3: return launch_tile<128, 128>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s);
-        case 4: return launch_tile<128, 64>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s);
+    switch (bm * 1000 + bn) {
+        case 256256: return launch_split(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s);
+        case 192256: return launch_tile<192, 256>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s);
+        case 256128: return launch_tile<256, 128>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s);
+        case 128128: return launch_tile<128, 128>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s);
+        case 128064: return launch_tile<128, 64>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s);
+        case 64064: return launch_tile<64, 64>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s);
         default: return launch_tile<64, 128>(B, n, A_vals, A_meta, m, K, B2, A2, K2, C, s);
     }
 }

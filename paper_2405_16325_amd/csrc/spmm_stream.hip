@@ -460,9 +460,8 @@ __global__ void __launch_bounds__(256) xl_reduce_kernel(const float* __restrict_
 
 }  // namespace
 
-// n <= 32, K % 64 == 0, K >= 128; T (bf16[n][K2]) and R (bf16[K2][m]) only when K2 > 0
-hipError_t launch_spmm_stream(const bf16_t* B, int64_t n, const bf16_t* A_vals, const uint8_t* A_meta, int64_t m,
-                              int64_t K, const bf16_t* T, const bf16_t* R, int64_t K2, bf16_t* C, hipStream_t s) {
+// Weight rows per workgroup of the small-batch kernel for n <= 32 tokens.
+int spmm_stream_rows(int64_t n, int64_t m, int64_t K) {
     if (n <= 16) {
         // Workgroups of 32, 48 or 64 weight rows (8, 6, 4 wavefronts: what fits in LDS).  One per
         // compute unit is resident; a round of 256 of them is bound by HBM, a thin last round by
@@ -479,15 +478,24 @@ hipError_t launch_spmm_stream(const bf16_t* B, int64_t n, const bf16_t* A_vals, 
             const double est = full * round_ns(RESIDENT) + (rest ? round_ns(rest) : 0.0);
             if (est < best_t) { best_t = est; best = c; }
         }
-        if (best == 0) return launch_stream_lds<2, 8, 1>(B, n, A_vals, A_meta, m, K, T, R, K2, C, s);
-        if (best == 1) return launch_stream_lds<3, 6, 1>(B, n, A_vals, A_meta, m, K, T, R, K2, C, s);
-        return launch_stream_lds<4, 4, 1>(B, n, A_vals, A_meta, m, K, T, R, K2, C, s);
+        return rows[best];
     }
     // 17 to 32 tokens: two token fragments per wavefront leave room for four wavefronts only
     const int64_t b32 = (m + 31) / 32, b48 = (m + 47) / 48;
     auto last_round = [](int64_t blocks) { int64_t r = blocks % RESIDENT; return r == 0 ? RESIDENT : r; };
-    if (last_round(b48) > last_round(b32) || b48 % RESIDENT == 0)
-        return launch_stream_lds<3, 4, 2>(B, n, A_vals, A_meta, m, K, T, R, K2, C, s);
+    return last_round(b48) > last_round(b32) || b48 % RESIDENT == 0 ? 48 : 32;
+}
+
+// n <= 32, K % 64 == 0, K >= 128; T (bf16[n][K2]) and R (bf16[K2][m]) only when K2 > 0
+hipError_t launch_spmm_stream(const bf16_t* B, int64_t n, const bf16_t* A_vals, const uint8_t* A_meta, int64_t m,
+                              int64_t K, const bf16_t* T, const bf16_t* R, int64_t K2, bf16_t* C, hipStream_t s) {
+    const int rows = spmm_stream_rows(n, m, K);
+    if (n <= 16) {
+        if (rows == 32) return launch_stream_lds<2, 8, 1>(B, n, A_vals, A_meta, m, K, T, R, K2, C, s);
+        if (rows == 48) return launch_stream_lds<3, 6, 1>(B, n, A_vals, A_meta, m, K, T, R, K2, C, s);
+        return launch_stream_lds<4, 4, 1>(B, n, A_vals, A_meta, m, K, T, R, K2, C, s);
+    }
+    if (rows == 48) return launch_stream_lds<3, 4, 2>(B, n, A_vals, A_meta, m, K, T, R, K2, C, s);
     return launch_stream_lds<2, 4, 2>(B, n, A_vals, A_meta, m, K, T, R, K2, C, s);
 }
 
@@ -495,7 +503,7 @@ hipError_t launch_spmm_stream(const bf16_t* B, int64_t n, const bf16_t* A_vals, 
 // Slabs of L per workgroup: single chunks of 64 rows for up to 32 tokens; beyond, up to four
 // chunks (smaller partial sums) as long as the launch still has a workgroup for every compute
 // unit.  Up to 16 tokens run on fp32 multiply-adds (xl_partial_kernel), more on MFMA.
-static int xl_subs(int64_t n, int64_t d_in, int64_t r) {
+int xl_subs(int64_t n, int64_t d_in, int64_t r) {
     if (n <= 32) return 1;
     const int64_t per_slab = ((r + 127) / 128) * ((n + 127) / 128);   // workgroups per slab
     for (int subs = 4; subs > 1; subs /= 2)
