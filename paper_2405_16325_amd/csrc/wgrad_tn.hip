@@ -23,10 +23,17 @@ namespace {
 // out[c][r] = in[r][c] for r < rows, zero for rows <= r < rows_pad; in is [rows][cols] bf16 with
 // cols % 8 == 0, out is [cols] rows of pitch ld >= rows_pad, rows_pad % 64 == 0, ld % 8 == 0.
 // 64 x 64 tiles through LDS, 16-byte global accesses on both sides.
-__global__ void __launch_bounds__(256) transpose_pad_kernel(const bf16_t* __restrict__ in, int rows, int cols,
-                                                            int rows_pad, int ld, bf16_t* __restrict__ out) {
+// blockIdx.z picks one of two matrices of the same row count (one launch for both operands of a product).
+__global__ void __launch_bounds__(256) transpose_pad_kernel(const bf16_t* __restrict__ in0, int cols0,
+                                                            bf16_t* __restrict__ out0, const bf16_t* __restrict__ in1,
+                                                            int cols1, bf16_t* __restrict__ out1, int rows,
+                                                            int rows_pad, int ld) {
     __shared__ bf16_t tile[64][66];
+    const bf16_t* __restrict__ in = blockIdx.z ? in1 : in0;
+    bf16_t* __restrict__ out = blockIdx.z ? out1 : out0;
+    const int cols = blockIdx.z ? cols1 : cols0;
     const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64, t = threadIdx.x;
+    if (c0 >= cols) return;                                   // uniform: the other matrix is wider
 #pragma unroll
     for (int p = 0; p < 2; ++p) {
         int r = (t >> 3) + 32 * p, c8 = (t & 7) * 8;
@@ -48,8 +55,16 @@ __global__ void __launch_bounds__(256) transpose_pad_kernel(const bf16_t* __rest
 
 inline void launch_transpose_pad(const bf16_t* in, int64_t rows, int64_t cols, int64_t rows_pad, int64_t ld,
                                  bf16_t* out, hipStream_t s) {
-    transpose_pad_kernel<<<dim3((unsigned)(rows_pad / 64), (unsigned)((cols + 63) / 64)), dim3(256), 0, s>>>(
-        in, (int)rows, (int)cols, (int)rows_pad, (int)ld, out);
+    transpose_pad_kernel<<<dim3((unsigned)(rows_pad / 64), (unsigned)((cols + 63) / 64), 1), dim3(256), 0, s>>>(
+        in, (int)cols, out, nullptr, 0, nullptr, (int)rows, (int)rows_pad, (int)ld);
+}
+
+// two matrices with the same rows, rows_pad and ld in one launch
+inline void launch_transpose_pad2(const bf16_t* in0, int64_t cols0, bf16_t* out0, const bf16_t* in1, int64_t cols1,
+                                  bf16_t* out1, int64_t rows, int64_t rows_pad, int64_t ld, hipStream_t s) {
+    const int64_t cmax = cols0 > cols1 ? cols0 : cols1;
+    transpose_pad_kernel<<<dim3((unsigned)(rows_pad / 64), (unsigned)((cmax + 63) / 64), 2), dim3(256), 0, s>>>(
+        in0, (int)cols0, out0, in1, (int)cols1, out1, (int)rows, (int)rows_pad, (int)ld);
 }
 
 // pitch (elements) of a token-contiguous copy with bp tokens per row
@@ -452,23 +467,23 @@ hipError_t launch_wgrad_masked_ws(const bf16_t* dY, const bf16_t* X, int64_t b, 
     const int64_t bp = (b + 63) / 64 * 64, ld = token_pitch(bp);
     bf16_t* Xt = (bf16_t*)workspace;
     bf16_t* dYt = Xt + (size_t)d_in * ld;
-    launch_transpose_pad(X, b, d_in, bp, ld, Xt, s);
-    launch_transpose_pad(dY, b, d_out, bp, ld, dYt, s);
+    launch_transpose_pad2(X, d_in, Xt, dY, d_out, dYt, b, bp, ld, s);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     // The kernel runs at the rate its compute units pull operands from L2: a launch costs about
     // (rounds of 256 resident tiles) x (rows per tile).  Take the cheapest shape, the larger on ties.
-    const int bms[3] = {256, 256, 128}, bns[3] = {256, 128, 128};
+    const int bms[4] = {256, 256, 128, 128}, bns[4] = {256, 128, 128, 64};
     int best = 0;
     int64_t best_cost = INT64_MAX;
-    for (int c = 0; c < 3; ++c) {
+    for (int c = 0; c < 4; ++c) {
         int64_t tiles = ((d_in + bms[c] - 1) / bms[c]) * ((d_out + bns[c] - 1) / bns[c]);
         int64_t cost = ((tiles + RESIDENT - 1) / RESIDENT) * (bms[c] + bns[c]);
         if (cost < best_cost) { best_cost = cost; best = c; }
     }
     if (best == 0) return launch_dense_tn_split<EPI_MASKED_PACKED>(Xt, d_in, dYt, d_out, bp, ld, meta, gvals, s);
     if (best == 1) return launch_dense_tn<256, 128, EPI_MASKED_PACKED, 3>(Xt, d_in, dYt, d_out, bp, ld, meta, gvals, s);
-    return launch_dense_tn<128, 128, EPI_MASKED_PACKED, 4>(Xt, d_in, dYt, d_out, bp, ld, meta, gvals, s);
+    if (best == 2) return launch_dense_tn<128, 128, EPI_MASKED_PACKED, 4>(Xt, d_in, dYt, d_out, bp, ld, meta, gvals, s);
+    return launch_dense_tn<128, 64, EPI_MASKED_PACKED, 6>(Xt, d_in, dYt, d_out, bp, ld, meta, gvals, s);
 }
 
 // C[n, m] = B[n, K] * A[m, K]^T, all bf16 row-major, K % 64 == 0 (the skinny product T = X L of the
@@ -557,8 +572,7 @@ hipError_t launch_wgrad_adapter(const bf16_t* dY, const bf16_t* X, int64_t b, co
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if ((e = launch_dense_tn_plain(X, b, Lt, r, d_in, T, nullptr, s)) != hipSuccess) return e;      // T  = X L
     if ((e = launch_dense_tn_plain(dY, b, R, r, d_out, T2, nullptr, s)) != hipSuccess) return e;    // T2 = dY R^T
-    launch_transpose_pad(T, b, r, bp, ld, Tt, s);
-    launch_transpose_pad(T2, b, r, bp, ld, T2t, s);
+    launch_transpose_pad2(T, r, Tt, T2, r, T2t, b, bp, ld, s);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     e = launch_dense_tn<128, 64, EPI_PLAIN, 6>(T2t, r, Xt, d_in, bp, ld, nullptr, dL, s);   // dL[d_in][r]
     if (e != hipSuccess) return e;
