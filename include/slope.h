@@ -235,9 +235,9 @@ slope_status slope_update_sparse(const void* Wnew_vals, const void* Wr_meta, int
  *       contraction split into slabs (needs the workspace), 2 tile kernel, 3 generic kernel
  *       (d_in not a multiple of 256)
  *   [1], [2] weight rows and tokens per workgroup      [3] slabs (1 = no split)
- *   [4] T = X L: 0 no adapter, 1 split over d_in on fp32 FMAs, 2 the same on MFMA,
- *       3 dense tile kernel, 4 dense tile kernel split over d_in
- *   [5] chunks of 64 rows of L per workgroup for [4] in {1, 2}
+ *   [4] T = X L: 0 no adapter, 1 split over d_in from L as stored (few tokens),
+ *       2 dense tile kernel, 3 dense tile kernel split over d_in
+ *   [5] chunks of 64 rows of L per workgroup for [4] == 1
  * with_workspace: whether the call would be given its scratch.  Errors as slope_spmm_fwd.
  */
 slope_status slope_spmm_fwd_plan(int64_t b, int64_t d_in, int64_t d_out, int64_t r, int with_workspace, int32_t* plan);

@@ -290,10 +290,10 @@ slope_status slope_spmm_fwd_plan(int64_t b, int64_t d_in, int64_t d_out, int64_t
     }
     if (r > 0) {
         if (b <= XL_SMALL_MAX_TOKENS) {
-            plan[4] = b <= 16 ? 1 : 2;
+            plan[4] = 1;
             plan[5] = xl_subs(b, d_in, r);
         } else {
-            plan[4] = dense_tn_plain_partial_bytes(b, r) ? 4 : 3;
+            plan[4] = dense_tn_plain_partial_bytes(b, r) ? 3 : 2;
         }
     }
     return SLOPE_OK;

@@ -9,7 +9,7 @@
 //     no barrier in the main loop, only the wavefront's own s_waitcnt;
 //   - the partial tiles are summed in a fixed order through LDS (bit-identical runs); before that
 //     the adapter term is added on dense MFMA from T = X L and the factor R as stored.
-// T itself comes from a split over d_in (xl_partial_kernel, fp32 partial sums in the workspace)
+// T itself comes from a split over d_in (xl_mfma_kernel, fp32 partial sums in the workspace)
 // followed by a fixed-order reduction that rounds to bf16 (xl_reduce_kernel).
 // (A first version kept the operands in registers and moved them into MFMA order with ds_bpermute;
 // the permutes capped a compute unit near 23 B/ns, against 44 B/ns with the LDS rings.)
@@ -17,7 +17,7 @@
 
 namespace {
 
-constexpr int XL_CHUNK = 64;        // rows of L per chunk of xl_partial_kernel
+constexpr int XL_CHUNK = 64;        // rows of L per chunk of the X L split
 
 union StB { u32x4 u[2]; bf16x16 v; };
 union StA { u32x4 u; bf16x8 v; };
@@ -259,78 +259,12 @@ hipError_t launch_stream_lds(const bf16_t* B, int64_t n, const bf16_t* Av, const
     return hipGetLastError();
 }
 
-// P[c][t][k] = sum over the rows i of slab c of X[t][i] * L[i][k]   (fp32; c = blockIdx.x, a slab is
-// `subs` chunks of 64 rows; blockIdx.y picks 128 columns of L, blockIdx.z a group of NT tokens)
-// A lane owns two columns of L (k and k + 64: its loads of a row are contiguous across the
-// wavefront, and all 64 rows of a chunk are requested before the first is used); the four
-// wavefronts split the NT tokens, whose values, the same for all lanes, are staged in LDS as fp32
-// and read back as broadcasts, each feeding two multiply-adds.
-template <int NT>
-__global__ void __launch_bounds__(256) xl_partial_kernel(const bf16_t* __restrict__ X, int n, int d_in,
-                                                         const bf16_t* __restrict__ L, int r, int subs,
-                                                         float* __restrict__ P) {
-    constexpr int TW = NT / 4;                                // tokens per wavefront
-    __shared__ __align__(16) float xs[NT][XL_CHUNK];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int c = blockIdx.x, t0 = blockIdx.z * NT, tw0 = wave * TW;
-    const int k0 = blockIdx.y * 128 + lane, k1 = k0 + 64;
-    const int kc0 = k0 < r ? k0 : r - 1, kc1 = k1 < r ? k1 : r - 1;
-    float acc[TW][2];
-#pragma unroll
-    for (int t = 0; t < TW; ++t) acc[t][0] = acc[t][1] = 0.f;
-    for (int sb = 0; sb < subs; ++sb) {
-        const int i0 = (c * subs + sb) * XL_CHUNK;           // d_in % 64 == 0: a chunk is full or absent
-        if (i0 >= d_in) break;                               // uniform
-        uint16_t la[XL_CHUNK], lb[XL_CHUNK];
-#pragma unroll
-        for (int i = 0; i < XL_CHUNK; ++i) {
-            la[i] = L[(size_t)(i0 + i) * r + kc0];
-            lb[i] = L[(size_t)(i0 + i) * r + kc1];
-        }
-        __syncthreads();                                     // the previous chunk's xs has been read
-        for (int idx = threadIdx.x; idx < NT * XL_CHUNK / 2; idx += 256) {
-            int t = idx / (XL_CHUNK / 2), i2 = idx % (XL_CHUNK / 2);
-            int tt = t0 + t < n ? t0 + t : n - 1;
-            uint32_t w = *(const uint32_t*)(X + (size_t)tt * d_in + i0 + 2 * i2);
-            xs[t][2 * i2] = __uint_as_float(w << 16);
-            xs[t][2 * i2 + 1] = __uint_as_float(w & 0xFFFF0000u);
-        }
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < XL_CHUNK; i += 4) {
-            float a0 = __uint_as_float((uint32_t)la[i] << 16), a1 = __uint_as_float((uint32_t)la[i + 1] << 16);
-            float a2 = __uint_as_float((uint32_t)la[i + 2] << 16), a3 = __uint_as_float((uint32_t)la[i + 3] << 16);
-            float b0 = __uint_as_float((uint32_t)lb[i] << 16), b1 = __uint_as_float((uint32_t)lb[i + 1] << 16);
-            float b2 = __uint_as_float((uint32_t)lb[i + 2] << 16), b3 = __uint_as_float((uint32_t)lb[i + 3] << 16);
-#pragma unroll
-            for (int t = 0; t < TW; ++t) {
-                f32x4 xv = *(const f32x4*)&xs[tw0 + t][i];    // same address in every lane: an LDS broadcast
-                acc[t][0] = __builtin_fmaf(xv[0], a0, acc[t][0]);
-                acc[t][1] = __builtin_fmaf(xv[0], b0, acc[t][1]);
-                acc[t][0] = __builtin_fmaf(xv[1], a1, acc[t][0]);
-                acc[t][1] = __builtin_fmaf(xv[1], b1, acc[t][1]);
-                acc[t][0] = __builtin_fmaf(xv[2], a2, acc[t][0]);
-                acc[t][1] = __builtin_fmaf(xv[2], b2, acc[t][1]);
-                acc[t][0] = __builtin_fmaf(xv[3], a3, acc[t][0]);
-                acc[t][1] = __builtin_fmaf(xv[3], b3, acc[t][1]);
-            }
-        }
-    }
-#pragma unroll
-    for (int t = 0; t < TW; ++t) {
-        const int tok = t0 + tw0 + t;
-        if (tok >= n) continue;
-        float* row = P + ((size_t)c * n + tok) * r;
-        if (k0 < r) row[k0] = acc[t][0];
-        if (k1 < r) row[k1] = acc[t][1];
-    }
-}
-
-// The same partial sums on MFMA, from 17 tokens (where the multiply-adds above become the
-// bottleneck) to XL_SMALL_MAX_TOKENS.  L is k-major (rows = d_in), the wrong way round for an
+// P[c][t][j] = sum over the rows i of slab c of X[t][i] * L[i][j]   (fp32 partial sums of T = X L for
+// up to XL_SMALL_MAX_TOKENS tokens, on MFMA).  L is k-major (rows = d_in), the wrong way round for an
 // MFMA operand, so a slab of it is staged in LDS as stored and read back with the transposing read
 // ds_read_b64_tr_b16: in each block of 16 lanes, lane s receives four consecutive rows (k) of
-// column s.  D rows are the
+// column s.  (A first version with fp32 multiply-adds and token values broadcast from LDS took
+// 24 us where this takes 6, at 9216 x 128 and 64 tokens, and was 2 us slower even for one token.)  D rows are the
 // columns of L, D columns the tokens: a lane ends up with four consecutive columns of one token.
 //   workgroup = slab c of 64 * subs rows x 128 columns (blockIdx.y) x 128 tokens (blockIdx.z);
 //   wavefront w takes columns 32 w .. 32 w + 31; token rows come straight from global memory
@@ -502,7 +436,7 @@ hipError_t launch_spmm_stream(const bf16_t* B, int64_t n, const bf16_t* A_vals, 
 // T = X L for few tokens (up to XL_SMALL_MAX_TOKENS), split over d_in; scratch holds xl_small_scratch_bytes.
 // Slabs of L per workgroup: single chunks of 64 rows for up to 32 tokens; beyond, up to four
 // chunks (smaller partial sums) as long as the launch still has a workgroup for every compute
-// unit.  Up to 16 tokens run on fp32 multiply-adds (xl_partial_kernel), more on MFMA.
+// unit.
 int xl_subs(int64_t n, int64_t d_in, int64_t r) {
     if (n <= 32) return 1;
     const int64_t per_slab = ((r + 127) / 128) * ((n + 127) / 128);   // workgroups per slab
@@ -520,18 +454,12 @@ hipError_t launch_xl_small(const bf16_t* X, int64_t n, int64_t d_in, const bf16_
                            bf16_t* T, hipStream_t s) {
     const int subs = xl_subs(n, d_in, r);
     const int slabs = (int)((d_in + XL_CHUNK * subs - 1) / (XL_CHUNK * subs));
-    if (n <= 16) {
-        dim3 grid((unsigned)slabs, (unsigned)((r + 127) / 128), 1);
-        xl_partial_kernel<16><<<grid, dim3(256), 0, s>>>(X, (int)n, (int)d_in, L, (int)r, subs, scratch);
-    } else {
-        const int lds = XL_CHUNK * subs * XLM_PITCH;
-        hipError_t e = hipFuncSetAttribute((const void*)xl_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        dim3 grid((unsigned)slabs, (unsigned)((r + 127) / 128), (unsigned)((n + 127) / 128));
-        xl_mfma_kernel<<<grid, dim3(256), lds, s>>>(X, (int)n, (int)d_in, L, (int)r, subs, scratch);
-    }
-    hipError_t e = hipGetLastError();
+    const int lds = XL_CHUNK * subs * XLM_PITCH;
+    hipError_t e = hipFuncSetAttribute((const void*)xl_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
+    dim3 grid((unsigned)slabs, (unsigned)((r + 127) / 128), (unsigned)((n + 127) / 128));
+    xl_mfma_kernel<<<grid, dim3(256), lds, s>>>(X, (int)n, (int)d_in, L, (int)r, subs, scratch);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
     const int count = (int)(n * r);
     xl_reduce_kernel<<<dim3((unsigned)((count + 31) / 32)), dim3(256), 0, s>>>(scratch, slabs, count, T);
     return hipGetLastError();

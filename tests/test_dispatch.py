@@ -64,10 +64,9 @@ def test_contractions_that_are_no_multiple_of_256_take_the_generic_kernel():
 def test_adapter_product_regimes():
     xl = lambda b, r=128, d_in=9216: sl.slope_spmm_fwd_plan(b, d_in, 9216, r)["xl"]
     assert sl.slope_spmm_fwd_plan(64, 9216, 9216, 0)["xl"] == 0
-    assert [xl(b) for b in (1, 16)] == [1, 1]                   # fp32 FMAs
-    assert [xl(b) for b in (17, 128, 512)] == [2, 2, 2]         # MFMA with transposing LDS reads
-    assert [xl(b) for b in (513, 4096)] == [4, 4]               # dense tile kernel, too few tiles: split over d_in
-    assert xl(16384) == 3                                       # 256 tiles: no split
+    assert [xl(b) for b in (1, 16, 17, 128, 512)] == [1] * 5    # split over d_in, L as stored
+    assert [xl(b) for b in (513, 4096)] == [3, 3]               # dense tile kernel, too few tiles: split over d_in
+    assert xl(16384) == 2                                       # 256 tiles: no split
     # chunks of 64 rows of L per workgroup: as many as still give every compute unit a workgroup
     chunks = lambda b, d_in: sl.slope_spmm_fwd_plan(b, d_in, 9216, 128)["xl_chunks"]
     assert chunks(16, 9216) == 1 and chunks(64, 9216) == 1 and chunks(64, 36864) == 2 and chunks(512, 36864) == 4
