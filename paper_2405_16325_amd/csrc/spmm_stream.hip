@@ -434,11 +434,9 @@ hipError_t launch_spmm_stream(const bf16_t* B, int64_t n, const bf16_t* A_vals, 
 }
 
 // T = X L for few tokens (up to XL_SMALL_MAX_TOKENS), split over d_in; scratch holds xl_small_scratch_bytes.
-// Slabs of L per workgroup: single chunks of 64 rows for up to 32 tokens; beyond, up to four
-// chunks (smaller partial sums) as long as the launch still has a workgroup for every compute
-// unit.
+// Slabs of L per workgroup: up to four chunks of 64 rows (smaller partial sums) as long as the launch
+// still has a workgroup for every compute unit.
 int xl_subs(int64_t n, int64_t d_in, int64_t r) {
-    if (n <= 32) return 1;
     const int64_t per_slab = ((r + 127) / 128) * ((n + 127) / 128);   // workgroups per slab
     for (int subs = 4; subs > 1; subs /= 2)
         if ((d_in + XL_CHUNK * subs - 1) / (XL_CHUNK * subs) * per_slab >= RESIDENT) return subs;

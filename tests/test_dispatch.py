@@ -69,7 +69,7 @@ def test_adapter_product_regimes():
     assert xl(16384) == 2                                       # 256 tiles: no split
     # chunks of 64 rows of L per workgroup: as many as still give every compute unit a workgroup
     chunks = lambda b, d_in: sl.slope_spmm_fwd_plan(b, d_in, 9216, 128)["xl_chunks"]
-    assert chunks(16, 9216) == 1 and chunks(64, 9216) == 1 and chunks(64, 36864) == 2 and chunks(512, 36864) == 4
+    assert chunks(16, 9216) == 1 and chunks(64, 9216) == 1 and chunks(16, 36864) == 2 and chunks(512, 36864) == 4
 
 
 def test_plan_rejects_what_the_call_rejects():
