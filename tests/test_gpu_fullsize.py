@@ -95,3 +95,37 @@ def test_opt66b_layer_sampled(name, d_out, d_in):
         lo, hi = m & 3, (m >> 2) & 3
         lo2, hi2 = (m >> 4) & 3, m >> 6
         assert bool((lo < hi).all()) and bool((lo2 < hi2).all())
+
+
+@pytest.mark.parametrize("name,d_out,d_in", [("fc1", 36864, 9216), ("fc2", 9216, 36864), ("attn", 9216, 9216)])
+def test_opt66b_inference_sampled(name, d_out, d_in):
+    """The same layers at the inference benchmark's batch sizes (1, 16, 128 tokens and two in between),
+    rank-128 adapters included: every token, sampled rows of W."""
+    rank = 128
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(inputs.SEED_BASE + 67)
+
+    def gauss(shape, std):
+        return (torch.randn(shape, generator=gen, device=dev, dtype=torch.float32) * std).to(torch.bfloat16)
+
+    W = gauss((d_out, d_in), 0.02)
+    L, R = gauss((d_in, rank), 0.02), gauss((rank, d_out), 0.02)
+    vals, meta, _ = sl.slope_prune_rows(W)
+    rng = np.random.default_rng(67)
+    rows = np.sort(rng.choice(d_out, 64, replace=False))
+    rows_t = torch.from_numpy(rows).to(dev)
+    w_rows = host(W[rows_t])
+    mask_rows = so.prune_rows(w_rows)
+    l_host, r_host = host(L), host(R[:, rows_t].contiguous())
+    for b in (1, 16, 24, 128, 300):
+        print(f"full-size inference {name}: b={b} d_out={d_out} d_in={d_in} rank={rank}", flush=True)
+        X = gauss((b, d_in), 1.0)
+        for with_adapter in (False, True):
+            Y = sl.slope_spmm_fwd(X, vals, meta, L, R) if with_adapter else sl.slope_spmm_fwd(X, vals, meta)
+            torch.cuda.synchronize()
+            want = so.spmm_fwd(host(X), w_rows, mask_rows, l_host, r_host) if with_adapter \
+                else so.spmm_fwd(host(X), w_rows, mask_rows)
+            err = so.rel_fro(so.bf16_to_f64(host(Y[:, rows_t].contiguous())), want)
+            print(f"  adapter={with_adapter} rel_fro {err:.3e}", flush=True)
+            assert err <= TOL
