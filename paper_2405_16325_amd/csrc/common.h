@@ -47,7 +47,7 @@ constexpr int64_t XL_SMALL_MAX_TOKENS = 512;
 size_t xl_small_scratch_bytes(int64_t n, int64_t d_in, int64_t r);
 hipError_t launch_xl_small(const bf16_t* X, int64_t n, int64_t d_in, const bf16_t* L, int64_t r, float* scratch,
                            bf16_t* T, hipStream_t s);
-// T[n, r] = X[n, K] * Lt[r, K]^T (dense), plus transposes of the adapter factors
+// T[n, r] = X[n, K] * Lt[r, K]^T (dense tile kernel) for many tokens, with the k-contiguous copy Lt of L
 hipError_t launch_lowrank_prepare(const bf16_t* X, int64_t n, int64_t d_in, const bf16_t* L, int64_t r, bf16_t* T,
                                   bf16_t* Lt, float* partial_or_null, hipStream_t s);
 hipError_t launch_wgrad_masked(const bf16_t* dY, const bf16_t* X, int64_t b, const uint8_t* meta, int64_t d_out,

@@ -4,8 +4,8 @@
 //     C[n, m] = sum_k B[n, k] * A[m, k]        A: packed 2:4 along k (vals + 4-bit metadata)
 //             + sum_k2 B2[n, k2] * A2[m, k2]   dense bf16, K2 = adapter rank (optional)
 //
-// fwd  : A = W^R        (m = d_out, k = d_in ), B = X,  C = Y,  A2 = R^T, B2 = X L
-// bwd_x: A = (W^{R,C})^T (m = d_in,  k = d_out), B = dY, C = dX
+// fwd  : A = W^R        (m = d_out, k = d_in ), B = X,  C = Y,  B2 = X L, A2 = R^T given as R (k-major)
+// bwd_x: A = (W^{R,C})^T (m = d_in,  k = d_out), B = dY, C = dX (with adapters: B2 = dY R^T, A2 = L)
 //
 // The instruction is v_smfmac_f32_16x16x64_bf16 (D[16 x 16] += Asparse[16 x 64] * B[64 x 16]):
 //   A   lane l holds row l%16 and the 8 packed values of logical k = 16*(l/16) .. +15
@@ -19,9 +19,9 @@
 // spmm_kernel<BM, BN> and spmm_split_kernel (the 256 x 256 tile) are the fast ones and need
 // K % 256 == 0; spmm_generic_kernel takes any K % 64 == 0 with a plain register-staged pipeline.
 //
-// spmm_kernel.  What bounds it on MI355X is the rate at which a compute unit can pull operands
-// from L2 (about one cache-line request per 2 clocks, 64 B/clk at best), not the matrix pipe, so
-// the data path is built around full 128-byte lines:
+// spmm_kernel.  What a compute unit can pull from L2 per unit of time matters as much as the matrix
+// pipe (whose clock the power management lowers well below nominal under this load), so the data
+// path is built around full 128-byte lines:
 //   - every global -> LDS load instruction (global_load_lds_dwordx4, no registers in between)
 //     fetches 8 rows x 128 contiguous bytes, 8 consecutive lanes per row;
 //   - a row of the token operand has 128 bytes per k-step of 64, so B sits in a ring of three
