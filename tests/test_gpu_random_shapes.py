@@ -1,0 +1,53 @@
+"""Seeded random layer shapes through every product call (needs an MI355X): a sweep over the
+dispatch regimes that the hand-picked shapes of test_gpu_parity.py may miss.  Same bar as there:
+relative Frobenius error of at most 1e-2 against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import slope_oracle as so
+from paper_2405_16325_amd import binding as sl
+from tests.test_gpu_parity import TOL, host, layer_on_device, say, u8
+
+pytestmark = pytest.mark.gpu
+
+
+def random_cases(count=28, seed=20240527):
+    rng = np.random.default_rng(seed)
+    token_pool = [1, 3, 16, 17, 31, 32, 33, 40, 64, 65, 100, 128, 129, 190, 256, 257, 300, 512, 513, 700, 1100]
+    cases = []
+    for _ in range(count):
+        b = int(rng.choice(token_pool))
+        d_out, d_in = (64 * int(rng.integers(1, 17)) for _ in range(2))       # 64 .. 1024
+        if rng.random() < 0.4:
+            d_in = 256 * int(rng.integers(1, 9))                               # the fast kernels' contraction lengths
+        if rng.random() < 0.25:
+            d_out = 256 * int(rng.integers(1, 13))
+        r = int(rng.choice([0, 32, 64, 96, 160]))
+        cases.append((b, d_out, d_in, r))
+    return cases
+
+
+@pytest.mark.parametrize("b,d_out,d_in,r", random_cases())
+def test_random_layer(b, d_out, d_in, r):
+    say(f"random layer b={b} d_out={d_out} d_in={d_in} r={r}")
+    t, d, mask_r, mask_rc = layer_on_device(b, d_out, d_in, r, seed=b * 7 + d_out + d_in + r)
+    if r:
+        y = sl.slope_spmm_fwd(d["X"], d["vals"], d["meta"], d["L"], d["R"])
+        want_y = so.spmm_fwd(t["X"], t["W"], mask_r, t["L"], t["R"])
+    else:
+        y = sl.slope_spmm_fwd(d["X"], d["vals"], d["meta"])
+        want_y = so.spmm_fwd(t["X"], t["W"], mask_r)
+    dx = sl.slope_spmm_bwd_x(d["dY"], d["vals_t"], d["meta_t"])
+    g_ws = sl.slope_wgrad_masked(d["dY"], d["X"], d["meta"], workspace="auto")
+    g_in = sl.slope_wgrad_masked(d["dY"], d["X"], d["meta"], workspace=None)
+    torch.cuda.synchronize()
+    want_g = so.wgrad_masked(t["dY"], t["X"], u8(d["meta"]))
+    errs = {
+        "fwd": so.rel_fro(so.bf16_to_f64(host(y)), want_y),
+        "bwd_x": so.rel_fro(so.bf16_to_f64(host(dx)), so.spmm_bwd_x(t["dY"], t["W"], mask_rc)),
+        "wgrad(workspace)": so.rel_fro(so.bf16_to_f64(host(g_ws)), want_g),
+        "wgrad(in place)": so.rel_fro(so.bf16_to_f64(host(g_in)), want_g),
+    }
+    say("  " + "  ".join(f"{k} {v:.2e}" for k, v in errs.items()))
+    assert all(v <= TOL for v in errs.values()), errs
