@@ -49,5 +49,14 @@ def test_random_layer(b, d_out, d_in, r):
         "wgrad(workspace)": so.rel_fro(so.bf16_to_f64(host(g_ws)), want_g),
         "wgrad(in place)": so.rel_fro(so.bf16_to_f64(host(g_in)), want_g),
     }
+    if r:                                                      # backward pass with adapters (chain rule of Eq. 11)
+        dxa = sl.slope_spmm_bwd_x_adapter(d["dY"], d["vals_t"], d["meta_t"], d["L"], d["R"])
+        ga, dl, dr = sl.slope_wgrad_adapter(d["dY"], d["X"], d["meta"], d["L"], d["R"])
+        torch.cuda.synchronize()
+        want_dl, want_dr = so.adapter_grads(t["dY"], t["X"], t["L"], t["R"])
+        errs["bwd_x(adapter)"] = so.rel_fro(so.bf16_to_f64(host(dxa)), so.spmm_bwd_x(t["dY"], t["W"], mask_rc, t["L"], t["R"]))
+        errs["dL"] = so.rel_fro(so.bf16_to_f64(host(dl)), want_dl)
+        errs["dR"] = so.rel_fro(so.bf16_to_f64(host(dr)), want_dr)
+        assert (host(ga) == host(g_ws)).all()
     say("  " + "  ".join(f"{k} {v:.2e}" for k, v in errs.items()))
     assert all(v <= TOL for v in errs.values()), errs
