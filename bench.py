@@ -41,6 +41,7 @@ def parse():
     ap.add_argument("--workload", default="opt66b",
                     help="opt66b (headline) | opt13b | opt2.7b | opt125m_fc1 | opt66b_infer (forward at 1/16/128 tokens)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sclk", action="store_true", help="skip the shader-clock sampling loops (for profiling runs)")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="also time the step (and the dense comparison) replayed from a captured HIP graph")
@@ -280,10 +281,10 @@ def main():
                        "calls": "slope_spmm_bwd_x_adapter + slope_wgrad_adapter per layer"}
 
     # Shader clock under load (outside the timed region): the published MFMA peaks assume 2.4 GHz, but the
-    # power management lowers the clock while MFMA-bound kernels run.  rocm-smi is sampled while one kind of
-    # call loops for about a second.
+    # power management lowers the clock while MFMA-bound kernels run.  The driver's clock table in sysfs is
+    # sampled while one kind of call loops for about a second.
     big = max(layers, key=lambda l: l["d_in"] * l["d_out"])
-    sclk = {
+    sclk = None if args.no_sclk else {
         "idle": sample_sclk(torch, None),
         "slope_spmm_bwd_x": sample_sclk(torch, lambda: sl.slope_spmm_bwd_x(big["dY"], big["vals_t"], big["meta_t"],
                                                                          out=big["dX"])),
@@ -292,7 +293,7 @@ def main():
         "dense_gemm": None if args.no_dense else sample_sclk(torch, lambda: torch.matmul(big["X"], big["W"].t(),
                                                                                         out=big["Y"])),
     }
-    if sclk["slope_spmm_bwd_x"]:
+    if sclk and sclk["slope_spmm_bwd_x"]:
         roofline["sclk_mhz_under_load"] = sclk["slope_spmm_bwd_x"]
         roofline["frac_at_that_clock"] = roofline["frac"] * NOMINAL_MHZ / sclk["slope_spmm_bwd_x"]
 
@@ -417,24 +418,34 @@ def read_traffic(kernel):
     return None
 
 
-def sample_sclk(torch, fn, seconds=1.2):
-    """Median shader clock (MHz) that rocm-smi reports while fn loops (None: idle); None if it cannot be read."""
+def read_sclk_mhz():
+    """Current shader clock (MHz) from the driver's sysfs table (the entry marked '*'), or None.  No child
+    process is started: this runs in a process that has initialised the GPU."""
+    import glob
     import re
-    import subprocess
+    for path in sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk")):
+        try:
+            for line in open(path):
+                if "*" in line:
+                    m = re.search(r"([0-9.]+)\s*[Mm][Hh]z", line)
+                    if m:
+                        return float(m.group(1))
+        except OSError:
+            continue
+    return None
+
+
+def sample_sclk(torch, fn, seconds=1.2):
+    """Median shader clock (MHz) while fn loops (None: idle); None if it cannot be read."""
     import threading
     vals, stop = [], [False]
 
     def sampler():
         while not stop[0]:
-            try:
-                txt = subprocess.run(["rocm-smi", "--showclocks", "--csv"], capture_output=True, text=True,
-                                     timeout=10).stdout
-                head, row = [ln.split(",") for ln in txt.strip().splitlines()[:2]]
-                idx = [i for i, h in enumerate(head) if h.startswith("sclk clock speed")][0]
-                vals.append(float(re.sub(r"[^0-9.]", "", row[idx])))
-            except Exception:
-                pass
-            time.sleep(0.1)
+            v = read_sclk_mhz()
+            if v is not None:
+                vals.append(v)
+            time.sleep(0.05)
     th = threading.Thread(target=sampler)
     th.start()
     t0 = time.perf_counter()
