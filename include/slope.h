@@ -48,7 +48,8 @@ typedef enum {
     SLOPE_ERR_SHAPE = -2,       /* extent <= 0, not a multiple of its quantum, too big */
     SLOPE_ERR_ALIGN = -3,       /* a pointer is not 16-byte aligned                    */
     SLOPE_ERR_UNSUPPORTED = -4, /* N:M other than 2:4, adapter rank not supported      */
-    SLOPE_ERR_HIP = -5          /* a launch failed; see slope_last_hip_error()         */
+    SLOPE_ERR_HIP = -5,         /* a launch failed; see slope_last_hip_error()         */
+    SLOPE_ERR_WORKSPACE = -6    /* the scratch buffer is smaller than the call needs   */
 } slope_status;
 
 /* Library version (major*100 + minor) and the last hipError_t seen by this thread. */
@@ -112,6 +113,27 @@ slope_status slope_spmm_fwd(const void* X, int64_t b, const void* Wr_vals, const
                             int64_t d_out, int64_t d_in,
                             const void* L_or_null, const void* R_or_null, int64_t r,
                             void* Y, void* workspace, void* stream);
+
+/*
+ * slope_spmm_fwd_static - slope_spmm_fwd for callers that cannot allocate device memory or carry a
+ * workspace around: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, same kernels and bit-identical results, but the scratch memory is a
+ * buffer of SLOPE_STATIC_SCRATCH_BYTES inside the library's own device image (every GPU the library
+ * runs on holds one copy until the process ends).  The call allocates and frees nothing.
+ *   - A shape whose slope_spmm_fwd_workspace_bytes(b, d_in, d_out, r) exceeds SLOPE_STATIC_SCRATCH_BYTES
+ *     is rejected with SLOPE_ERR_WORKSPACE before anything is launched; that query is the test.  (Every
+ *     token count up to 128 fits for the OPT-66B layers with rank-128 adapters, and so does every
+ *     training-size batch of them, whose need is T = X L plus a copy of L, about 10-18 MiB.)
+ *   - The buffer is found once per device, on the first call made while that device is current
+ *     (make that call outside stream capture); the stream must belong to the current device.
+ *   - All calls on one GPU share the buffer: calls that overlap in time on one GPU (different
+ *     streams, different threads) race.  Calls queued on one stream are safe.
+ */
+#define SLOPE_STATIC_SCRATCH_BYTES (72u << 20)
+slope_status slope_spmm_fwd_static(const void* X, int64_t b, const void* Wr_vals, const void* Wr_meta,
+                                   int64_t d_out, int64_t d_in,
+                                   const void* L_or_null, const void* R_or_null, int64_t r,
+                                   void* Y, void* stream);
 
 /*
  * slope_spmm_bwd_x - dX = dY W^{R,C}  (Eq. 6; Algorithm 1 line 11).

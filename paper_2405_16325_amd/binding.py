@@ -20,6 +20,8 @@ SLOPE_ERR_SHAPE = -2
 SLOPE_ERR_ALIGN = -3
 SLOPE_ERR_UNSUPPORTED = -4
 SLOPE_ERR_HIP = -5
+SLOPE_ERR_WORKSPACE = -6
+SLOPE_STATIC_SCRATCH_BYTES = 72 << 20      # include/slope.h
 
 _P, _I64, _INT, _SZ = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
 
@@ -35,6 +37,7 @@ SIGNATURES = {
     "slope_prune_rows": (_INT, [_P, _I64, _I64, _INT, _INT, _P, _P, _P, _P]),
     "slope_double_prune": (_INT, [_P, _P, _I64, _I64, _P, _P, _P, _P]),
     "slope_spmm_fwd": (_INT, [_P, _I64, _P, _P, _I64, _I64, _P, _P, _I64, _P, _P, _P]),
+    "slope_spmm_fwd_static": (_INT, [_P, _I64, _P, _P, _I64, _I64, _P, _P, _I64, _P, _P]),
     "slope_spmm_bwd_x": (_INT, [_P, _I64, _P, _P, _I64, _I64, _P, _P]),
     "slope_wgrad_workspace_bytes": (_SZ, [_I64, _I64, _I64]),
     "slope_wgrad_masked": (_INT, [_P, _P, _I64, _P, _I64, _I64, _P, _P, _P]),
@@ -144,6 +147,19 @@ def slope_spmm_fwd(X: torch.Tensor, vals: torch.Tensor, meta: torch.Tensor, L=No
             workspace = torch.empty(nbytes, dtype=torch.uint8, device=X.device)
     _check("slope_spmm_fwd", lib().slope_spmm_fwd(_ptr(X), b, _ptr(vals), _ptr(meta), d_out, d_in, _ptr(L), _ptr(R),
                                                   r, _ptr(Y), _ptr(workspace), _stream()))
+    return Y
+
+
+def slope_spmm_fwd_static(X: torch.Tensor, vals: torch.Tensor, meta: torch.Tensor, L=None, R=None, out=None):
+    """slope_spmm_fwd on the library's own scratch buffer: the call itself allocates nothing (pass `out`
+    to keep this wrapper from allocating Y)."""
+    _dev(X, vals, meta, L, R)
+    b, d_in = X.shape
+    d_out = vals.shape[0]
+    r = 0 if L is None else L.shape[1]
+    Y = out if out is not None else torch.empty((b, d_out), dtype=torch.bfloat16, device=X.device)
+    _check("slope_spmm_fwd_static", lib().slope_spmm_fwd_static(_ptr(X), b, _ptr(vals), _ptr(meta), d_out, d_in,
+                                                                _ptr(L), _ptr(R), r, _ptr(Y), _stream()))
     return Y
 
 

@@ -1,5 +1,7 @@
 // C ABI of the double-pruned 2:4 sparse linear layer (declared in include/slope.h):
 // argument checks on the host, then the launchers.  No allocation, no synchronisation, no state.
+#include <atomic>
+
 #include "pipeline.h"
 
 namespace {
@@ -34,6 +36,7 @@ const char* slope_status_string(int status) {
         case SLOPE_ERR_ALIGN: return "a pointer is not sufficiently aligned";
         case SLOPE_ERR_UNSUPPORTED: return "unsupported N:M pattern or adapter rank";
         case SLOPE_ERR_HIP: return "a HIP launch failed";
+        case SLOPE_ERR_WORKSPACE: return "the call needs more scratch memory than the buffer it was given holds";
         default: return "unknown status";
     }
 }
@@ -90,21 +93,28 @@ slope_status slope_double_prune(const void* Wr_vals, const void* Wr_meta, int64_
                                       (hipStream_t)stream));
 }
 
-slope_status slope_spmm_fwd(const void* X, int64_t b, const void* Wr_vals, const void* Wr_meta, int64_t d_out,
-                            int64_t d_in, const void* L_or_null, const void* R_or_null, int64_t r, void* Y,
-                            void* workspace, void* stream) {
+// Argument checks of slope_spmm_fwd and slope_spmm_fwd_static, up to the scratch buffer.
+static slope_status spmm_fwd_check(const void* X, int64_t b, const void* Wr_vals, const void* Wr_meta, int64_t d_out,
+                                   int64_t d_in, const void* L_or_null, const void* R_or_null, int64_t r, void* Y) {
     if (!X || !Wr_vals || !Wr_meta || !Y) return SLOPE_ERR_NULL;
     if (bad_extent(b, 1) || bad_extent(d_out, 64) || bad_extent(d_in, 64)) return SLOPE_ERR_SHAPE;
-    const bool adapter = r > 0 && (L_or_null || R_or_null);
     if (r < 0) return SLOPE_ERR_SHAPE;
-    if (adapter) {
-        if (!L_or_null || !R_or_null || !workspace) return SLOPE_ERR_NULL;
+    if (r > 0 && (L_or_null || R_or_null)) {
+        if (!L_or_null || !R_or_null) return SLOPE_ERR_NULL;
         if (r % 32 != 0 || r > 512) return SLOPE_ERR_UNSUPPORTED;
         if (misaligned(L_or_null, 16) || misaligned(R_or_null, 16)) return SLOPE_ERR_ALIGN;
     }
-    if (misaligned(X, 16) || misaligned(Wr_vals, 16) || misaligned(Wr_meta, 16) || misaligned(Y, 16) ||
-        misaligned(workspace, 256))
+    if (misaligned(X, 16) || misaligned(Wr_vals, 16) || misaligned(Wr_meta, 16) || misaligned(Y, 16))
         return SLOPE_ERR_ALIGN;
+    return SLOPE_OK;
+}
+
+// The launches of slope_spmm_fwd; arguments are checked, `workspace` (if any) has
+// slope_spmm_fwd_workspace_bytes(b, d_in, d_out, r) bytes.
+static slope_status spmm_fwd_run(const void* X, int64_t b, const void* Wr_vals, const void* Wr_meta, int64_t d_out,
+                                 int64_t d_in, const void* L_or_null, const void* R_or_null, int64_t r, void* Y,
+                                 void* workspace, void* stream) {
+    const bool adapter = r > 0 && (L_or_null || R_or_null);
     hipStream_t s = (hipStream_t)stream;
     const bf16_t* x = (const bf16_t*)X;
     const bf16_t* wv = (const bf16_t*)Wr_vals;
@@ -142,6 +152,62 @@ slope_status slope_spmm_fwd(const void* X, int64_t b, const void* Wr_vals, const
     const int64_t K2 = adapter ? -r : 0;
     if (slabs) return finish(launch_spmm_slabs(x, b, wv, wm, d_out, d_in, B2, A2, K2, (bf16_t*)Y, slabs, s));
     return finish(launch_spmm(x, b, wv, wm, d_out, d_in, B2, A2, K2, (bf16_t*)Y, s));
+}
+
+slope_status slope_spmm_fwd(const void* X, int64_t b, const void* Wr_vals, const void* Wr_meta, int64_t d_out,
+                            int64_t d_in, const void* L_or_null, const void* R_or_null, int64_t r, void* Y,
+                            void* workspace, void* stream) {
+    slope_status st = spmm_fwd_check(X, b, Wr_vals, Wr_meta, d_out, d_in, L_or_null, R_or_null, r, Y);
+    if (st != SLOPE_OK) return st;
+    if (r > 0 && (L_or_null || R_or_null) && !workspace) return SLOPE_ERR_NULL;
+    if (misaligned(workspace, 256)) return SLOPE_ERR_ALIGN;
+    return spmm_fwd_run(X, b, Wr_vals, Wr_meta, d_out, d_in, L_or_null, R_or_null, r, Y, workspace, stream);
+}
+
+// ---- slope_spmm_fwd_static: the same call on a scratch buffer that lives in the library's image.
+// `scratch` below is the host-side stand-in of the device array: its device address differs from
+// GPU to GPU and is looked up once per device with hipGetSymbolAddress; only that address is ever
+// handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[SLOPE_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::atomic<void*> g_scratch_ptr[MAX_DEVICES];
+
+// Device address of `scratch` on the current device (first call per device asks the runtime).
+hipError_t static_scratch(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);   // racing first calls store the same address
+    }
+    *out = p;
+    return hipSuccess;
+}
+}  // namespace
+
+slope_status slope_spmm_fwd_static(const void* X, int64_t b, const void* Wr_vals, const void* Wr_meta, int64_t d_out,
+                                   int64_t d_in, const void* L_or_null, const void* R_or_null, int64_t r, void* Y,
+                                   void* stream) {
+    slope_status st = spmm_fwd_check(X, b, Wr_vals, Wr_meta, d_out, d_in, L_or_null, R_or_null, r, Y);
+    if (st != SLOPE_OK) return st;
+    const bool adapter = r > 0 && (L_or_null || R_or_null);
+    const size_t need = slope_spmm_fwd_workspace_bytes(b, d_in, d_out, adapter ? r : 0);
+    if (need > (size_t)SLOPE_STATIC_SCRATCH_BYTES) return SLOPE_ERR_WORKSPACE;
+    void* ws = nullptr;
+    if (need > 0) {
+        hipError_t e = static_scratch(&ws);
+        if (e != hipSuccess) return finish(e);
+    }
+    // Nothing in the buffer has to start at zero: every partial sum that is read was written by this
+    // call's own kernels first.
+    return spmm_fwd_run(X, b, Wr_vals, Wr_meta, d_out, d_in, L_or_null, R_or_null, r, Y, ws, stream);
 }
 
 slope_status slope_spmm_bwd_x(const void* dY, int64_t b, const void* WrcT_vals, const void* WrcT_meta, int64_t d_out,

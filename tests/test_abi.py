@@ -87,6 +87,19 @@ def test_argument_errors_are_reported_before_launch():
     assert b"NULL" in lib.slope_status_string(binding.SLOPE_ERR_NULL)
 
 
+def test_static_scratch_rejects_a_shape_beyond_its_buffer():
+    lib = binding.lib()
+    b, d_out, d_in, r = 512, 9216, 36864, 128
+    assert binding.slope_spmm_fwd_workspace_bytes(b, d_in, d_out, r) > binding.SLOPE_STATIC_SCRATCH_BYTES
+    p = ctypes.c_void_p(0x1000)            # never dereferenced: the size is refused on the host, before any launch
+    assert lib.slope_spmm_fwd_static(p, b, p, p, d_out, d_in, p, p, r, p, None) == binding.SLOPE_ERR_WORKSPACE
+    assert lib.slope_spmm_fwd_static(p, b, p, p, d_out, d_in + 8, p, p, r, p, None) == binding.SLOPE_ERR_SHAPE
+    assert lib.slope_spmm_fwd_static(p, 8, p, p, 64, 64, p, None, 32, p, None) == binding.SLOPE_ERR_NULL
+    text = open(os.path.join(ROOT, "include", "slope.h")).read()
+    assert "#define SLOPE_STATIC_SCRATCH_BYTES (%du << 20)" % (binding.SLOPE_STATIC_SCRATCH_BYTES >> 20) in text
+    assert b"scratch" in lib.slope_status_string(binding.SLOPE_ERR_WORKSPACE)
+
+
 def test_binding_refuses_host_tensors():
     import torch
     with pytest.raises(ValueError):
