@@ -28,9 +28,14 @@
  *   - Magnitude order: the bf16 bit pattern with the sign cleared, compared as an
  *     integer; on equal magnitude the lower index inside the group wins.  (+0 == -0;
  *     NaN ranks above Inf.)
- *   - Shape limits: slope_prune_rows needs d_in % 8 == 0 (any d_out >= 1); slope_double_prune
- *     and the three product calls need d_in % 64 == 0 and d_out % 64 == 0; b >= 1 is
- *     arbitrary; every extent must stay below 2^31 (SLOPE_ERR_SHAPE otherwise).
+ *   - Shape limits: d_in % 8 == 0 and d_out % 8 == 0 (slope_prune_rows: any d_out >= 1); b >= 1 is
+ *     arbitrary; every extent must stay below 2^31 (SLOPE_ERR_SHAPE otherwise).  The fast kernels
+ *     want more (contraction lengths that are multiples of 256, or of 64); other extents are routed to
+ *     slower general kernels inside the same calls, never refused.
+ *   - Scratch memory ("workspace") is the caller's, 256-byte aligned, and its contents are undefined
+ *     after the call.  slope_workspace_bytes tells how much a call wants.  Calls whose names end in
+ *     _ws, and the adapter calls, take the buffer's size and return SLOPE_ERR_WORKSPACE when it is too
+ *     small; slope_spmm_fwd itself takes the pointer on trust.
  */
 #ifndef SLOPE_H
 #define SLOPE_H
@@ -64,10 +69,26 @@ size_t slope_packed_vals_bytes(int64_t rows, int64_t cols);
 size_t slope_packed_meta_bytes(int64_t rows, int64_t cols);
 size_t slope_mask_bytes(int64_t rows, int64_t cols);
 
-/* Scratch of slope_spmm_fwd.  Required when adapters are active (T = X L as bf16[b, r], a
- * K-contiguous copy of L for many tokens, partial sums); optional otherwise: for a few dozen to
- * about a thousand tokens the call, given this many bytes, also splits the contraction over d_in
- * and keeps fp32 partial sums there, which is much faster at those sizes.  0 = no scratch is of use. */
+/* The calls, as numbered for slope_workspace_bytes (1-5: the five steps of the layer, Algorithm 1). */
+typedef enum {
+    SLOPE_CALL_PRUNE_ROWS = 1,
+    SLOPE_CALL_DOUBLE_PRUNE = 2,
+    SLOPE_CALL_SPMM_FWD = 3,
+    SLOPE_CALL_SPMM_BWD_X = 4,
+    SLOPE_CALL_WGRAD_MASKED = 5,
+    SLOPE_CALL_WGRAD_MASKED_WS = 6,
+    SLOPE_CALL_SPMM_BWD_X_ADAPTER = 7,
+    SLOPE_CALL_WGRAD_ADAPTER = 8
+} slope_call_id;
+
+/* Bytes of scratch memory a call wants for b tokens, a d_out x d_in layer and adapter rank r (0: none);
+ * 0 for the calls that take no workspace, for unknown ids and for invalid extents.  The per-call
+ * queries below return the same numbers.
+ *   slope_spmm_fwd: required when adapters are active (T = X L as bf16[b, r], a K-contiguous copy of L
+ *   for many tokens, partial sums); optional otherwise: for a few dozen to about a thousand tokens the
+ *   call, given this many bytes, also splits the contraction over d_in and keeps fp32 partial sums
+ *   there, which is much faster at those sizes. */
+size_t slope_workspace_bytes(int call_id, int64_t b, int64_t d_in, int64_t d_out, int64_t r);
 size_t slope_spmm_fwd_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out, int64_t r);
 
 /*
@@ -105,14 +126,20 @@ slope_status slope_double_prune(const void* Wr_vals, const void* Wr_meta, int64_
  *       adapter (the case for all but the last 1 % of pretraining, Sec. 2.2).
  *       r must be a multiple of 32 and at most 512.
  *   Y   out bf16[b, d_out]; fp32 accumulation; X L is rounded to bf16 before it meets R.
- *   workspace: device scratch of slope_spmm_fwd_workspace_bytes(...) bytes, 256-byte
+ *   workspace: device scratch of slope_workspace_bytes(SLOPE_CALL_SPMM_FWD, ...) bytes, 256-byte
  *       aligned; may be NULL when no adapter is active (if given, it must have that many
- *       bytes all the same).  Contents are undefined after the call.
+ *       bytes all the same).
+ * slope_spmm_fwd_ws is the same call with the size of the buffer stated, so that a buffer that is
+ * too small is refused (SLOPE_ERR_WORKSPACE) instead of overrun.
  */
 slope_status slope_spmm_fwd(const void* X, int64_t b, const void* Wr_vals, const void* Wr_meta,
                             int64_t d_out, int64_t d_in,
                             const void* L_or_null, const void* R_or_null, int64_t r,
                             void* Y, void* workspace, void* stream);
+slope_status slope_spmm_fwd_ws(const void* X, int64_t b, const void* Wr_vals, const void* Wr_meta,
+                               int64_t d_out, int64_t d_in,
+                               const void* L_or_null, const void* R_or_null, int64_t r,
+                               void* Y, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * slope_spmm_fwd_static - slope_spmm_fwd for callers that cannot allocate device memory or carry a
@@ -151,15 +178,29 @@ slope_status slope_spmm_bwd_x(const void* dY, int64_t b, const void* WrcT_vals, 
  * App. K: the result is d_out x d_in/2).
  *   dY in bf16[b, d_out], X in bf16[b, d_in], Wr_meta in u8[d_out, d_in/8]
  *   dW_vals out bf16[d_out, d_in/2]; fp32 accumulation.
- *   workspace_or_null: device scratch of slope_wgrad_workspace_bytes(b, d_in, d_out) bytes,
- *       256-byte aligned, or NULL.  With scratch, large layers run on token-contiguous copies of
- *       dY and X (faster); without it an in-place kernel is used.  The result is the same up to
- *       fp32 summation order.  Contents are undefined after the call.
+ * No scratch memory: the operands are read as stored, tokens being their slow index.
+ *
+ * slope_wgrad_masked_ws - the same result (up to fp32 summation order) through token-contiguous copies
+ * of X and dY in the caller's workspace, which is what large layers should use: the product then runs at
+ * the rate of the other tile kernels.
+ *   workspace  slope_workspace_bytes(SLOPE_CALL_WGRAD_MASKED_WS, b, d_in, d_out, 0) bytes
+ *
+ * Layers that share an operand (q, k and v share X) need its copy only once:
+ *   slope_transpose_tokens  At = token-contiguous copy of A bf16[b, d] (an X or a dY); At has
+ *                           slope_token_copy_bytes(b, d) bytes (rows of b rounded up to 64 tokens, zero-filled,
+ *                           plus padding of the row pitch; the layout is the library's own)
+ *   slope_wgrad_masked_t    the product from two such copies; d_in % 32 == 0 (SLOPE_ERR_SHAPE otherwise)
  */
-size_t slope_wgrad_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out);
 slope_status slope_wgrad_masked(const void* dY, const void* X, int64_t b, const void* Wr_meta,
-                                int64_t d_out, int64_t d_in, void* dW_vals, void* workspace_or_null,
-                                void* stream);
+                                int64_t d_out, int64_t d_in, void* dW_vals, void* stream);
+size_t slope_wgrad_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out);
+slope_status slope_wgrad_masked_ws(const void* dY, const void* X, int64_t b, const void* Wr_meta,
+                                   int64_t d_out, int64_t d_in, void* dW_vals,
+                                   void* workspace, size_t workspace_bytes, void* stream);
+size_t slope_token_copy_bytes(int64_t b, int64_t d);
+slope_status slope_transpose_tokens(const void* A, int64_t b, int64_t d, void* At, size_t At_bytes, void* stream);
+slope_status slope_wgrad_masked_t(const void* dYt, const void* Xt, int64_t b, const void* Wr_meta,
+                                  int64_t d_out, int64_t d_in, void* dW_vals, void* stream);
 
 /*
  * slope_spmm_bwd_x_adapter - input gradient of a layer with adapters:
@@ -173,7 +214,7 @@ slope_status slope_wgrad_masked(const void* dY, const void* X, int64_t b, const 
 size_t slope_spmm_bwd_x_adapter_workspace_bytes(int64_t b, int64_t r);
 slope_status slope_spmm_bwd_x_adapter(const void* dY, int64_t b, const void* WrcT_vals, const void* WrcT_meta,
                                       int64_t d_out, int64_t d_in, const void* L, const void* R, int64_t r, void* dX,
-                                      void* workspace, void* stream);
+                                      void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * slope_wgrad_adapter - all weight gradients of a layer with adapters in one call: the packed,
@@ -189,7 +230,7 @@ slope_status slope_spmm_bwd_x_adapter(const void* dY, int64_t b, const void* Wrc
 size_t slope_wgrad_adapter_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out, int64_t r);
 slope_status slope_wgrad_adapter(const void* dY, const void* X, int64_t b, const void* Wr_meta, int64_t d_out,
                                  int64_t d_in, const void* L, const void* R, int64_t r, void* dW_vals, void* dL,
-                                 void* dR, void* workspace, void* stream);
+                                 void* dR, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * slope_prune_mask - magnitude N:M pruning for the patterns that have no sparse MFMA (Sec. 2.1:
@@ -202,7 +243,7 @@ slope_status slope_wgrad_adapter(const void* dY, const void* X, int64_t b, const
  *              1: groups inside a column (the second prune of W^{R,C}); rows % m == 0
  *   candidates_or_null in u8[rows, cols/8]  bit mask; only set positions compete and can be kept
  *              (double pruning: pass the mask of the first prune); NULL = all positions
- *   mask_out   out u8[rows, cols/8]         kept positions
+ *   mask_out   out u8[rows, cols/8]         kept positions (16-byte aligned, like candidates)
  *   masked_out_or_null    out bf16[rows, cols]   W where kept, +0.0 elsewhere
  *   masked_t_out_or_null  out bf16[cols, rows]   the transpose of the same (the backward operand)
  */
@@ -224,7 +265,7 @@ slope_status slope_gemm_tn(const void* B, int64_t n, const void* A, int64_t m, i
  * one sparsity pattern (App. K, sparse matrix addition).  Algorithm 1 line 15 is the case
  * A = packed masked gradient, beta = 1 / gradient scale, B = packed W^R, gamma = weight decay.
  *   A_vals, B_vals  in   bf16[rows, cols/2]   packed values of two [rows, cols] matrices
- *   rows, cols           logical extents; cols % 16 == 0
+ *   rows, cols           logical extents; cols % 8 == 0
  *   out_vals        out  bf16[rows, cols/2]   may be A_vals or B_vals (in place)
  * Each element is fma(beta, a, gamma * b) in fp32, rounded to bf16 (nearest even).  The metadata
  * is not touched: the result has the operands' pattern.
@@ -244,7 +285,6 @@ slope_status slope_sparse_add(const void* A_vals, const void* B_vals, int64_t ro
  *   Wr_vals    out  bf16[d_out, d_in/2]   receives a copy of Wnew_vals (no copy if it is Wnew_vals)
  *   WrcT_meta  in   u8[d_in, d_out/8]     metadata of (W^{R,C})^T as written by slope_double_prune
  *   WrcT_vals  out  bf16[d_in, d_out/2]   rewritten completely
- * d_in % 64 == 0 and d_out % 64 == 0.
  */
 slope_status slope_update_sparse(const void* Wnew_vals, const void* Wr_meta, int64_t d_out, int64_t d_in,
                                  void* Wr_vals, const void* WrcT_meta, void* WrcT_vals, void* stream);
@@ -255,10 +295,10 @@ slope_status slope_update_sparse(const void* Wnew_vals, const void* Wr_meta, int
  * pin the regimes.  plan: host int32[6]
  *   [0] product: 0 small-batch kernel (one pass over the packed weight), 1 tile kernel with the
  *       contraction split into slabs (needs the workspace), 2 tile kernel, 3 generic kernel
- *       (d_in not a multiple of 256)
+ *       (d_in not a multiple of 256; not a multiple of 64: its form for ragged rows)
  *   [1], [2] weight rows and tokens per workgroup      [3] slabs (1 = no split)
  *   [4] T = X L: 0 no adapter, 1 split over d_in from L as stored (few tokens),
- *       2 dense tile kernel, 3 dense tile kernel split over d_in
+ *       2 dense tile kernel, 3 dense tile kernel split over d_in, 4 plain arithmetic (d_in % 64 != 0)
  *   [5] chunks of 64 rows of L per workgroup for [4] == 1
  * with_workspace: whether the call would be given its scratch.  Errors as slope_spmm_fwd.
  */

@@ -38,8 +38,9 @@ size_t spmm_slab_bytes(int64_t n, int64_t m, int64_t K);
 hipError_t launch_spmm_slabs(const bf16_t* B, int64_t n, const bf16_t* A_vals, const uint8_t* A_meta, int64_t m,
                              int64_t K, const bf16_t* B2, const bf16_t* A2, int64_t K2, bf16_t* C, float* slabs,
                              hipStream_t s);
-// the same product for n <= 32 tokens (any K % 64 == 0); adapters as T[n, K2] and R[K2, m] as stored
+// the same product for n <= 32 tokens (any K % 64 == 0, K >= 128); adapters as T[n, K2] and R[K2, m] as stored
 constexpr int64_t STREAM_MAX_TOKENS = 32;
+inline bool spmm_stream_fits(int64_t n, int64_t K) { return n <= STREAM_MAX_TOKENS && K >= 128 && K % 64 == 0; }
 hipError_t launch_spmm_stream(const bf16_t* B, int64_t n, const bf16_t* A_vals, const uint8_t* A_meta, int64_t m,
                               int64_t K, const bf16_t* T, const bf16_t* R, int64_t K2, bf16_t* C, hipStream_t s);
 // T = X L for few tokens (n <= XL_SMALL_MAX_TOKENS), split over d_in with fp32 partial sums in `scratch`
@@ -50,12 +51,20 @@ hipError_t launch_xl_small(const bf16_t* X, int64_t n, int64_t d_in, const bf16_
 // T[n, r] = X[n, K] * Lt[r, K]^T (dense tile kernel) for many tokens, with the k-contiguous copy Lt of L
 hipError_t launch_lowrank_prepare(const bf16_t* X, int64_t n, int64_t d_in, const bf16_t* L, int64_t r, bf16_t* T,
                                   bf16_t* Lt, float* partial_or_null, hipStream_t s);
+// C[n, m] = sum_k B[i sbn + k sbk] * A[j sam + k sak]: any strides and extents, plain fp32 arithmetic (the
+// skinny adapter products of layers whose extents are not multiples of 64)
+hipError_t launch_plain_gemm(const bf16_t* B, int64_t sbn, int64_t sbk, const bf16_t* A, int64_t sam, int64_t sak,
+                             int64_t n, int64_t m, int64_t K, bf16_t* C, hipStream_t s);
 hipError_t launch_wgrad_masked(const bf16_t* dY, const bf16_t* X, int64_t b, const uint8_t* meta, int64_t d_out,
                                int64_t d_in, bf16_t* gvals, hipStream_t s);
-// same result through token-contiguous copies of dY and X in `workspace`
-size_t wgrad_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out);
-hipError_t launch_wgrad_masked_ws(const bf16_t* dY, const bf16_t* X, int64_t b, const uint8_t* meta, int64_t d_out,
-                                  int64_t d_in, bf16_t* gvals, void* workspace, hipStream_t s);
+// the same result from token-contiguous copies Xt [d_in][ld], dYt [d_out][ld] (ld = the pitch behind
+// token_copy_bytes); launch_token_copies writes one or two such copies (in1 == nullptr: one)
+size_t token_copy_bytes(int64_t b, int64_t d);
+hipError_t launch_token_copies(const bf16_t* in0, int64_t cols0, bf16_t* out0, const bf16_t* in1, int64_t cols1,
+                               bf16_t* out1, int64_t b, hipStream_t s);
+bool wgrad_tn_fits(int64_t d_in);
+hipError_t launch_wgrad_masked_t(const bf16_t* dYt, const bf16_t* Xt, int64_t b, const uint8_t* meta, int64_t d_out,
+                                 int64_t d_in, bf16_t* gvals, hipStream_t s);
 
 // C[n, m] = B[n, K] * A[m, K]^T (dense bf16, fp32 accumulation), K % 64 == 0
 size_t dense_tn_plain_partial_bytes(int64_t n, int64_t m);

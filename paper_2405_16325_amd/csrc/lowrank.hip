@@ -27,7 +27,66 @@ __global__ void __launch_bounds__(256) transpose_kernel(const bf16_t* __restrict
     }
 }
 
+// C[i][j] = sum_k B[i * sbn + k * sbk] * A[j * sam + k * sak], bf16 operands with arbitrary element
+// strides, fp32 accumulation, bf16 result, C row-major [n][m].  The fallback for the skinny products
+// of the adapters when an extent is not a multiple of 64 (the MFMA tile kernels want whole k-steps
+// and 16-byte rows): plain fp32 multiply-adds, 32 x 32 outputs per workgroup through LDS, 2 x 2 per
+// thread.  Layer shapes of real models never come here.
+__global__ void __launch_bounds__(256) plain_gemm_kernel(const bf16_t* __restrict__ B, int64_t sbn, int64_t sbk,
+                                                         const bf16_t* __restrict__ A, int64_t sam, int64_t sak, int n,
+                                                         int m, int K, bf16_t* __restrict__ C) {
+    __shared__ float sB[32][33], sA[32][33];                  // [k][row]
+    const int t = threadIdx.x, ti = t >> 4, tj = t & 15;
+    const int tiles_m = (m + 31) / 32;
+    const int i0 = (int)(blockIdx.x / tiles_m) * 32, j0 = (int)(blockIdx.x % tiles_m) * 32;
+    float acc[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
+    for (int k0 = 0; k0 < K; k0 += 32) {
+        for (int idx = t; idx < 32 * 32; idx += 256) {
+            // the fast index of the staging loop follows the operand's unit stride
+            int a = idx >> 5, c = idx & 31;
+            int rb = sbk == 1 ? a : c, kb = sbk == 1 ? c : a;
+            int ra = sak == 1 ? a : c, ka = sak == 1 ? c : a;
+            float vb = 0.f, va = 0.f;
+            if (i0 + rb < n && k0 + kb < K)
+                vb = __uint_as_float((uint32_t)B[(int64_t)(i0 + rb) * sbn + (int64_t)(k0 + kb) * sbk] << 16);
+            if (j0 + ra < m && k0 + ka < K)
+                va = __uint_as_float((uint32_t)A[(int64_t)(j0 + ra) * sam + (int64_t)(k0 + ka) * sak] << 16);
+            sB[kb][rb] = vb;
+            sA[ka][ra] = va;
+        }
+        __syncthreads();
+#pragma unroll 8
+        for (int k = 0; k < 32; ++k) {
+            float b0 = sB[k][ti], b1 = sB[k][ti + 16], a0 = sA[k][tj], a1 = sA[k][tj + 16];
+            acc[0][0] = __builtin_fmaf(b0, a0, acc[0][0]);
+            acc[0][1] = __builtin_fmaf(b0, a1, acc[0][1]);
+            acc[1][0] = __builtin_fmaf(b1, a0, acc[1][0]);
+            acc[1][1] = __builtin_fmaf(b1, a1, acc[1][1]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int v = 0; v < 2; ++v) {
+            int i = i0 + ti + 16 * u, j = j0 + tj + 16 * v;
+            if (i < n && j < m) {
+                union { __bf16 h; bf16_t b; } o;
+                o.h = (__bf16)acc[u][v];
+                C[(int64_t)i * m + j] = o.b;
+            }
+        }
+}
+
 }  // namespace
+
+hipError_t launch_plain_gemm(const bf16_t* B, int64_t sbn, int64_t sbk, const bf16_t* A, int64_t sam, int64_t sak,
+                             int64_t n, int64_t m, int64_t K, bf16_t* C, hipStream_t s) {
+    const int64_t tiles = ((m + 31) / 32) * ((n + 31) / 32);
+    if (tiles > 0x7FFFFFFF) return hipErrorInvalidValue;
+    plain_gemm_kernel<<<dim3((unsigned)tiles), dim3(256), 0, s>>>(B, sbn, sbk, A, sam, sak, (int)n, (int)m, (int)K, C);
+    return hipGetLastError();
+}
 
 hipError_t launch_lowrank_prepare(const bf16_t* X, int64_t n, int64_t d_in, const bf16_t* L, int64_t r, bf16_t* T,
                                   bf16_t* Lt, float* partial_or_null, hipStream_t s) {

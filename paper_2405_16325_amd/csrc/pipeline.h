@@ -1,6 +1,23 @@
 // Building blocks shared by the MFMA kernels: tile order, global -> LDS loads, barriers.
 #pragma once
+#include <atomic>
+
 #include "common.h"
+
+// Dynamic LDS beyond the default limit has to be enabled per kernel; once per device is enough, and the
+// call is not free (it is what made 20 us launches of small layers measurably slower).
+template <auto Kernel>
+inline hipError_t allow_dynamic_lds(int bytes) {
+    static std::atomic<uint64_t> done{0};                     // one bit per device
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = dev >= 0 && dev < 64 ? (uint64_t)1 << dev : 0;
+    if (bit && (done.load(std::memory_order_acquire) & bit)) return hipSuccess;
+    e = hipFuncSetAttribute((const void*)Kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && bit) done.fetch_or(bit, std::memory_order_release);
+    return e;
+}
 
 constexpr int XCDS = 8;
 constexpr int SUPER = 16;                 // fewer tiles than this along an axis make a grid narrow

@@ -100,7 +100,11 @@ constexpr int DP_NPITCH = 36;       // bytes per nibble row [i][og]
 //                 masks, Alg. 1 line 18); only the values of the transposed copy are rewritten.
 //                 A slot that names a position outside W^R's mask reads the zero that the
 //                 decompression left there, so padding stays +0.0.
-template <bool GIVEN, bool MASK>
+// RAGGED: d_in is not a multiple of 16 or d_out not one of 32.  Rows of the packed arrays are then only
+//                 8-byte (values) and 1-byte (metadata) aligned and may end inside a lane's piece, so every
+//                 access is made in pieces of 8 logical elements (8 bytes of values, 1 byte of metadata),
+//                 each wholly inside the row or skipped.
+template <bool GIVEN, bool MASK, bool RAGGED>
 __global__ void __launch_bounds__(256) double_prune_kernel(const bf16_t* __restrict__ vals,
                                                            const uint8_t* __restrict__ meta, int d_out, int d_in,
                                                            bf16_t* __restrict__ valsT, uint8_t* __restrict__ metaT,
@@ -128,9 +132,18 @@ __global__ void __launch_bounds__(256) double_prune_kernel(const bf16_t* __restr
         uint4 v = make_uint4(0, 0, 0, 0);
         uint32_t m = 0;
         bool ok = o < d_out && i < d_in;
-        if (ok) {
+        if (ok && !RAGGED) {
             v = *(const uint4*)(vals + (size_t)o * vpitch + i / 2);
             m = *(const uint16_t*)(meta + (size_t)o * mpitch + i / 8);
+        }
+        bool ok_hi = ok;                                       // columns i + 8 .. i + 15 exist as well
+        if (RAGGED && ok) {
+            ok_hi = i + 8 < d_in;
+            const uint2 lo = *(const uint2*)(vals + (size_t)o * vpitch + i / 2);
+            const uint2 hi = ok_hi ? *(const uint2*)(vals + (size_t)o * vpitch + i / 2 + 4) : make_uint2(0, 0);
+            v = make_uint4(lo.x, lo.y, hi.x, hi.y);
+            m = meta[(size_t)o * mpitch + i / 8];
+            if (ok_hi) m |= (uint32_t)meta[(size_t)o * mpitch + i / 8 + 1] << 8;
         }
         uint32_t pk[4] = {v.x, v.y, v.z, v.w};
         uint32_t dense[8];
@@ -141,7 +154,7 @@ __global__ void __launch_bounds__(256) double_prune_kernel(const bf16_t* __restr
             uint64_t q = ((uint64_t)(pk[g] & 0xFFFFu) << (16u * a)) | ((uint64_t)(pk[g] >> 16) << (16u * b));
             dense[2 * g] = (uint32_t)q;
             dense[2 * g + 1] = (uint32_t)(q >> 32);
-            uint32_t bits = ok ? ((1u << a) | (1u << b)) : 0u;
+            uint32_t bits = (g < 2 ? ok : ok_hi) ? ((1u << a) | (1u << b)) : 0u;
             cand |= bits << (4 * g);
         }
         uint4* dst = (uint4*)(sD + row * DP_PITCH + 32 * c);
@@ -153,7 +166,16 @@ __global__ void __launch_bounds__(256) double_prune_kernel(const bf16_t* __restr
         int row = t >> 1, half = t & 1;
         int i = i0 + row, o = o0 + 64 * half;
         uint2 x = make_uint2(0, 0);
-        if (i < d_in && o < d_out) x = *(const uint2*)(metaT_in + (size_t)i * ((size_t)d_out / 8) + o / 8);
+        if (!RAGGED && i < d_in && o < d_out) x = *(const uint2*)(metaT_in + (size_t)i * ((size_t)d_out / 8) + o / 8);
+        if (RAGGED && i < d_in) {
+            const uint8_t* src = metaT_in + (size_t)i * ((size_t)d_out / 8) + o / 8;
+#pragma unroll
+            for (int q = 0; q < 8; ++q)
+                if (o + 8 * q < d_out) {
+                    if (q < 4) x.x |= (uint32_t)src[q] << (8 * q);
+                    else x.y |= (uint32_t)src[q] << (8 * (q - 4));
+                }
+        }
         uint8_t* dst = sG + row * DP_NPITCH + 16 * half;
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
@@ -225,7 +247,12 @@ __global__ void __launch_bounds__(256) double_prune_kernel(const bf16_t* __restr
         int i = i0 + row, o = o0 + 16 * c;
         if (i < d_in && o < d_out) {
             const uint32_t* src = sO + row * DP_OPITCH + 4 * c;
-            *(uint4*)(valsT + (size_t)i * vtp + o / 2) = make_uint4(src[0], src[1], src[2], src[3]);
+            if (!RAGGED) {
+                *(uint4*)(valsT + (size_t)i * vtp + o / 2) = make_uint4(src[0], src[1], src[2], src[3]);
+            } else {
+                *(uint2*)(valsT + (size_t)i * vtp + o / 2) = make_uint2(src[0], src[1]);
+                if (o + 8 < d_out) *(uint2*)(valsT + (size_t)i * vtp + o / 2 + 4) = make_uint2(src[2], src[3]);
+            }
         }
     }
     if (GIVEN) return;
@@ -238,7 +265,14 @@ __global__ void __launch_bounds__(256) double_prune_kernel(const bf16_t* __restr
             uint32_t x = src[0], y = src[1];
             uint32_t lo = (x & 0xFu) | ((x >> 4) & 0xF0u) | ((x >> 8) & 0xF00u) | ((x >> 12) & 0xF000u);
             uint32_t hi = (y & 0xFu) | ((y >> 4) & 0xF0u) | ((y >> 8) & 0xF00u) | ((y >> 12) & 0xF000u);
-            *(uint32_t*)(metaT + (size_t)i * mtp + o / 8) = lo | (hi << 16);
+            const uint32_t word = lo | (hi << 16);
+            if (!RAGGED) {
+                *(uint32_t*)(metaT + (size_t)i * mtp + o / 8) = word;
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (o + 8 * q < d_out) metaT[(size_t)i * mtp + o / 8 + q] = (uint8_t)(word >> (8 * q));
+            }
         }
     }
 }
@@ -246,12 +280,19 @@ __global__ void __launch_bounds__(256) double_prune_kernel(const bf16_t* __restr
 hipError_t launch_double_prune(const bf16_t* vals, const uint8_t* meta, int64_t d_out, int64_t d_in, bf16_t* valsT,
                                uint8_t* metaT, uint8_t* maskrc, hipStream_t s) {
     dim3 grid((unsigned)((d_in + DP_TILE - 1) / DP_TILE), (unsigned)((d_out + DP_TILE - 1) / DP_TILE));
-    if (maskrc)
-        double_prune_kernel<false, true><<<grid, dim3(256), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT, metaT,
-                                                                    maskrc, nullptr);
+    const bool ragged = d_in % 16 != 0 || d_out % 32 != 0;
+    if (ragged && maskrc)
+        double_prune_kernel<false, true, true><<<grid, dim3(256), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT,
+                                                                          metaT, maskrc, nullptr);
+    else if (ragged)
+        double_prune_kernel<false, false, true><<<grid, dim3(256), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT,
+                                                                           metaT, nullptr, nullptr);
+    else if (maskrc)
+        double_prune_kernel<false, true, false><<<grid, dim3(256), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT,
+                                                                           metaT, maskrc, nullptr);
     else
-        double_prune_kernel<false, false><<<grid, dim3(256), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT, metaT,
-                                                                     nullptr, nullptr);
+        double_prune_kernel<false, false, false><<<grid, dim3(256), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT,
+                                                                            metaT, nullptr, nullptr);
     return hipGetLastError();
 }
 
@@ -259,8 +300,12 @@ hipError_t launch_double_prune(const bf16_t* vals, const uint8_t* meta, int64_t 
 hipError_t launch_update_transposed(const bf16_t* vals, const uint8_t* meta, int64_t d_out, int64_t d_in,
                                     const uint8_t* metaT, bf16_t* valsT, hipStream_t s) {
     dim3 grid((unsigned)((d_in + DP_TILE - 1) / DP_TILE), (unsigned)((d_out + DP_TILE - 1) / DP_TILE));
-    double_prune_kernel<true, false><<<grid, dim3(256), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT, nullptr,
-                                                                nullptr, metaT);
+    if (d_in % 16 != 0 || d_out % 64 != 0)
+        double_prune_kernel<true, false, true><<<grid, dim3(256), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT,
+                                                                          nullptr, nullptr, metaT);
+    else
+        double_prune_kernel<true, false, false><<<grid, dim3(256), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT,
+                                                                           nullptr, nullptr, metaT);
     return hipGetLastError();
 }
 
@@ -270,10 +315,24 @@ hipError_t launch_update_transposed(const bf16_t* vals, const uint8_t* meta, int
 // A plain stream: 16 bytes of each operand per lane, 6 bytes of traffic per element.
 constexpr int SA_UNROLL = 4;
 
+__device__ __forceinline__ uint32_t sparse_add_pair(uint32_t wa, uint32_t wb, float beta, float gamma) {
+    float a0 = __uint_as_float(wa << 16), a1 = __uint_as_float(wa & 0xFFFF0000u);
+    float b0 = __uint_as_float(wb << 16), b1 = __uint_as_float(wb & 0xFFFF0000u);
+    union { __bf16 h[2]; uint32_t x; } o;
+    o.h[0] = (__bf16)__builtin_fmaf(beta, a0, gamma * b0);
+    o.h[1] = (__bf16)__builtin_fmaf(beta, a1, gamma * b1);
+    return o.x;
+}
+
+// tail4: four more elements follow the nvec whole vectors of eight (a layer whose rows x cols / 2 is odd in eights)
 __global__ void __launch_bounds__(256) sparse_add_kernel(const u32x4* __restrict__ a, const u32x4* __restrict__ b,
-                                                         size_t nvec, float beta, float gamma,
+                                                         size_t nvec, bool tail4, float beta, float gamma,
                                                          u32x4* __restrict__ out) {
     const size_t stride = (size_t)gridDim.x * 256;
+    if (tail4 && blockIdx.x == 0 && threadIdx.x == 0) {
+        const u32x2 ta = *(const u32x2*)(a + nvec), tb = *(const u32x2*)(b + nvec);
+        *(u32x2*)(out + nvec) = (u32x2){sparse_add_pair(ta[0], tb[0], beta, gamma), sparse_add_pair(ta[1], tb[1], beta, gamma)};
+    }
     for (size_t base = (size_t)blockIdx.x * 256 + threadIdx.x; base < nvec; base += stride * SA_UNROLL) {
         u32x4 va[SA_UNROLL], vb[SA_UNROLL];
 #pragma unroll
@@ -290,14 +349,7 @@ __global__ void __launch_bounds__(256) sparse_add_kernel(const u32x4* __restrict
             if (i >= nvec) continue;
             u32x4 r;
 #pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                float a0 = __uint_as_float(va[u][w] << 16), a1 = __uint_as_float(va[u][w] & 0xFFFF0000u);
-                float b0 = __uint_as_float(vb[u][w] << 16), b1 = __uint_as_float(vb[u][w] & 0xFFFF0000u);
-                union { __bf16 h[2]; uint32_t x; } o;
-                o.h[0] = (__bf16)__builtin_fmaf(beta, a0, gamma * b0);
-                o.h[1] = (__bf16)__builtin_fmaf(beta, a1, gamma * b1);
-                r[w] = o.x;
-            }
+            for (int w = 0; w < 4; ++w) r[w] = sparse_add_pair(va[u][w], vb[u][w], beta, gamma);
             __builtin_nontemporal_store(r, out + i);
         }
     }
@@ -305,11 +357,11 @@ __global__ void __launch_bounds__(256) sparse_add_kernel(const u32x4* __restrict
 
 hipError_t launch_sparse_add(const bf16_t* a, const bf16_t* b, size_t count, float beta, float gamma, bf16_t* out,
                              hipStream_t s) {
-    size_t nvec = count / 8;                                  // count is a multiple of 8
+    size_t nvec = count / 8;                                  // count is a multiple of 4
     size_t blocks = (nvec + 256 * SA_UNROLL - 1) / (256 * SA_UNROLL);
     if (blocks > 256 * 16) blocks = 256 * 16;
     if (blocks == 0) blocks = 1;
-    sparse_add_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>((const u32x4*)a, (const u32x4*)b, nvec, beta, gamma,
-                                                                   (u32x4*)out);
+    sparse_add_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>((const u32x4*)a, (const u32x4*)b, nvec, count % 8 != 0,
+                                                                   beta, gamma, (u32x4*)out);
     return hipGetLastError();
 }

@@ -1,5 +1,6 @@
 // C ABI of the double-pruned 2:4 sparse linear layer (declared in include/slope.h):
-// argument checks on the host, then the launchers.  No allocation, no synchronisation, no state.
+// argument checks on the host, then the launchers.  No allocation, no synchronisation; the only
+// state is the per-device address of the static scratch array of slope_spmm_fwd_static.
 #include <atomic>
 
 #include "pipeline.h"
@@ -20,11 +21,41 @@ inline slope_status finish(hipError_t e) {
 
 inline bool bad_extent(int64_t v, int64_t quantum) { return v <= 0 || v >= EXTENT_MAX || (v % quantum) != 0; }
 
+// b tokens, a d_out x d_in layer: the extents every product call accepts
+inline bool bad_layer(int64_t b, int64_t d_out, int64_t d_in) {
+    return bad_extent(b, 1) || bad_extent(d_out, 8) || bad_extent(d_in, 8);
+}
+
+inline bool bad_rank(int64_t r) { return r % 32 != 0 || r > 512; }
+
+inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// [ T | Lt | partial sums of X L ] when adapters are active, then the slab buffer of the split over K
+size_t adapter_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out, int64_t r) {
+    (void)d_out;
+    if (r <= 0) return 0;
+    size_t tiles = round256((size_t)b * r * 2) + round256((size_t)d_in * r * 2);
+    // T = X L comes from a split over d_in whose partial sums also live here (none for many tokens)
+    return tiles + round256(b <= XL_SMALL_MAX_TOKENS ? xl_small_scratch_bytes(b, d_in, r)
+                                                     : dense_tn_plain_partial_bytes(b, r));
+}
+
+// T[n, r] = B[n, K] A^T for the skinny products of the adapters.  a_kmajor: A is [K][r] (the factor L as
+// stored) instead of [r][K].  Whole k-steps of 64 go to the MFMA kernels, anything else to plain arithmetic.
+hipError_t skinny_product(const bf16_t* B, int64_t n, int64_t K, const bf16_t* A, bool a_kmajor, int64_t r, bf16_t* T,
+                          bf16_t* At_scratch, float* partial, hipStream_t s) {
+    if (K % 64 != 0)
+        return a_kmajor ? launch_plain_gemm(B, K, 1, A, 1, r, n, r, K, T, s)
+                        : launch_plain_gemm(B, K, 1, A, K, 1, n, r, K, T, s);
+    if (a_kmajor) return launch_lowrank_prepare(B, n, K, A, r, T, At_scratch, partial, s);
+    return launch_dense_tn_plain(B, n, A, r, K, T, partial, s);
+}
+
 }  // namespace
 
 extern "C" {
 
-int slope_version(void) { return 100; }
+int slope_version(void) { return 200; }
 
 int slope_last_hip_error(void) { return g_last_hip_error; }
 
@@ -53,21 +84,39 @@ size_t slope_packed_meta_bytes(int64_t rows, int64_t cols) {
 
 size_t slope_mask_bytes(int64_t rows, int64_t cols) { return slope_packed_meta_bytes(rows, cols); }
 
-static size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
-
-// [ T | Lt | partial sums of X L ] when adapters are active, then the slab buffer of the split over K
-static size_t adapter_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out, int64_t r) {
-    (void)d_out;
-    if (r <= 0) return 0;
-    size_t tiles = round256((size_t)b * r * 2) + round256((size_t)d_in * r * 2);
-    // T = X L comes from a split over d_in whose partial sums also live here (none for many tokens)
-    return tiles + round256(b <= XL_SMALL_MAX_TOKENS ? xl_small_scratch_bytes(b, d_in, r)
-                                                     : dense_tn_plain_partial_bytes(b, r));
-}
-
 size_t slope_spmm_fwd_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out, int64_t r) {
     if (b <= 0 || d_in <= 0 || d_out <= 0) return 0;
     return adapter_workspace_bytes(b, d_in, d_out, r) + round256(spmm_slab_bytes(b, d_out, d_in));
+}
+
+size_t slope_token_copy_bytes(int64_t b, int64_t d) {
+    if (b <= 0 || d <= 0) return 0;
+    return round256(token_copy_bytes(b, d));
+}
+
+size_t slope_wgrad_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out) {
+    if (b <= 0 || d_in <= 0 || d_out <= 0) return 0;
+    return slope_token_copy_bytes(b, d_in) + slope_token_copy_bytes(b, d_out);
+}
+
+size_t slope_spmm_bwd_x_adapter_workspace_bytes(int64_t b, int64_t r) {
+    if (b <= 0 || r <= 0) return 0;
+    return round256((size_t)b * r * 2) + round256(dense_tn_plain_partial_bytes(b, r));
+}
+
+size_t slope_wgrad_adapter_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out, int64_t r) {
+    if (b <= 0 || d_in <= 0 || d_out <= 0 || r <= 0) return 0;
+    return round256(wgrad_adapter_workspace_bytes(b, d_in, d_out, r));
+}
+
+size_t slope_workspace_bytes(int call_id, int64_t b, int64_t d_in, int64_t d_out, int64_t r) {
+    switch (call_id) {
+        case SLOPE_CALL_SPMM_FWD: return slope_spmm_fwd_workspace_bytes(b, d_in, d_out, r);
+        case SLOPE_CALL_WGRAD_MASKED_WS: return slope_wgrad_workspace_bytes(b, d_in, d_out);
+        case SLOPE_CALL_SPMM_BWD_X_ADAPTER: return slope_spmm_bwd_x_adapter_workspace_bytes(b, r);
+        case SLOPE_CALL_WGRAD_ADAPTER: return slope_wgrad_adapter_workspace_bytes(b, d_in, d_out, r);
+        default: return 0;      // prune_rows, double_prune, spmm_bwd_x, wgrad_masked need no scratch; unknown ids
+    }
 }
 
 slope_status slope_prune_rows(const void* W, int64_t d_out, int64_t d_in, int n, int m, void* Wr_vals, void* Wr_meta,
@@ -84,7 +133,7 @@ slope_status slope_prune_rows(const void* W, int64_t d_out, int64_t d_in, int n,
 slope_status slope_double_prune(const void* Wr_vals, const void* Wr_meta, int64_t d_out, int64_t d_in,
                                 void* WrcT_vals, void* WrcT_meta, void* maskrc_or_null, void* stream) {
     if (!Wr_vals || !Wr_meta || !WrcT_vals || !WrcT_meta) return SLOPE_ERR_NULL;
-    if (bad_extent(d_out, 64) || bad_extent(d_in, 64)) return SLOPE_ERR_SHAPE;
+    if (bad_extent(d_out, 8) || bad_extent(d_in, 8)) return SLOPE_ERR_SHAPE;
     if (misaligned(Wr_vals, 16) || misaligned(Wr_meta, 16) || misaligned(WrcT_vals, 16) ||
         misaligned(WrcT_meta, 16) || misaligned(maskrc_or_null, 16))
         return SLOPE_ERR_ALIGN;
@@ -93,15 +142,15 @@ slope_status slope_double_prune(const void* Wr_vals, const void* Wr_meta, int64_
                                       (hipStream_t)stream));
 }
 
-// Argument checks of slope_spmm_fwd and slope_spmm_fwd_static, up to the scratch buffer.
+// Argument checks of the three forms of slope_spmm_fwd, up to the scratch buffer.
 static slope_status spmm_fwd_check(const void* X, int64_t b, const void* Wr_vals, const void* Wr_meta, int64_t d_out,
                                    int64_t d_in, const void* L_or_null, const void* R_or_null, int64_t r, void* Y) {
     if (!X || !Wr_vals || !Wr_meta || !Y) return SLOPE_ERR_NULL;
-    if (bad_extent(b, 1) || bad_extent(d_out, 64) || bad_extent(d_in, 64)) return SLOPE_ERR_SHAPE;
+    if (bad_layer(b, d_out, d_in)) return SLOPE_ERR_SHAPE;
     if (r < 0) return SLOPE_ERR_SHAPE;
     if (r > 0 && (L_or_null || R_or_null)) {
         if (!L_or_null || !R_or_null) return SLOPE_ERR_NULL;
-        if (r % 32 != 0 || r > 512) return SLOPE_ERR_UNSUPPORTED;
+        if (bad_rank(r)) return SLOPE_ERR_UNSUPPORTED;
         if (misaligned(L_or_null, 16) || misaligned(R_or_null, 16)) return SLOPE_ERR_ALIGN;
     }
     if (misaligned(X, 16) || misaligned(Wr_vals, 16) || misaligned(Wr_meta, 16) || misaligned(Y, 16))
@@ -121,34 +170,25 @@ static slope_status spmm_fwd_run(const void* X, int64_t b, const void* Wr_vals, 
     const uint8_t* wm = (const uint8_t*)Wr_meta;
     uint8_t* ws = (uint8_t*)workspace;
     bf16_t* T = (bf16_t*)ws;
-    if (b <= STREAM_MAX_TOKENS && d_in >= 128) {   // inference-size batch: one HBM-bound pass over the packed weight
-        if (adapter) {
-            hipError_t e = launch_xl_small(x, b, d_in, (const bf16_t*)L_or_null, r,
-                                           (float*)(ws + round256((size_t)b * r * 2)), T, s);
-            if (e != hipSuccess) return finish(e);
-        }
+    if (adapter) {                                            // T = X L, rounded to bf16
+        bf16_t* Lt = (bf16_t*)(ws + round256((size_t)b * r * 2));
+        float* partial = (float*)((uint8_t*)Lt + round256((size_t)d_in * r * 2));
+        hipError_t e;
+        if (d_in % 64 == 0 && b <= XL_SMALL_MAX_TOKENS)       // too few tokens for the tile kernel to spread X L over the chip
+            e = launch_xl_small(x, b, d_in, (const bf16_t*)L_or_null, r, partial, T, s);
+        else
+            e = skinny_product(x, b, d_in, (const bf16_t*)L_or_null, true, r, T, Lt,
+                               b > XL_SMALL_MAX_TOKENS && dense_tn_plain_partial_bytes(b, r) ? partial : nullptr, s);
+        if (e != hipSuccess) return finish(e);
+    }
+    if (spmm_stream_fits(b, d_in))                            // inference-size batch: one HBM-bound pass over the packed weight
         return finish(launch_spmm_stream(x, b, wv, wm, d_out, d_in, adapter ? T : nullptr,
                                          adapter ? (const bf16_t*)R_or_null : nullptr, adapter ? r : 0, (bf16_t*)Y, s));
-    }
     // With scratch memory a batch of a few dozen to a few hundred tokens is split over K as well.
     float* slabs = workspace && spmm_slab_count(b, d_out, d_in) > 0
                        ? (float*)(ws + adapter_workspace_bytes(b, d_in, d_out, adapter ? r : 0)) : nullptr;
-    const bf16_t* B2 = nullptr;
-    const bf16_t* A2 = nullptr;
-    if (adapter) {
-        bf16_t* Lt = (bf16_t*)(ws + round256((size_t)b * r * 2));
-        float* scratch = (float*)((uint8_t*)Lt + round256((size_t)d_in * r * 2));
-        hipError_t e;
-        if (b <= XL_SMALL_MAX_TOKENS) {   // too few tokens for the tile kernel to spread X L over the chip
-            e = launch_xl_small(x, b, d_in, (const bf16_t*)L_or_null, r, scratch, T, s);
-        } else {
-            e = launch_lowrank_prepare(x, b, d_in, (const bf16_t*)L_or_null, r, T, Lt,
-                                       dense_tn_plain_partial_bytes(b, r) ? scratch : nullptr, s);
-        }
-        if (e != hipSuccess) return finish(e);
-        B2 = T;
-        A2 = (const bf16_t*)R_or_null;                        // as stored, [r][d_out]: the kernels take it k-major
-    }
+    const bf16_t* B2 = adapter ? T : nullptr;
+    const bf16_t* A2 = adapter ? (const bf16_t*)R_or_null : nullptr;   // as stored, [r][d_out]: the kernels take it k-major
     const int64_t K2 = adapter ? -r : 0;
     if (slabs) return finish(launch_spmm_slabs(x, b, wv, wm, d_out, d_in, B2, A2, K2, (bf16_t*)Y, slabs, s));
     return finish(launch_spmm(x, b, wv, wm, d_out, d_in, B2, A2, K2, (bf16_t*)Y, s));
@@ -161,6 +201,19 @@ slope_status slope_spmm_fwd(const void* X, int64_t b, const void* Wr_vals, const
     if (st != SLOPE_OK) return st;
     if (r > 0 && (L_or_null || R_or_null) && !workspace) return SLOPE_ERR_NULL;
     if (misaligned(workspace, 256)) return SLOPE_ERR_ALIGN;
+    return spmm_fwd_run(X, b, Wr_vals, Wr_meta, d_out, d_in, L_or_null, R_or_null, r, Y, workspace, stream);
+}
+
+slope_status slope_spmm_fwd_ws(const void* X, int64_t b, const void* Wr_vals, const void* Wr_meta, int64_t d_out,
+                               int64_t d_in, const void* L_or_null, const void* R_or_null, int64_t r, void* Y,
+                               void* workspace, size_t workspace_bytes, void* stream) {
+    slope_status st = spmm_fwd_check(X, b, Wr_vals, Wr_meta, d_out, d_in, L_or_null, R_or_null, r, Y);
+    if (st != SLOPE_OK) return st;
+    const bool adapter = r > 0 && (L_or_null || R_or_null);
+    if (adapter && !workspace) return SLOPE_ERR_NULL;
+    if (misaligned(workspace, 256)) return SLOPE_ERR_ALIGN;
+    if (workspace && workspace_bytes < slope_spmm_fwd_workspace_bytes(b, d_in, d_out, adapter ? r : 0))
+        return SLOPE_ERR_WORKSPACE;
     return spmm_fwd_run(X, b, Wr_vals, Wr_meta, d_out, d_in, L_or_null, R_or_null, r, Y, workspace, stream);
 }
 
@@ -213,78 +266,97 @@ slope_status slope_spmm_fwd_static(const void* X, int64_t b, const void* Wr_vals
 slope_status slope_spmm_bwd_x(const void* dY, int64_t b, const void* WrcT_vals, const void* WrcT_meta, int64_t d_out,
                               int64_t d_in, void* dX, void* stream) {
     if (!dY || !WrcT_vals || !WrcT_meta || !dX) return SLOPE_ERR_NULL;
-    if (bad_extent(b, 1) || bad_extent(d_out, 64) || bad_extent(d_in, 64)) return SLOPE_ERR_SHAPE;
+    if (bad_layer(b, d_out, d_in)) return SLOPE_ERR_SHAPE;
     if (misaligned(dY, 16) || misaligned(WrcT_vals, 16) || misaligned(WrcT_meta, 16) || misaligned(dX, 16))
         return SLOPE_ERR_ALIGN;
     // sparse rows = d_in, contraction over d_out
-    if (b <= STREAM_MAX_TOKENS && d_out >= 128)
+    if (spmm_stream_fits(b, d_out))
         return finish(launch_spmm_stream((const bf16_t*)dY, b, (const bf16_t*)WrcT_vals, (const uint8_t*)WrcT_meta,
                                          d_in, d_out, nullptr, nullptr, 0, (bf16_t*)dX, (hipStream_t)stream));
     return finish(launch_spmm((const bf16_t*)dY, b, (const bf16_t*)WrcT_vals, (const uint8_t*)WrcT_meta, d_in, d_out,
                               nullptr, nullptr, 0, (bf16_t*)dX, (hipStream_t)stream));
 }
 
-size_t slope_wgrad_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out) {
-    if (b <= 0 || d_in <= 0 || d_out <= 0) return 0;
-    return round256(wgrad_workspace_bytes(b, d_in, d_out));
-}
-
 slope_status slope_wgrad_masked(const void* dY, const void* X, int64_t b, const void* Wr_meta, int64_t d_out,
-                                int64_t d_in, void* dW_vals, void* workspace_or_null, void* stream) {
+                                int64_t d_in, void* dW_vals, void* stream) {
     if (!dY || !X || !Wr_meta || !dW_vals) return SLOPE_ERR_NULL;
-    if (bad_extent(b, 1) || bad_extent(d_out, 64) || bad_extent(d_in, 64)) return SLOPE_ERR_SHAPE;
-    if (misaligned(dY, 16) || misaligned(X, 16) || misaligned(Wr_meta, 16) || misaligned(dW_vals, 16) ||
-        misaligned(workspace_or_null, 256))
+    if (bad_layer(b, d_out, d_in)) return SLOPE_ERR_SHAPE;
+    if (misaligned(dY, 16) || misaligned(X, 16) || misaligned(Wr_meta, 16) || misaligned(dW_vals, 16))
         return SLOPE_ERR_ALIGN;
-    // With scratch memory the product runs on token-contiguous copies (faster at every size measured,
-    // 256 x 256 to 36864 x 9216); callers without it get the in-place kernel.
-    if (workspace_or_null)
-        return finish(launch_wgrad_masked_ws((const bf16_t*)dY, (const bf16_t*)X, b, (const uint8_t*)Wr_meta, d_out,
-                                             d_in, (bf16_t*)dW_vals, workspace_or_null, (hipStream_t)stream));
     return finish(launch_wgrad_masked((const bf16_t*)dY, (const bf16_t*)X, b, (const uint8_t*)Wr_meta, d_out, d_in,
                                       (bf16_t*)dW_vals, (hipStream_t)stream));
 }
 
-size_t slope_spmm_bwd_x_adapter_workspace_bytes(int64_t b, int64_t r) {
-    if (b <= 0 || r <= 0) return 0;
-    return round256((size_t)b * r * 2) + round256(dense_tn_plain_partial_bytes(b, r));
+slope_status slope_wgrad_masked_ws(const void* dY, const void* X, int64_t b, const void* Wr_meta, int64_t d_out,
+                                   int64_t d_in, void* dW_vals, void* workspace, size_t workspace_bytes,
+                                   void* stream) {
+    if (!dY || !X || !Wr_meta || !dW_vals || !workspace) return SLOPE_ERR_NULL;
+    if (bad_layer(b, d_out, d_in)) return SLOPE_ERR_SHAPE;
+    if (misaligned(dY, 16) || misaligned(X, 16) || misaligned(Wr_meta, 16) || misaligned(dW_vals, 16) ||
+        misaligned(workspace, 256))
+        return SLOPE_ERR_ALIGN;
+    if (workspace_bytes < slope_wgrad_workspace_bytes(b, d_in, d_out)) return SLOPE_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    if (!wgrad_tn_fits(d_in))                                 // the packed epilogue of the tile kernels reads metadata by dwords
+        return finish(launch_wgrad_masked((const bf16_t*)dY, (const bf16_t*)X, b, (const uint8_t*)Wr_meta, d_out, d_in,
+                                          (bf16_t*)dW_vals, s));
+    bf16_t* Xt = (bf16_t*)workspace;
+    bf16_t* dYt = (bf16_t*)((uint8_t*)workspace + slope_token_copy_bytes(b, d_in));
+    hipError_t e = launch_token_copies((const bf16_t*)X, d_in, Xt, (const bf16_t*)dY, d_out, dYt, b, s);
+    if (e != hipSuccess) return finish(e);
+    return finish(launch_wgrad_masked_t(dYt, Xt, b, (const uint8_t*)Wr_meta, d_out, d_in, (bf16_t*)dW_vals, s));
+}
+
+slope_status slope_transpose_tokens(const void* A, int64_t b, int64_t d, void* At, size_t At_bytes, void* stream) {
+    if (!A || !At) return SLOPE_ERR_NULL;
+    if (bad_extent(b, 1) || bad_extent(d, 8)) return SLOPE_ERR_SHAPE;
+    if (misaligned(A, 16) || misaligned(At, 256)) return SLOPE_ERR_ALIGN;
+    if (At_bytes < slope_token_copy_bytes(b, d)) return SLOPE_ERR_WORKSPACE;
+    return finish(launch_token_copies((const bf16_t*)A, d, (bf16_t*)At, nullptr, 0, nullptr, b, (hipStream_t)stream));
+}
+
+slope_status slope_wgrad_masked_t(const void* dYt, const void* Xt, int64_t b, const void* Wr_meta, int64_t d_out,
+                                  int64_t d_in, void* dW_vals, void* stream) {
+    if (!dYt || !Xt || !Wr_meta || !dW_vals) return SLOPE_ERR_NULL;
+    if (bad_layer(b, d_out, d_in) || !wgrad_tn_fits(d_in)) return SLOPE_ERR_SHAPE;
+    if (misaligned(dYt, 256) || misaligned(Xt, 256) || misaligned(Wr_meta, 16) || misaligned(dW_vals, 16))
+        return SLOPE_ERR_ALIGN;
+    return finish(launch_wgrad_masked_t((const bf16_t*)dYt, (const bf16_t*)Xt, b, (const uint8_t*)Wr_meta, d_out, d_in,
+                                        (bf16_t*)dW_vals, (hipStream_t)stream));
 }
 
 slope_status slope_spmm_bwd_x_adapter(const void* dY, int64_t b, const void* WrcT_vals, const void* WrcT_meta,
                                       int64_t d_out, int64_t d_in, const void* L, const void* R, int64_t r, void* dX,
-                                      void* workspace, void* stream) {
+                                      void* workspace, size_t workspace_bytes, void* stream) {
     if (!dY || !WrcT_vals || !WrcT_meta || !dX || !L || !R || !workspace) return SLOPE_ERR_NULL;
-    if (bad_extent(b, 1) || bad_extent(d_out, 64) || bad_extent(d_in, 64) || r <= 0) return SLOPE_ERR_SHAPE;
-    if (r % 32 != 0 || r > 512) return SLOPE_ERR_UNSUPPORTED;
+    if (bad_layer(b, d_out, d_in) || r <= 0) return SLOPE_ERR_SHAPE;
+    if (bad_rank(r)) return SLOPE_ERR_UNSUPPORTED;
     if (misaligned(dY, 16) || misaligned(WrcT_vals, 16) || misaligned(WrcT_meta, 16) || misaligned(dX, 16) ||
         misaligned(L, 16) || misaligned(R, 16) || misaligned(workspace, 256))
         return SLOPE_ERR_ALIGN;
+    if (workspace_bytes < slope_spmm_bwd_x_adapter_workspace_bytes(b, r)) return SLOPE_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     bf16_t* T2 = (bf16_t*)workspace;                          // dY R^T, bf16[b, r]
     float* partial = dense_tn_plain_partial_bytes(b, r)
                          ? (float*)((uint8_t*)workspace + round256((size_t)b * r * 2)) : nullptr;
-    hipError_t e = launch_dense_tn_plain((const bf16_t*)dY, b, (const bf16_t*)R, r, d_out, T2, partial, s);
+    hipError_t e = skinny_product((const bf16_t*)dY, b, d_out, (const bf16_t*)R, false, r, T2, nullptr, partial, s);
     if (e != hipSuccess) return finish(e);
     // sparse rows = d_in, contraction over d_out, then r more k-steps on T2 and L (K-contiguous as stored)
     return finish(launch_spmm((const bf16_t*)dY, b, (const bf16_t*)WrcT_vals, (const uint8_t*)WrcT_meta, d_in, d_out,
                               T2, (const bf16_t*)L, r, (bf16_t*)dX, s));
 }
 
-size_t slope_wgrad_adapter_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out, int64_t r) {
-    if (b <= 0 || d_in <= 0 || d_out <= 0 || r <= 0) return 0;
-    return round256(wgrad_adapter_workspace_bytes(b, d_in, d_out, r));
-}
-
 slope_status slope_wgrad_adapter(const void* dY, const void* X, int64_t b, const void* Wr_meta, int64_t d_out,
                                  int64_t d_in, const void* L, const void* R, int64_t r, void* dW_vals, void* dL,
-                                 void* dR, void* workspace, void* stream) {
+                                 void* dR, void* workspace, size_t workspace_bytes, void* stream) {
     if (!dY || !X || !Wr_meta || !dW_vals || !L || !R || !dL || !dR || !workspace) return SLOPE_ERR_NULL;
-    if (bad_extent(b, 1) || bad_extent(d_out, 64) || bad_extent(d_in, 64) || r <= 0) return SLOPE_ERR_SHAPE;
-    if (r % 32 != 0 || r > 512) return SLOPE_ERR_UNSUPPORTED;
+    if (bad_layer(b, d_out, d_in) || r <= 0) return SLOPE_ERR_SHAPE;
+    if (bad_rank(r)) return SLOPE_ERR_UNSUPPORTED;
     if (misaligned(dY, 16) || misaligned(X, 16) || misaligned(Wr_meta, 16) || misaligned(dW_vals, 16) ||
         misaligned(L, 16) || misaligned(R, 16) || misaligned(dL, 16) || misaligned(dR, 16) ||
         misaligned(workspace, 256))
         return SLOPE_ERR_ALIGN;
+    if (workspace_bytes < slope_wgrad_adapter_workspace_bytes(b, d_in, d_out, r)) return SLOPE_ERR_WORKSPACE;
     return finish(launch_wgrad_adapter((const bf16_t*)dY, (const bf16_t*)X, b, (const uint8_t*)Wr_meta, d_out, d_in,
                                        (const bf16_t*)L, (const bf16_t*)R, r, (bf16_t*)dW_vals, (bf16_t*)dL,
                                        (bf16_t*)dR, workspace, (hipStream_t)stream));
@@ -296,7 +368,8 @@ slope_status slope_prune_mask(const void* W, int64_t rows, int64_t cols, int n, 
     if (!W || !mask_out) return SLOPE_ERR_NULL;
     if ((m != 2 && m != 4 && m != 8) || n < 1 || n > m || (axis != 0 && axis != 1)) return SLOPE_ERR_UNSUPPORTED;
     if (bad_extent(rows, axis == 1 ? m : 1) || bad_extent(cols, 8)) return SLOPE_ERR_SHAPE;
-    if (misaligned(W, 16) || misaligned(masked_out_or_null, 16) || misaligned(masked_t_out_or_null, 16))
+    if (misaligned(W, 16) || misaligned(masked_out_or_null, 16) || misaligned(masked_t_out_or_null, 16) ||
+        misaligned(mask_out, 16) || misaligned(candidates_or_null, 16))
         return SLOPE_ERR_ALIGN;
     return finish(launch_nm_mask((const bf16_t*)W, rows, cols, n, m, axis, (const uint8_t*)candidates_or_null,
                                  (uint8_t*)mask_out, (bf16_t*)masked_out_or_null, (bf16_t*)masked_t_out_or_null,
@@ -313,7 +386,7 @@ slope_status slope_gemm_tn(const void* B, int64_t n, const void* A, int64_t m, i
 slope_status slope_sparse_add(const void* A_vals, const void* B_vals, int64_t rows, int64_t cols, float beta,
                               float gamma, void* out_vals, void* stream) {
     if (!A_vals || !B_vals || !out_vals) return SLOPE_ERR_NULL;
-    if (bad_extent(rows, 1) || bad_extent(cols, 16)) return SLOPE_ERR_SHAPE;
+    if (bad_extent(rows, 1) || bad_extent(cols, 8)) return SLOPE_ERR_SHAPE;
     if (misaligned(A_vals, 16) || misaligned(B_vals, 16) || misaligned(out_vals, 16)) return SLOPE_ERR_ALIGN;
     return finish(launch_sparse_add((const bf16_t*)A_vals, (const bf16_t*)B_vals, (size_t)rows * (size_t)(cols / 2),
                                     beta, gamma, (bf16_t*)out_vals, (hipStream_t)stream));
@@ -322,7 +395,7 @@ slope_status slope_sparse_add(const void* A_vals, const void* B_vals, int64_t ro
 slope_status slope_update_sparse(const void* Wnew_vals, const void* Wr_meta, int64_t d_out, int64_t d_in,
                                  void* Wr_vals, const void* WrcT_meta, void* WrcT_vals, void* stream) {
     if (!Wnew_vals || !Wr_meta || !Wr_vals || !WrcT_meta || !WrcT_vals) return SLOPE_ERR_NULL;
-    if (bad_extent(d_out, 64) || bad_extent(d_in, 64)) return SLOPE_ERR_SHAPE;
+    if (bad_extent(d_out, 8) || bad_extent(d_in, 8)) return SLOPE_ERR_SHAPE;
     if (misaligned(Wnew_vals, 16) || misaligned(Wr_meta, 16) || misaligned(Wr_vals, 16) ||
         misaligned(WrcT_meta, 16) || misaligned(WrcT_vals, 16))
         return SLOPE_ERR_ALIGN;
@@ -338,11 +411,11 @@ slope_status slope_update_sparse(const void* Wnew_vals, const void* Wr_meta, int
 
 slope_status slope_spmm_fwd_plan(int64_t b, int64_t d_in, int64_t d_out, int64_t r, int with_workspace, int32_t* plan) {
     if (!plan) return SLOPE_ERR_NULL;
-    if (bad_extent(b, 1) || bad_extent(d_out, 64) || bad_extent(d_in, 64) || r < 0) return SLOPE_ERR_SHAPE;
-    if (r > 0 && (r % 32 != 0 || r > 512)) return SLOPE_ERR_UNSUPPORTED;
+    if (bad_layer(b, d_out, d_in) || r < 0) return SLOPE_ERR_SHAPE;
+    if (r > 0 && bad_rank(r)) return SLOPE_ERR_UNSUPPORTED;
     for (int i = 0; i < 6; ++i) plan[i] = 0;
     plan[3] = 1;
-    if (b <= STREAM_MAX_TOKENS && d_in >= 128) {
+    if (spmm_stream_fits(b, d_in)) {
         plan[0] = 0;
         plan[1] = spmm_stream_rows(b, d_out, d_in);
         plan[2] = b <= 16 ? 16 : 32;
@@ -355,7 +428,9 @@ slope_status slope_spmm_fwd_plan(int64_t b, int64_t d_in, int64_t d_out, int64_t
         else { plan[0] = 2; plan[1] = bm; plan[2] = bn; }
     }
     if (r > 0) {
-        if (b <= XL_SMALL_MAX_TOKENS) {
+        if (d_in % 64 != 0) {
+            plan[4] = 4;
+        } else if (b <= XL_SMALL_MAX_TOKENS) {
             plan[4] = 1;
             plan[5] = xl_subs(b, d_in, r);
         } else {

@@ -497,14 +497,20 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_split_kernel(const bf16_t* 
 }
 
 // ------------------------------------------------------------------------------------------
-// Generic kernel (any K % 64 == 0): 128 x 128 tile, 4 wavefronts (2 x 2), operands staged through
+// Generic kernel (any K % 8 == 0): 128 x 128 tile, 4 wavefronts (2 x 2), operands staged through
 // registers into two LDS buffers in fragment order (the 16 bytes a lane feeds to the MFMA sit at
 // 16 * lane inside a 1 KiB fragment), one barrier per k-step.
+// RAGGED (K not a multiple of 64): the last k-step is partly past the end of the rows, and rows of
+// the packed weight are only 8-byte, rows of the metadata only 1-byte aligned.  Loads then come in
+// pieces of 8 logical k (8 bytes of packed values, 16 bytes of tokens, 1 byte of metadata), each
+// either wholly inside the row or replaced: zeros for values and tokens, the nibble pair 0x44
+// (positions 0, 1: a legal encoding) for metadata, so the tail contributes exact zeros.
 struct GenSmem {
     static constexpr int A_BYTES = 128 * 64, B_BYTES = 128 * 128, M_BYTES = 128 * 8;
     static constexpr int STAGE = A_BYTES + B_BYTES + M_BYTES;
 };
 
+template <bool RAGGED>
 __global__ void __launch_bounds__(256) spmm_generic_kernel(const bf16_t* __restrict__ B, int n,
                                                            const bf16_t* __restrict__ Av,
                                                            const uint8_t* __restrict__ Am, int m, int K,
@@ -546,11 +552,39 @@ __global__ void __launch_bounds__(256) spmm_generic_kernel(const bf16_t* __restr
 #pragma unroll
         for (int j = 0; j < NF; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    const int ksteps = K / 64;
+    const int ksteps = (K + 63) / 64;
     u32x4 a_reg[A_LD], b_reg[B_LD];
     u32x2 m_reg;
+    // first logical k of the lane's 16 of the sparse operand, and of its two token pieces, in k-step 0
+    const int a_k = lq * 16;
+    int b_k[B_LD];
+#pragma unroll
+    for (int i = 0; i < B_LD; ++i) b_k[i] = ((wave * B_LD + i) & 1) * 32 + lq * 8;
+    auto load_ragged = [&](int kk) {
+        const int k0 = kk * 64;
+#pragma unroll
+        for (int i = 0; i < A_LD; ++i) {
+            u32x2 lo = {0u, 0u}, hi = {0u, 0u};
+            if (k0 + a_k < K) lo = *(const u32x2*)(a_src[i] + kk * 32);
+            if (k0 + a_k + 8 < K) hi = *(const u32x2*)(a_src[i] + kk * 32 + 4);
+            a_reg[i] = (u32x4){lo[0], lo[1], hi[0], hi[1]};
+        }
+#pragma unroll
+        for (int i = 0; i < B_LD; ++i) {
+            b_reg[i] = (u32x4){0u, 0u, 0u, 0u};
+            if (k0 + b_k[i] < K) b_reg[i] = *(const u32x4*)(b_src[i] + kk * 64);
+        }
+        uint32_t w[2] = {0x44444444u, 0x44444444u};
+        const int have = K / 8 - kk * 8;                      // metadata bytes of this k-step inside the row
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (e < have) w[e >> 2] = (w[e >> 2] & ~(0xFFu << (8 * (e & 3)))) | ((uint32_t)m_src[kk * 8 + e] << (8 * (e & 3)));
+        m_reg = (u32x2){w[0], w[1]};
+    };
 #define GEN_LOAD(kk)                                                                                   \
-    {                                                                                                  \
+    if (RAGGED) {                                                                                      \
+        load_ragged(kk);                                                                               \
+    } else {                                                                                           \
         _Pragma("unroll") for (int i = 0; i < A_LD; ++i) a_reg[i] = *(const u32x4*)(a_src[i] + (kk) * 32); \
         _Pragma("unroll") for (int i = 0; i < B_LD; ++i) b_reg[i] = *(const u32x4*)(b_src[i] + (kk) * 64); \
         m_reg = *(const u32x2*)(m_src + (kk) * 8);                                                     \
@@ -604,7 +638,7 @@ hipError_t launch_tile(const bf16_t* B, int64_t n, const bf16_t* Av, const uint8
     static_assert(S::TOTAL <= 160 * 1024, "LDS budget");
     int tiles_m = (int)((m + BM - 1) / BM), tiles_n = (int)((n + BN - 1) / BN);
     auto kern = spmm_kernel<BM, BN>;
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, S::TOTAL);
+    hipError_t e = allow_dynamic_lds<spmm_kernel<BM, BN>>(S::TOTAL);
     if (e != hipSuccess) return e;
     if (!slabs) { nslabs = 1; slab_steps = (int)(K / 64); }
     kern<<<dim3((unsigned)super_grid(tiles_m, tiles_n), (unsigned)nslabs), dim3(SPMM_THREADS), S::TOTAL, s>>>(
@@ -632,8 +666,7 @@ hipError_t launch_split(const bf16_t* B, int64_t n, const bf16_t* Av, const uint
     using S = SplitSmem;
     static_assert(S::TOTAL <= 160 * 1024, "LDS budget");
     int tiles_m = (int)((m + S::BM - 1) / S::BM), tiles_n = (int)((n + S::BN - 1) / S::BN);
-    hipError_t e = hipFuncSetAttribute((const void*)spmm_split_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       S::TOTAL);
+    hipError_t e = allow_dynamic_lds<spmm_split_kernel>(S::TOTAL);
     if (e != hipSuccess) return e;
     spmm_split_kernel<<<dim3((unsigned)super_grid(tiles_m, tiles_n)), dim3(SPMM_THREADS), S::TOTAL, s>>>(
         B, (int)n, Av, Am, (int)m, (int)K, B2, A2, (int)K2, C, tiles_m, tiles_n);
@@ -719,8 +752,12 @@ hipError_t launch_spmm(const bf16_t* B, int64_t n, const bf16_t* A_vals, const u
     spmm_tile_choice(n, m, K, bm, bn);
     if (bm == 0) {
         int tiles_m = (int)((m + 127) / 128), tiles_n = (int)((n + 127) / 128);
-        spmm_generic_kernel<<<dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 0, s>>>(
-            B, (int)n, A_vals, A_meta, (int)m, (int)K, B2, A2, (int)K2, C, tiles_m);
+        if (K % 64 == 0)
+            spmm_generic_kernel<false><<<dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 0, s>>>(
+                B, (int)n, A_vals, A_meta, (int)m, (int)K, B2, A2, (int)K2, C, tiles_m);
+        else
+            spmm_generic_kernel<true><<<dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 0, s>>>(
+                B, (int)n, A_vals, A_meta, (int)m, (int)K, B2, A2, (int)K2, C, tiles_m);
         return hipGetLastError();
     }
     switch (bm * 1000 + bn) {

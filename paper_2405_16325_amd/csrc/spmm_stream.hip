@@ -252,7 +252,7 @@ hipError_t launch_stream_lds(const bf16_t* B, int64_t n, const bf16_t* Av, const
     using S = StreamLds<MF, WAVES, NF>;
     static_assert(S::TOTAL <= 160 * 1024, "LDS budget");
     auto kern = spmm_stream_lds_kernel<MF, WAVES, NF>;
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, S::TOTAL);
+    hipError_t e = allow_dynamic_lds<spmm_stream_lds_kernel<MF, WAVES, NF>>(S::TOTAL);
     if (e != hipSuccess) return e;
     kern<<<dim3((unsigned)((m + S::BM - 1) / S::BM)), dim3(WAVES * 64), S::TOTAL, s>>>(B, (int)n, Av, Am, (int)m, (int)K,
                                                                                      T, R, (int)K2, C);
@@ -453,7 +453,7 @@ hipError_t launch_xl_small(const bf16_t* X, int64_t n, int64_t d_in, const bf16_
     const int subs = xl_subs(n, d_in, r);
     const int slabs = (int)((d_in + XL_CHUNK * subs - 1) / (XL_CHUNK * subs));
     const int lds = XL_CHUNK * subs * XLM_PITCH;
-    hipError_t e = hipFuncSetAttribute((const void*)xl_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    hipError_t e = allow_dynamic_lds<xl_mfma_kernel>(XL_CHUNK * 4 * XLM_PITCH);   // the largest slab (subs <= 4)
     if (e != hipSuccess) return e;
     dim3 grid((unsigned)slabs, (unsigned)((r + 127) / 128), (unsigned)((n + 127) / 128));
     xl_mfma_kernel<<<grid, dim3(256), lds, s>>>(X, (int)n, (int)d_in, L, (int)r, subs, scratch);

@@ -10,14 +10,13 @@
 //   D lane l holds column (d_out) l%16 and rows (d_in) 4*(l/16) .. +3 = exactly one group of four
 //   of W^R's row, so the epilogue picks two of a lane's four accumulators with the group's
 //   metadata nibble and stores them as one 4-byte pair of the packed gradient.
-#include "common.h"
+#include "pipeline.h"
 
 namespace {
 
-constexpr int XCDS = 8;
 constexpr int WG_KS = 32;                      // tokens per LDS stage
 
-__device__ __forceinline__ void tile_of_block(int nblocks, int tiles_m, int tiles_n, int& tm, int& tn) {
+__device__ __forceinline__ void wgrad_tile_of_block(int nblocks, int tiles_m, int tiles_n, int& tm, int& tn) {
     int b = blockIdx.x;
     int xcd = b % XCDS, pos = b / XCDS;
     int q = nblocks / XCDS, rem = nblocks % XCDS;
@@ -55,7 +54,7 @@ __global__ void __launch_bounds__(256) wgrad_kernel(const bf16_t* __restrict__ d
     extern __shared__ __align__(16) uint8_t smem[];
 
     int tm, tn;
-    tile_of_block(tiles_m * tiles_n, tiles_m, tiles_n, tm, tn);
+    wgrad_tile_of_block(tiles_m * tiles_n, tiles_m, tiles_n, tm, tn);
     const int i0 = tm * BM, o0 = tn * BN;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -165,7 +164,7 @@ hipError_t launch_tile(const bf16_t* dY, const bf16_t* X, int64_t b, const uint8
     int tiles_m = (int)((d_in + BM - 1) / BM), tiles_n = (int)((d_out + BN - 1) / BN);
     size_t smem = 2 * S::STAGE;
     auto kern = wgrad_kernel<BM, BN>;
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    hipError_t e = allow_dynamic_lds<wgrad_kernel<BM, BN>>((int)smem);
     if (e != hipSuccess) return e;
     kern<<<dim3((unsigned)(tiles_m * tiles_n)), dim3(256), smem, s>>>(dY, X, (int)b, meta, (int)d_out, (int)d_in, G,
                                                                        tiles_m, tiles_n);

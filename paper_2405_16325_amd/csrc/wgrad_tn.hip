@@ -435,7 +435,7 @@ hipError_t launch_dense_tn(const bf16_t* At, int64_t m, const bf16_t* Bt, int64_
     static_assert(S::TOTAL <= 160 * 1024, "LDS budget");
     int tiles_m = (int)((m + BM - 1) / BM), tiles_n = (int)((n + BN - 1) / BN);
     auto kern = dense_tn_kernel<BM, BN, EPI, NS>;
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, S::TOTAL);
+    hipError_t e = allow_dynamic_lds<dense_tn_kernel<BM, BN, EPI, NS>>(S::TOTAL);
     if (e != hipSuccess) return e;
     kern<<<dim3((unsigned)super_grid(tiles_m, tiles_n), (unsigned)nslabs), dim3(TN_THREADS), S::TOTAL, s>>>(
         At, (int)m, Bt, (int)n, (int)kp, (int)ld, meta, out, tiles_m, tiles_n, slab_steps, partial);
@@ -448,8 +448,7 @@ hipError_t launch_dense_tn_split(const bf16_t* At, int64_t m, const bf16_t* Bt, 
     using S = SplitSmem;
     static_assert(S::TOTAL <= 160 * 1024, "LDS budget");
     int tiles_m = (int)((m + S::BM - 1) / S::BM), tiles_n = (int)((n + S::BN - 1) / S::BN);
-    hipError_t e = hipFuncSetAttribute((const void*)dense_tn_split_kernel<EPI>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, S::TOTAL);
+    hipError_t e = allow_dynamic_lds<dense_tn_split_kernel<EPI>>(S::TOTAL);
     if (e != hipSuccess) return e;
     dense_tn_split_kernel<EPI><<<dim3((unsigned)super_grid(tiles_m, tiles_n)), dim3(TN_THREADS), S::TOTAL, s>>>(
         At, (int)m, Bt, (int)n, (int)kp, (int)ld, meta, out, tiles_m, tiles_n);
@@ -458,18 +457,30 @@ hipError_t launch_dense_tn_split(const bf16_t* At, int64_t m, const bf16_t* Bt, 
 
 }  // namespace
 
-size_t wgrad_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out) {
-    return (size_t)(d_in + d_out) * (size_t)token_pitch((b + 63) / 64 * 64) * 2;
+namespace {
+inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
+}  // namespace
+
+// Token-contiguous copy of a [b][d] activation: d rows of token_pitch(b rounded up to 64) elements.
+size_t token_copy_bytes(int64_t b, int64_t d) { return (size_t)d * (size_t)token_pitch((b + 63) / 64 * 64) * 2; }
+
+// One or two copies (in1 == nullptr: one) of matrices with b rows in one launch.
+hipError_t launch_token_copies(const bf16_t* in0, int64_t cols0, bf16_t* out0, const bf16_t* in1, int64_t cols1,
+                               bf16_t* out1, int64_t b, hipStream_t s) {
+    const int64_t bp = (b + 63) / 64 * 64, ld = token_pitch(bp);
+    if (in1) launch_transpose_pad2(in0, cols0, out0, in1, cols1, out1, b, bp, ld, s);
+    else launch_transpose_pad(in0, b, cols0, bp, ld, out0, s);
+    return hipGetLastError();
 }
 
-hipError_t launch_wgrad_masked_ws(const bf16_t* dY, const bf16_t* X, int64_t b, const uint8_t* meta, int64_t d_out,
-                                  int64_t d_in, bf16_t* gvals, void* workspace, hipStream_t s) {
+// The packed epilogue reads the metadata of 32 columns of W^R as one dword: rows of d_in / 8 bytes must
+// keep those dwords aligned.  Other layers take the in-place kernel.
+bool wgrad_tn_fits(int64_t d_in) { return d_in % 32 == 0; }
+
+// dW (masked, packed) from token-contiguous copies Xt [d_in][ld], dYt [d_out][ld]
+hipError_t launch_wgrad_masked_t(const bf16_t* dYt, const bf16_t* Xt, int64_t b, const uint8_t* meta, int64_t d_out,
+                                 int64_t d_in, bf16_t* gvals, hipStream_t s) {
     const int64_t bp = (b + 63) / 64 * 64, ld = token_pitch(bp);
-    bf16_t* Xt = (bf16_t*)workspace;
-    bf16_t* dYt = Xt + (size_t)d_in * ld;
-    launch_transpose_pad2(X, d_in, Xt, dY, d_out, dYt, b, bp, ld, s);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
     // The kernel runs at the rate its compute units pull operands from L2: a launch costs about
     // (rounds of 256 resident tiles) x (rows per tile).  Take the cheapest shape, the larger on ties.
     const int bms[4] = {256, 256, 128, 128}, bns[4] = {256, 128, 128, 64};
@@ -542,13 +553,9 @@ hipError_t launch_dense_tn_any(const bf16_t* B, int64_t n, const bf16_t* A, int6
 // (chain rule of Eq. 11)   dL = X^T (dY R^T)  [d_in, r],   dR = (X L)^T dY  [r, d_out],
 // all three contractions over the tokens sharing the token-contiguous copies of X and dY.
 // Workspace: Xt | dYt | Lt [r][d_in] | T = X L [b][r] | T2 = dY R^T [b][r] | Tt [r][ld] | T2t [r][ld].
-namespace {
-inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
-}  // namespace
-
 size_t wgrad_adapter_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out, int64_t r) {
     size_t ld = (size_t)token_pitch((b + 63) / 64 * 64);
-    return round256(wgrad_workspace_bytes(b, d_in, d_out)) + round256((size_t)r * d_in * 2) +
+    return round256(token_copy_bytes(b, d_in)) + round256(token_copy_bytes(b, d_out)) + round256((size_t)r * d_in * 2) +
            2 * round256((size_t)b * r * 2) + 2 * round256((size_t)r * ld * 2);
 }
 
@@ -557,17 +564,26 @@ hipError_t launch_wgrad_adapter(const bf16_t* dY, const bf16_t* X, int64_t b, co
                                 bf16_t* dR, void* workspace, hipStream_t s) {
     const int64_t bp = (b + 63) / 64 * 64, ld = token_pitch(bp);
     uint8_t* w = (uint8_t*)workspace;
-    bf16_t* Xt = (bf16_t*)w;
-    bf16_t* dYt = Xt + (size_t)d_in * ld;
-    w += round256(wgrad_workspace_bytes(b, d_in, d_out));
+    bf16_t* Xt = (bf16_t*)w;   w += round256(token_copy_bytes(b, d_in));
+    bf16_t* dYt = (bf16_t*)w;  w += round256(token_copy_bytes(b, d_out));
     bf16_t* Lt = (bf16_t*)w;   w += round256((size_t)r * d_in * 2);
     bf16_t* T = (bf16_t*)w;    w += round256((size_t)b * r * 2);
     bf16_t* T2 = (bf16_t*)w;   w += round256((size_t)b * r * 2);
     bf16_t* Tt = (bf16_t*)w;   w += round256((size_t)r * ld * 2);
     bf16_t* T2t = (bf16_t*)w;
 
-    hipError_t e = launch_wgrad_masked_ws(dY, X, b, meta, d_out, d_in, gvals, workspace, s);   // fills Xt, dYt
-    if (e != hipSuccess) return e;
+    hipError_t e;
+    if (d_in % 64 != 0 || d_out % 64 != 0) {
+        // Extents that are not whole k-steps of the MFMA kernels: the in-place kernel for dW and plain
+        // arithmetic for the four skinny products (T and T2 rounded to bf16 as on the fast path).
+        if ((e = launch_wgrad_masked(dY, X, b, meta, d_out, d_in, gvals, s)) != hipSuccess) return e;
+        if ((e = launch_plain_gemm(X, d_in, 1, L, 1, r, b, r, d_in, T, s)) != hipSuccess) return e;        // T  = X L
+        if ((e = launch_plain_gemm(dY, d_out, 1, R, d_out, 1, b, r, d_out, T2, s)) != hipSuccess) return e; // T2 = dY R^T
+        if ((e = launch_plain_gemm(X, 1, d_in, T2, 1, r, d_in, r, b, dL, s)) != hipSuccess) return e;       // dL = X^T T2
+        return launch_plain_gemm(T, 1, r, dY, 1, d_out, r, d_out, b, dR, s);                               // dR = T^T dY
+    }
+    if ((e = launch_token_copies(X, d_in, Xt, dY, d_out, dYt, b, s)) != hipSuccess) return e;
+    if ((e = launch_wgrad_masked_t(dYt, Xt, b, meta, d_out, d_in, gvals, s)) != hipSuccess) return e;
     launch_transpose_pad(L, d_in, r, d_in, d_in, Lt, s);                          // Lt[r][d_in]
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if ((e = launch_dense_tn_plain(X, b, Lt, r, d_in, T, nullptr, s)) != hipSuccess) return e;      // T  = X L

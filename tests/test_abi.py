@@ -46,45 +46,115 @@ def test_argument_errors_are_reported_before_launch():
     lib = binding.lib()
     p = ctypes.c_void_p(0x1000)       # aligned, never dereferenced: every call below must fail first
     odd = ctypes.c_void_p(0x1008)
-    assert lib.slope_prune_rows(None, 64, 64, 2, 4, p, p, None, None) == binding.SLOPE_ERR_NULL
-    assert lib.slope_prune_rows(p, 64, 64, 1, 2, p, p, None, None) == binding.SLOPE_ERR_UNSUPPORTED
-    assert lib.slope_prune_rows(p, 64, 60, 2, 4, p, p, None, None) == binding.SLOPE_ERR_SHAPE
-    assert lib.slope_prune_rows(p, 0, 64, 2, 4, p, p, None, None) == binding.SLOPE_ERR_SHAPE
-    assert lib.slope_prune_rows(p, 64, 64, 2, 4, odd, p, None, None) == binding.SLOPE_ERR_ALIGN
-    assert lib.slope_double_prune(p, p, 64, 96, p, p, None, None) == binding.SLOPE_ERR_SHAPE
-    assert lib.slope_double_prune(p, None, 64, 64, p, p, None, None) == binding.SLOPE_ERR_NULL
-    assert lib.slope_spmm_fwd(p, 0, p, p, 64, 64, None, None, 0, p, None, None) == binding.SLOPE_ERR_SHAPE
-    assert lib.slope_spmm_fwd(p, 8, p, p, 64, 64, p, p, 48, p, p, None) == binding.SLOPE_ERR_UNSUPPORTED
-    assert lib.slope_spmm_fwd(p, 8, p, p, 64, 64, p, None, 32, p, p, None) == binding.SLOPE_ERR_NULL
-    assert lib.slope_spmm_fwd(p, 8, p, p, 64, 64, p, p, 32, p, None, None) == binding.SLOPE_ERR_NULL
-    assert lib.slope_spmm_fwd(p, 8, p, p, 64, 1 << 31, None, None, 0, p, None, None) == binding.SLOPE_ERR_SHAPE
-    assert lib.slope_spmm_bwd_x(p, 8, p, p, 64, 72, p, None) == binding.SLOPE_ERR_SHAPE
-    assert lib.slope_spmm_bwd_x(odd, 8, p, p, 64, 64, p, None) == binding.SLOPE_ERR_ALIGN
-    assert lib.slope_wgrad_masked(p, p, 8, None, 64, 64, p, None, None) == binding.SLOPE_ERR_NULL
-    assert lib.slope_wgrad_masked(p, p, -1, p, 64, 64, p, None, None) == binding.SLOPE_ERR_SHAPE
-    assert lib.slope_wgrad_masked(p, p, 8, p, 64, 64, p, odd, None) == binding.SLOPE_ERR_ALIGN
-    assert lib.slope_spmm_bwd_x_adapter(p, 8, p, p, 64, 64, p, None, 32, p, p, None) == binding.SLOPE_ERR_NULL
-    assert lib.slope_spmm_bwd_x_adapter(p, 8, p, p, 64, 64, p, p, 48, p, p, None) == binding.SLOPE_ERR_UNSUPPORTED
-    assert lib.slope_spmm_bwd_x_adapter(p, 8, p, p, 64, 64, p, p, 32, p, odd, None) == binding.SLOPE_ERR_ALIGN
-    assert lib.slope_wgrad_adapter(p, p, 8, p, 64, 64, p, p, 32, p, p, p, None, None) == binding.SLOPE_ERR_NULL
-    assert lib.slope_wgrad_adapter(p, p, 8, p, 64, 72, p, p, 32, p, p, p, p, None) == binding.SLOPE_ERR_SHAPE
-    assert lib.slope_wgrad_adapter(p, p, 8, p, 64, 64, p, p, 1024, p, p, p, p, None) == binding.SLOPE_ERR_UNSUPPORTED
-    assert lib.slope_wgrad_adapter_workspace_bytes(100, 64, 128, 32) > lib.slope_wgrad_workspace_bytes(100, 64, 128)
-    assert lib.slope_prune_mask(p, 8, 64, 1, 3, 0, None, p, None, None, None) == binding.SLOPE_ERR_UNSUPPORTED
-    assert lib.slope_prune_mask(p, 8, 64, 5, 4, 0, None, p, None, None, None) == binding.SLOPE_ERR_UNSUPPORTED
-    assert lib.slope_prune_mask(p, 6, 64, 2, 4, 1, None, p, None, None, None) == binding.SLOPE_ERR_SHAPE
-    assert lib.slope_prune_mask(p, 8, 60, 2, 4, 0, None, p, None, None, None) == binding.SLOPE_ERR_SHAPE
-    assert lib.slope_prune_mask(p, 8, 64, 2, 4, 0, None, None, None, None, None) == binding.SLOPE_ERR_NULL
-    assert lib.slope_gemm_tn(p, 8, p, 64, 100, p, None) == binding.SLOPE_ERR_SHAPE
-    assert lib.slope_gemm_tn(p, 8, None, 64, 128, p, None) == binding.SLOPE_ERR_NULL
-    assert lib.slope_sparse_add(p, None, 4, 64, 1.0, 1.0, p, None) == binding.SLOPE_ERR_NULL
-    assert lib.slope_sparse_add(p, p, 4, 24, 1.0, 1.0, p, None) == binding.SLOPE_ERR_SHAPE
-    assert lib.slope_sparse_add(p, p, 4, 64, 1.0, 1.0, odd, None) == binding.SLOPE_ERR_ALIGN
-    assert lib.slope_update_sparse(p, p, 64, 64, p, None, p, None) == binding.SLOPE_ERR_NULL
-    assert lib.slope_update_sparse(p, p, 64, 96, p, p, p, None) == binding.SLOPE_ERR_SHAPE
-    assert lib.slope_update_sparse(p, p, 64, 64, p, p, odd, None) == binding.SLOPE_ERR_ALIGN
-    assert lib.slope_wgrad_workspace_bytes(100, 64, 128) >= (64 + 128) * 128 * 2
-    assert b"NULL" in lib.slope_status_string(binding.SLOPE_ERR_NULL)
+    big = 1 << 40
+    E = binding
+    assert lib.slope_prune_rows(None, 64, 64, 2, 4, p, p, None, None) == E.SLOPE_ERR_NULL
+    assert lib.slope_prune_rows(p, 64, 64, 1, 2, p, p, None, None) == E.SLOPE_ERR_UNSUPPORTED
+    assert lib.slope_prune_rows(p, 64, 60, 2, 4, p, p, None, None) == E.SLOPE_ERR_SHAPE
+    assert lib.slope_prune_rows(p, 0, 64, 2, 4, p, p, None, None) == E.SLOPE_ERR_SHAPE
+    assert lib.slope_prune_rows(p, 64, 64, 2, 4, odd, p, None, None) == E.SLOPE_ERR_ALIGN
+    assert lib.slope_double_prune(p, p, 64, 100, p, p, None, None) == E.SLOPE_ERR_SHAPE
+    assert lib.slope_double_prune(p, p, 68, 64, p, p, None, None) == E.SLOPE_ERR_SHAPE
+    assert lib.slope_double_prune(p, None, 64, 64, p, p, None, None) == E.SLOPE_ERR_NULL
+    assert lib.slope_spmm_fwd(p, 0, p, p, 64, 64, None, None, 0, p, None, None) == E.SLOPE_ERR_SHAPE
+    assert lib.slope_spmm_fwd(p, 8, p, p, 64, 64, p, p, 48, p, p, None) == E.SLOPE_ERR_UNSUPPORTED
+    assert lib.slope_spmm_fwd(p, 8, p, p, 64, 64, p, None, 32, p, p, None) == E.SLOPE_ERR_NULL
+    assert lib.slope_spmm_fwd(p, 8, p, p, 64, 64, p, p, 32, p, None, None) == E.SLOPE_ERR_NULL
+    assert lib.slope_spmm_fwd(p, 8, p, p, 64, 1 << 31, None, None, 0, p, None, None) == E.SLOPE_ERR_SHAPE
+    assert lib.slope_spmm_fwd(p, 8, p, p, 64, 68, None, None, 0, p, None, None) == E.SLOPE_ERR_SHAPE
+    assert lib.slope_spmm_fwd(p, 8, p, p, 64, 64, None, None, 0, p, odd, None) == E.SLOPE_ERR_ALIGN
+    # the sized form refuses a workspace that is too small (here: adapters need T, a copy of L, partial sums)
+    need = lib.slope_workspace_bytes(E.SLOPE_CALL_SPMM_FWD, 8, 64, 64, 32)
+    assert need > 0 and need == lib.slope_spmm_fwd_workspace_bytes(8, 64, 64, 32)
+    assert lib.slope_spmm_fwd_ws(p, 8, p, p, 64, 64, p, p, 32, p, p, need - 1, None) == E.SLOPE_ERR_WORKSPACE
+    assert lib.slope_spmm_fwd_ws(p, 8, p, p, 64, 64, p, p, 32, p, None, big, None) == E.SLOPE_ERR_NULL
+    assert lib.slope_spmm_bwd_x(p, 8, p, p, 64, 76, p, None) == E.SLOPE_ERR_SHAPE
+    assert lib.slope_spmm_bwd_x(odd, 8, p, p, 64, 64, p, None) == E.SLOPE_ERR_ALIGN
+    assert lib.slope_wgrad_masked(p, p, 8, None, 64, 64, p, None) == E.SLOPE_ERR_NULL
+    assert lib.slope_wgrad_masked(p, p, -1, p, 64, 64, p, None) == E.SLOPE_ERR_SHAPE
+    assert lib.slope_wgrad_masked(p, odd, 8, p, 64, 64, p, None) == E.SLOPE_ERR_ALIGN
+    need = lib.slope_workspace_bytes(E.SLOPE_CALL_WGRAD_MASKED_WS, 100, 64, 128, 0)
+    assert need == lib.slope_wgrad_workspace_bytes(100, 64, 128) >= (64 + 128) * 128 * 2
+    assert need == lib.slope_token_copy_bytes(100, 64) + lib.slope_token_copy_bytes(100, 128)
+    assert lib.slope_wgrad_masked_ws(p, p, 100, p, 128, 64, p, None, big, None) == E.SLOPE_ERR_NULL
+    assert lib.slope_wgrad_masked_ws(p, p, 100, p, 128, 64, p, odd, big, None) == E.SLOPE_ERR_ALIGN
+    assert lib.slope_wgrad_masked_ws(p, p, 100, p, 128, 64, p, p, need - 1, None) == E.SLOPE_ERR_WORKSPACE
+    assert lib.slope_transpose_tokens(p, 100, 64, p, lib.slope_token_copy_bytes(100, 64) - 1, None) == E.SLOPE_ERR_WORKSPACE
+    assert lib.slope_transpose_tokens(p, 100, 60, p, big, None) == E.SLOPE_ERR_SHAPE
+    assert lib.slope_transpose_tokens(None, 100, 64, p, big, None) == E.SLOPE_ERR_NULL
+    assert lib.slope_wgrad_masked_t(p, p, 100, p, 128, 72, p, None) == E.SLOPE_ERR_SHAPE     # d_in % 32 for this form
+    assert lib.slope_wgrad_masked_t(p, None, 100, p, 128, 64, p, None) == E.SLOPE_ERR_NULL
+    assert lib.slope_wgrad_masked_t(odd, p, 100, p, 128, 64, p, None) == E.SLOPE_ERR_ALIGN
+    assert lib.slope_spmm_bwd_x_adapter(p, 8, p, p, 64, 64, p, None, 32, p, p, big, None) == E.SLOPE_ERR_NULL
+    assert lib.slope_spmm_bwd_x_adapter(p, 8, p, p, 64, 64, p, p, 48, p, p, big, None) == E.SLOPE_ERR_UNSUPPORTED
+    assert lib.slope_spmm_bwd_x_adapter(p, 8, p, p, 64, 64, p, p, 32, p, odd, big, None) == E.SLOPE_ERR_ALIGN
+    need = lib.slope_workspace_bytes(E.SLOPE_CALL_SPMM_BWD_X_ADAPTER, 8, 64, 64, 32)
+    assert need == lib.slope_spmm_bwd_x_adapter_workspace_bytes(8, 32) > 0
+    assert lib.slope_spmm_bwd_x_adapter(p, 8, p, p, 64, 64, p, p, 32, p, p, need - 1, None) == E.SLOPE_ERR_WORKSPACE
+    assert lib.slope_wgrad_adapter(p, p, 8, p, 64, 64, p, p, 32, p, p, p, None, big, None) == E.SLOPE_ERR_NULL
+    assert lib.slope_wgrad_adapter(p, p, 8, p, 64, 76, p, p, 32, p, p, p, p, big, None) == E.SLOPE_ERR_SHAPE
+    assert lib.slope_wgrad_adapter(p, p, 8, p, 64, 64, p, p, 1024, p, p, p, p, big, None) == E.SLOPE_ERR_UNSUPPORTED
+    need = lib.slope_workspace_bytes(E.SLOPE_CALL_WGRAD_ADAPTER, 100, 64, 128, 32)
+    assert need == lib.slope_wgrad_adapter_workspace_bytes(100, 64, 128, 32) > lib.slope_wgrad_workspace_bytes(100, 64, 128)
+    assert lib.slope_wgrad_adapter(p, p, 100, p, 128, 64, p, p, 32, p, p, p, p, need - 1, None) == E.SLOPE_ERR_WORKSPACE
+    for call in (E.SLOPE_CALL_PRUNE_ROWS, E.SLOPE_CALL_DOUBLE_PRUNE, E.SLOPE_CALL_SPMM_BWD_X, E.SLOPE_CALL_WGRAD_MASKED, 0, 99):
+        assert lib.slope_workspace_bytes(call, 100, 64, 128, 32) == 0
+    assert lib.slope_prune_mask(p, 8, 64, 1, 3, 0, None, p, None, None, None) == E.SLOPE_ERR_UNSUPPORTED
+    assert lib.slope_prune_mask(p, 8, 64, 5, 4, 0, None, p, None, None, None) == E.SLOPE_ERR_UNSUPPORTED
+    assert lib.slope_prune_mask(p, 6, 64, 2, 4, 1, None, p, None, None, None) == E.SLOPE_ERR_SHAPE
+    assert lib.slope_prune_mask(p, 8, 60, 2, 4, 0, None, p, None, None, None) == E.SLOPE_ERR_SHAPE
+    assert lib.slope_prune_mask(p, 8, 64, 2, 4, 0, None, None, None, None, None) == E.SLOPE_ERR_NULL
+    assert lib.slope_prune_mask(p, 8, 64, 2, 4, 0, None, odd, None, None, None) == E.SLOPE_ERR_ALIGN
+    assert lib.slope_prune_mask(p, 8, 64, 2, 4, 0, odd, p, None, None, None) == E.SLOPE_ERR_ALIGN
+    assert lib.slope_gemm_tn(p, 8, p, 64, 100, p, None) == E.SLOPE_ERR_SHAPE
+    assert lib.slope_gemm_tn(p, 8, None, 64, 128, p, None) == E.SLOPE_ERR_NULL
+    assert lib.slope_sparse_add(p, None, 4, 64, 1.0, 1.0, p, None) == E.SLOPE_ERR_NULL
+    assert lib.slope_sparse_add(p, p, 4, 20, 1.0, 1.0, p, None) == E.SLOPE_ERR_SHAPE
+    assert lib.slope_sparse_add(p, p, 4, 64, 1.0, 1.0, odd, None) == E.SLOPE_ERR_ALIGN
+    assert lib.slope_update_sparse(p, p, 64, 64, p, None, p, None) == E.SLOPE_ERR_NULL
+    assert lib.slope_update_sparse(p, p, 64, 100, p, p, p, None) == E.SLOPE_ERR_SHAPE
+    assert lib.slope_update_sparse(p, p, 64, 64, p, p, odd, None) == E.SLOPE_ERR_ALIGN
+    assert b"NULL" in lib.slope_status_string(E.SLOPE_ERR_NULL)
+
+
+def test_binding_checks_dtypes_and_shapes_before_the_call():
+    """The library sees raw pointers only; the binding refuses tensors of the wrong dtype, shape or size."""
+    import torch
+
+    class Fake:
+        """Stands in for a device tensor (there is no GPU here): only what the checks look at."""
+        def __init__(self, shape, dtype, cuda=True, contiguous=True):
+            self.shape, self.dtype, self.is_cuda, self._c = tuple(shape), dtype, cuda, contiguous
+            self.device = "cuda:0"
+        def dim(self): return len(self.shape)
+        def is_contiguous(self): return self._c
+        def numel(self):
+            n = 1
+            for e in self.shape: n *= e
+            return n
+        def data_ptr(self): raise AssertionError("the call must be refused before a pointer is taken")
+
+    bf, u8 = torch.bfloat16, torch.uint8
+    vals, meta = Fake((64, 32), bf), Fake((64, 8), u8)
+    with pytest.raises(ValueError, match="bfloat16"):
+        binding.slope_spmm_fwd(Fake((8, 64), torch.float16), vals, meta)
+    with pytest.raises(ValueError, match="shape"):
+        binding.slope_spmm_fwd(Fake((8, 72), bf), vals, meta)
+    with pytest.raises(ValueError, match="shape"):
+        binding.slope_spmm_fwd(Fake((8, 64), bf), vals, Fake((64, 16), u8))
+    with pytest.raises(ValueError, match="shape"):
+        binding.slope_spmm_fwd(Fake((8, 64), bf), vals, meta, out=Fake((8, 32), bf))
+    with pytest.raises(ValueError, match="shape"):
+        binding.slope_spmm_fwd(Fake((8, 64), bf), vals, meta, Fake((64, 32), bf), Fake((16, 64), bf))
+    with pytest.raises(ValueError, match="bytes"):
+        binding.slope_spmm_fwd(Fake((8, 64), bf), vals, meta, Fake((64, 32), bf), Fake((32, 64), bf),
+                               workspace=Fake((256,), u8))
+    with pytest.raises(ValueError, match="shape"):
+        binding.slope_wgrad_masked(Fake((8, 64), bf), Fake((9, 64), bf), meta)
+    with pytest.raises(ValueError, match="contiguous"):
+        binding.slope_spmm_bwd_x(Fake((8, 64), bf, contiguous=False), vals, meta)
+    with pytest.raises(ValueError, match="device"):
+        binding.slope_prune_rows(Fake((8, 8), bf, cuda=False))
 
 
 def test_static_scratch_rejects_a_shape_beyond_its_buffer():
@@ -93,7 +163,7 @@ def test_static_scratch_rejects_a_shape_beyond_its_buffer():
     assert binding.slope_spmm_fwd_workspace_bytes(b, d_in, d_out, r) > binding.SLOPE_STATIC_SCRATCH_BYTES
     p = ctypes.c_void_p(0x1000)            # never dereferenced: the size is refused on the host, before any launch
     assert lib.slope_spmm_fwd_static(p, b, p, p, d_out, d_in, p, p, r, p, None) == binding.SLOPE_ERR_WORKSPACE
-    assert lib.slope_spmm_fwd_static(p, b, p, p, d_out, d_in + 8, p, p, r, p, None) == binding.SLOPE_ERR_SHAPE
+    assert lib.slope_spmm_fwd_static(p, b, p, p, d_out, d_in + 4, p, p, r, p, None) == binding.SLOPE_ERR_SHAPE
     assert lib.slope_spmm_fwd_static(p, 8, p, p, 64, 64, p, None, 32, p, None) == binding.SLOPE_ERR_NULL
     text = open(os.path.join(ROOT, "include", "slope.h")).read()
     assert "#define SLOPE_STATIC_SCRATCH_BYTES (%du << 20)" % (binding.SLOPE_STATIC_SCRATCH_BYTES >> 20) in text

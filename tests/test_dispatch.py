@@ -78,4 +78,14 @@ def test_plan_rejects_what_the_call_rejects():
     with pytest.raises(sl.SlopeError):
         sl.slope_spmm_fwd_plan(16, 9216, 9216, 48)
     with pytest.raises(sl.SlopeError):
-        sl.slope_spmm_fwd_plan(16, 9200, 9216)
+        sl.slope_spmm_fwd_plan(16, 9204, 9216)
+
+
+def test_extents_that_are_not_multiples_of_64_take_the_general_kernels():
+    # any multiple of 8 is accepted; a contraction that is not a whole number of k-steps of 64 goes to the
+    # generic kernel's form for ragged rows (also for inference-size batches) and to plain arithmetic for X L
+    for b in (1, 16, 300, 5000):
+        plan = sl.slope_spmm_fwd_plan(b, 1000, 1000, 64)
+        assert plan["product"] == GENERIC and plan["xl"] == 4
+    assert sl.slope_spmm_fwd_plan(16, 1024, 1000, 64)["product"] == 0      # d_out may be ragged on the fast paths
+    assert sl.slope_spmm_fwd_plan(4096, 1024, 1000, 64)["product"] == TILE
