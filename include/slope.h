@@ -315,6 +315,25 @@ slope_status slope_spmm_fwd_plan(int64_t b, int64_t d_in, int64_t d_out, int64_t
  */
 int64_t slope_tile_order(int64_t tiles_m, int64_t tiles_n, int32_t* tm, int32_t* tn, int64_t capacity);
 
+/*
+ * slope_ceiling - diagnostics: micro-benchmarks of what the chip gives the simplest kernel of each kind,
+ * so that the rooflines of the products (Eq. 4-6) and of the prune streams (Sec. 2.1) can be quoted
+ * against ceilings measured in the same run, next to the published peaks.  One launch per call.
+ *   kind   SLOPE_CEILING_SPARSE_MFMA  register-resident loop of v_smfmac_f32_16x16x64_bf16
+ *          SLOPE_CEILING_DENSE_MFMA   register-resident loop of v_mfma_f32_16x16x32_bf16
+ *          SLOPE_CEILING_READ         read-only stream over buf
+ *          SLOPE_CEILING_COPY         copy of the first half of buf onto the second half
+ *   buf    device memory, 256-byte aligned, at least slope_ceiling_min_bytes() bytes (the MFMA loops take
+ *          their operands from its start: fill it with the values the products see); overwritten
+ *   iters  iterations of the MFMA loops (16 instructions per wavefront each); ignored by the streams
+ *   work   out (host): dense-equivalent flops, or bytes moved, of the launch
+ */
+typedef enum {
+    SLOPE_CEILING_SPARSE_MFMA = 0, SLOPE_CEILING_DENSE_MFMA = 1, SLOPE_CEILING_READ = 2, SLOPE_CEILING_COPY = 3
+} slope_ceiling_kind;
+size_t slope_ceiling_min_bytes(void);
+slope_status slope_ceiling(int kind, void* buf, size_t bytes, int iters, double* work, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -58,6 +58,8 @@ SIGNATURES = {
     "slope_gemm_tn": (_INT, [_P, _I64, _P, _I64, _I64, _P, _P]),
     "slope_sparse_add": (_INT, [_P, _P, _I64, _I64, ctypes.c_float, ctypes.c_float, _P, _P]),
     "slope_update_sparse": (_INT, [_P, _P, _I64, _I64, _P, _P, _P, _P]),
+    "slope_ceiling_min_bytes": (_SZ, []),
+    "slope_ceiling": (_INT, [_INT, _P, _SZ, _INT, _P, _P]),
     "slope_tile_order": (_I64, [_I64, _I64, _P, _P, _I64]),
     "slope_spmm_fwd_plan": (_INT, [_I64, _I64, _I64, _I64, _INT, _P]),
 }
@@ -408,6 +410,18 @@ def slope_update_sparse(Wnew_vals: torch.Tensor, meta: torch.Tensor, vals: torch
     _check("slope_update_sparse", lib().slope_update_sparse(_ptr(Wnew_vals), _ptr(meta), d_out, d_in, _ptr(vals),
                                                             _ptr(meta_t), _ptr(vals_t), _stream()))
     return vals, vals_t
+
+
+SLOPE_CEILING_SPARSE_MFMA, SLOPE_CEILING_DENSE_MFMA, SLOPE_CEILING_READ, SLOPE_CEILING_COPY = range(4)
+
+
+def slope_ceiling(kind: int, buf: torch.Tensor, iters: int = 1) -> float:
+    """Queues one micro-benchmark launch on buf (uint8 device tensor); returns its flops or bytes."""
+    if buf is None or not buf.is_cuda or buf.dtype != U8 or not buf.is_contiguous():
+        raise ValueError("buf must be a contiguous uint8 device tensor")
+    work = ctypes.c_double(0.0)
+    _check("slope_ceiling", lib().slope_ceiling(kind, _ptr(buf), buf.numel(), iters, ctypes.byref(work), _stream()))
+    return work.value
 
 
 # ---------------------------------------------------------------- host <-> device helpers (plumbing)

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(ROOT, "_build")
 LIB_PATH = os.environ.get("SLOPE_LIB", os.path.join(HERE, "libslope.so"))
-SOURCES = ["slope_api.hip", "prune.hip", "spmm.hip", "spmm_stream.hip", "wgrad.hip", "wgrad_tn.hip", "lowrank.hip", "nm_mask.hip"]
+SOURCES = ["slope_api.hip", "prune.hip", "spmm.hip", "spmm_stream.hip", "wgrad.hip", "wgrad_tn.hip", "lowrank.hip", "nm_mask.hip", "ceilings.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

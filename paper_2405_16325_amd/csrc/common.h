@@ -13,6 +13,9 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
+// what slope_last_hip_error() reports for the calling thread
+void note_hip_error(hipError_t e);
+
 // Launchers (host side, one per kernel family).  Each returns the hipError_t of its launches.
 hipError_t launch_prune_rows(const bf16_t* W, int64_t d_out, int64_t d_in, bf16_t* vals, uint8_t* meta,
                              uint8_t* mask, hipStream_t s);

@@ -53,6 +53,8 @@ hipError_t skinny_product(const bf16_t* B, int64_t n, int64_t K, const bf16_t* A
 
 }  // namespace
 
+void note_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
+
 extern "C" {
 
 int slope_version(void) { return 200; }
