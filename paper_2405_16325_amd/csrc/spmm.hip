@@ -210,9 +210,13 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_kernel(const bf16_t* __rest
     const bool meta_wave = wave < M_WAVES;                    // wave-uniform
     const uint8_t* m_src;
     {
-        int rl = (meta_wave ? wave : 0) * 32 + (lane >> 1);   // two lanes (16 bytes each) per row
+        // 32 rows = two fragments per instruction; lane l brings the 16-byte half (l >> 4) & 1 of row
+        // 16 (l >> 5) + (l & 15), so that LDS holds each fragment as [half][row]: the sixteen rows of a
+        // 2-byte metadata read then fall on sixteen different bank groups ([row][half] made rows r and r + 8
+        // collide: over a third of the LDS-active cycles of the 256 x 256 kernel were bank conflicts)
+        int rl = (meta_wave ? wave : 0) * 32 + (lane >> 5) * 16 + (lane & 15);
         int row = wrap_row(m0 + rl, m);
-        m_src = Am + (size_t)row * (K / 8) + (lane & 1) * 16;
+        m_src = Am + (size_t)row * (K / 8) + ((lane >> 4) & 1) * 16;
     }
     uint8_t* const m_dst0 = smem + (meta_wave ? S::M_OFF + wave * 1024 : S::DUMMY);
     const int m_dst_step = meta_wave ? S::M_QUAD : 0;
@@ -223,7 +227,7 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_kernel(const bf16_t* __rest
     const int rd1 = l16 * 128 + (((4 + lq) ^ sw) * 16);       // h = 1
     const int a_rd = (wm * MF) * 2048;
     const int b_rd = S::B_OFF + (wn * NF) * 2048;
-    const int m_rd = S::M_OFF + (wm * MF * 16 + l16) * 32 + lq * 2;
+    const int m_rd = S::M_OFF + wm * MF * 512 + l16 * 16 + lq * 2;
 
     // A split over k: workgroup row blockIdx.y takes k-steps [k_first, k_first + ksteps) and leaves
     // fp32 partial sums in its slab; without a slab buffer there is one row and it takes all of K.
@@ -276,7 +280,7 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_kernel(const bf16_t* __rest
         constexpr int QUEUED = B_LD + ((S4 & 1) == 0 ? A_LD : 0) + (S4 == 0 ? 1 : 0);                  \
         const uint8_t* pa = smem + ((S4 >> 1) & 1) * S::A_PAIR + a_rd + ((S4 & 1) ? rd1 : rd0);        \
         const uint8_t* pb = smem + b_rd + bst * S::B_STAGE;                                            \
-        const uint8_t* pm = smem + m_rd + ((ks0 >> 2) & 1) * S::M_QUAD + S4 * 8;                       \
+        const uint8_t* pm = smem + m_rd + ((ks0 >> 2) & 1) * S::M_QUAD + (S4 >> 1) * 256 + (S4 & 1) * 8; \
         BFrag bf[NF];                                                                                  \
         AFrag af[MF];                                                                                  \
         int ai[MF];                                                                                    \
@@ -374,11 +378,11 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_split_kernel(const bf16_t* 
         a_src[q] = (const uint8_t*)Av + (size_t)ra * K + sw16;
         b_src[q] = (const uint8_t*)B + (size_t)rb * K * 2 + sw16;
     }
-    const uint8_t* m_src;                                    // 32 rows per wavefront, two lanes per row
+    const uint8_t* m_src;                                    // 32 rows per wavefront
     {
-        int rl = wave * 32 + (lane >> 1);
+        int rl = wave * 32 + (lane >> 5) * 16 + (lane & 15);  // fragments land as [half][row], see spmm_kernel
         int row = wrap_row(m0 + rl, m);
-        m_src = Am + (size_t)row * (K / 8) + (lane & 1) * 16;
+        m_src = Am + (size_t)row * (K / 8) + ((lane >> 4) & 1) * 16;
     }
 
     // ---- reader lanes: fragment f = rows 16f .. 16f+15 = 2 KiB; lane (l16, lq) wants chunk 4h + lq
@@ -387,7 +391,7 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_split_kernel(const bf16_t* 
     const int rd1 = l16 * 128 + (((4 + lq) ^ sw) * 16);       // h = 1
     const int a_rd = (wm * MF) * 2048;
     const int b_rd = S::B_OFF + group * 2 * S::B_HALF + ((wn & 1) * NF) * 2048;
-    const int m_rd = S::M_OFF + (wm * MF * 16 + l16) * 32 + lq * 2;
+    const int m_rd = S::M_OFF + wm * MF * 512 + l16 * 16 + lq * 2;
 
     const int ksteps = K / 64;                                // a multiple of 4
     auto issue_b = [&](int g, int ks) {                       // token half g of k-step ks (clamped)
@@ -428,7 +432,7 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_split_kernel(const bf16_t* 
 #define SPLIT_READ(S4)                                                                                 \
         const uint8_t* pa = smem + (((S4) >> 1) & 1) * S::A_PAIR + a_rd + (((S4) & 1) ? rd1 : rd0);    \
         const uint8_t* pb = smem + b_rd + ((S4) & 1) * S::B_HALF;                                      \
-        const uint8_t* pm = smem + m_rd + ((ks0 >> 2) & 1) * S::M_QUAD + (S4) * 8;                     \
+        const uint8_t* pm = smem + m_rd + ((ks0 >> 2) & 1) * S::M_QUAD + ((S4) >> 1) * 256 + ((S4) & 1) * 8; \
         BFrag bf[NF];                                                                                  \
         AFrag af[MF];                                                                                  \
         int ai[MF];                                                                                    \
