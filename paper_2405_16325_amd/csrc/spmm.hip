@@ -45,14 +45,18 @@ namespace {
 //    workgroup stages the tile's BMT columns of 128 rows at a time in LDS (the rings are idle by
 //    then) and the wavefronts read their fragments back with the transposing LDS read; every
 //    thread of the workgroup must make the call (it contains barriers);
-//  - epilogue: four consecutive features of one token per lane, one 8-byte store.
+//  - epilogue: a lane holds four consecutive features of one token.  Stored straight from the registers that
+//    is 8 bytes per lane in pieces of 32 contiguous bytes: sixteen rows per instruction, each a partial
+//    line.  So the workgroup's tile goes through LDS (the rings are idle by then) as [token][feature] rows
+//    and leaves in whole rows: 8 bytes per lane, up to 512 contiguous bytes per instruction.
+//    BNT = tokens of the workgroup's tile, tile_t0 its first token; every thread must make the call.
 //  - with a slab buffer (a split over k, see launch_spmm_slabs): the fp32 accumulators go to
 //    partial[token][feature] instead, 16 bytes per lane, and a reduction kernel finishes.
-template <int MF, int NF, int BMT>
+template <int MF, int NF, int BMT, int BNT>
 __device__ __forceinline__ void extend_and_store(f32x4 (&acc)[MF][NF], int f0, int t0, int m, int n, int l16, int lq,
                                                  const bf16_t* __restrict__ B2, const bf16_t* __restrict__ A2,
                                                  int K2, bf16_t* __restrict__ C, uint8_t* smem, int tile_f0,
-                                                 float* __restrict__ partial = nullptr) {
+                                                 int tile_t0, float* __restrict__ partial = nullptr) {
     if (K2 < 0) {
         constexpr int PITCH = BMT * 2 + 32;                   // pitch % 128 == 32: the four rows of a transposing
                                                               // read fall on distinct banks
@@ -136,23 +140,37 @@ __device__ __forceinline__ void extend_and_store(f32x4 (&acc)[MF][NF], int f0, i
             }
         }
     }
+    if (partial) {
 #pragma unroll
-    for (int j = 0; j < NF; ++j) {
-        int row = t0 + j * 16 + l16;                      // token
-        if (row >= n) continue;
+        for (int j = 0; j < NF; ++j) {
+            int row = t0 + j * 16 + l16;                      // token
+            if (row >= n) continue;
+#pragma unroll
+            for (int i = 0; i < MF; ++i) {
+                int col = f0 + i * 16 + lq * 4;               // feature
+                if (col < m) *(f32x4*)(partial + (size_t)row * m + col) = acc[i][j];
+            }
+        }
+        return;
+    }
+    constexpr int CP = BMT * 2 + 16;                          // bytes per staged token row: 16 rows x 4 lanes x 8 B
+                                                              // of one store fall on 64 different banks
+    constexpr int LPR = BMT / 4;                              // 8-byte pieces per row
+    __syncthreads();                                          // every wavefront is done with the rings / the staged factor
+#pragma unroll
+    for (int j = 0; j < NF; ++j)
 #pragma unroll
         for (int i = 0; i < MF; ++i) {
-            int col = f0 + i * 16 + lq * 4;               // feature
-            if (col >= m) continue;
             f32x4 v = acc[i][j];
-            if (partial) {
-                *(f32x4*)(partial + (size_t)row * m + col) = v;
-                continue;
-            }
             union { __bf16 h[4]; u32x2 u; } o;
             o.h[0] = (__bf16)v[0]; o.h[1] = (__bf16)v[1]; o.h[2] = (__bf16)v[2]; o.h[3] = (__bf16)v[3];
-            *(u32x2*)(C + (size_t)row * m + col) = o.u;
+            *(u32x2*)(smem + (t0 - tile_t0 + j * 16 + l16) * CP + (f0 - tile_f0 + i * 16 + lq * 4) * 2) = o.u;
         }
+    __syncthreads();
+    for (int idx = (int)threadIdx.x; idx < BNT * LPR; idx += (int)blockDim.x) {
+        int row = idx / LPR, c4 = (idx % LPR) * 4;
+        int tok = tile_t0 + row, col = tile_f0 + c4;
+        if (tok < n && col < m) *(u32x2*)(C + (size_t)tok * m + col) = *(const u32x2*)(smem + row * CP + c4 * 2);
     }
 }
 
@@ -316,9 +334,10 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_kernel(const bf16_t* __rest
     WAIT_HERE(waitcnt_imm(0, 15));           // drain the clamped look-ahead loads
 
     // the dense extension is added once, by the first slab
-    extend_and_store<MF, NF, BM>(acc, m0 + wm * MF * 16, n0 + wn * NF * 16, m, n, l16, lq, B2, A2,
-                                 blockIdx.y == 0 ? K2 : 0, C, smem, m0,
-                                 slabs ? slabs + (size_t)blockIdx.y * (size_t)n * (size_t)m : nullptr);
+    static_assert(BN * (BM * 2 + 16) <= S::TOTAL, "the staged output tile fits in the rings");
+    extend_and_store<MF, NF, BM, BN>(acc, m0 + wm * MF * 16, n0 + wn * NF * 16, m, n, l16, lq, B2, A2,
+                                     blockIdx.y == 0 ? K2 : 0, C, smem, m0, n0,
+                                     slabs ? slabs + (size_t)blockIdx.y * (size_t)n * (size_t)m : nullptr);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -497,7 +516,9 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_split_kernel(const bf16_t* 
 #undef SPLIT_STEP0
 #undef SPLIT_STEP1
     WAIT_HERE(waitcnt_imm(0, 15));                            // drain the clamped look-ahead loads
-    extend_and_store<MF, NF, S::BM>(acc, m0 + wm * MF * 16, n0 + wn * NF * 16, m, n, l16, lq, B2, A2, K2, C, smem, m0);
+    static_assert(S::BN * (S::BM * 2 + 16) <= S::TOTAL, "the staged output tile fits in the rings");
+    extend_and_store<MF, NF, S::BM, S::BN>(acc, m0 + wm * MF * 16, n0 + wn * NF * 16, m, n, l16, lq, B2, A2, K2, C, smem,
+                                           m0, n0);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -631,7 +652,9 @@ __global__ void __launch_bounds__(256) spmm_generic_kernel(const bf16_t* __restr
     }
 #undef GEN_LOAD
 #undef GEN_STORE
-    extend_and_store<MF, NF, 128>(acc, m0 + wm * MF * 16, n0 + wn * NF * 16, m, n, l16, lq, B2, A2, K2, C, smem, m0);
+    static_assert(128 * (128 * 2 + 16) <= 2 * S::STAGE, "the staged output tile fits in the stages");
+    extend_and_store<MF, NF, 128, 128>(acc, m0 + wm * MF * 16, n0 + wn * NF * 16, m, n, l16, lq, B2, A2, K2, C, smem, m0,
+                                       n0);
 }
 
 template <int BM, int BN>

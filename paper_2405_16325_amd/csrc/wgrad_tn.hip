@@ -80,29 +80,34 @@ struct TnSmem {
 constexpr int TN_THREADS = 512;
 enum { EPI_MASKED_PACKED = 0, EPI_PLAIN = 1 };
 
-// Masked, packed epilogue of one wavefront: acc[i][j] is the 16 x 16 fragment at D rows
-// c0 + 16 i (d_in) and D columns o0 + 16 j (d_out).  A lane's four accumulators are one group of
-// four along d_in of row o: the group's metadata nibble picks the two that W^R keeps.
-template <int MF, int NF>
+// Masked, packed epilogue: acc[i][j] of a wavefront is the 16 x 16 fragment at D rows c0 + 16 i (d_in) and D
+// columns o0 + 16 j (d_out).  A lane's four accumulators are one group of four along d_in of row o: the
+// group's metadata nibble picks the two that W^R keeps.  Stored straight from the registers a pair is a
+// 4-byte piece and an instruction touches sixteen rows; so the workgroup's tile of pairs goes through LDS
+// (the rings are idle) as [d_out row][pair] and leaves in whole rows, 8 bytes per lane.
+// BMT x BNT = the workgroup's tile (d_in x d_out) at (tile_c0, tile_o0); every thread must make the call.
+template <int MF, int NF, int BMT, int BNT>
 __device__ __forceinline__ void store_masked_packed(const f32x4 (&acc)[MF][NF], int m, int n, int c0, int o0,
-                                                    int l16, int lq, const uint8_t* __restrict__ meta,
-                                                    bf16_t* __restrict__ out) {
+                                                    int tile_c0, int tile_o0, int l16, int lq,
+                                                    const uint8_t* __restrict__ meta, bf16_t* __restrict__ out,
+                                                    uint8_t* smem) {
     constexpr int WM = MF * 16;
+    constexpr int CP = BMT + 16;                              // bytes per staged row of pairs: 16 rows x 4 lanes x 4 B
+                                                              // of one store fall on 64 different banks
+    constexpr int LPR = BMT / 8;                              // 8-byte pieces per row
     const size_t mpitch = (size_t)m / 8, gpitch = (size_t)m / 2;
+    __syncthreads();                                          // every wavefront is done with the rings
 #pragma unroll
     for (int j = 0; j < NF; ++j) {
         int o = o0 + j * 16 + l16;
-        if (o >= n) continue;
         // metadata of the wavefront's WM d_in columns of row o: WM / 4 groups = WM / 8 bytes
         uint32_t mw[WM / 32];
 #pragma unroll
         for (int q = 0; q < WM / 32; ++q)
-            mw[q] = c0 + 32 * q < m ? *(const uint32_t*)(meta + (size_t)o * mpitch + c0 / 8 + 4 * q) : 0u;
+            mw[q] = o < n && c0 + 32 * q < m ? *(const uint32_t*)(meta + (size_t)o * mpitch + c0 / 8 + 4 * q) : 0u;
 #pragma unroll
         for (int i = 0; i < MF; ++i) {
-            int col = c0 + i * 16 + lq * 4;               // first d_in index of the group
-            if (col >= m) continue;
-            int gl = i * 4 + lq;                          // group index inside the WM columns
+            int gl = i * 4 + lq;                              // group index inside the WM columns
             uint32_t nib = (mw[i >> 1] >> (4 * (gl & 7))) & 0xFu;
             uint32_t a = nib & 3u, c = nib >> 2;
             f32x4 v = acc[i][j];
@@ -111,8 +116,14 @@ __device__ __forceinline__ void store_masked_packed(const f32x4 (&acc)[MF][NF], 
             union { __bf16 h[2]; uint32_t u; } pr;
             pr.h[0] = (__bf16)v0;
             pr.h[1] = (__bf16)v1;
-            *(uint32_t*)(out + (size_t)o * gpitch + (col >> 1)) = pr.u;
+            *(uint32_t*)(smem + (o - tile_o0) * CP + ((c0 - tile_c0) / 4 + gl) * 4) = pr.u;
         }
+    }
+    __syncthreads();
+    for (int idx = (int)threadIdx.x; idx < BNT * LPR; idx += (int)blockDim.x) {
+        int row = idx / LPR, c8 = (idx % LPR) * 8;            // 8 bytes = two pairs = eight columns of W
+        int o = tile_o0 + row, col = tile_c0 + c8;
+        if (o < n && col < m) *(u32x2*)(out + (size_t)o * gpitch + (col >> 1)) = *(const u32x2*)(smem + row * CP + c8);
     }
 }
 
@@ -262,7 +273,8 @@ __global__ void __launch_bounds__(TN_THREADS) dense_tn_kernel(const bf16_t* __re
                             partial ? partial + (size_t)blockIdx.y * n * m : nullptr);
         return;
     }
-    store_masked_packed<MF, NF>(acc, m, n, m0 + wm * WM, n0 + wn * NF * 16, l16, lq, meta, out);
+    static_assert(BN * (BM + 16) <= S::TOTAL, "the staged tile of pairs fits in the ring");
+    store_masked_packed<MF, NF, BM, BN>(acc, m, n, m0 + wm * WM, n0 + wn * NF * 16, m0, n0, l16, lq, meta, out, smem);
 }
 
 // out = sum over the slabs (in slab order: runs are bit-identical), rounded to bf16; four elements per lane
@@ -424,7 +436,8 @@ __global__ void __launch_bounds__(TN_THREADS) dense_tn_split_kernel(const bf16_t
 #undef ODD_LOADS
     WAIT_HERE(waitcnt_imm(0, 15));                            // drain the clamped look-ahead loads
     if (EPI == EPI_PLAIN) store_plain<MF, NF>(acc, m, n, m0 + wm * WM, n0 + wn * NF * 16, l16, lq, out, nullptr);
-    else store_masked_packed<MF, NF>(acc, m, n, m0 + wm * WM, n0 + wn * NF * 16, l16, lq, meta, out);
+    else store_masked_packed<MF, NF, S::BM, S::BN>(acc, m, n, m0 + wm * WM, n0 + wn * NF * 16, m0, n0, l16, lq, meta, out,
+                                                   smem);
 }
 
 template <int BM, int BN, int EPI, int NS>

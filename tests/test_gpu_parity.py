@@ -202,3 +202,47 @@ def test_error_status_raises():
     with pytest.raises(sl.SlopeError) as e:
         sl.slope_prune_rows(w)
     assert e.value.status == sl.SLOPE_ERR_SHAPE
+
+
+@pytest.mark.parametrize("b,d_out,d_in", [(2048, 3072, 768), (1000, 320, 448), (4100, 4160, 256), (77, 2048, 4096), (1, 64, 64)])
+def test_wgrad_from_prepared_token_copies(b, d_out, d_in):
+    """slope_transpose_tokens + slope_wgrad_masked_t (copies made once, reusable by layers that share an operand)
+    give what slope_wgrad_masked_ws gives, bit for bit, and the oracle's result within the bar."""
+    say(f"wgrad from prepared copies b={b} d_out={d_out} d_in={d_in}")
+    t, d, _, _ = layer_on_device(b, d_out, d_in, 0, seed=b + 11)
+    xt, dyt = sl.slope_transpose_tokens(d["X"]), sl.slope_transpose_tokens(d["dY"])
+    g = sl.slope_wgrad_masked_t(dyt, xt, b, d["meta"])
+    g_ws = sl.slope_wgrad_masked(d["dY"], d["X"], d["meta"], workspace="auto")
+    # a second layer with the same input: the copy of X is used again
+    w2 = dev(inputs.gaussian_bf16((d_out, d_in), 0.02, b + 12, 2))
+    _, meta2, _ = sl.slope_prune_rows(w2)
+    g2 = sl.slope_wgrad_masked_t(dyt, xt, b, meta2)
+    torch.cuda.synchronize()
+    assert (host(g) == host(g_ws)).all()
+    check_product(host(g), so.wgrad_masked(t["dY"], t["X"], u8(d["meta"])), "dW")
+    check_product(host(g2), so.wgrad_masked(t["dY"], t["X"], u8(meta2)), "dW of the second layer")
+
+
+def test_sized_workspaces_are_checked():
+    t, d, _, _ = layer_on_device(300, 256, 512, 32, seed=5)
+    need = sl.slope_spmm_fwd_workspace_bytes(300, 512, 256, 32)
+    small = torch.empty(need - 256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(ValueError):
+        sl.slope_spmm_fwd(d["X"], d["vals"], d["meta"], d["L"], d["R"], workspace=small)
+    import ctypes
+    p = lambda x: ctypes.c_void_p(x.data_ptr())
+    y = torch.empty((300, 256), dtype=torch.bfloat16, device="cuda")
+    st = sl.lib().slope_spmm_fwd_ws(p(d["X"]), 300, p(d["vals"]), p(d["meta"]), 256, 512, p(d["L"]), p(d["R"]), 32, p(y),
+                                    p(small), small.numel(), None)
+    assert st == sl.SLOPE_ERR_WORKSPACE
+
+
+def test_ceiling_micro_benchmarks_run():
+    buf = torch.zeros(64 << 20, dtype=torch.uint8, device="cuda")
+    for kind in (sl.SLOPE_CEILING_SPARSE_MFMA, sl.SLOPE_CEILING_DENSE_MFMA, sl.SLOPE_CEILING_READ, sl.SLOPE_CEILING_COPY):
+        assert sl.slope_ceiling(kind, buf, 4) > 0
+    torch.cuda.synchronize()
+    with pytest.raises(sl.SlopeError):
+        sl.slope_ceiling(7, buf, 4)
+    with pytest.raises(sl.SlopeError):
+        sl.slope_ceiling(sl.SLOPE_CEILING_READ, buf[:1 << 20], 4)
