@@ -94,6 +94,15 @@ constexpr int DP_PITCH = 272;       // bytes per decompressed row in LDS (128 * 
 constexpr int DP_OPITCH = 33;       // dwords per output row [i][og] (32 + 1: conflict-free columns)
 constexpr int DP_NPITCH = 36;       // bytes per nibble row [i][og]
 
+// Per 16-bit half: 1 where kj > ki, else 0 (saturating subtract, then min with 1).  Written as instructions
+// because the compiler turns the portable form back into one compare and one select per half.
+__device__ __forceinline__ uint32_t pk_beats(uint32_t kj, uint32_t ki, uint32_t ones) {
+    uint32_t d, c;
+    asm("v_pk_sub_u16 %0, %1, %2 clamp" : "=v"(d) : "v"(kj), "v"(ki));
+    asm("v_pk_min_u16 %0, %1, %2" : "=v"(c) : "v"(d), "v"(ones));
+    return c;
+}
+
 // GIVEN = false: slope_double_prune, the pairs are chosen here by magnitude among the survivors
 //                 and their metadata is written.
 // GIVEN = true : slope_update_sparse, the pairs are the ones metaT_in already names (static
@@ -198,35 +207,61 @@ __global__ void __launch_bounds__(256) double_prune_kernel(const bf16_t* __restr
         }
     }
     __syncthreads();                                           // the input tile is in registers: reuse its memory
+    // The kernel is bound by vector ALU work, not by memory (the SIMDs issue vector instructions in over 90 %
+    // of their cycles), so two neighbouring columns are ranked at once in the two 16-bit halves of a register:
+    // a row's dword already holds the pair, keys are at most 0x8000, and "j beats i" is min(k_j -sat k_i, 1).
+    const uint32_t ones = 0x00010001u;
 #pragma unroll
     for (int n = 0; n < 2; ++n) {
         int u = t + 256 * n, og = u >> 4, i8 = u & 15;
         uint32_t keep[4] = {0, 0, 0, 0};
+        uint32_t spread[4];                                    // candidate bits: even columns at bits 0, 2, 4, 6, odd ones 16 higher
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            uint32_t e[4], key[4], cd[4];
+        for (int k = 0; k < 4; ++k) spread[k] = (cb[n][k] & 0x55u) | ((cb[n][k] & 0xAAu) << 15);
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                e[k] = (r[n][k][j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
-                cd[k] = (cb[n][k] >> j) & 1u;
-                key[k] = cd[k] ? (e[k] & 0x7FFFu) + 1u : 0u;   // survivors outrank every pruned slot
+        for (int q = 0; q < 4; ++q) {                          // columns 8 i8 + 2 q (low halves) and + 1 (high halves)
+            uint32_t x[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) x[k] = r[n][k][q];
+            uint32_t set2 = 0;                                 // the two 4-bit sets, at bits 0 and 16
+            if (!GIVEN) {
+                uint32_t key[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    // magnitude + 1 for a survivor of the row prune, 0 for a pruned slot (whose stored value is +0):
+                    // survivors outrank every pruned slot, zeros included
+                    key[k] = (x[k] & 0x7FFF7FFFu) + ((spread[k] >> (2 * q)) & 0x00010001u);
+                const uint32_t c01 = pk_beats(key[1], key[0], ones), c02 = pk_beats(key[2], key[0], ones),
+                               c03 = pk_beats(key[3], key[0], ones), c12 = pk_beats(key[2], key[1], ones),
+                               c13 = pk_beats(key[3], key[1], ones), c23 = pk_beats(key[3], key[2], ones);
+                // rank = how many of the others come first (larger key, or equal key and lower index); the halves
+                // hold at most 3, so plain 32-bit arithmetic never carries from one into the other
+                const uint32_t r0 = c01 + c02 + c03;
+                const uint32_t r1 = (0x00010001u - c01) + c12 + c13;
+                const uint32_t r2 = (0x00020002u - c02 - c12) + c23;
+                const uint32_t r3 = 0x00030003u - c03 - c13 - c23;
+                // rank 2 or 3 = pruned: bit 1 of the rank
+                const uint32_t out = ((r0 >> 1) & 0x00010001u) | (r1 & 0x00020002u) | ((r2 << 1) & 0x00040004u) |
+                                     ((r3 << 2) & 0x00080008u);
+                set2 = out ^ 0x000F000Fu;
             }
-            const int col = 8 * i8 + j;
-            uint32_t set = 0, nib;
-            if (GIVEN) {
-                nib = sG[col * DP_NPITCH + og];
-            } else {
-                set = top2_of_4(key[0], key[1], key[2], key[3]);
-                nib = nibble_of_pair(set);
-            }
-            uint64_t q = (uint64_t)(e[0] | (e[1] << 16)) | ((uint64_t)(e[2] | (e[3] << 16)) << 32);
-            uint32_t v0 = (uint32_t)(q >> (16u * (nib & 3u))) & 0xFFFFu;
-            uint32_t v1 = (uint32_t)(q >> (16u * (nib >> 2))) & 0xFFFFu;
-            sO[col * DP_OPITCH + og] = v0 | (v1 << 16);
-            if (!GIVEN) sN[col * DP_NPITCH + og] = (uint8_t)nib;
-            if (MASK)
+            // the four rows' values of either column as one 64-bit word
+            const uint32_t qlo[2] = {__builtin_amdgcn_perm(x[1], x[0], 0x05040100u), __builtin_amdgcn_perm(x[3], x[2], 0x05040100u)};
+            const uint32_t qhi[2] = {__builtin_amdgcn_perm(x[1], x[0], 0x07060302u), __builtin_amdgcn_perm(x[3], x[2], 0x07060302u)};
 #pragma unroll
-                for (int k = 0; k < 4; ++k) keep[k] |= (((set >> k) & 1u) & cd[k]) << j;
+            for (int h = 0; h < 2; ++h) {
+                const int j = 2 * q + h, col = 8 * i8 + j;
+                const uint32_t set = h ? set2 >> 16 : set2 & 0xFu;
+                const uint32_t nib = GIVEN ? sG[col * DP_NPITCH + og] : nibble_of_pair(set);
+                const uint64_t qq = h ? ((uint64_t)qhi[0] | ((uint64_t)qhi[1] << 32)) : ((uint64_t)qlo[0] | ((uint64_t)qlo[1] << 32));
+                const uint32_t v0 = (uint32_t)(qq >> (16u * (nib & 3u))) & 0xFFFFu;
+                const uint32_t v1 = (uint32_t)(qq >> (16u * (nib >> 2))) & 0xFFFFu;
+                sO[col * DP_OPITCH + og] = v0 | (v1 << 16);
+                if (!GIVEN) sN[col * DP_NPITCH + og] = (uint8_t)nib;
+                if (MASK)
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) keep[k] |= (((set >> k) & 1u) & ((cb[n][k] >> j) & 1u)) << j;
+            }
         }
         if (MASK) {
             int i = i0 + 8 * i8;
