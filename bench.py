@@ -92,13 +92,15 @@ def measure_ceilings(torch, sl, dev):
 
     out["sparse_bf16_tflops"] = rate(sl.SLOPE_CEILING_SPARSE_MFMA, 8000, 6) / 1e12
     out["dense_bf16_tflops"] = rate(sl.SLOPE_CEILING_DENSE_MFMA, 8000, 6) / 1e12
+    out["sparse_bf16_tflops_32x32"] = rate(sl.SLOPE_CEILING_SPARSE_MFMA_32, 8000, 6) / 1e12
+    out["dense_bf16_tflops_32x32"] = rate(sl.SLOPE_CEILING_DENSE_MFMA_32, 8000, 6) / 1e12
     buf[:head].zero_()
     out["sparse_bf16_tflops_zero_operands"] = rate(sl.SLOPE_CEILING_SPARSE_MFMA, 8000, 6) / 1e12
     out["dense_bf16_tflops_zero_operands"] = rate(sl.SLOPE_CEILING_DENSE_MFMA, 8000, 6) / 1e12
     out["hbm_read_gbs"] = rate(sl.SLOPE_CEILING_READ, 1, 10) / 1e9
     out["hbm_copy_gbs"] = rate(sl.SLOPE_CEILING_COPY, 1, 10) / 1e9
-    out["how"] = ("slope_ceiling: register-resident loops of v_smfmac_f32_16x16x64_bf16 / v_mfma_f32_16x16x32_bf16 on "
-                  "Gaussian operands (and on zeros), a read-only stream and a copy over 1 GiB; each about a second")
+    out["how"] = ("slope_ceiling: register-resident loops of v_smfmac_f32_16x16x64_bf16 / v_mfma_f32_16x16x32_bf16 (and of "
+                  "their 32 x 32 forms) on Gaussian operands, the same on zeros, a read-only stream and a copy over 1 GiB")
     del buf
     return out
 

@@ -321,6 +321,8 @@ int64_t slope_tile_order(int64_t tiles_m, int64_t tiles_n, int32_t* tm, int32_t*
  * against ceilings measured in the same run, next to the published peaks.  One launch per call.
  *   kind   SLOPE_CEILING_SPARSE_MFMA  register-resident loop of v_smfmac_f32_16x16x64_bf16
  *          SLOPE_CEILING_DENSE_MFMA   register-resident loop of v_mfma_f32_16x16x32_bf16
+ *          SLOPE_CEILING_SPARSE_MFMA_32, SLOPE_CEILING_DENSE_MFMA_32   the same with the 32 x 32 forms
+ *                                     (v_smfmac_f32_32x32x32_bf16, v_mfma_f32_32x32x16_bf16)
  *          SLOPE_CEILING_READ         read-only stream over buf
  *          SLOPE_CEILING_COPY         copy of the first half of buf onto the second half
  *   buf    device memory, 256-byte aligned, at least slope_ceiling_min_bytes() bytes (the MFMA loops take
@@ -329,7 +331,8 @@ int64_t slope_tile_order(int64_t tiles_m, int64_t tiles_n, int32_t* tm, int32_t*
  *   work   out (host): dense-equivalent flops, or bytes moved, of the launch
  */
 typedef enum {
-    SLOPE_CEILING_SPARSE_MFMA = 0, SLOPE_CEILING_DENSE_MFMA = 1, SLOPE_CEILING_READ = 2, SLOPE_CEILING_COPY = 3
+    SLOPE_CEILING_SPARSE_MFMA = 0, SLOPE_CEILING_DENSE_MFMA = 1, SLOPE_CEILING_READ = 2, SLOPE_CEILING_COPY = 3,
+    SLOPE_CEILING_SPARSE_MFMA_32 = 4, SLOPE_CEILING_DENSE_MFMA_32 = 5
 } slope_ceiling_kind;
 size_t slope_ceiling_min_bytes(void);
 slope_status slope_ceiling(int kind, void* buf, size_t bytes, int iters, double* work, void* stream);

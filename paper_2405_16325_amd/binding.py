@@ -412,7 +412,8 @@ def slope_update_sparse(Wnew_vals: torch.Tensor, meta: torch.Tensor, vals: torch
     return vals, vals_t
 
 
-SLOPE_CEILING_SPARSE_MFMA, SLOPE_CEILING_DENSE_MFMA, SLOPE_CEILING_READ, SLOPE_CEILING_COPY = range(4)
+(SLOPE_CEILING_SPARSE_MFMA, SLOPE_CEILING_DENSE_MFMA, SLOPE_CEILING_READ, SLOPE_CEILING_COPY,
+ SLOPE_CEILING_SPARSE_MFMA_32, SLOPE_CEILING_DENSE_MFMA_32) = range(6)
 
 
 def slope_ceiling(kind: int, buf: torch.Tensor, iters: int = 1) -> float:

@@ -12,6 +12,50 @@ namespace {
 
 constexpr int CEIL_ACC = 16;          // independent accumulators per wavefront
 
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+// the 32 x 32 forms of the same instructions (four independent 16-register accumulators per wavefront):
+// kind 0: v_smfmac_f32_32x32x32_bf16 (2 * 32 * 32 * 32 dense-equivalent flops each)
+// kind 1: v_mfma_f32_32x32x16_bf16   (2 * 32 * 32 * 16 flops each)
+template <int KIND>
+__global__ void __launch_bounds__(256) mfma32_loop_kernel(const u32x4* __restrict__ src, int iters, float* __restrict__ sink) {
+    const int t = threadIdx.x, g = blockIdx.x * 256 + t;
+    AFrag a[4];
+    BFrag b[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        a[i].u = src[(size_t)g * 12 + i];
+        b[i].u[0] = src[(size_t)g * 12 + 4 + 2 * i];
+        b[i].u[1] = src[(size_t)g * 12 + 5 + 2 * i];
+    }
+    const int idx = 0xD8E4;
+    f32x16 acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (KIND == 0) {
+                    acc[i] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a[(i + r) & 3].v, b[i].v, acc[i], idx, 0, 0);
+                } else {
+                    AFrag bb;
+                    bb.u = b[i].u[r];
+                    acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(i + r) & 3].v, bb.v, acc[i], 0, 0, 0);
+                }
+            }
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s += acc[i][e];
+    sink[g] = s;
+}
+
 // kind 0: v_smfmac_f32_16x16x64_bf16 (2 * 16 * 16 * 64 dense-equivalent flops each)
 // kind 1: v_mfma_f32_16x16x32_bf16   (2 * 16 * 16 * 32 flops each)
 template <int KIND>
@@ -99,6 +143,14 @@ slope_status slope_ceiling(int kind, void* buf, size_t bytes, int iters, double*
         case SLOPE_CEILING_DENSE_MFMA:
             mfma_loop_kernel<1><<<dim3(CEIL_BLOCKS), dim3(256), 0, s>>>((const u32x4*)buf, iters, sink);
             *work = (double)(lanes / 64) * iters * CEIL_ACC * 2.0 * 16 * 16 * 32;
+            break;
+        case SLOPE_CEILING_SPARSE_MFMA_32:
+            mfma32_loop_kernel<0><<<dim3(CEIL_BLOCKS), dim3(256), 0, s>>>((const u32x4*)buf, iters, sink);
+            *work = (double)(lanes / 64) * iters * 8 * 2.0 * 32 * 32 * 32;
+            break;
+        case SLOPE_CEILING_DENSE_MFMA_32:
+            mfma32_loop_kernel<1><<<dim3(CEIL_BLOCKS), dim3(256), 0, s>>>((const u32x4*)buf, iters, sink);
+            *work = (double)(lanes / 64) * iters * 8 * 2.0 * 32 * 32 * 16;
             break;
         case SLOPE_CEILING_READ: {
             const size_t sink_bytes = (size_t)CEIL_BLOCKS * 4 * 256 * 4;      // one sum per lane, past the data
