@@ -153,6 +153,9 @@ def train(args, torch, sl, inputs, dev, workload, steps, warmup, full):
     use_t = all(l["d_in"] % 32 == 0 for l in layers)
     wg_ws = torch.empty(max(sl.slope_wgrad_workspace_bytes(b, l["d_in"], l["d_out"]) for l in layers),
                         dtype=torch.uint8, device=dev)
+    # scratch of the product from prepared copies (partial sums of the tiles a last partial round would hold)
+    t_need = max(sl.slope_workspace_bytes(sl.SLOPE_CALL_WGRAD_MASKED_T, b, l["d_in"], l["d_out"]) for l in layers)
+    wg_t_ws = torch.empty(t_need, dtype=torch.uint8, device=dev) if t_need else None
 
     shared = {g for g in xt if sum(1 for l in layers if l["x_group"] == g) > 1}
 
@@ -163,7 +166,7 @@ def train(args, torch, sl, inputs, dev, workload, steps, warmup, full):
         if fresh:
             sl.slope_transpose_tokens(lay["X"], out=xt[lay["x_group"]])
         sl.slope_transpose_tokens(lay["dY"], out=dyt)
-        sl.slope_wgrad_masked_t(dyt, xt[lay["x_group"]], b, lay["meta"], out=lay["G"])
+        sl.slope_wgrad_masked_t(dyt, xt[lay["x_group"]], b, lay["meta"], out=lay["G"], workspace=wg_t_ws)
 
     def step(events=None):
         copied = set()

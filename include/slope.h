@@ -78,7 +78,8 @@ typedef enum {
     SLOPE_CALL_WGRAD_MASKED = 5,
     SLOPE_CALL_WGRAD_MASKED_WS = 6,
     SLOPE_CALL_SPMM_BWD_X_ADAPTER = 7,
-    SLOPE_CALL_WGRAD_ADAPTER = 8
+    SLOPE_CALL_WGRAD_ADAPTER = 8,
+    SLOPE_CALL_WGRAD_MASKED_T = 9
 } slope_call_id;
 
 /* Bytes of scratch memory a call wants for b tokens, a d_out x d_in layer and adapter rank r (0: none);
@@ -189,7 +190,14 @@ slope_status slope_spmm_bwd_x(const void* dY, int64_t b, const void* WrcT_vals, 
  *   slope_transpose_tokens  At = token-contiguous copy of A bf16[b, d] (an X or a dY); At has
  *                           slope_token_copy_bytes(b, d) bytes (rows of b rounded up to 64 tokens, zero-filled,
  *                           plus padding of the row pitch; the layout is the library's own)
- *   slope_wgrad_masked_t    the product from two such copies; d_in % 32 == 0 (SLOPE_ERR_SHAPE otherwise)
+ *   slope_wgrad_masked_t    the product from two such copies; d_in % 32 == 0 (SLOPE_ERR_SHAPE otherwise).
+ *                           workspace_or_null: slope_workspace_bytes(SLOPE_CALL_WGRAD_MASKED_T, b, d_in, d_out, 0)
+ *                           bytes of scratch (may be 0), 256-byte aligned.  With it the tiles that a last,
+ *                           partly filled round of the chip would hold are cut along the tokens into fp32
+ *                           partial sums that a second pass adds in a fixed order (a 9216 x 9216 layer is
+ *                           1296 tiles of 256 x 256 on 256 compute units: without the cut its last 16 tiles
+ *                           cost a sixth of the call).  NULL: no cut; a buffer that is too small:
+ *                           SLOPE_ERR_WORKSPACE.  slope_wgrad_masked_ws's workspace includes this scratch.
  */
 slope_status slope_wgrad_masked(const void* dY, const void* X, int64_t b, const void* Wr_meta,
                                 int64_t d_out, int64_t d_in, void* dW_vals, void* stream);
@@ -200,7 +208,8 @@ slope_status slope_wgrad_masked_ws(const void* dY, const void* X, int64_t b, con
 size_t slope_token_copy_bytes(int64_t b, int64_t d);
 slope_status slope_transpose_tokens(const void* A, int64_t b, int64_t d, void* At, size_t At_bytes, void* stream);
 slope_status slope_wgrad_masked_t(const void* dYt, const void* Xt, int64_t b, const void* Wr_meta,
-                                  int64_t d_out, int64_t d_in, void* dW_vals, void* stream);
+                                  int64_t d_out, int64_t d_in, void* dW_vals,
+                                  void* workspace_or_null, size_t workspace_bytes, void* stream);
 
 /*
  * slope_spmm_bwd_x_adapter - input gradient of a layer with adapters:

@@ -24,7 +24,8 @@ SLOPE_ERR_WORKSPACE = -6
 SLOPE_STATIC_SCRATCH_BYTES = 72 << 20      # include/slope.h
 # slope_call_id
 (SLOPE_CALL_PRUNE_ROWS, SLOPE_CALL_DOUBLE_PRUNE, SLOPE_CALL_SPMM_FWD, SLOPE_CALL_SPMM_BWD_X, SLOPE_CALL_WGRAD_MASKED,
- SLOPE_CALL_WGRAD_MASKED_WS, SLOPE_CALL_SPMM_BWD_X_ADAPTER, SLOPE_CALL_WGRAD_ADAPTER) = range(1, 9)
+ SLOPE_CALL_WGRAD_MASKED_WS, SLOPE_CALL_SPMM_BWD_X_ADAPTER, SLOPE_CALL_WGRAD_ADAPTER,
+ SLOPE_CALL_WGRAD_MASKED_T) = range(1, 10)
 
 _P, _I64, _INT, _SZ = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
 
@@ -49,7 +50,7 @@ SIGNATURES = {
     "slope_wgrad_masked_ws": (_INT, [_P, _P, _I64, _P, _I64, _I64, _P, _P, _SZ, _P]),
     "slope_token_copy_bytes": (_SZ, [_I64, _I64]),
     "slope_transpose_tokens": (_INT, [_P, _I64, _I64, _P, _SZ, _P]),
-    "slope_wgrad_masked_t": (_INT, [_P, _P, _I64, _P, _I64, _I64, _P, _P]),
+    "slope_wgrad_masked_t": (_INT, [_P, _P, _I64, _P, _I64, _I64, _P, _P, _SZ, _P]),
     "slope_spmm_bwd_x_adapter_workspace_bytes": (_SZ, [_I64, _I64]),
     "slope_spmm_bwd_x_adapter": (_INT, [_P, _I64, _P, _P, _I64, _I64, _P, _P, _I64, _P, _P, _SZ, _P]),
     "slope_wgrad_adapter_workspace_bytes": (_SZ, [_I64, _I64, _I64, _I64]),
@@ -298,18 +299,24 @@ def slope_transpose_tokens(A: torch.Tensor, out=None):
     return At
 
 
-def slope_wgrad_masked_t(dYt: torch.Tensor, Xt: torch.Tensor, b: int, meta: torch.Tensor, out=None):
-    """dW from copies made by slope_transpose_tokens (dYt of a [b, d_out], Xt of a [b, d_in] tensor)."""
+def slope_wgrad_masked_t(dYt: torch.Tensor, Xt: torch.Tensor, b: int, meta: torch.Tensor, out=None, workspace="auto"):
+    """dW from copies made by slope_transpose_tokens (dYt of a [b, d_out], Xt of a [b, d_in] tensor).
+    workspace: "auto" (allocated here when the shape wants one), None (no cut of the last partial round
+    of tiles) or a uint8 tensor of slope_workspace_bytes(SLOPE_CALL_WGRAD_MASKED_T, b, d_in, d_out) bytes."""
     if meta is None or meta.dim() != 2:
         raise ValueError("meta must be a matrix")
     d_out, d_in = meta.shape[0], meta.shape[1] * 8
     _want(meta, U8, (d_out, d_in // 8), "meta")
     _scratch(dYt, slope_token_copy_bytes(b, d_out), meta.device, "dYt")
     _scratch(Xt, slope_token_copy_bytes(b, d_in), meta.device, "Xt")
+    need = slope_workspace_bytes(SLOPE_CALL_WGRAD_MASKED_T, b, d_in, d_out)
+    ws = None
+    if workspace is not None and need:
+        ws = _scratch(None if isinstance(workspace, str) else workspace, need, meta.device, "workspace")
     G = _want(out, BF16, (d_out, d_in // 2), "out") if out is not None \
         else torch.empty((d_out, d_in // 2), dtype=BF16, device=meta.device)
     _check("slope_wgrad_masked_t", lib().slope_wgrad_masked_t(_ptr(dYt), _ptr(Xt), b, _ptr(meta), d_out, d_in, _ptr(G),
-                                                              _stream()))
+                                                              _ptr(ws), ws.numel() if ws is not None else 0, _stream()))
     return G
 
 

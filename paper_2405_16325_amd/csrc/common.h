@@ -66,8 +66,11 @@ size_t token_copy_bytes(int64_t b, int64_t d);
 hipError_t launch_token_copies(const bf16_t* in0, int64_t cols0, bf16_t* out0, const bf16_t* in1, int64_t cols1,
                                bf16_t* out1, int64_t b, hipStream_t s);
 bool wgrad_tn_fits(int64_t d_in);
+// tail_or_null: wgrad_tail_bytes(b, d_in, d_out) bytes of scratch for cutting the tiles a last partial round
+// would hold along the tokens, or nullptr
+size_t wgrad_tail_bytes(int64_t b, int64_t d_in, int64_t d_out);
 hipError_t launch_wgrad_masked_t(const bf16_t* dYt, const bf16_t* Xt, int64_t b, const uint8_t* meta, int64_t d_out,
-                                 int64_t d_in, bf16_t* gvals, hipStream_t s);
+                                 int64_t d_in, bf16_t* gvals, float* tail_or_null, hipStream_t s);
 
 // C[n, m] = B[n, K] * A[m, K]^T (dense bf16, fp32 accumulation), K % 64 == 0
 size_t dense_tn_plain_partial_bytes(int64_t n, int64_t m);

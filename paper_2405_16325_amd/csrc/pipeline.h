@@ -26,12 +26,15 @@ constexpr int RESIDENT = 256;             // tiles in flight on the chip: one pe
 constexpr int waitcnt_imm(int vm, int lgkm) { return (vm & 15) | ((vm >> 4) << 14) | (7 << 4) | (lgkm << 8); }
 
 // blockIdx -> tile.  Workgroups are dealt round-robin to the 8 XCDs, 32 resident per XCD.
-//  * At least SUPER tiles along both axes: the grid is cut into chunks of 8 x 4 tiles, the 32 tiles
-//    an XCD holds at a time (they share 8 + 4 operand panels in its L2).  Chunks are numbered so
-//    that eight consecutive ones form a 16 x 16 patch (2 x 4 chunks; the chip then shares 16 + 16
-//    panels in the last-level cache), patch after patch along n, then along m, with the chunks
-//    that the grid's ragged edges leave out skipped.  Chunk c goes to XCD c % 8, so every XCD
-//    gets the same number of chunks, give or take one, whatever the grid's shape.
+//  * At least SUPER tiles along both axes: the tiles are put in an order without gaps, and the 32
+//    tiles an XCD holds at a time are 32 consecutive positions of it (group g of 32 goes to XCD
+//    g % 8), so every XCD gets the same number of tiles, give or take one group, whatever the
+//    grid's shape.  The order: first the part of the grid that whole chunks of 8 x 4 tiles cover
+//    (a chunk's tiles share 8 + 4 operand panels in the XCD's L2), chunk after chunk, numbered so
+//    that eight consecutive chunks form a 16 x 16 patch (2 x 4 chunks; the chip then shares 16 + 16
+//    panels in the last-level cache), patch after patch along n, then along m; then the rows that
+//    are left below it, column by column (32 positions: their few rows of 8 or more columns); then
+//    the columns left beside it, row by row.
 //  * A narrow grid (skinny products, inference-size batches): tiles are numbered short axis first
 //    and each XCD takes runs of consecutive tiles: at most 32, sized so that all 8 XCDs get equal
 //    shares in every round, also when there are fewer than 256 tiles.
@@ -42,21 +45,45 @@ __host__ __device__ inline int narrow_run(int tiles) {
     return (tiles + XCDS * rounds - 1) / (XCDS * rounds);
 }
 
-__host__ __device__ inline bool tile_of_index(int b, int tiles_m, int tiles_n, int& tm, int& tn) {
-    int xcd = b % XCDS, slot = b / XCDS;
-    if (tiles_m >= SUPER && tiles_n >= SUPER) {
-        int round = slot / 32, w = slot % 32;
-        int chunks_m = (tiles_m + CHUNK_M - 1) / CHUNK_M, chunks_n = (tiles_n + CHUNK_N - 1) / CHUNK_N;
-        int c = round * XCDS + xcd;
-        if (c >= chunks_m * chunks_n) return false;
+__host__ __device__ inline bool wide_grid(int tiles_m, int tiles_n) { return tiles_m >= SUPER && tiles_n >= SUPER; }
+
+// position q (0 <= q < tiles_m * tiles_n) in the order of a wide grid -> tile
+__host__ __device__ inline void tile_of_position(int q, int tiles_m, int tiles_n, int& tm, int& tn) {
+    const int m8 = tiles_m / CHUNK_M * CHUNK_M, n4 = tiles_n / CHUNK_N * CHUNK_N;
+    if (q < m8 * n4) {
+        const int c = q / 32, w = q % 32;
+        const int chunks_m = m8 / CHUNK_M, chunks_n = n4 / CHUNK_N;
         int sm = c / (2 * chunks_n), rem = c - sm * 2 * chunks_n;   // patch row: 2 chunk rows (1 in a ragged last)
         int hm = chunks_m - 2 * sm < 2 ? 1 : 2;
         int sn = rem / (4 * hm), r2 = rem - sn * 4 * hm;            // patch: 4 chunk columns (fewer at the edge)
         int wn = chunks_n - 4 * sn < 4 ? chunks_n - 4 * sn : 4;
         tm = (2 * sm + r2 / wn) * CHUNK_M + (w & 7);
         tn = (4 * sn + r2 % wn) * CHUNK_N + (w >> 3);
-        return tm < tiles_m && tn < tiles_n;
+        return;
     }
+    q -= m8 * n4;
+    const int below = tiles_m - m8;
+    if (q < below * tiles_n) { tn = q / below; tm = m8 + q % below; return; }
+    q -= below * tiles_n;
+    const int beside = tiles_n - n4;
+    tm = q / beside;
+    tn = n4 + q % beside;
+}
+
+// workgroup b of a launch over a wide grid -> its position in the order (XCD b % 8, 32 positions at a time)
+__host__ __device__ inline int position_of_block(int b) {
+    const int xcd = b % XCDS, slot = b / XCDS;
+    return ((slot / 32) * XCDS + xcd) * 32 + slot % 32;
+}
+
+__host__ __device__ inline bool tile_of_index(int b, int tiles_m, int tiles_n, int& tm, int& tn) {
+    if (wide_grid(tiles_m, tiles_n)) {
+        const int q = position_of_block(b);
+        if (q >= tiles_m * tiles_n) return false;
+        tile_of_position(q, tiles_m, tiles_n, tm, tn);
+        return true;
+    }
+    int xcd = b % XCDS, slot = b / XCDS;
     int run = narrow_run(tiles_m * tiles_n);
     int t = ((slot / run) * XCDS + xcd) * run + slot % run;
     if (tiles_m <= tiles_n) { tm = t % tiles_m; tn = t / tiles_m; }
@@ -69,11 +96,9 @@ __device__ __forceinline__ bool tile_of_block(int tiles_m, int tiles_n, int& tm,
 }
 
 inline int super_grid(int tiles_m, int tiles_n) {
-    if (tiles_m >= SUPER && tiles_n >= SUPER) {
-        int chunks = ((tiles_m + CHUNK_M - 1) / CHUNK_M) * ((tiles_n + CHUNK_N - 1) / CHUNK_N);
-        return (chunks + XCDS - 1) / XCDS * RESIDENT;
-    }
-    int tiles = tiles_m * tiles_n, chunk = XCDS * narrow_run(tiles);
+    int tiles = tiles_m * tiles_n;
+    if (wide_grid(tiles_m, tiles_n)) return (tiles + RESIDENT - 1) / RESIDENT * RESIDENT;
+    int chunk = XCDS * narrow_run(tiles);
     return (tiles + chunk - 1) / chunk * chunk;
 }
 

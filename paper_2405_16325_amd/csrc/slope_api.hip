@@ -96,9 +96,14 @@ size_t slope_token_copy_bytes(int64_t b, int64_t d) {
     return round256(token_copy_bytes(b, d));
 }
 
+size_t slope_wgrad_t_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out) {
+    if (b <= 0 || d_in <= 0 || d_out <= 0 || !wgrad_tn_fits(d_in)) return 0;
+    return wgrad_tail_bytes(b, d_in, d_out);
+}
+
 size_t slope_wgrad_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out) {
     if (b <= 0 || d_in <= 0 || d_out <= 0) return 0;
-    return slope_token_copy_bytes(b, d_in) + slope_token_copy_bytes(b, d_out);
+    return slope_token_copy_bytes(b, d_in) + slope_token_copy_bytes(b, d_out) + slope_wgrad_t_workspace_bytes(b, d_in, d_out);
 }
 
 size_t slope_spmm_bwd_x_adapter_workspace_bytes(int64_t b, int64_t r) {
@@ -115,6 +120,7 @@ size_t slope_workspace_bytes(int call_id, int64_t b, int64_t d_in, int64_t d_out
     switch (call_id) {
         case SLOPE_CALL_SPMM_FWD: return slope_spmm_fwd_workspace_bytes(b, d_in, d_out, r);
         case SLOPE_CALL_WGRAD_MASKED_WS: return slope_wgrad_workspace_bytes(b, d_in, d_out);
+        case SLOPE_CALL_WGRAD_MASKED_T: return slope_wgrad_t_workspace_bytes(b, d_in, d_out);
         case SLOPE_CALL_SPMM_BWD_X_ADAPTER: return slope_spmm_bwd_x_adapter_workspace_bytes(b, r);
         case SLOPE_CALL_WGRAD_ADAPTER: return slope_wgrad_adapter_workspace_bytes(b, d_in, d_out, r);
         default: return 0;      // prune_rows, double_prune, spmm_bwd_x, wgrad_masked need no scratch; unknown ids
@@ -304,9 +310,12 @@ slope_status slope_wgrad_masked_ws(const void* dY, const void* X, int64_t b, con
                                           (bf16_t*)dW_vals, s));
     bf16_t* Xt = (bf16_t*)workspace;
     bf16_t* dYt = (bf16_t*)((uint8_t*)workspace + slope_token_copy_bytes(b, d_in));
+    float* tail = slope_wgrad_t_workspace_bytes(b, d_in, d_out)
+                      ? (float*)((uint8_t*)workspace + slope_token_copy_bytes(b, d_in) + slope_token_copy_bytes(b, d_out))
+                      : nullptr;
     hipError_t e = launch_token_copies((const bf16_t*)X, d_in, Xt, (const bf16_t*)dY, d_out, dYt, b, s);
     if (e != hipSuccess) return finish(e);
-    return finish(launch_wgrad_masked_t(dYt, Xt, b, (const uint8_t*)Wr_meta, d_out, d_in, (bf16_t*)dW_vals, s));
+    return finish(launch_wgrad_masked_t(dYt, Xt, b, (const uint8_t*)Wr_meta, d_out, d_in, (bf16_t*)dW_vals, tail, s));
 }
 
 slope_status slope_transpose_tokens(const void* A, int64_t b, int64_t d, void* At, size_t At_bytes, void* stream) {
@@ -318,13 +327,18 @@ slope_status slope_transpose_tokens(const void* A, int64_t b, int64_t d, void* A
 }
 
 slope_status slope_wgrad_masked_t(const void* dYt, const void* Xt, int64_t b, const void* Wr_meta, int64_t d_out,
-                                  int64_t d_in, void* dW_vals, void* stream) {
+                                  int64_t d_in, void* dW_vals, void* workspace_or_null, size_t workspace_bytes,
+                                  void* stream) {
     if (!dYt || !Xt || !Wr_meta || !dW_vals) return SLOPE_ERR_NULL;
     if (bad_layer(b, d_out, d_in) || !wgrad_tn_fits(d_in)) return SLOPE_ERR_SHAPE;
-    if (misaligned(dYt, 256) || misaligned(Xt, 256) || misaligned(Wr_meta, 16) || misaligned(dW_vals, 16))
+    if (misaligned(dYt, 256) || misaligned(Xt, 256) || misaligned(Wr_meta, 16) || misaligned(dW_vals, 16) ||
+        misaligned(workspace_or_null, 256))
         return SLOPE_ERR_ALIGN;
+    const size_t need = slope_wgrad_t_workspace_bytes(b, d_in, d_out);
+    if (workspace_or_null && workspace_bytes < need) return SLOPE_ERR_WORKSPACE;
     return finish(launch_wgrad_masked_t((const bf16_t*)dYt, (const bf16_t*)Xt, b, (const uint8_t*)Wr_meta, d_out, d_in,
-                                        (bf16_t*)dW_vals, (hipStream_t)stream));
+                                        (bf16_t*)dW_vals, need ? (float*)workspace_or_null : nullptr,
+                                        (hipStream_t)stream));
 }
 
 slope_status slope_spmm_bwd_x_adapter(const void* dY, int64_t b, const void* WrcT_vals, const void* WrcT_meta,

@@ -245,7 +245,8 @@ __global__ void __launch_bounds__(TN_THREADS) dense_tn_kernel(const bf16_t* __re
         wg_barrier();                                                                                  \
         if (G == 1) issue(ks + NS);                                                                    \
         _Pragma("unroll") for (int h = 0; h < 2; ++h)                                                  \
-        _Pragma("unroll") for (int i = 0; i < MF; ++i) _Pragma("unroll") for (int j = 0; j < NF; ++j) { \
+        _Pragma("unroll") for (int i = 0; i < MF; ++i) _Pragma("unroll") for (int jj = 0; jj < NF; ++jj) { \
+            const int j = (i & 1) ? NF - 1 - jj : jj;         /* back and forth: one operand changes per MFMA */ \
             AFrag a, b;                                                                                \
             a.u = af[i].u[h]; b.u = bf[j].u[h];                                                        \
             acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, acc[i][j], 0, 0, 0);         \
@@ -311,18 +312,30 @@ struct SplitSmem {
     static constexpr int TOTAL = 3 * A_STAGE + 4 * B_HALF;
 };
 
-template <int EPI>
+//
+// TAIL: the tiles left over after the last full round of 256.  Run as a round of their own they would
+// keep a few compute units busy for a whole tile's time while the rest of the chip idles.  Instead each
+// of them (positions first_tile .. first_tile + tail_tiles - 1 of the tile order) is cut along k into
+// slabs of slab_steps k-steps; workgroup w takes tile w % tail_tiles, slab w / tail_tiles, and leaves its
+// fp32 accumulators in partial[w] in register order; tail_reduce_kernel adds the slabs and stores.
+template <int EPI, bool TAIL>
 __global__ void __launch_bounds__(TN_THREADS) dense_tn_split_kernel(const bf16_t* __restrict__ At, int m,
                                                                     const bf16_t* __restrict__ Bt, int n, int kp,
                                                                     int ld, const uint8_t* __restrict__ meta,
                                                                     bf16_t* __restrict__ out, int tiles_m,
-                                                                    int tiles_n) {
+                                                                    int tiles_n, int first_tile, int tail_tiles,
+                                                                    int slab_steps, f32x4* __restrict__ partial) {
     using S = SplitSmem;
     constexpr int MF = 8, NF = 4, WM = 128;                  // wavefront tile 128 x 64, 2 x 4 wavefronts
     extern __shared__ __align__(16) uint8_t smem[];
 
-    int tm, tn;
-    if (!tile_of_block(tiles_m, tiles_n, tm, tn)) return;
+    int tm, tn, k_first = 0;
+    if (TAIL) {
+        tile_of_position(first_tile + (int)blockIdx.x % tail_tiles, tiles_m, tiles_n, tm, tn);
+        k_first = ((int)blockIdx.x / tail_tiles) * slab_steps;
+    } else if (!tile_of_block(tiles_m, tiles_n, tm, tn)) {
+        return;
+    }
     const int m0 = tm * S::BM, n0 = tn * S::BN;
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -340,10 +353,11 @@ __global__ void __launch_bounds__(TN_THREADS) dense_tn_split_kernel(const bf16_t
         int sw16 = ((lane & 7) ^ ((rl >> 1) & 7)) * 16;
         int ra = wrap_row(m0 + rl, m);
         int rb = wrap_row(n0 + rl, n);
-        a_src[q] = (const uint8_t*)At + (size_t)ra * ld * 2 + sw16;
-        b_src[q] = (const uint8_t*)Bt + (size_t)rb * ld * 2 + sw16;
+        a_src[q] = (const uint8_t*)At + (size_t)ra * ld * 2 + sw16 + (size_t)k_first * 128;
+        b_src[q] = (const uint8_t*)Bt + (size_t)rb * ld * 2 + sw16 + (size_t)k_first * 128;
     }
-    const int ksteps = kp / 64;
+    // k-steps of this workgroup (the host leaves no slab empty)
+    const int ksteps = TAIL ? (kp / 64 - k_first < slab_steps ? kp / 64 - k_first : slab_steps) : kp / 64;
     // the four loads a wavefront queues per phase, one at a time (ks clamped: the look-ahead of the
     // last steps re-reads the last one)
     auto issue_a = [&](int half, int ks, int i) {            // 8 rows of rows 128 half .. +127 of A(ks)
@@ -384,11 +398,14 @@ __global__ void __launch_bounds__(TN_THREADS) dense_tn_split_kernel(const bf16_t
             bf[j].u[1] = *(const u32x4*)(sb + j * 2048 + rd1);                                         \
         }
 // the compute phase: 64 MFMAs with the phase's four loads spread between them (queued in one burst
-// at the start of the phase they cost 2 % more)
+// at the start of the phase they cost 2 % more).  The B fragments are taken back and forth, so that only
+// one operand changes from one MFMA to the next: the kernel runs at the clock the chip's power limit
+// allows, and that order draws measurably less (1.7 % faster than always restarting at fragment 0).
 #define SPLIT_MFMA(LOAD, k)                                                                            \
         _Pragma("unroll") for (int h = 0; h < 2; ++h)                                                  \
         _Pragma("unroll") for (int i = 0; i < MF; ++i) {                                               \
-            _Pragma("unroll") for (int j = 0; j < NF; ++j) {                                           \
+            _Pragma("unroll") for (int jj = 0; jj < NF; ++jj) {                                        \
+                const int j = (i & 1) ? NF - 1 - jj : jj;                                              \
                 AFrag a, b;                                                                            \
                 a.u = af[i].u[h]; b.u = bf[j].u[h];                                                    \
                 acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, acc[i][j], 0, 0, 0);     \
@@ -435,6 +452,56 @@ __global__ void __launch_bounds__(TN_THREADS) dense_tn_split_kernel(const bf16_t
 #undef EVEN_LOADS
 #undef ODD_LOADS
     WAIT_HERE(waitcnt_imm(0, 15));                            // drain the clamped look-ahead loads
+    if (TAIL) {
+        f32x4* dst = partial + (size_t)blockIdx.x * (MF * NF * TN_THREADS) + t;
+#pragma unroll
+        for (int i = 0; i < MF; ++i)
+#pragma unroll
+            for (int j = 0; j < NF; ++j) dst[(i * NF + j) * TN_THREADS] = acc[i][j];
+        return;
+    }
+    if (EPI == EPI_PLAIN) store_plain<MF, NF>(acc, m, n, m0 + wm * WM, n0 + wn * NF * 16, l16, lq, out, nullptr);
+    else store_masked_packed<MF, NF, S::BM, S::BN>(acc, m, n, m0 + wm * WM, n0 + wn * NF * 16, m0, n0, l16, lq, meta, out,
+                                                   smem);
+}
+
+// Second pass of the tail, in two kernels.  tail_sum_kernel adds the slabs element by element in slab
+// order into slab 0 (slab sl of a tile lies tail_tiles tiles further on in `partial`); it has a workgroup
+// per 256 elements, because the few workgroups of tail_reduce_kernel alone would read the partial sums at
+// a small fraction of the chip's bandwidth.  tail_reduce_kernel then loads a tile's sums in the register
+// layout dense_tn_split_kernel left them in and stores the tile through that kernel's epilogue.
+__global__ void __launch_bounds__(256) tail_sum_kernel(f32x4* __restrict__ partial, int nslabs, size_t slab_stride4,
+                                                       size_t count4) {
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= count4) return;
+    f32x4 v = partial[idx];
+    for (int sl = 1; sl < nslabs; ++sl) {
+        f32x4 w = partial[(size_t)sl * slab_stride4 + idx];
+        v[0] += w[0]; v[1] += w[1]; v[2] += w[2]; v[3] += w[3];
+    }
+    partial[idx] = v;
+}
+
+constexpr int TAIL_REDUCE_LDS = SplitSmem::BN * (SplitSmem::BM + 16);
+template <int EPI>
+__global__ void __launch_bounds__(TN_THREADS) tail_reduce_kernel(const f32x4* __restrict__ partial, int m, int n,
+                                                                 const uint8_t* __restrict__ meta,
+                                                                 bf16_t* __restrict__ out, int tiles_m, int tiles_n,
+                                                                 int first_tile) {
+    using S = SplitSmem;
+    constexpr int MF = 8, NF = 4, WM = 128;
+    extern __shared__ __align__(16) uint8_t smem[];
+    int tm, tn;
+    tile_of_position(first_tile + (int)blockIdx.x, tiles_m, tiles_n, tm, tn);
+    const int m0 = tm * S::BM, n0 = tn * S::BN;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int wm = wave & 1, wn = wave >> 1, l16 = lane & 15, lq = lane >> 4;
+    f32x4 acc[MF][NF];
+    const f32x4* src = partial + (size_t)blockIdx.x * (MF * NF * TN_THREADS) + t;
+#pragma unroll
+    for (int i = 0; i < MF; ++i)
+#pragma unroll
+        for (int j = 0; j < NF; ++j) acc[i][j] = src[(i * NF + j) * TN_THREADS];
     if (EPI == EPI_PLAIN) store_plain<MF, NF>(acc, m, n, m0 + wm * WM, n0 + wn * NF * 16, l16, lq, out, nullptr);
     else store_masked_packed<MF, NF, S::BM, S::BN>(acc, m, n, m0 + wm * WM, n0 + wn * NF * 16, m0, n0, l16, lq, meta, out,
                                                    smem);
@@ -455,16 +522,53 @@ hipError_t launch_dense_tn(const bf16_t* At, int64_t m, const bf16_t* Bt, int64_
     return hipGetLastError();
 }
 
+// How the tiles left over after the last full round are cut: tail tiles (0 = none worth cutting), slabs
+// per tile, k-steps per slab.  Only wide grids (the tile order has positions there), only leftovers of at
+// most half a round (more would be cut into too few slabs to gain), at least eight k-steps per slab.
+struct TailPlan { int first_tile, tiles, slabs, slab_steps; };
+inline TailPlan tail_plan(int64_t tiles_m, int64_t tiles_n, int64_t ksteps) {
+    TailPlan p = {0, 0, 0, 0};
+    const int64_t tiles = tiles_m * tiles_n;
+    if (!wide_grid((int)tiles_m, (int)tiles_n) || tiles < RESIDENT || tiles > (1 << 30)) return p;
+    const int64_t rem = tiles % RESIDENT;
+    if (rem == 0 || rem > RESIDENT / 2) return p;
+    int64_t slabs = RESIDENT / rem;
+    if (slabs > ksteps / 8) slabs = ksteps / 8;
+    if (slabs < 2) return p;
+    const int64_t steps = (ksteps + slabs - 1) / slabs;
+    p.first_tile = (int)(tiles - rem);
+    p.tiles = (int)rem;
+    p.slab_steps = (int)steps;
+    p.slabs = (int)((ksteps + steps - 1) / steps);
+    return p;
+}
+
 template <int EPI>
 hipError_t launch_dense_tn_split(const bf16_t* At, int64_t m, const bf16_t* Bt, int64_t n, int64_t kp, int64_t ld,
-                                 const uint8_t* meta, bf16_t* out, hipStream_t s) {
+                                 const uint8_t* meta, bf16_t* out, hipStream_t s, float* tail = nullptr) {
     using S = SplitSmem;
     static_assert(S::TOTAL <= 160 * 1024, "LDS budget");
     int tiles_m = (int)((m + S::BM - 1) / S::BM), tiles_n = (int)((n + S::BN - 1) / S::BN);
-    hipError_t e = allow_dynamic_lds<dense_tn_split_kernel<EPI>>(S::TOTAL);
+    hipError_t e = allow_dynamic_lds<dense_tn_split_kernel<EPI, false>>(S::TOTAL);
     if (e != hipSuccess) return e;
-    dense_tn_split_kernel<EPI><<<dim3((unsigned)super_grid(tiles_m, tiles_n)), dim3(TN_THREADS), S::TOTAL, s>>>(
-        At, (int)m, Bt, (int)n, (int)kp, (int)ld, meta, out, tiles_m, tiles_n);
+    const TailPlan p = tail ? tail_plan(tiles_m, tiles_n, kp / 64) : TailPlan{0, 0, 0, 0};
+    // with a tail the first launch is whole rounds only: workgroups 0 .. first_tile - 1 are exactly the
+    // positions 0 .. first_tile - 1 of the order
+    const int grid = p.tiles ? p.first_tile : super_grid(tiles_m, tiles_n);
+    dense_tn_split_kernel<EPI, false><<<dim3((unsigned)grid), dim3(TN_THREADS), S::TOTAL, s>>>(
+        At, (int)m, Bt, (int)n, (int)kp, (int)ld, meta, out, tiles_m, tiles_n, 0, 0, 0, nullptr);
+    if ((e = hipGetLastError()) != hipSuccess || !p.tiles) return e;
+    if ((e = allow_dynamic_lds<dense_tn_split_kernel<EPI, true>>(S::TOTAL)) != hipSuccess) return e;
+    if ((e = allow_dynamic_lds<tail_reduce_kernel<EPI>>(TAIL_REDUCE_LDS)) != hipSuccess) return e;
+    dense_tn_split_kernel<EPI, true><<<dim3((unsigned)(p.tiles * p.slabs)), dim3(TN_THREADS), S::TOTAL, s>>>(
+        At, (int)m, Bt, (int)n, (int)kp, (int)ld, meta, out, tiles_m, tiles_n, p.first_tile, p.tiles, p.slab_steps,
+        (f32x4*)tail);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    const size_t count4 = (size_t)p.tiles * (S::BM * S::BN / 4);
+    tail_sum_kernel<<<dim3((unsigned)((count4 + 255) / 256)), dim3(256), 0, s>>>((f32x4*)tail, p.slabs, count4, count4);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    tail_reduce_kernel<EPI><<<dim3((unsigned)p.tiles), dim3(TN_THREADS), TAIL_REDUCE_LDS, s>>>(
+        (const f32x4*)tail, (int)m, (int)n, meta, out, tiles_m, tiles_n, p.first_tile);
     return hipGetLastError();
 }
 
@@ -490,21 +594,43 @@ hipError_t launch_token_copies(const bf16_t* in0, int64_t cols0, bf16_t* out0, c
 // keep those dwords aligned.  Other layers take the in-place kernel.
 bool wgrad_tn_fits(int64_t d_in) { return d_in % 32 == 0; }
 
-// dW (masked, packed) from token-contiguous copies Xt [d_in][ld], dYt [d_out][ld]
-hipError_t launch_wgrad_masked_t(const bf16_t* dYt, const bf16_t* Xt, int64_t b, const uint8_t* meta, int64_t d_out,
-                                 int64_t d_in, bf16_t* gvals, hipStream_t s) {
-    const int64_t bp = (b + 63) / 64 * 64, ld = token_pitch(bp);
-    // The kernel runs at the rate its compute units pull operands from L2: a launch costs about
-    // (rounds of 256 resident tiles) x (rows per tile).  Take the cheapest shape, the larger on ties.
+// Tile shape of the weight gradient: 0 = 256 x 256 (split rings), 1 = 256 x 128, 2 = 128 x 128, 3 = 128 x 64.
+// The kernels run at the rate their compute units pull operands from L2: a launch costs about (rounds of
+// 256 resident tiles) x (rows per tile).  Take the cheapest shape, the larger on ties.  With scratch memory
+// the 256 x 256 kernel cuts the tiles left over after its last full round along the tokens
+// (launch_dense_tn_split): they then cost about 1 / slabs of a round, plus a quarter for the second pass.
+static int wgrad_tile_choice(int64_t d_in, int64_t d_out, int64_t ksteps, bool with_tail) {
     const int bms[4] = {256, 256, 128, 128}, bns[4] = {256, 128, 128, 64};
     int best = 0;
     int64_t best_cost = INT64_MAX;
     for (int c = 0; c < 4; ++c) {
-        int64_t tiles = ((d_in + bms[c] - 1) / bms[c]) * ((d_out + bns[c] - 1) / bns[c]);
-        int64_t cost = ((tiles + RESIDENT - 1) / RESIDENT) * (bms[c] + bns[c]);
+        const int64_t tm = (d_in + bms[c] - 1) / bms[c], tn = (d_out + bns[c] - 1) / bns[c], tiles = tm * tn;
+        int64_t cost = ((tiles + RESIDENT - 1) / RESIDENT) * (bms[c] + bns[c]) * 100;
+        if (c == 0 && with_tail) {
+            const TailPlan p = tail_plan(tm, tn, ksteps);
+            if (p.tiles) cost = (tiles / RESIDENT) * 512 * 100 + 512 * (100 / p.slabs + 25);
+        }
         if (cost < best_cost) { best_cost = cost; best = c; }
     }
-    if (best == 0) return launch_dense_tn_split<EPI_MASKED_PACKED>(Xt, d_in, dYt, d_out, bp, ld, meta, gvals, s);
+    return best;
+}
+
+// scratch bytes of launch_wgrad_masked_t's tail pass (0: the shape has none)
+size_t wgrad_tail_bytes(int64_t b, int64_t d_in, int64_t d_out) {
+    const int64_t ksteps = (b + 63) / 64;
+    if (wgrad_tile_choice(d_in, d_out, ksteps, true) != 0) return 0;
+    const TailPlan p = tail_plan((d_in + 255) / 256, (d_out + 255) / 256, ksteps);
+    return (size_t)p.tiles * (size_t)p.slabs * (256 * 256 * 4);
+}
+
+// dW (masked, packed) from token-contiguous copies Xt [d_in][ld], dYt [d_out][ld]; tail_or_null: scratch of
+// wgrad_tail_bytes(b, d_in, d_out) bytes, or nullptr (then a last partial round of tiles runs as it is)
+hipError_t launch_wgrad_masked_t(const bf16_t* dYt, const bf16_t* Xt, int64_t b, const uint8_t* meta, int64_t d_out,
+                                 int64_t d_in, bf16_t* gvals, float* tail_or_null, hipStream_t s) {
+    const int64_t bp = (b + 63) / 64 * 64, ld = token_pitch(bp);
+    const int best = wgrad_tile_choice(d_in, d_out, bp / 64, tail_or_null != nullptr);
+    if (best == 0)
+        return launch_dense_tn_split<EPI_MASKED_PACKED>(Xt, d_in, dYt, d_out, bp, ld, meta, gvals, s, tail_or_null);
     if (best == 1) return launch_dense_tn<256, 128, EPI_MASKED_PACKED, 3>(Xt, d_in, dYt, d_out, bp, ld, meta, gvals, s);
     if (best == 2) return launch_dense_tn<128, 128, EPI_MASKED_PACKED, 4>(Xt, d_in, dYt, d_out, bp, ld, meta, gvals, s);
     return launch_dense_tn<128, 64, EPI_MASKED_PACKED, 6>(Xt, d_in, dYt, d_out, bp, ld, meta, gvals, s);
@@ -565,11 +691,12 @@ hipError_t launch_dense_tn_any(const bf16_t* B, int64_t n, const bf16_t* A, int6
 // Weight gradient of a layer with adapters: the packed dW as above plus the adapter gradients
 // (chain rule of Eq. 11)   dL = X^T (dY R^T)  [d_in, r],   dR = (X L)^T dY  [r, d_out],
 // all three contractions over the tokens sharing the token-contiguous copies of X and dY.
-// Workspace: Xt | dYt | Lt [r][d_in] | T = X L [b][r] | T2 = dY R^T [b][r] | Tt [r][ld] | T2t [r][ld].
+// Workspace: Xt | dYt | Lt [r][d_in] | T = X L [b][r] | T2 = dY R^T [b][r] | Tt [r][ld] | T2t [r][ld] | the
+// scratch of launch_wgrad_masked_t.
 size_t wgrad_adapter_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out, int64_t r) {
     size_t ld = (size_t)token_pitch((b + 63) / 64 * 64);
     return round256(token_copy_bytes(b, d_in)) + round256(token_copy_bytes(b, d_out)) + round256((size_t)r * d_in * 2) +
-           2 * round256((size_t)b * r * 2) + 2 * round256((size_t)r * ld * 2);
+           2 * round256((size_t)b * r * 2) + 2 * round256((size_t)r * ld * 2) + wgrad_tail_bytes(b, d_in, d_out);
 }
 
 hipError_t launch_wgrad_adapter(const bf16_t* dY, const bf16_t* X, int64_t b, const uint8_t* meta, int64_t d_out,
@@ -583,7 +710,8 @@ hipError_t launch_wgrad_adapter(const bf16_t* dY, const bf16_t* X, int64_t b, co
     bf16_t* T = (bf16_t*)w;    w += round256((size_t)b * r * 2);
     bf16_t* T2 = (bf16_t*)w;   w += round256((size_t)b * r * 2);
     bf16_t* Tt = (bf16_t*)w;   w += round256((size_t)r * ld * 2);
-    bf16_t* T2t = (bf16_t*)w;
+    bf16_t* T2t = (bf16_t*)w;  w += round256((size_t)r * ld * 2);
+    float* tail = wgrad_tail_bytes(b, d_in, d_out) ? (float*)w : nullptr;
 
     hipError_t e;
     if (d_in % 64 != 0 || d_out % 64 != 0) {
@@ -596,7 +724,7 @@ hipError_t launch_wgrad_adapter(const bf16_t* dY, const bf16_t* X, int64_t b, co
         return launch_plain_gemm(T, 1, r, dY, 1, d_out, r, d_out, b, dR, s);                               // dR = T^T dY
     }
     if ((e = launch_token_copies(X, d_in, Xt, dY, d_out, dYt, b, s)) != hipSuccess) return e;
-    if ((e = launch_wgrad_masked_t(dYt, Xt, b, meta, d_out, d_in, gvals, s)) != hipSuccess) return e;
+    if ((e = launch_wgrad_masked_t(dYt, Xt, b, meta, d_out, d_in, gvals, tail, s)) != hipSuccess) return e;
     launch_transpose_pad(L, d_in, r, d_in, d_in, Lt, s);                          // Lt[r][d_in]
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if ((e = launch_dense_tn_plain(X, b, Lt, r, d_in, T, nullptr, s)) != hipSuccess) return e;      // T  = X L

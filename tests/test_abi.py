@@ -82,9 +82,20 @@ def test_argument_errors_are_reported_before_launch():
     assert lib.slope_transpose_tokens(p, 100, 64, p, lib.slope_token_copy_bytes(100, 64) - 1, None) == E.SLOPE_ERR_WORKSPACE
     assert lib.slope_transpose_tokens(p, 100, 60, p, big, None) == E.SLOPE_ERR_SHAPE
     assert lib.slope_transpose_tokens(None, 100, 64, p, big, None) == E.SLOPE_ERR_NULL
-    assert lib.slope_wgrad_masked_t(p, p, 100, p, 128, 72, p, None) == E.SLOPE_ERR_SHAPE     # d_in % 32 for this form
-    assert lib.slope_wgrad_masked_t(p, None, 100, p, 128, 64, p, None) == E.SLOPE_ERR_NULL
-    assert lib.slope_wgrad_masked_t(odd, p, 100, p, 128, 64, p, None) == E.SLOPE_ERR_ALIGN
+    assert lib.slope_wgrad_masked_t(p, p, 100, p, 128, 72, p, None, 0, None) == E.SLOPE_ERR_SHAPE   # d_in % 32 for this form
+    assert lib.slope_wgrad_masked_t(p, None, 100, p, 128, 64, p, None, 0, None) == E.SLOPE_ERR_NULL
+    assert lib.slope_wgrad_masked_t(odd, p, 100, p, 128, 64, p, None, 0, None) == E.SLOPE_ERR_ALIGN
+    assert lib.slope_wgrad_masked_t(p, p, 100, p, 128, 64, p, odd, big, None) == E.SLOPE_ERR_ALIGN
+    # a 9216 x 9216 layer is 1296 tiles of 256 x 256: the 16 left over after five rounds are cut into 16 slabs
+    tail = lib.slope_workspace_bytes(E.SLOPE_CALL_WGRAD_MASKED_T, 16384, 9216, 9216, 0)
+    assert tail == 16 * 16 * 256 * 256 * 4
+    assert lib.slope_wgrad_masked_t(p, p, 16384, p, 9216, 9216, p, p, tail - 1, None) == E.SLOPE_ERR_WORKSPACE
+    assert lib.slope_workspace_bytes(E.SLOPE_CALL_WGRAD_MASKED_WS, 16384, 9216, 9216, 0) == \
+        lib.slope_token_copy_bytes(16384, 9216) * 2 + tail
+    # whole rounds (36864 x 9216 at 128 x ... no: 4096 x 4096 is exactly 256 tiles), narrow grids and few tokens: no cut
+    assert lib.slope_workspace_bytes(E.SLOPE_CALL_WGRAD_MASKED_T, 16384, 4096, 4096, 0) == 0
+    assert lib.slope_workspace_bytes(E.SLOPE_CALL_WGRAD_MASKED_T, 16384, 2560, 2560, 0) == 0
+    assert lib.slope_workspace_bytes(E.SLOPE_CALL_WGRAD_MASKED_T, 512, 9216, 9216, 0) == 0
     assert lib.slope_spmm_bwd_x_adapter(p, 8, p, p, 64, 64, p, None, 32, p, p, big, None) == E.SLOPE_ERR_NULL
     assert lib.slope_spmm_bwd_x_adapter(p, 8, p, p, 64, 64, p, p, 48, p, p, big, None) == E.SLOPE_ERR_UNSUPPORTED
     assert lib.slope_spmm_bwd_x_adapter(p, 8, p, p, 64, 64, p, p, 32, p, odd, big, None) == E.SLOPE_ERR_ALIGN
@@ -202,11 +213,30 @@ def test_tile_order_balances_the_xcds(tiles_m, tiles_n):
 
 
 def test_tile_order_keeps_chunks_together():
-    # wide grids: the 32 tiles an XCD holds at a time form one 8 x 4 chunk
+    # wide grids: the 32 tiles an XCD holds at a time share few operand panels: an 8 x 4 chunk where whole chunks
+    # cover the grid (here 32 of the 36 rows), 4 rows x 8 columns in the rows below that
     tm, tn = sl.slope_tile_order(36, 144)
+    assert tm.size == 36 * 144 + (-36 * 144) % 256
     for start in range(0, tm.size, 256):
         for x in range(8):
             a, b = tm[start + x:start + 256:8], tn[start + x:start + 256:8]
             a, b = a[a >= 0], b[b >= 0]
-            if a.size:
+            if a.size == 0:
+                continue
+            if a.max() < 32:
                 assert a.max() - a.min() < 8 and b.max() - b.min() < 4 and a.min() % 8 == 0 and b.min() % 4 == 0
+            else:
+                assert a.min() >= 32 and b.max() - b.min() < 8
+
+
+@pytest.mark.parametrize("tiles_m,tiles_n", [(16, 16), (36, 36), (36, 144), (17, 19), (33, 47), (100, 100)])
+def test_tile_order_of_wide_grids_has_no_gaps(tiles_m, tiles_n):
+    # every XCD's share of every round is full except at the very end: workgroup w is live iff its position
+    # in the order is below the number of tiles
+    tm, _ = sl.slope_tile_order(tiles_m, tiles_n)
+    tiles = tiles_m * tiles_n
+    w = np.arange(tm.size)
+    pos = ((w // 8 // 32) * 8 + w % 8) * 32 + (w // 8) % 32
+    assert np.array_equal(tm >= 0, pos < tiles)
+    whole = tiles // 256 * 256
+    assert (tm[:whole] >= 0).all()                            # the first launch of a cut weight gradient: whole rounds

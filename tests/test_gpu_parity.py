@@ -223,6 +223,29 @@ def test_wgrad_from_prepared_token_copies(b, d_out, d_in):
     check_product(host(g2), so.wgrad_masked(t["dY"], t["X"], u8(meta2)), "dW of the second layer")
 
 
+@pytest.mark.parametrize("b,d_out,d_in", [(1536, 4096, 4352), (1100, 4360, 4320), (4096, 4608, 4096)])
+def test_wgrad_cuts_the_tiles_of_a_last_partial_round(b, d_out, d_in):
+    """Grids of 256 x 256 tiles that leave a few tiles after the last full round of 256 (272, 306, 288 here):
+    with scratch memory those tiles are cut along the tokens and summed in a second pass.  Both forms must meet
+    the oracle; the cut one is also what slope_wgrad_masked gives with its workspace, bit for bit."""
+    say(f"wgrad with a cut last round b={b} d_out={d_out} d_in={d_in}")
+    need = sl.slope_workspace_bytes(sl.SLOPE_CALL_WGRAD_MASKED_T, b, d_in, d_out)
+    assert need > 0
+    t, d, _, _ = layer_on_device(b, d_out, d_in, 0, seed=b + 31)
+    xt, dyt = sl.slope_transpose_tokens(d["X"]), sl.slope_transpose_tokens(d["dY"])
+    ws = torch.full((need,), 0xFF, dtype=torch.uint8, device="cuda")     # stale bytes (NaNs) must not leak
+    g_cut = sl.slope_wgrad_masked_t(dyt, xt, b, d["meta"], workspace=ws)
+    g_plain = sl.slope_wgrad_masked_t(dyt, xt, b, d["meta"], workspace=None)
+    g_ws = sl.slope_wgrad_masked(d["dY"], d["X"], d["meta"], workspace="auto")
+    torch.cuda.synchronize()
+    want = so.wgrad_masked(t["dY"], t["X"], u8(d["meta"]))
+    check_product(host(g_cut), want, "dW, last round cut")
+    check_product(host(g_plain), want, "dW, last round whole")
+    assert (host(g_cut) == host(g_ws)).all()
+    with pytest.raises(ValueError):
+        sl.slope_wgrad_masked_t(dyt, xt, b, d["meta"], workspace=ws[:need - 256])
+
+
 def test_sized_workspaces_are_checked():
     t, d, _, _ = layer_on_device(300, 256, 512, 32, seed=5)
     need = sl.slope_spmm_fwd_workspace_bytes(300, 512, 256, 32)
