@@ -404,6 +404,38 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_split_kernel(const bf16_t* 
         m_src = Am + (size_t)row * (K / 8) + ((lane >> 4) & 1) * 16;
     }
 
+    // ---- L2 prefetch of the token panel through the scalar cache.  A compute unit holds about 128 vector-memory
+    //      requests of 128 bytes in flight, so its operand feed is that many lines per mean latency, and the
+    //      latency is set by the lines that miss the XCD's L2 (a sixth of them, compulsory: each operand panel
+    //      enters the L2 once per chunk of 8 x 4 tiles), on which all tiles that share the panel wait together.
+    //      Scalar loads take another path into the same L2.  The 8 tiles of a chunk that share a token panel
+    //      each touch an eighth of its rows PF_AHEAD k-steps ahead (4 rows per wavefront, both 64-byte halves of
+    //      a row's 128 bytes: the L2 fills halves), so the vector loads of the token panel hit: 3-6 % on the
+    //      whole product.  The scalar path takes about 70 such requests per microsecond and compute unit, which
+    //      these 64 per k-step use up; touching only part of the panel, or the weight panels instead, gained
+    //      nothing.  The loaded dwords are not used; they stay allocated until the wavefront's next
+    //      s_waitcnt lgkmcnt(0), since a scalar load may return any time before that.
+    constexpr int PF_AHEAD = 6, PF_ROWS = S::BN / CHUNK_M / 8;
+    const uint8_t* pf_row[PF_ROWS];
+#pragma unroll
+    for (int r = 0; r < PF_ROWS; ++r) {
+        int row = wrap_row(n0 + (tm % CHUNK_M) * (S::BN / CHUNK_M) + wave * PF_ROWS + r, n);
+        pf_row[r] = (const uint8_t*)B + (size_t)row * K * 2;
+    }
+    uint32_t pf[2 * PF_ROWS];
+#pragma unroll
+    for (int r = 0; r < 2 * PF_ROWS; ++r) pf[r] = 0;
+    // to be placed right after an s_waitcnt lgkmcnt(0): retires the previous k-step's loads, issues the next
+#define PF_ISSUE(ks)                                                                                   \
+    {                                                                                                  \
+        _Pragma("unroll") for (int r = 0; r < 2 * PF_ROWS; ++r) asm volatile("" ::"s"(pf[r]));         \
+        const int kpf = (ks) + PF_AHEAD < ksteps ? (ks) + PF_AHEAD : ksteps - 1;                       \
+        const uint32_t off = (uint32_t)kpf * 128u;            /* inside the row: K * 2 bytes, K < 2^31 */ \
+        _Pragma("unroll") for (int r = 0; r < PF_ROWS; ++r) {                                          \
+            asm volatile("s_load_dword %0, %1, %2" : "=s"(pf[2 * r]) : "s"(pf_row[r]), "s"(off));       \
+            asm volatile("s_load_dword %0, %1, %2" : "=s"(pf[2 * r + 1]) : "s"(pf_row[r]), "s"(off + 64u)); \
+        }                                                                                              \
+    }
     // ---- reader lanes: fragment f = rows 16f .. 16f+15 = 2 KiB; lane (l16, lq) wants chunk 4h + lq
     const int sw = (l16 >> 1) & 7;
     const int rd0 = l16 * 128 + ((lq ^ sw) * 16);             // h = 0
@@ -473,6 +505,7 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_split_kernel(const bf16_t* 
         SPLIT_READ(S4)                                                                                 \
         EVEN_LOADS(ks, S4)                                                                             \
         WAIT_HERE(waitcnt_imm(split_even(S4) + split_odd((S4) + 3), 0));                               \
+        PF_ISSUE(ks)                                                                                   \
         wg_barrier();                                                                                  \
         ODD_LOADS(ks, S4)                                                                              \
         SPLIT_MFMA                                                                                     \
@@ -486,6 +519,7 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_split_kernel(const bf16_t* 
         SPLIT_READ(S4)                                                                                 \
         ODD_LOADS(ks, S4)                                                                              \
         WAIT_HERE(waitcnt_imm(split_odd(S4) + split_even(S4), 0));                                     \
+        PF_ISSUE(ks)                                                                                   \
         wg_barrier();                                                                                  \
         EVEN_LOADS(ks + 1, (S4) + 1)                                                                   \
         SPLIT_MFMA                                                                                     \
@@ -515,6 +549,10 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_split_kernel(const bf16_t* 
 #undef SPLIT_MFMA
 #undef SPLIT_STEP0
 #undef SPLIT_STEP1
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");        // the last scalar prefetches have returned
+#pragma unroll
+    for (int r = 0; r < 2 * PF_ROWS; ++r) asm volatile("" ::"s"(pf[r]));
+#undef PF_ISSUE
     WAIT_HERE(waitcnt_imm(0, 15));                            // drain the clamped look-ahead loads
     static_assert(S::BN * (S::BM * 2 + 16) <= S::TOTAL, "the staged output tile fits in the rings");
     extend_and_store<MF, NF, S::BM, S::BN>(acc, m0 + wm * MF * 16, n0 + wn * NF * 16, m, n, l16, lq, B2, A2, K2, C, smem,
