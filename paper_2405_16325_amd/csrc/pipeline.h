@@ -20,13 +20,13 @@ inline hipError_t allow_dynamic_lds(int bytes) {
 }
 
 constexpr int XCDS = 8;
-constexpr int SUPER = 16;                 // fewer tiles than this along an axis make a grid narrow
 constexpr int RESIDENT = 256;             // tiles in flight on the chip: one per compute unit
+constexpr size_t LAST_LEVEL_CACHE_BYTES = (size_t)256 << 20;   // the memory-side cache in front of HBM
 // s_waitcnt immediate (gfx9 encoding): vmcnt <= vm, lgkmcnt <= lgkm, expcnt unconstrained.
 constexpr int waitcnt_imm(int vm, int lgkm) { return (vm & 15) | ((vm >> 4) << 14) | (7 << 4) | (lgkm << 8); }
 
 // blockIdx -> tile.  Workgroups are dealt round-robin to the 8 XCDs, 32 resident per XCD.
-//  * At least SUPER tiles along both axes: the tiles are put in an order without gaps, and the 32
+//  * A grid of at least 8 x 4 tiles that fills the chip: the tiles are put in an order without gaps, and the 32
 //    tiles an XCD holds at a time are 32 consecutive positions of it (group g of 32 goes to XCD
 //    g % 8), so every XCD gets the same number of tiles, give or take one group, whatever the
 //    grid's shape.  The order: first the part of the grid that whole chunks of 8 x 4 tiles cover
@@ -34,7 +34,8 @@ constexpr int waitcnt_imm(int vm, int lgkm) { return (vm & 15) | ((vm >> 4) << 1
 //    that eight consecutive chunks form a 16 x 16 patch (2 x 4 chunks; the chip then shares 16 + 16
 //    panels in the last-level cache), patch after patch along n, then along m; then the rows that
 //    are left below it, column by column (32 positions: their few rows of 8 or more columns); then
-//    the columns left beside it, row by row.
+//    the columns left beside it, row by row.  What is left of the order after the last whole round of 256 is dealt
+//    out in eight equal runs.
 //  * A narrow grid (skinny products, inference-size batches): tiles are numbered short axis first
 //    and each XCD takes runs of consecutive tiles: at most 32, sized so that all 8 XCDs get equal
 //    shares in every round, also when there are fewer than 256 tiles.
@@ -45,7 +46,14 @@ __host__ __device__ inline int narrow_run(int tiles) {
     return (tiles + XCDS * rounds - 1) / (XCDS * rounds);
 }
 
-__host__ __device__ inline bool wide_grid(int tiles_m, int tiles_n) { return tiles_m >= SUPER && tiles_n >= SUPER; }
+// a grid has the chunked order if it holds at least one whole chunk and fills the chip at least once
+__host__ __device__ inline bool wide_grid(int tiles_m, int tiles_n) {
+    return tiles_m >= CHUNK_M && tiles_n >= CHUNK_N && (int64_t)tiles_m * tiles_n >= RESIDENT;
+}
+// the tile belongs to a whole 8 x 4 chunk of a wide grid: then the 32 tiles its XCD holds with it are that chunk
+__host__ __device__ inline bool in_whole_chunk(int tm, int tn, int tiles_m, int tiles_n) {
+    return wide_grid(tiles_m, tiles_n) && tm < tiles_m / CHUNK_M * CHUNK_M && tn < tiles_n / CHUNK_N * CHUNK_N;
+}
 
 // position q (0 <= q < tiles_m * tiles_n) in the order of a wide grid -> tile
 __host__ __device__ inline void tile_of_position(int q, int tiles_m, int tiles_n, int& tm, int& tn) {
@@ -77,13 +85,23 @@ __host__ __device__ inline int position_of_block(int b) {
 }
 
 __host__ __device__ inline bool tile_of_index(int b, int tiles_m, int tiles_n, int& tm, int& tn) {
+    int xcd = b % XCDS, slot = b / XCDS;
     if (wide_grid(tiles_m, tiles_n)) {
-        const int q = position_of_block(b);
-        if (q >= tiles_m * tiles_n) return false;
+        // whole rounds of 256: 32 consecutive positions per XCD; the tiles left for a last, partial round are
+        // dealt out in equal runs, so that all 8 XCDs (their L2s, their links to memory) share them
+        const int tiles = tiles_m * tiles_n, whole = tiles / RESIDENT * RESIDENT;
+        int q;
+        if (b < whole) {
+            q = position_of_block(b);
+        } else {
+            const int run = (tiles - whole + XCDS - 1) / XCDS;
+            slot -= whole / XCDS;
+            q = whole + xcd * run + slot;
+            if (slot >= run || q >= tiles) return false;
+        }
         tile_of_position(q, tiles_m, tiles_n, tm, tn);
         return true;
     }
-    int xcd = b % XCDS, slot = b / XCDS;
     int run = narrow_run(tiles_m * tiles_n);
     int t = ((slot / run) * XCDS + xcd) * run + slot % run;
     if (tiles_m <= tiles_n) { tm = t % tiles_m; tn = t / tiles_m; }
@@ -97,7 +115,10 @@ __device__ __forceinline__ bool tile_of_block(int tiles_m, int tiles_n, int& tm,
 
 inline int super_grid(int tiles_m, int tiles_n) {
     int tiles = tiles_m * tiles_n;
-    if (wide_grid(tiles_m, tiles_n)) return (tiles + RESIDENT - 1) / RESIDENT * RESIDENT;
+    if (wide_grid(tiles_m, tiles_n)) {
+        const int whole = tiles / RESIDENT * RESIDENT;
+        return whole + (tiles - whole + XCDS - 1) / XCDS * XCDS;
+    }
     int chunk = XCDS * narrow_run(tiles);
     return (tiles + chunk - 1) / chunk * chunk;
 }

@@ -365,6 +365,7 @@ struct SplitSmem {
 constexpr int split_even(int k) { return 2 + ((k & 1) == 0 ? 2 : 0) + ((k & 3) == 1 ? 1 : 0); }
 constexpr int split_odd(int k) { return 2 + ((k & 1) == 0 ? 2 : 0); }
 
+template <bool PREFETCH>
 __global__ void __launch_bounds__(SPMM_THREADS) spmm_split_kernel(const bf16_t* __restrict__ B, int n,
                                                                   const bf16_t* __restrict__ Av,
                                                                   const uint8_t* __restrict__ Am, int m, int K,
@@ -411,7 +412,7 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_split_kernel(const bf16_t* 
     //      Scalar loads take another path into the same L2.  The 8 tiles of a chunk that share a token panel
     //      each touch an eighth of its rows PF_AHEAD k-steps ahead (4 rows per wavefront, both 64-byte halves of
     //      a row's 128 bytes: the L2 fills halves), so the vector loads of the token panel hit: 3-6 % on the
-    //      whole product.  The scalar path takes about 70 such requests per microsecond and compute unit, which
+    //      whole product at OPT-66B sizes.  The scalar path takes about 70 such requests per microsecond and compute unit, which
     //      these 64 per k-step use up; touching only part of the panel, or the weight panels instead, gained
     //      nothing.  The loaded dwords are not used; they stay allocated until the wavefront's next
     //      s_waitcnt lgkmcnt(0), since a scalar load may return any time before that.
@@ -422,6 +423,12 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_split_kernel(const bf16_t* 
         int row = wrap_row(n0 + (tm % CHUNK_M) * (S::BN / CHUNK_M) + wave * PF_ROWS + r, n);
         pf_row[r] = (const uint8_t*)B + (size_t)row * K * 2;
     }
+    // PREFETCH is the host's choice (launch_split): only for grids in the chunked order, and only if the tokens do
+    // not fit into the last-level cache: lines that come from there rather than from HBM arrive soon enough anyway,
+    // and the scalar loads then cost more than they gain (measured: 1-5 % faster with 16384 tokens of 9216 features
+    // or more, 3-12 % slower with 8192 tokens or fewer).  It is a template parameter because a branch around the
+    // loads inside the k-loop cost what they gain.  Tiles outside whole chunks touch rows as if they were in one:
+    // harmless, and they are few.
     uint32_t pf[2 * PF_ROWS];
 #pragma unroll
     for (int r = 0; r < 2 * PF_ROWS; ++r) pf[r] = 0;
@@ -431,9 +438,11 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_split_kernel(const bf16_t* 
         _Pragma("unroll") for (int r = 0; r < 2 * PF_ROWS; ++r) asm volatile("" ::"s"(pf[r]));         \
         const int kpf = (ks) + PF_AHEAD < ksteps ? (ks) + PF_AHEAD : ksteps - 1;                       \
         const uint32_t off = (uint32_t)kpf * 128u;            /* inside the row: K * 2 bytes, K < 2^31 */ \
-        _Pragma("unroll") for (int r = 0; r < PF_ROWS; ++r) {                                          \
-            asm volatile("s_load_dword %0, %1, %2" : "=s"(pf[2 * r]) : "s"(pf_row[r]), "s"(off));       \
-            asm volatile("s_load_dword %0, %1, %2" : "=s"(pf[2 * r + 1]) : "s"(pf_row[r]), "s"(off + 64u)); \
+        if (PREFETCH) {                                                                                \
+            _Pragma("unroll") for (int r = 0; r < PF_ROWS; ++r) {                                      \
+                asm volatile("s_load_dword %0, %1, %2" : "=s"(pf[2 * r]) : "s"(pf_row[r]), "s"(off));   \
+                asm volatile("s_load_dword %0, %1, %2" : "=s"(pf[2 * r + 1]) : "s"(pf_row[r]), "s"(off + 64u)); \
+            }                                                                                          \
         }                                                                                              \
     }
     // ---- reader lanes: fragment f = rows 16f .. 16f+15 = 2 KiB; lane (l16, lq) wants chunk 4h + lq
@@ -731,10 +740,17 @@ hipError_t launch_split(const bf16_t* B, int64_t n, const bf16_t* Av, const uint
     using S = SplitSmem;
     static_assert(S::TOTAL <= 160 * 1024, "LDS budget");
     int tiles_m = (int)((m + S::BM - 1) / S::BM), tiles_n = (int)((n + S::BN - 1) / S::BN);
-    hipError_t e = allow_dynamic_lds<spmm_split_kernel>(S::TOTAL);
+    const bool prefetch = wide_grid(tiles_m, tiles_n) && (size_t)n * (size_t)K * 2 > LAST_LEVEL_CACHE_BYTES;
+    hipError_t e = prefetch ? allow_dynamic_lds<spmm_split_kernel<true>>(S::TOTAL)
+                            : allow_dynamic_lds<spmm_split_kernel<false>>(S::TOTAL);
     if (e != hipSuccess) return e;
-    spmm_split_kernel<<<dim3((unsigned)super_grid(tiles_m, tiles_n)), dim3(SPMM_THREADS), S::TOTAL, s>>>(
-        B, (int)n, Av, Am, (int)m, (int)K, B2, A2, (int)K2, C, tiles_m, tiles_n);
+    const dim3 grid((unsigned)super_grid(tiles_m, tiles_n));
+    if (prefetch)
+        spmm_split_kernel<true><<<grid, dim3(SPMM_THREADS), S::TOTAL, s>>>(B, (int)n, Av, Am, (int)m, (int)K, B2, A2,
+                                                                           (int)K2, C, tiles_m, tiles_n);
+    else
+        spmm_split_kernel<false><<<grid, dim3(SPMM_THREADS), S::TOTAL, s>>>(B, (int)n, Av, Am, (int)m, (int)K, B2, A2,
+                                                                            (int)K2, C, tiles_m, tiles_n);
     return hipGetLastError();
 }
 
