@@ -312,7 +312,6 @@ struct SplitSmem {
     static constexpr int TOTAL = 3 * A_STAGE + 4 * B_HALF;
 };
 
-//
 // TAIL: the tiles left over after the last full round of 256.  Run as a round of their own they would
 // keep a few compute units busy for a whole tile's time while the rest of the chip idles.  Instead each
 // of them (positions first_tile .. first_tile + tail_tiles - 1 of the tile order) is cut along k into
