@@ -92,31 +92,19 @@ __global__ void __launch_bounds__(256) mfma_loop_kernel(const u32x4* __restrict_
     sink[g] = s[0] + s[1] + s[2] + s[3];
 }
 
+// One 16-byte vector per lane and no loop: workgroups that come and go in address order keep the accesses in
+// flight close together, which is what the memory likes best (a grid-stride loop over the same data, every lane
+// walking through windows far apart, reads 5.6 instead of 7.0 TB/s and copies 4.5 instead of 6.5).
 __global__ void __launch_bounds__(256) read_stream_kernel(const u32x4* __restrict__ src, size_t nvec, uint32_t* __restrict__ sink) {
-    const size_t stride = (size_t)gridDim.x * 256;
-    uint32_t s = 0;
-    for (size_t base = (size_t)blockIdx.x * 256 + threadIdx.x; base < nvec; base += 4 * stride) {
-        u32x4 v[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-            v[u] = base + u * stride < nvec ? __builtin_nontemporal_load(src + base + u * stride) : (u32x4){0u, 0u, 0u, 0u};
-#pragma unroll
-        for (int u = 0; u < 4; ++u) s += v[u][0] ^ v[u][1] ^ v[u][2] ^ v[u][3];
-    }
-    sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= nvec) return;
+    const u32x4 v = __builtin_nontemporal_load(src + i);
+    if ((v[0] ^ v[1] ^ v[2] ^ v[3]) == 0x9E3779B9u) sink[threadIdx.x] = v[0];   // keeps the load; (almost) never taken
 }
 
 __global__ void __launch_bounds__(256) copy_stream_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, size_t nvec) {
-    const size_t stride = (size_t)gridDim.x * 256;
-    for (size_t base = (size_t)blockIdx.x * 256 + threadIdx.x; base < nvec; base += 4 * stride) {
-        u32x4 v[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-            if (base + u * stride < nvec) v[u] = __builtin_nontemporal_load(src + base + u * stride);
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-            if (base + u * stride < nvec) __builtin_nontemporal_store(v[u], dst + base + u * stride);
-    }
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < nvec) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
 constexpr int CEIL_BLOCKS = 256 * 4;  // four workgroups of four wavefronts per compute unit
@@ -153,17 +141,20 @@ slope_status slope_ceiling(int kind, void* buf, size_t bytes, int iters, double*
             *work = (double)(lanes / 64) * iters * 8 * 2.0 * 32 * 32 * 16;
             break;
         case SLOPE_CEILING_READ: {
-            const size_t sink_bytes = (size_t)CEIL_BLOCKS * 4 * 256 * 4;      // one sum per lane, past the data
+            const size_t sink_bytes = 4096;                   // past the data
             if (bytes < 2 * sink_bytes) return SLOPE_ERR_SHAPE;
             const size_t nvec = (bytes - sink_bytes) / 16;
-            read_stream_kernel<<<dim3(CEIL_BLOCKS * 4), dim3(256), 0, s>>>((const u32x4*)buf, nvec,
-                                                                          (uint32_t*)((uint8_t*)buf + nvec * 16));
+            if ((nvec + 255) / 256 > 0x7FFFFFFFu) return SLOPE_ERR_SHAPE;
+            read_stream_kernel<<<dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, s>>>(
+                (const u32x4*)buf, nvec, (uint32_t*)((uint8_t*)buf + nvec * 16));
             *work = (double)nvec * 16;
             break;
         }
         case SLOPE_CEILING_COPY: {
             const size_t nvec = bytes / 32;
-            copy_stream_kernel<<<dim3(CEIL_BLOCKS * 4), dim3(256), 0, s>>>((const u32x4*)buf, (u32x4*)buf + nvec, nvec);
+            if ((nvec + 255) / 256 > 0x7FFFFFFFu) return SLOPE_ERR_SHAPE;
+            copy_stream_kernel<<<dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, s>>>((const u32x4*)buf,
+                                                                                         (u32x4*)buf + nvec, nvec);
             *work = (double)nvec * 32;                        // read + written
             break;
         }

@@ -22,20 +22,22 @@ namespace {
 
 // out[c][r] = in[r][c] for r < rows, zero for rows <= r < rows_pad; in is [rows][cols] bf16 with
 // cols % 8 == 0, out is [cols] rows of pitch ld >= rows_pad, rows_pad % 64 == 0, ld % 8 == 0.
-// 64 x 64 tiles through LDS, 16-byte global accesses on both sides.
+// Tiles of TP_ROWS rows x 64 columns through LDS, 16-byte global accesses on both sides; consecutive
+// workgroups go down the rows, so that every output row is written front to back.
 // blockIdx.z picks one of two matrices of the same row count (one launch for both operands of a product).
+constexpr int TP_ROWS = 64;                                   // 128 and 256 measured the same
 __global__ void __launch_bounds__(256) transpose_pad_kernel(const bf16_t* __restrict__ in0, int cols0,
                                                             bf16_t* __restrict__ out0, const bf16_t* __restrict__ in1,
                                                             int cols1, bf16_t* __restrict__ out1, int rows,
                                                             int rows_pad, int ld) {
-    __shared__ bf16_t tile[64][66];
+    __shared__ bf16_t tile[64][TP_ROWS + 2];
     const bf16_t* __restrict__ in = blockIdx.z ? in1 : in0;
     bf16_t* __restrict__ out = blockIdx.z ? out1 : out0;
     const int cols = blockIdx.z ? cols1 : cols0;
-    const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64, t = threadIdx.x;
+    const int r0 = blockIdx.x * TP_ROWS, c0 = blockIdx.y * 64, t = threadIdx.x;
     if (c0 >= cols) return;                                   // uniform: the other matrix is wider
 #pragma unroll
-    for (int p = 0; p < 2; ++p) {
+    for (int p = 0; p < TP_ROWS / 32; ++p) {
         int r = (t >> 3) + 32 * p, c8 = (t & 7) * 8;
         u32x4 v = {0u, 0u, 0u, 0u};
         if (r0 + r < rows && c0 + c8 < cols) v = *(const u32x4*)(in + (size_t)(r0 + r) * cols + c0 + c8);
@@ -44,9 +46,9 @@ __global__ void __launch_bounds__(256) transpose_pad_kernel(const bf16_t* __rest
     }
     __syncthreads();
 #pragma unroll
-    for (int p = 0; p < 2; ++p) {
-        int c = (t >> 3) + 32 * p, r8 = (t & 7) * 8;
-        if (c0 + c >= cols) continue;
+    for (int p = 0; p < TP_ROWS / 32; ++p) {
+        int idx = t + 256 * p, c = idx / (TP_ROWS / 8), r8 = (idx % (TP_ROWS / 8)) * 8;
+        if (c0 + c >= cols || r0 + r8 >= rows_pad) continue;
         const uint32_t* src = (const uint32_t*)&tile[c][r8];
         u32x4 v = {src[0], src[1], src[2], src[3]};
         *(u32x4*)(out + (size_t)(c0 + c) * ld + r0 + r8) = v;
@@ -55,7 +57,7 @@ __global__ void __launch_bounds__(256) transpose_pad_kernel(const bf16_t* __rest
 
 inline void launch_transpose_pad(const bf16_t* in, int64_t rows, int64_t cols, int64_t rows_pad, int64_t ld,
                                  bf16_t* out, hipStream_t s) {
-    transpose_pad_kernel<<<dim3((unsigned)(rows_pad / 64), (unsigned)((cols + 63) / 64), 1), dim3(256), 0, s>>>(
+    transpose_pad_kernel<<<dim3((unsigned)((rows_pad + TP_ROWS - 1) / TP_ROWS), (unsigned)((cols + 63) / 64), 1), dim3(256), 0, s>>>(
         in, (int)cols, out, nullptr, 0, nullptr, (int)rows, (int)rows_pad, (int)ld);
 }
 
@@ -63,7 +65,7 @@ inline void launch_transpose_pad(const bf16_t* in, int64_t rows, int64_t cols, i
 inline void launch_transpose_pad2(const bf16_t* in0, int64_t cols0, bf16_t* out0, const bf16_t* in1, int64_t cols1,
                                   bf16_t* out1, int64_t rows, int64_t rows_pad, int64_t ld, hipStream_t s) {
     const int64_t cmax = cols0 > cols1 ? cols0 : cols1;
-    transpose_pad_kernel<<<dim3((unsigned)(rows_pad / 64), (unsigned)((cmax + 63) / 64), 2), dim3(256), 0, s>>>(
+    transpose_pad_kernel<<<dim3((unsigned)((rows_pad + TP_ROWS - 1) / TP_ROWS), (unsigned)((cmax + 63) / 64), 2), dim3(256), 0, s>>>(
         in0, (int)cols0, out0, in1, (int)cols1, out1, (int)rows, (int)rows_pad, (int)ld);
 }
 
