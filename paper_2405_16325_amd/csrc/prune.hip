@@ -4,9 +4,10 @@
 //                ranks each group with a branch-free comparison network and writes 8 bytes of
 //                kept values, one metadata byte and (optionally) one mask byte.  A wavefront
 //                reads 1 KiB and writes 512 + 64 (+ 64) contiguous bytes.
-// double_prune : a 128 x 128 tile of W^R is decompressed into LDS, regrouped along d_out,
-//                ranked again among the surviving positions, and written out transposed
-//                through a second LDS stage so that both the read and the write are coalesced.
+// double_prune : a workgroup takes a 128 x 128 tile of W^R; every lane reads 4 rows x 8 columns of it
+//                (packed, whole lines per 16 lanes), decompresses them in registers, ranks each column's
+//                group of four along d_out among the surviving positions, and the tile is written out
+//                transposed through an LDS stage so that the write is coalesced as well.
 #include "common.h"
 
 // ------------------------------------------------------------------------------------------
@@ -89,7 +90,6 @@ hipError_t launch_prune_rows(const bf16_t* W, int64_t d_out, int64_t d_in, bf16_
 
 // ------------------------------------------------------------------------------------------
 constexpr int DP_TILE = 128;        // logical tile edge along d_out and d_in
-constexpr int DP_PITCH = 272;       // bytes per decompressed row in LDS (128 * 2 + 16)
 constexpr int DP_OPITCH = 33;       // dwords per output row [i][og] (32 + 1: conflict-free columns)
 constexpr int DP_NPITCH = 36;       // bytes per nibble row [i][og]
 
@@ -108,23 +108,25 @@ __device__ __forceinline__ uint32_t pk_beats(uint32_t kj, uint32_t ki, uint32_t 
 //                 masks, Alg. 1 line 18); only the values of the transposed copy are rewritten.
 //                 A slot that names a position outside W^R's mask reads the zero that the
 //                 decompression left there, so padding stays +0.0.
-// RAGGED: d_in is not a multiple of 16 or d_out not one of 32.  Rows of the packed arrays are then only
-//                 8-byte (values) and 1-byte (metadata) aligned and may end inside a lane's piece, so every
-//                 access is made in pieces of 8 logical elements (8 bytes of values, 1 byte of metadata),
-//                 each wholly inside the row or skipped.
+// RAGGED: d_out is not a multiple of 32: rows of the transposed arrays are then only 8-byte (values) and
+//                 1-byte (metadata) aligned and may end inside a lane's piece, so they are written in pieces
+//                 of 8 logical elements (8 bytes of values, 1 byte of metadata), each wholly inside the row
+//                 or skipped.  The input needs no such care: a lane reads 8 logical columns of a row at a
+//                 time (8 bytes of values, 1 byte of metadata), and d_in is a multiple of 8.
+//
+// A lane ranks 4 rows x 8 columns (one group of four along d_out per column), twice.  It reads exactly those
+// pieces of packed W^R itself: 16 neighbouring lanes cover 128 contiguous bytes of a row, so the loads are
+// whole lines without a stage in LDS (an earlier version decompressed the tile into LDS first: 15 % more
+// vector instructions and two more barriers for nothing).
 template <bool GIVEN, bool MASK, bool RAGGED>
 __global__ void __launch_bounds__(256) double_prune_kernel(const bf16_t* __restrict__ vals,
                                                            const uint8_t* __restrict__ meta, int d_out, int d_in,
                                                            bf16_t* __restrict__ valsT, uint8_t* __restrict__ metaT,
                                                            uint8_t* __restrict__ maskrc,
                                                            const uint8_t* __restrict__ metaT_in) {
-    // The input tile (sD, sC) and the output tile (sO, sN) share one buffer: every lane holds its
-    // inputs in registers before the first output is written.  Given metadata (GIVEN) has its own.
-    constexpr int IN_BYTES = DP_TILE * DP_PITCH + DP_TILE * 16, OUT_BYTES = DP_TILE * DP_OPITCH * 4 + DP_TILE * DP_NPITCH;
-    __shared__ __align__(16) uint8_t sbuf[IN_BYTES > OUT_BYTES ? IN_BYTES : OUT_BYTES];
+    // the output tile: kept value pairs [i][og] and metadata nibbles [i][og]; given metadata (GIVEN) has its own
+    __shared__ __align__(16) uint8_t sbuf[DP_TILE * DP_OPITCH * 4 + DP_TILE * DP_NPITCH];
     __shared__ __align__(4) uint8_t sG[GIVEN ? DP_TILE * DP_NPITCH : 4];
-    uint8_t* const sD = sbuf;                                  // decompressed W^R tile [o][i]
-    uint8_t* const sC = sbuf + DP_TILE * DP_PITCH;             // candidate bits [o][i/8]
     uint32_t* const sO = (uint32_t*)sbuf;                      // kept value pairs [i][og]
     uint8_t* const sN = sbuf + DP_TILE * DP_OPITCH * 4;        // metadata nibbles [i][og]
 
@@ -132,43 +134,25 @@ __global__ void __launch_bounds__(256) double_prune_kernel(const bf16_t* __restr
     const int o0 = blockIdx.y * DP_TILE, i0 = blockIdx.x * DP_TILE;
     const size_t vpitch = (size_t)d_in / 2, mpitch = (size_t)d_in / 8;
 
-    // phase 1: coalesced read of packed W^R (16 logical columns per lane), decompress to LDS
+    // phase 1: every lane reads its 2 x (4 rows x 8 columns) of packed W^R and decompresses them in registers:
+    // r[n][k][q] = columns 2q, 2q + 1 of row k as one dword (zeros where W^R has none), cb = candidate bits
+    u32x2 pk[2][4];
+    uint32_t mb[2][4];
+    {
+        const int og = t >> 4, i8 = t & 15;                    // n = 1: 16 row groups (64 rows) further down
+        const int i = i0 + 8 * i8, o = o0 + 4 * og;
+        const bool col_ok = i < d_in;
+        const bf16_t* vp = vals + (size_t)o * vpitch + i / 2;
+        const uint8_t* mp = meta + (size_t)o * mpitch + i / 8;
 #pragma unroll
-    for (int pass = 0; pass < 4; ++pass) {
-        int row = pass * 32 + (t >> 3), c = t & 7;
-        int o = o0 + row, i = i0 + 16 * c;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        uint32_t m = 0;
-        bool ok = o < d_out && i < d_in;
-        if (ok && !RAGGED) {
-            v = *(const uint4*)(vals + (size_t)o * vpitch + i / 2);
-            m = *(const uint16_t*)(meta + (size_t)o * mpitch + i / 8);
-        }
-        bool ok_hi = ok;                                       // columns i + 8 .. i + 15 exist as well
-        if (RAGGED && ok) {
-            ok_hi = i + 8 < d_in;
-            const uint2 lo = *(const uint2*)(vals + (size_t)o * vpitch + i / 2);
-            const uint2 hi = ok_hi ? *(const uint2*)(vals + (size_t)o * vpitch + i / 2 + 4) : make_uint2(0, 0);
-            v = make_uint4(lo.x, lo.y, hi.x, hi.y);
-            m = meta[(size_t)o * mpitch + i / 8];
-            if (ok_hi) m |= (uint32_t)meta[(size_t)o * mpitch + i / 8 + 1] << 8;
-        }
-        uint32_t pk[4] = {v.x, v.y, v.z, v.w};
-        uint32_t dense[8];
-        uint32_t cand = 0;
+        for (int n = 0; n < 2; ++n)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            uint32_t nib = (m >> (4 * g)) & 0xFu, a = nib & 3u, b = nib >> 2;
-            uint64_t q = ((uint64_t)(pk[g] & 0xFFFFu) << (16u * a)) | ((uint64_t)(pk[g] >> 16) << (16u * b));
-            dense[2 * g] = (uint32_t)q;
-            dense[2 * g + 1] = (uint32_t)(q >> 32);
-            uint32_t bits = (g < 2 ? ok : ok_hi) ? ((1u << a) | (1u << b)) : 0u;
-            cand |= bits << (4 * g);
-        }
-        uint4* dst = (uint4*)(sD + row * DP_PITCH + 32 * c);
-        dst[0] = make_uint4(dense[0], dense[1], dense[2], dense[3]);
-        dst[1] = make_uint4(dense[4], dense[5], dense[6], dense[7]);
-        *(uint16_t*)(sC + row * 16 + 2 * c) = (uint16_t)cand;
+            for (int k = 0; k < 4; ++k) {
+                const int row = 64 * n + k;
+                const bool ok = col_ok && o + row < d_out;
+                pk[n][k] = ok ? *(const u32x2*)(vp + (size_t)row * vpitch) : (u32x2){0u, 0u};
+                mb[n][k] = ok ? (uint32_t)mp[(size_t)row * mpitch] : 0x100u;       // 0x100: no candidates
+            }
     }
     if (GIVEN) {   // the tile of the given metadata, one nibble per byte: 128 rows (d_in) x 32 groups along d_out
         int row = t >> 1, half = t & 1;
@@ -190,22 +174,25 @@ __global__ void __launch_bounds__(256) double_prune_kernel(const bf16_t* __restr
             dst[q] = (uint8_t)((x.x >> (4 * q)) & 0xFu);
             dst[8 + q] = (uint8_t)((x.y >> (4 * q)) & 0xFu);
         }
+        __syncthreads();
     }
-    __syncthreads();
-
-    // phase 2: one lane ranks 8 columns x 4 rows (one group of four along d_out per column), twice
     uint32_t r[2][4][4], cb[2][4];
 #pragma unroll
-    for (int n = 0; n < 2; ++n) {
-        int u = t + 256 * n, og = u >> 4, i8 = u & 15;
+    for (int n = 0; n < 2; ++n)
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            uint4 x = *(const uint4*)(sD + (4 * og + k) * DP_PITCH + 16 * i8);
-            r[n][k][0] = x.x; r[n][k][1] = x.y; r[n][k][2] = x.z; r[n][k][3] = x.w;
-            cb[n][k] = sC[(4 * og + k) * 16 + i8];
+            uint32_t cand = 0;
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {
+                const uint32_t m = mb[n][k], w = pk[n][k][g];
+                const uint32_t a = (m >> (4 * g)) & 3u, b = (m >> (4 * g + 2)) & 3u;
+                const uint64_t q = ((uint64_t)(w & 0xFFFFu) << (16u * a)) | ((uint64_t)(w >> 16) << (16u * b));
+                r[n][k][2 * g] = (uint32_t)q;
+                r[n][k][2 * g + 1] = (uint32_t)(q >> 32);
+                cand |= ((1u << a) | (1u << b)) << (4 * g);
+            }
+            cb[n][k] = (mb[n][k] >> 8) ? 0u : cand;           // rows and columns outside the matrix compete nowhere
         }
-    }
-    __syncthreads();                                           // the input tile is in registers: reuse its memory
     // The kernel is bound by vector ALU work, not by memory (the SIMDs issue vector instructions in over 90 %
     // of their cycles), so two neighbouring columns are ranked at once in the two 16-bit halves of a register:
     // a row's dword already holds the pair, keys are at most 0x8000, and "j beats i" is min(k_j -sat k_i, 1).
@@ -252,10 +239,9 @@ __global__ void __launch_bounds__(256) double_prune_kernel(const bf16_t* __restr
                 const int j = 2 * q + h, col = 8 * i8 + j;
                 const uint32_t set = h ? set2 >> 16 : set2 & 0xFu;
                 const uint32_t nib = GIVEN ? sG[col * DP_NPITCH + og] : nibble_of_pair(set);
-                const uint64_t qq = h ? ((uint64_t)qhi[0] | ((uint64_t)qhi[1] << 32)) : ((uint64_t)qlo[0] | ((uint64_t)qlo[1] << 32));
-                const uint32_t v0 = (uint32_t)(qq >> (16u * (nib & 3u))) & 0xFFFFu;
-                const uint32_t v1 = (uint32_t)(qq >> (16u * (nib >> 2))) & 0xFFFFu;
-                sO[col * DP_OPITCH + og] = v0 | (v1 << 16);
+                // the values of rows idx0 = nib & 3 and idx1 = nib >> 2: bytes 2 idx, 2 idx + 1 of the eight
+                const uint32_t sel = 0x01000100u + (nib & 3u) * 0x0202u + (((nib >> 2) * 0x0202u) << 16);
+                sO[col * DP_OPITCH + og] = h ? __builtin_amdgcn_perm(qhi[1], qhi[0], sel) : __builtin_amdgcn_perm(qlo[1], qlo[0], sel);
                 if (!GIVEN) sN[col * DP_NPITCH + og] = (uint8_t)nib;
                 if (MASK)
 #pragma unroll
@@ -314,7 +300,7 @@ __global__ void __launch_bounds__(256) double_prune_kernel(const bf16_t* __restr
 hipError_t launch_double_prune(const bf16_t* vals, const uint8_t* meta, int64_t d_out, int64_t d_in, bf16_t* valsT,
                                uint8_t* metaT, uint8_t* maskrc, hipStream_t s) {
     dim3 grid((unsigned)((d_in + DP_TILE - 1) / DP_TILE), (unsigned)((d_out + DP_TILE - 1) / DP_TILE));
-    const bool ragged = d_in % 16 != 0 || d_out % 32 != 0;
+    const bool ragged = d_out % 32 != 0;
     if (ragged && maskrc)
         double_prune_kernel<false, true, true><<<grid, dim3(256), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT,
                                                                           metaT, maskrc, nullptr);
