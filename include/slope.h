@@ -114,6 +114,7 @@ slope_status slope_prune_rows(const void* W, int64_t d_out, int64_t d_in, int n,
  *   WrcT_vals  out  bf16[d_in, d_out/2]   packed (W^{R,C})^T: rows = d_in, groups along d_out
  *   WrcT_meta  out  u8[d_in, d_out/8]
  *   maskrc_or_null out u8[d_out, d_in/8]  bit mask of W^{R,C} in W's orientation, or NULL
+ * d_out and d_in are multiples of 8 and at most 2^23 each (SLOPE_ERR_SHAPE otherwise).
  */
 slope_status slope_double_prune(const void* Wr_vals, const void* Wr_meta, int64_t d_out, int64_t d_in,
                                 void* WrcT_vals, void* WrcT_meta, void* maskrc_or_null, void* stream);
@@ -294,6 +295,7 @@ slope_status slope_sparse_add(const void* A_vals, const void* B_vals, int64_t ro
  *   Wr_vals    out  bf16[d_out, d_in/2]   receives a copy of Wnew_vals (no copy if it is Wnew_vals)
  *   WrcT_meta  in   u8[d_in, d_out/8]     metadata of (W^{R,C})^T as written by slope_double_prune
  *   WrcT_vals  out  bf16[d_in, d_out/2]   rewritten completely
+ * d_out and d_in are multiples of 8 and at most 2^23 each (SLOPE_ERR_SHAPE otherwise).
  */
 slope_status slope_update_sparse(const void* Wnew_vals, const void* Wr_meta, int64_t d_out, int64_t d_in,
                                  void* Wr_vals, const void* WrcT_meta, void* WrcT_vals, void* stream);

@@ -19,6 +19,9 @@ void note_hip_error(hipError_t e);
 // Launchers (host side, one per kernel family).  Each returns the hipError_t of its launches.
 hipError_t launch_prune_rows(const bf16_t* W, int64_t d_out, int64_t d_in, bf16_t* vals, uint8_t* meta,
                              uint8_t* mask, hipStream_t s);
+// largest d_out and d_in of the two calls below: 128 rows of any of their arrays stay below 2^30 bytes, which the
+// kernel's 32-bit offsets into a tile's rows rely on
+constexpr int64_t DP_EXTENT_MAX = (int64_t)1 << 23;
 hipError_t launch_double_prune(const bf16_t* vals, const uint8_t* meta, int64_t d_out, int64_t d_in,
                                bf16_t* valsT, uint8_t* metaT, uint8_t* maskrc, hipStream_t s);
 hipError_t launch_update_transposed(const bf16_t* vals, const uint8_t* meta, int64_t d_out, int64_t d_in,

@@ -90,8 +90,18 @@ hipError_t launch_prune_rows(const bf16_t* W, int64_t d_out, int64_t d_in, bf16_
 
 // ------------------------------------------------------------------------------------------
 constexpr int DP_TILE = 128;        // logical tile edge along d_out and d_in
+constexpr int DP_THREADS = 512;     // a lane ranks 4 rows x 8 columns of the tile
+constexpr int DP_CHUNK = 8;         // an XCD takes chunks of 8 x 8 neighbouring tiles
 constexpr int DP_OPITCH = 33;       // dwords per output row [i][og] (32 + 1: conflict-free columns)
 constexpr int DP_NPITCH = 36;       // bytes per nibble row [i][og]
+
+// A raw buffer descriptor over `bytes` bytes from `base` (the same for all lanes of a workgroup): loads at offsets
+// beyond it return 0 and stores there are dropped, which replaces every bounds branch of the kernel below.
+typedef __amdgpu_buffer_rsrc_t buffer_t;
+__device__ __forceinline__ buffer_t tile_buffer(const void* base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+constexpr uint32_t NOWHERE = 0x80000000u;   // an offset outside every descriptor (they cover less than 2^31 bytes)
 
 // Per 16-bit half: 1 where kj > ki, else 0 (saturating subtract, then min with 1).  Written as instructions
 // because the compiler turns the portable form back into one compare and one select per half.
@@ -114,218 +124,256 @@ __device__ __forceinline__ uint32_t pk_beats(uint32_t kj, uint32_t ki, uint32_t 
 //                 or skipped.  The input needs no such care: a lane reads 8 logical columns of a row at a
 //                 time (8 bytes of values, 1 byte of metadata), and d_in is a multiple of 8.
 //
-// A lane ranks 4 rows x 8 columns (one group of four along d_out per column), twice.  It reads exactly those
-// pieces of packed W^R itself: 16 neighbouring lanes cover 128 contiguous bytes of a row, so the loads are
-// whole lines without a stage in LDS (an earlier version decompressed the tile into LDS first: 15 % more
-// vector instructions and two more barriers for nothing).
+// A lane ranks 4 rows x 8 columns (one group of four along d_out per column).  It reads exactly those pieces of
+// packed W^R itself: 16 neighbouring lanes cover 128 contiguous bytes of a row, so the loads are whole lines
+// without a stage in LDS (an earlier version decompressed the tile into LDS first: 15 % more vector instructions
+// and two more barriers for nothing).  512 lanes of 43 registers rather than 256 lanes with two pieces each: 8
+// waves per SIMD hide the loads; walking several tiles per workgroup with the next tile's loads in flight was
+// slower than one tile per short-lived workgroup (175 -> 185 us with two tiles, 192 with four).
 template <bool GIVEN, bool MASK, bool RAGGED>
-__global__ void __launch_bounds__(256) double_prune_kernel(const bf16_t* __restrict__ vals,
+__global__ void __launch_bounds__(DP_THREADS) double_prune_kernel(const bf16_t* __restrict__ vals,
                                                            const uint8_t* __restrict__ meta, int d_out, int d_in,
                                                            bf16_t* __restrict__ valsT, uint8_t* __restrict__ metaT,
                                                            uint8_t* __restrict__ maskrc,
-                                                           const uint8_t* __restrict__ metaT_in) {
+                                                           const uint8_t* __restrict__ metaT_in, int tiles_x,
+                                                           int tiles_y) {
     // the output tile: kept value pairs [i][og] and metadata nibbles [i][og]; given metadata (GIVEN) has its own
     __shared__ __align__(16) uint8_t sbuf[DP_TILE * DP_OPITCH * 4 + DP_TILE * DP_NPITCH];
     __shared__ __align__(4) uint8_t sG[GIVEN ? DP_TILE * DP_NPITCH : 4];
     uint32_t* const sO = (uint32_t*)sbuf;                      // kept value pairs [i][og]
     uint8_t* const sN = sbuf + DP_TILE * DP_OPITCH * 4;        // metadata nibbles [i][og]
+    // Decompression by table: a packed dword (the values at positions a < b of a group of four) becomes the two
+    // dwords of the group's four columns through two byte permutes, whose selectors depend on the metadata nibble
+    // alone: bytes 0, 1 for position a, bytes 2, 3 for position b, the constant zero (selector 12) elsewhere.
+    __shared__ uint2 sSel[16];
 
     const int t = threadIdx.x;
-    const int o0 = blockIdx.y * DP_TILE, i0 = blockIdx.x * DP_TILE;
-    const size_t vpitch = (size_t)d_in / 2, mpitch = (size_t)d_in / 8;
+    // Workgroup -> tile.  A tile's rows of metadata are 16-byte pieces of 128-byte lines, which 8 neighbours along
+    // d_in share on the input side and 8 along d_out on the output side.  Workgroups go to the 8 XCDs in turn and
+    // each XCD has its own L2, so with neighbouring tiles on neighbouring workgroup numbers every XCD fetched every
+    // such line: as many bytes again as the values.  Instead an XCD takes chunks of 8 x 8 neighbouring tiles, whose
+    // rows are 1 KB runs of values in both arrays (measured: 171 -> 157 us at 36864 x 9216; 8 x 4 163, 16 x 8 166,
+    // 8 x 16 161, 8 x 1 180).
+    const uint32_t xcd = blockIdx.x & 7u, slot = blockIdx.x >> 3;
+    const uint32_t chunk = (slot / (DP_CHUNK * DP_CHUNK)) * 8 + xcd, within = slot % (DP_CHUNK * DP_CHUNK);
+    const uint32_t chunks_x = ((uint32_t)tiles_x + DP_CHUNK - 1) / DP_CHUNK;
+    const int tile_x = (int)((chunk % chunks_x) * DP_CHUNK + within % DP_CHUNK);
+    const int tile_y = (int)((chunk / chunks_x) * DP_CHUNK + within / DP_CHUNK);
+    if (tile_x >= tiles_x || tile_y >= tiles_y) return;         // the whole workgroup: padding of the chunked order
+    const int o0 = tile_y * DP_TILE;
+    // Bytes per row: packed W^R values d_in, its metadata (and the mask) d_in / 8; transposed values d_out,
+    // transposed metadata d_out / 8.  Every access goes through a buffer descriptor that covers the tile's rows
+    // of its array: rows past the end of the matrix fall outside the descriptor (loads return 0, stores are
+    // dropped), and a lane whose columns lie past the end of a row gets an offset that no descriptor covers.
+    // No access is under a branch, so the compiler knows how many are in flight at any point.
+    const uint32_t vrow = (uint32_t)d_in, mrow = (uint32_t)d_in / 8, vtrow = (uint32_t)d_out, mtrow = (uint32_t)d_out / 8;
+    const uint32_t rows_o = (uint32_t)min(DP_TILE, d_out - o0);
+    const buffer_t bV = tile_buffer((const uint8_t*)vals + (size_t)o0 * vrow, rows_o * vrow);
+    const buffer_t bM = tile_buffer(meta + (size_t)o0 * mrow, rows_o * mrow);
+    const buffer_t bK = tile_buffer(MASK ? maskrc + (size_t)o0 * mrow : nullptr, MASK ? rows_o * mrow : 0u);
 
-    // phase 1: every lane reads its 2 x (4 rows x 8 columns) of packed W^R and decompresses them in registers:
-    // r[n][k][q] = columns 2q, 2q + 1 of row k as one dword (zeros where W^R has none), cb = candidate bits
-    u32x2 pk[2][4];
-    uint32_t mb[2][4];
+    // A lane's 4 rows x 8 columns of packed W^R: 8 bytes of values and the metadata byte per row.
+    const uint32_t og = t >> 4, i8 = t & 15;
+    const int i0 = tile_x * DP_TILE;
+    const uint32_t rows_i = (uint32_t)min(DP_TILE, d_in - i0);
+    const bool col_ok = i0 + 8 * (int)i8 < d_in;
+    u32x2 pk[4];
+    uint32_t mb[4];
     {
-        const int og = t >> 4, i8 = t & 15;                    // n = 1: 16 row groups (64 rows) further down
-        const int i = i0 + 8 * i8, o = o0 + 4 * og;
-        const bool col_ok = i < d_in;
-        const bf16_t* vp = vals + (size_t)o * vpitch + i / 2;
-        const uint8_t* mp = meta + (size_t)o * mpitch + i / 8;
-#pragma unroll
-        for (int n = 0; n < 2; ++n)
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int row = 64 * n + k;
-                const bool ok = col_ok && o + row < d_out;
-                pk[n][k] = ok ? *(const u32x2*)(vp + (size_t)row * vpitch) : (u32x2){0u, 0u};
-                mb[n][k] = ok ? (uint32_t)mp[(size_t)row * mpitch] : 0x100u;       // 0x100: no candidates
-            }
-    }
-    if (GIVEN) {   // the tile of the given metadata, one nibble per byte: 128 rows (d_in) x 32 groups along d_out
-        int row = t >> 1, half = t & 1;
-        int i = i0 + row, o = o0 + 64 * half;
-        uint2 x = make_uint2(0, 0);
-        if (!RAGGED && i < d_in && o < d_out) x = *(const uint2*)(metaT_in + (size_t)i * ((size_t)d_out / 8) + o / 8);
-        if (RAGGED && i < d_in) {
-            const uint8_t* src = metaT_in + (size_t)i * ((size_t)d_out / 8) + o / 8;
-#pragma unroll
-            for (int q = 0; q < 8; ++q)
-                if (o + 8 * q < d_out) {
-                    if (q < 4) x.x |= (uint32_t)src[q] << (8 * q);
-                    else x.y |= (uint32_t)src[q] << (8 * (q - 4));
-                }
-        }
-        uint8_t* dst = sG + row * DP_NPITCH + 16 * half;
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            dst[q] = (uint8_t)((x.x >> (4 * q)) & 0xFu);
-            dst[8 + q] = (uint8_t)((x.y >> (4 * q)) & 0xFu);
-        }
-        __syncthreads();
-    }
-    uint32_t r[2][4][4], cb[2][4];
-#pragma unroll
-    for (int n = 0; n < 2; ++n)
+        const uint32_t voff = col_ok ? 4u * og * vrow + (uint32_t)i0 + 8u * i8 : NOWHERE;
+        const uint32_t moff = col_ok ? 4u * og * mrow + (uint32_t)i0 / 8 + i8 : NOWHERE;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            uint32_t cand = 0;
-#pragma unroll
-            for (int g = 0; g < 2; ++g) {
-                const uint32_t m = mb[n][k], w = pk[n][k][g];
-                const uint32_t a = (m >> (4 * g)) & 3u, b = (m >> (4 * g + 2)) & 3u;
-                const uint64_t q = ((uint64_t)(w & 0xFFFFu) << (16u * a)) | ((uint64_t)(w >> 16) << (16u * b));
-                r[n][k][2 * g] = (uint32_t)q;
-                r[n][k][2 * g + 1] = (uint32_t)(q >> 32);
-                cand |= ((1u << a) | (1u << b)) << (4 * g);
-            }
-            cb[n][k] = (mb[n][k] >> 8) ? 0u : cand;           // rows and columns outside the matrix compete nowhere
+            pk[k] = __builtin_amdgcn_raw_buffer_load_b64(bV, voff + k * vrow, 0, 0);
+            mb[k] = __builtin_amdgcn_raw_buffer_load_b8(bM, moff + k * mrow, 0, 0);
         }
-    // The kernel is bound by vector ALU work, not by memory (the SIMDs issue vector instructions in over 90 %
-    // of their cycles), so two neighbouring columns are ranked at once in the two 16-bit halves of a register:
-    // a row's dword already holds the pair, keys are at most 0x8000, and "j beats i" is min(k_j -sat k_i, 1).
-    const uint32_t ones = 0x00010001u;
+    }
+    // (the table is filled while the loads are in flight)
+    if (t < 16) {
+        const uint32_t a = t & 3u, b = t >> 2;
+        uint32_t src[4];
 #pragma unroll
-    for (int n = 0; n < 2; ++n) {
-        int u = t + 256 * n, og = u >> 4, i8 = u & 15;
-        uint32_t keep[4] = {0, 0, 0, 0};
-        uint32_t spread[4];                                    // candidate bits: even columns at bits 0, 2, 4, 6, odd ones 16 higher
+        for (uint32_t p = 0; p < 4; ++p) src[p] = p == a ? 0x0100u : (p == b ? 0x0302u : 0x0C0Cu);
+        sSel[t] = make_uint2(src[0] | (src[1] << 16), src[2] | (src[3] << 16));
+    }
+    __syncthreads();
+    if (GIVEN) {   // the tile of the given metadata, one nibble per byte: 128 rows (d_in) x 32 groups along d_out
+        const buffer_t bG = tile_buffer(metaT_in + (size_t)i0 * mtrow, rows_i * mtrow);
+        const uint32_t row = t >> 2, quarter = t & 3;
+        const int o = o0 + 32 * quarter;
+        const uint32_t off = row * mtrow + (uint32_t)o / 8;
+        uint32_t x = 0;
+        if (!RAGGED) {
+            x = __builtin_amdgcn_raw_buffer_load_b32(bG, o < d_out ? off : NOWHERE, 0, 0);
+        } else {
 #pragma unroll
-        for (int k = 0; k < 4; ++k) spread[k] = (cb[n][k] & 0x55u) | ((cb[n][k] & 0xAAu) << 15);
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t byte = __builtin_amdgcn_raw_buffer_load_b8(bG, o + 8 * q < d_out ? off + q : NOWHERE, 0, 0);
+                x |= byte << (8 * q);
+            }
+        }
+        uint8_t* dst = sG + row * DP_NPITCH + 8 * quarter;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {                          // columns 8 i8 + 2 q (low halves) and + 1 (high halves)
-            uint32_t x[4];
+        for (int q = 0; q < 8; ++q) dst[q] = (uint8_t)((x >> (4 * q)) & 0xFu);
+        __syncthreads();
+    }
+    // r[k][q] = the values of columns 2q, 2q + 1 of row k as one dword (zeros where W^R has none);
+    // ky[k][q] = their ranking keys in the same places: magnitude + 1 for a survivor of the row prune, 0 for a
+    // pruned slot, so that survivors outrank every pruned slot, zeros included.  Both come out of the same two
+    // permutes; the keys' source is the packed dword with the signs cleared and 1 added to both halves.  Rows and
+    // columns outside the matrix read as zeros with metadata 0; what is ranked there is never stored (d_out is a
+    // multiple of 4, so a group of four rows is inside or outside as a whole).
+    uint32_t r[4][4], ky[4][4], cb[4];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) x[k] = r[n][k][q];
-            uint32_t set2 = 0;                                 // the two 4-bit sets, at bits 0 and 16
+    for (int k = 0; k < 4; ++k) {
+        const uint32_t m = mb[k];
+        uint32_t cand = 0;
+#pragma unroll
+        for (int g = 0; g < 2; ++g) {
+            const uint32_t w = pk[k][g], nib = (m >> (4 * g)) & 0xFu;
+            const uint2 sel = sSel[nib];
+            r[k][2 * g] = __builtin_amdgcn_perm(0u, w, sel.x);
+            r[k][2 * g + 1] = __builtin_amdgcn_perm(0u, w, sel.y);
             if (!GIVEN) {
-                uint32_t key[4];
-#pragma unroll
-                for (int k = 0; k < 4; ++k)
-                    // magnitude + 1 for a survivor of the row prune, 0 for a pruned slot (whose stored value is +0):
-                    // survivors outrank every pruned slot, zeros included
-                    key[k] = (x[k] & 0x7FFF7FFFu) + ((spread[k] >> (2 * q)) & 0x00010001u);
-                const uint32_t c01 = pk_beats(key[1], key[0], ones), c02 = pk_beats(key[2], key[0], ones),
-                               c03 = pk_beats(key[3], key[0], ones), c12 = pk_beats(key[2], key[1], ones),
-                               c13 = pk_beats(key[3], key[1], ones), c23 = pk_beats(key[3], key[2], ones);
-                // rank = how many of the others come first (larger key, or equal key and lower index); the halves
-                // hold at most 3, so plain 32-bit arithmetic never carries from one into the other
-                const uint32_t r0 = c01 + c02 + c03;
-                const uint32_t r1 = (0x00010001u - c01) + c12 + c13;
-                const uint32_t r2 = (0x00020002u - c02 - c12) + c23;
-                const uint32_t r3 = 0x00030003u - c03 - c13 - c23;
-                // rank 2 or 3 = pruned: bit 1 of the rank
-                const uint32_t out = ((r0 >> 1) & 0x00010001u) | (r1 & 0x00020002u) | ((r2 << 1) & 0x00040004u) |
-                                     ((r3 << 2) & 0x00080008u);
-                set2 = out ^ 0x000F000Fu;
+                const uint32_t kw = (w & 0x7FFF7FFFu) + 0x00010001u;
+                ky[k][2 * g] = __builtin_amdgcn_perm(0u, kw, sel.x);
+                ky[k][2 * g + 1] = __builtin_amdgcn_perm(0u, kw, sel.y);
             }
-            // the four rows' values of either column as one 64-bit word
-            const uint32_t qlo[2] = {__builtin_amdgcn_perm(x[1], x[0], 0x05040100u), __builtin_amdgcn_perm(x[3], x[2], 0x05040100u)};
-            const uint32_t qhi[2] = {__builtin_amdgcn_perm(x[1], x[0], 0x07060302u), __builtin_amdgcn_perm(x[3], x[2], 0x07060302u)};
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int j = 2 * q + h, col = 8 * i8 + j;
-                const uint32_t set = h ? set2 >> 16 : set2 & 0xFu;
-                const uint32_t nib = GIVEN ? sG[col * DP_NPITCH + og] : nibble_of_pair(set);
-                // the values of rows idx0 = nib & 3 and idx1 = nib >> 2: bytes 2 idx, 2 idx + 1 of the eight
-                const uint32_t sel = 0x01000100u + (nib & 3u) * 0x0202u + (((nib >> 2) * 0x0202u) << 16);
-                sO[col * DP_OPITCH + og] = h ? __builtin_amdgcn_perm(qhi[1], qhi[0], sel) : __builtin_amdgcn_perm(qlo[1], qlo[0], sel);
-                if (!GIVEN) sN[col * DP_NPITCH + og] = (uint8_t)nib;
-                if (MASK)
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) keep[k] |= (((set >> k) & 1u) & ((cb[n][k] >> j) & 1u)) << j;
-            }
+            if (MASK) cand |= ((1u << (nib & 3u)) | (1u << (nib >> 2))) << (4 * g);
         }
-        if (MASK) {
-            int i = i0 + 8 * i8;
+        cb[k] = cand;                                             // only the mask output needs the candidate bits
+    }
+    // Two neighbouring columns are ranked at once in the two 16-bit halves of a register: a row's dword already
+    // holds the pair, keys are at most 0x8000, and "j beats i" is min(k_j -sat k_i, 1).
+    const uint32_t ones = 0x00010001u;
+    const uint32_t swz = (i8 >> 3) << 2;                           // = ((column >> 6) << 2)
+    uint32_t keep[4] = {0, 0, 0, 0};
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                int o = o0 + 4 * og + k;
-                if (o < d_out && i < d_in) maskrc[(size_t)o * mpitch + i / 8] = (uint8_t)keep[k];
-            }
+    for (int q = 0; q < 4; ++q) {                                  // columns 8 i8 + 2 q (low halves) and + 1 (high halves)
+        uint32_t x[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) x[k] = r[k][q];
+        uint32_t set2 = 0;                                         // the two 4-bit sets, at bits 0 and 16
+        if (!GIVEN) {
+            uint32_t key[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) key[k] = ky[k][q];
+            const uint32_t c01 = pk_beats(key[1], key[0], ones), c02 = pk_beats(key[2], key[0], ones),
+                           c03 = pk_beats(key[3], key[0], ones), c12 = pk_beats(key[2], key[1], ones),
+                           c13 = pk_beats(key[3], key[1], ones), c23 = pk_beats(key[3], key[2], ones);
+            // rank = how many of the others come first (larger key, or equal key and lower index); the halves
+            // hold at most 3, so plain 32-bit arithmetic never carries from one into the other
+            const uint32_t r0 = c01 + c02 + c03;
+            const uint32_t r1 = (0x00010001u - c01) + c12 + c13;
+            const uint32_t r2 = (0x00020002u - c02 - c12) + c23;
+            const uint32_t r3 = 0x00030003u - c03 - c13 - c23;
+            // rank 2 or 3 = pruned: bit 1 of the rank
+            const uint32_t out = ((r0 >> 1) & 0x00010001u) | (r1 & 0x00020002u) | ((r2 << 1) & 0x00040004u) |
+                                 ((r3 << 2) & 0x00080008u);
+            set2 = out ^ 0x000F000Fu;
         }
+        // the four rows' values of either column as one 64-bit word
+        const uint32_t qlo[2] = {__builtin_amdgcn_perm(x[1], x[0], 0x05040100u), __builtin_amdgcn_perm(x[3], x[2], 0x05040100u)};
+        const uint32_t qhi[2] = {__builtin_amdgcn_perm(x[1], x[0], 0x07060302u), __builtin_amdgcn_perm(x[3], x[2], 0x07060302u)};
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int j = 2 * q + h;
+            const uint32_t col = 8 * i8 + j;
+            const uint32_t set = h ? set2 >> 16 : set2 & 0xFu;
+            const uint32_t nib = GIVEN ? sG[col * DP_NPITCH + og] : nibble_of_pair(set);
+            // the values of rows idx0 = nib & 3 and idx1 = nib >> 2: bytes 2 idx, 2 idx + 1 of the eight
+            const uint32_t sel = 0x01000100u + (nib & 3u) * 0x0202u + (((nib >> 2) * 0x0202u) << 16);
+            // a wave's 16 columns x 4 row groups: columns 64 apart would share banks, so the upper 64 swap
+            // neighbouring fours of row groups
+            sO[col * DP_OPITCH + (og ^ swz)] = h ? __builtin_amdgcn_perm(qhi[1], qhi[0], sel) : __builtin_amdgcn_perm(qlo[1], qlo[0], sel);
+            if (!GIVEN) sN[col * DP_NPITCH + (og ^ swz)] = (uint8_t)nib;
+            if (MASK)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) keep[k] |= (((set >> k) & 1u) & ((cb[k] >> j) & 1u)) << j;
+        }
+    }
+    if (MASK) {
+        const uint32_t off = col_ok ? 4u * og * mrow + (uint32_t)i0 / 8 + i8 : NOWHERE;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) __builtin_amdgcn_raw_buffer_store_b8((uint8_t)keep[k], bK, off + k * mrow, 0, 0);
     }
     __syncthreads();
 
-    // phase 3: coalesced write of packed (W^{R,C})^T rows
-    const size_t vtp = (size_t)d_out / 2, mtp = (size_t)d_out / 8;
-#pragma unroll
-    for (int n = 0; n < 4; ++n) {
-        int idx = t + 256 * n, row = idx >> 3, c = idx & 7;
-        int i = i0 + row, o = o0 + 16 * c;
-        if (i < d_in && o < d_out) {
-            const uint32_t* src = sO + row * DP_OPITCH + 4 * c;
-            if (!RAGGED) {
-                *(uint4*)(valsT + (size_t)i * vtp + o / 2) = make_uint4(src[0], src[1], src[2], src[3]);
-            } else {
-                *(uint2*)(valsT + (size_t)i * vtp + o / 2) = make_uint2(src[0], src[1]);
-                if (o + 8 < d_out) *(uint2*)(valsT + (size_t)i * vtp + o / 2 + 4) = make_uint2(src[2], src[3]);
-            }
-        }
-    }
-    if (GIVEN) return;
+    // coalesced write of packed (W^{R,C})^T rows
+    const buffer_t bVT = tile_buffer((uint8_t*)valsT + (size_t)i0 * vtrow, rows_i * vtrow);
 #pragma unroll
     for (int n = 0; n < 2; ++n) {
-        int idx = t + 256 * n, row = idx >> 2, c = idx & 3;
-        int i = i0 + row, o = o0 + 32 * c;
-        if (i < d_in && o < d_out) {
-            const uint32_t* src = (const uint32_t*)(sN + row * DP_NPITCH + 8 * c);
-            uint32_t x = src[0], y = src[1];
-            uint32_t lo = (x & 0xFu) | ((x >> 4) & 0xF0u) | ((x >> 8) & 0xF00u) | ((x >> 12) & 0xF000u);
-            uint32_t hi = (y & 0xFu) | ((y >> 4) & 0xF0u) | ((y >> 8) & 0xF00u) | ((y >> 12) & 0xF000u);
-            const uint32_t word = lo | (hi << 16);
-            if (!RAGGED) {
-                *(uint32_t*)(metaT + (size_t)i * mtp + o / 8) = word;
-            } else {
+        const uint32_t idx = t + DP_THREADS * n, row = idx >> 3, c = idx & 7;
+        const int o = o0 + 16 * c;
+        const uint32_t* src = sO + row * DP_OPITCH + 4 * (c ^ (row >> 6));
+        const uint32_t off = row * vtrow + (uint32_t)o;
+        if (!RAGGED) {
+            __builtin_amdgcn_raw_buffer_store_b128((u32x4){src[0], src[1], src[2], src[3]}, bVT, o < d_out ? off : NOWHERE, 0, 0);
+        } else {
+            __builtin_amdgcn_raw_buffer_store_b64((u32x2){src[0], src[1]}, bVT, o < d_out ? off : NOWHERE, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b64((u32x2){src[2], src[3]}, bVT, o + 8 < d_out ? off + 8 : NOWHERE, 0, 0);
+        }
+    }
+    if (!GIVEN) {
+        const buffer_t bMT = tile_buffer(metaT + (size_t)i0 * mtrow, rows_i * mtrow);
+        const uint32_t row = t >> 2, c = t & 3;
+        const int o = o0 + 32 * c;
+        const uint32_t* src = (const uint32_t*)(sN + row * DP_NPITCH + 8 * c);
+        const uint32_t x = src[row >> 6], y = src[1 - (row >> 6)];
+        const uint32_t lo = (x & 0xFu) | ((x >> 4) & 0xF0u) | ((x >> 8) & 0xF00u) | ((x >> 12) & 0xF000u);
+        const uint32_t hi = (y & 0xFu) | ((y >> 4) & 0xF0u) | ((y >> 8) & 0xF00u) | ((y >> 12) & 0xF000u);
+        const uint32_t word = lo | (hi << 16);
+        const uint32_t off = row * mtrow + (uint32_t)o / 8;
+        if (!RAGGED) {
+            __builtin_amdgcn_raw_buffer_store_b32(word, bMT, o < d_out ? off : NOWHERE, 0, 0);
+        } else {
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    if (o + 8 * q < d_out) metaT[(size_t)i * mtp + o / 8 + q] = (uint8_t)(word >> (8 * q));
-            }
+            for (int q = 0; q < 4; ++q)
+                __builtin_amdgcn_raw_buffer_store_b8((uint8_t)(word >> (8 * q)), bMT, o + 8 * q < d_out ? off + q : NOWHERE, 0, 0);
         }
     }
 }
 
+// Grid of the chunked tile order: whole chunks of 8 x 8 tiles, a multiple of 8 chunks (one per XCD); workgroups
+// whose tile lies outside the matrix leave at once.
+static dim3 double_prune_grid(int64_t tiles_x, int64_t tiles_y) {
+    const int64_t chunks = ((tiles_x + DP_CHUNK - 1) / DP_CHUNK) * ((tiles_y + DP_CHUNK - 1) / DP_CHUNK);
+    return dim3((unsigned)(((chunks + 7) / 8) * 8 * DP_CHUNK * DP_CHUNK));
+}
+
 hipError_t launch_double_prune(const bf16_t* vals, const uint8_t* meta, int64_t d_out, int64_t d_in, bf16_t* valsT,
                                uint8_t* metaT, uint8_t* maskrc, hipStream_t s) {
-    dim3 grid((unsigned)((d_in + DP_TILE - 1) / DP_TILE), (unsigned)((d_out + DP_TILE - 1) / DP_TILE));
+    const int64_t tiles_x = (d_in + DP_TILE - 1) / DP_TILE, tiles_y = (d_out + DP_TILE - 1) / DP_TILE;
+    const dim3 grid = double_prune_grid(tiles_x, tiles_y);
+    if (d_in > DP_EXTENT_MAX || d_out > DP_EXTENT_MAX) return hipErrorInvalidValue;
     const bool ragged = d_out % 32 != 0;
     if (ragged && maskrc)
-        double_prune_kernel<false, true, true><<<grid, dim3(256), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT,
-                                                                          metaT, maskrc, nullptr);
+        double_prune_kernel<false, true, true><<<grid, dim3(DP_THREADS), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT,
+                                                                          metaT, maskrc, nullptr, (int)tiles_x, (int)tiles_y);
     else if (ragged)
-        double_prune_kernel<false, false, true><<<grid, dim3(256), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT,
-                                                                           metaT, nullptr, nullptr);
+        double_prune_kernel<false, false, true><<<grid, dim3(DP_THREADS), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT,
+                                                                           metaT, nullptr, nullptr, (int)tiles_x, (int)tiles_y);
     else if (maskrc)
-        double_prune_kernel<false, true, false><<<grid, dim3(256), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT,
-                                                                           metaT, maskrc, nullptr);
+        double_prune_kernel<false, true, false><<<grid, dim3(DP_THREADS), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT,
+                                                                           metaT, maskrc, nullptr, (int)tiles_x, (int)tiles_y);
     else
-        double_prune_kernel<false, false, false><<<grid, dim3(256), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT,
-                                                                            metaT, nullptr, nullptr);
+        double_prune_kernel<false, false, false><<<grid, dim3(DP_THREADS), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT,
+                                                                            metaT, nullptr, nullptr, (int)tiles_x, (int)tiles_y);
     return hipGetLastError();
 }
 
 // Values of packed (W^{R,C})^T from new packed values of W^R, metadata of both unchanged.
 hipError_t launch_update_transposed(const bf16_t* vals, const uint8_t* meta, int64_t d_out, int64_t d_in,
                                     const uint8_t* metaT, bf16_t* valsT, hipStream_t s) {
-    dim3 grid((unsigned)((d_in + DP_TILE - 1) / DP_TILE), (unsigned)((d_out + DP_TILE - 1) / DP_TILE));
+    const int64_t tiles_x = (d_in + DP_TILE - 1) / DP_TILE, tiles_y = (d_out + DP_TILE - 1) / DP_TILE;
+    const dim3 grid = double_prune_grid(tiles_x, tiles_y);
+    if (d_in > DP_EXTENT_MAX || d_out > DP_EXTENT_MAX) return hipErrorInvalidValue;
     if (d_in % 16 != 0 || d_out % 64 != 0)
-        double_prune_kernel<true, false, true><<<grid, dim3(256), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT,
-                                                                          nullptr, nullptr, metaT);
+        double_prune_kernel<true, false, true><<<grid, dim3(DP_THREADS), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT,
+                                                                          nullptr, nullptr, metaT, (int)tiles_x, (int)tiles_y);
     else
-        double_prune_kernel<true, false, false><<<grid, dim3(256), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT,
-                                                                           nullptr, nullptr, metaT);
+        double_prune_kernel<true, false, false><<<grid, dim3(DP_THREADS), 0, s>>>(vals, meta, (int)d_out, (int)d_in, valsT,
+                                                                           nullptr, nullptr, metaT, (int)tiles_x, (int)tiles_y);
     return hipGetLastError();
 }
 

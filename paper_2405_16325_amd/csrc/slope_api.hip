@@ -141,7 +141,8 @@ slope_status slope_prune_rows(const void* W, int64_t d_out, int64_t d_in, int n,
 slope_status slope_double_prune(const void* Wr_vals, const void* Wr_meta, int64_t d_out, int64_t d_in,
                                 void* WrcT_vals, void* WrcT_meta, void* maskrc_or_null, void* stream) {
     if (!Wr_vals || !Wr_meta || !WrcT_vals || !WrcT_meta) return SLOPE_ERR_NULL;
-    if (bad_extent(d_out, 8) || bad_extent(d_in, 8)) return SLOPE_ERR_SHAPE;
+    if (bad_extent(d_out, 8) || bad_extent(d_in, 8) || d_out > DP_EXTENT_MAX || d_in > DP_EXTENT_MAX)
+        return SLOPE_ERR_SHAPE;
     if (misaligned(Wr_vals, 16) || misaligned(Wr_meta, 16) || misaligned(WrcT_vals, 16) ||
         misaligned(WrcT_meta, 16) || misaligned(maskrc_or_null, 16))
         return SLOPE_ERR_ALIGN;
@@ -411,7 +412,8 @@ slope_status slope_sparse_add(const void* A_vals, const void* B_vals, int64_t ro
 slope_status slope_update_sparse(const void* Wnew_vals, const void* Wr_meta, int64_t d_out, int64_t d_in,
                                  void* Wr_vals, const void* WrcT_meta, void* WrcT_vals, void* stream) {
     if (!Wnew_vals || !Wr_meta || !Wr_vals || !WrcT_meta || !WrcT_vals) return SLOPE_ERR_NULL;
-    if (bad_extent(d_out, 8) || bad_extent(d_in, 8)) return SLOPE_ERR_SHAPE;
+    if (bad_extent(d_out, 8) || bad_extent(d_in, 8) || d_out > DP_EXTENT_MAX || d_in > DP_EXTENT_MAX)
+        return SLOPE_ERR_SHAPE;
     if (misaligned(Wnew_vals, 16) || misaligned(Wr_meta, 16) || misaligned(Wr_vals, 16) ||
         misaligned(WrcT_meta, 16) || misaligned(WrcT_vals, 16))
         return SLOPE_ERR_ALIGN;
