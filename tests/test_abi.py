@@ -55,6 +55,8 @@ def test_argument_errors_are_reported_before_launch():
     assert lib.slope_prune_rows(p, 64, 64, 2, 4, odd, p, None, None) == E.SLOPE_ERR_ALIGN
     assert lib.slope_double_prune(p, p, 64, 100, p, p, None, None) == E.SLOPE_ERR_SHAPE
     assert lib.slope_double_prune(p, p, 68, 64, p, p, None, None) == E.SLOPE_ERR_SHAPE
+    assert lib.slope_double_prune(p, p, 64, (1 << 23) + 8, p, p, None, None) == E.SLOPE_ERR_SHAPE   # 2^23 at most
+    assert lib.slope_double_prune(p, p, (1 << 23) + 8, 64, p, p, None, None) == E.SLOPE_ERR_SHAPE
     assert lib.slope_double_prune(p, None, 64, 64, p, p, None, None) == E.SLOPE_ERR_NULL
     assert lib.slope_spmm_fwd(p, 0, p, p, 64, 64, None, None, 0, p, None, None) == E.SLOPE_ERR_SHAPE
     assert lib.slope_spmm_fwd(p, 8, p, p, 64, 64, p, p, 48, p, p, None) == E.SLOPE_ERR_UNSUPPORTED
@@ -124,6 +126,7 @@ def test_argument_errors_are_reported_before_launch():
     assert lib.slope_sparse_add(p, p, 4, 64, 1.0, 1.0, odd, None) == E.SLOPE_ERR_ALIGN
     assert lib.slope_update_sparse(p, p, 64, 64, p, None, p, None) == E.SLOPE_ERR_NULL
     assert lib.slope_update_sparse(p, p, 64, 100, p, p, p, None) == E.SLOPE_ERR_SHAPE
+    assert lib.slope_update_sparse(p, p, 64, (1 << 23) + 8, p, p, p, None) == E.SLOPE_ERR_SHAPE
     assert lib.slope_update_sparse(p, p, 64, 64, p, p, odd, None) == E.SLOPE_ERR_ALIGN
     assert b"NULL" in lib.slope_status_string(E.SLOPE_ERR_NULL)
 

@@ -60,7 +60,7 @@ def test_sparse_add_in_place_and_same_operand():
 
 
 UPDATE_CASES = [(64, 64, False), (3072, 768, False), (448, 320, False), (320, 192, True), (4160, 256, False),
-                (192, 4160, False), (1024, 1280, False)]
+                (192, 4160, False), (1024, 1280, False), (1344, 1168, False), (1160, 1288, False)]
 
 
 @pytest.mark.parametrize("d_out,d_in,coarse", UPDATE_CASES)

@@ -73,6 +73,9 @@ DP_CASES = [
     ("cfg1_fc1", lambda: inputs.gaussian_bf16((3072, 768), 0.02, 0, 2)),
     ("one_tile_part", lambda: inputs.gaussian_bf16((64, 64), 0.02, 5, 2)),
     ("ragged_tiles", lambda: inputs.gaussian_bf16((192, 320), 0.02, 6, 2)),
+    # more than one chunk of 8 x 8 tiles in both directions, the last chunks partly outside the matrix
+    ("many_chunks", lambda: inputs.gaussian_bf16((1312, 1160), 0.02, 8, 2)),
+    ("many_chunks_byte_rows", lambda: inputs.gaussian_bf16((1160, 1288), 0.02, 9, 2)),
     ("ties", lambda: inputs.coarse_weights(320, 192, 7)),
     ("zeros", lambda: np.zeros((128, 64), dtype=np.uint16)),
     ("special", special_weights),
