@@ -306,8 +306,10 @@ slope_status slope_update_sparse(const void* Wnew_vals, const void* Wr_meta, int
  * pin the regimes.  plan: host int32[6]
  *   [0] product: 0 small-batch kernel (one pass over the packed weight), 1 tile kernel with the
  *       contraction split into slabs (needs the workspace), 2 tile kernel, 3 generic kernel
- *       (d_in not a multiple of 256; not a multiple of 64: its form for ragged rows)
- *   [1], [2] weight rows and tokens per workgroup      [3] slabs (1 = no split)
+ *       (d_in not a multiple of 256; not a multiple of 64: its form for ragged rows), 4 small-batch
+ *       kernel in its row-split form (d_in a multiple of 1024 and enough weight rows, or the
+ *       workspace to cut the contraction into slices)
+ *   [1], [2] weight rows and tokens per workgroup      [3] slabs or slices (1 = no split)
  *   [4] T = X L: 0 no adapter, 1 split over d_in from L as stored (few tokens),
  *       2 dense tile kernel, 3 dense tile kernel split over d_in, 4 plain arithmetic (d_in % 64 != 0)
  *   [5] chunks of 64 rows of L per workgroup for [4] == 1

@@ -47,8 +47,13 @@ hipError_t launch_spmm_slabs(const bf16_t* B, int64_t n, const bf16_t* A_vals, c
 // the same product for n <= 32 tokens (any K % 64 == 0, K >= 128); adapters as T[n, K2] and R[K2, m] as stored
 constexpr int64_t STREAM_MAX_TOKENS = 32;
 inline bool spmm_stream_fits(int64_t n, int64_t K) { return n <= STREAM_MAX_TOKENS && K >= 128 && K % 64 == 0; }
+// (K % 1024 == 0 and enough rows: the row-split kernel, with the contraction cut into spmm_rows_slices slices when
+// there is scratch for the partial sums, spmm_rows_partial_bytes of it; 0 slices = not this kernel)
+int spmm_rows_slices(int64_t n, int64_t m, int64_t K, bool with_partial);
+size_t spmm_rows_partial_bytes(int64_t n, int64_t m, int64_t K);
 hipError_t launch_spmm_stream(const bf16_t* B, int64_t n, const bf16_t* A_vals, const uint8_t* A_meta, int64_t m,
-                              int64_t K, const bf16_t* T, const bf16_t* R, int64_t K2, bf16_t* C, hipStream_t s);
+                              int64_t K, const bf16_t* T, const bf16_t* R, int64_t K2, bf16_t* C, float* partial_or_null,
+                              hipStream_t s);
 // T = X L for few tokens (n <= XL_SMALL_MAX_TOKENS), split over d_in with fp32 partial sums in `scratch`
 constexpr int64_t XL_SMALL_MAX_TOKENS = 512;
 size_t xl_small_scratch_bytes(int64_t n, int64_t d_in, int64_t r);

@@ -88,7 +88,9 @@ size_t slope_mask_bytes(int64_t rows, int64_t cols) { return slope_packed_meta_b
 
 size_t slope_spmm_fwd_workspace_bytes(int64_t b, int64_t d_in, int64_t d_out, int64_t r) {
     if (b <= 0 || d_in <= 0 || d_out <= 0) return 0;
-    return adapter_workspace_bytes(b, d_in, d_out, r) + round256(spmm_slab_bytes(b, d_out, d_in));
+    // the slabs of mid-size batches or the slices of inference-size ones: never both
+    return adapter_workspace_bytes(b, d_in, d_out, r) + round256(spmm_slab_bytes(b, d_out, d_in)) +
+           round256(spmm_rows_partial_bytes(b, d_out, d_in));
 }
 
 size_t slope_token_copy_bytes(int64_t b, int64_t d) {
@@ -190,9 +192,13 @@ static slope_status spmm_fwd_run(const void* X, int64_t b, const void* Wr_vals, 
                                b > XL_SMALL_MAX_TOKENS && dense_tn_plain_partial_bytes(b, r) ? partial : nullptr, s);
         if (e != hipSuccess) return finish(e);
     }
-    if (spmm_stream_fits(b, d_in))                            // inference-size batch: one HBM-bound pass over the packed weight
+    if (spmm_stream_fits(b, d_in)) {                          // inference-size batch: one HBM-bound pass over the packed weight
+        float* slices = workspace && spmm_rows_partial_bytes(b, d_out, d_in)
+                            ? (float*)(ws + adapter_workspace_bytes(b, d_in, d_out, adapter ? r : 0)) : nullptr;
         return finish(launch_spmm_stream(x, b, wv, wm, d_out, d_in, adapter ? T : nullptr,
-                                         adapter ? (const bf16_t*)R_or_null : nullptr, adapter ? r : 0, (bf16_t*)Y, s));
+                                         adapter ? (const bf16_t*)R_or_null : nullptr, adapter ? r : 0, (bf16_t*)Y,
+                                         slices, s));
+    }
     // With scratch memory a batch of a few dozen to a few hundred tokens is split over K as well.
     float* slabs = workspace && spmm_slab_count(b, d_out, d_in) > 0
                        ? (float*)(ws + adapter_workspace_bytes(b, d_in, d_out, adapter ? r : 0)) : nullptr;
@@ -281,7 +287,7 @@ slope_status slope_spmm_bwd_x(const void* dY, int64_t b, const void* WrcT_vals, 
     // sparse rows = d_in, contraction over d_out
     if (spmm_stream_fits(b, d_out))
         return finish(launch_spmm_stream((const bf16_t*)dY, b, (const bf16_t*)WrcT_vals, (const uint8_t*)WrcT_meta,
-                                         d_in, d_out, nullptr, nullptr, 0, (bf16_t*)dX, (hipStream_t)stream));
+                                         d_in, d_out, nullptr, nullptr, 0, (bf16_t*)dX, nullptr, (hipStream_t)stream));
     return finish(launch_spmm((const bf16_t*)dY, b, (const bf16_t*)WrcT_vals, (const uint8_t*)WrcT_meta, d_in, d_out,
                               nullptr, nullptr, 0, (bf16_t*)dX, (hipStream_t)stream));
 }
@@ -434,9 +440,11 @@ slope_status slope_spmm_fwd_plan(int64_t b, int64_t d_in, int64_t d_out, int64_t
     for (int i = 0; i < 6; ++i) plan[i] = 0;
     plan[3] = 1;
     if (spmm_stream_fits(b, d_in)) {
-        plan[0] = 0;
-        plan[1] = spmm_stream_rows(b, d_out, d_in);
+        const int slices = spmm_rows_slices(b, d_out, d_in, with_workspace != 0);
+        plan[0] = slices > 0 ? 4 : 0;
+        plan[1] = slices > 0 ? 48 : spmm_stream_rows(b, d_out, d_in);
         plan[2] = b <= 16 ? 16 : 32;
+        if (slices > 0) plan[3] = slices;
     } else {
         const int slabs = with_workspace ? spmm_slab_count(b, d_out, d_in) : 0;
         int bm, bn;

@@ -259,6 +259,230 @@ hipError_t launch_stream_lds(const bf16_t* B, int64_t n, const bf16_t* Av, const
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------
+// The row-split form of the same product, for contractions that are whole multiples of 1024 (16 k-steps: the
+// metadata of a row then comes in whole 128-byte lines).  What the kernel above pays for beyond the weight's own
+// bytes is the rest of its load mix: every wavefront loads its own copy of the token operand (two thirds as many
+// requests as the values) and a 16-byte piece of metadata per row and pair of k-steps (as many requests again, each
+// for an eighth of a line).  Here a workgroup of three wavefronts owns 48 weight rows, every wavefront its own 16 of
+// them over the workgroup's whole share of the contraction, so that
+//   - the token operand of a pair of k-steps is loaded once per workgroup into a shared ring (the wavefronts deal
+//     its loads among themselves; one barrier per pair),
+//   - metadata is loaded a whole line per row at a time, for 8 pairs,
+//   - a wavefront's accumulators are complete sums: no reduction across wavefronts,
+//   - the rings are 3 pairs deep and small (42 KiB per workgroup for up to 16 tokens), so three workgroups share a
+//     compute unit and cover each other's first loads and epilogues.  (The loads alone stream fastest with a ring of
+//     8 pairs, 62 us against 65 us at 36864 x 9216, and 73 us for the mix of the kernel above; but then one workgroup
+//     fills a compute unit, and the whole kernel took 83 us where this takes 76 us.)
+// Few weight rows would leave most compute units without a workgroup; then the contraction is cut into slices
+// (blockIdx.y) of whole chunks of 8 pairs, each leaving fp32 partial sums that rows_sum_kernel adds in slice order.
+// About 768 workgroups, one round of three per compute unit, measured best (512: +10 % time, 1024 and more: +5-10 %).
+// 36864 x 9216 at 16 tokens, rank-128 adapters: 91 -> 78 us; 9216 x 36864: 107 -> 85 us; without adapters 67 and 72 us
+// (5.7 and 5.3 TB/s of packed weight).
+constexpr int ROWS_WAVES = 3, ROWS_DEPTH = 3, ROWS_BM = 16 * ROWS_WAVES;
+template <int NF>
+struct RowsLds {
+    static constexpr int A_STAGE = 2048;                      // 16 rows x 128 B: both steps of a pair
+    static constexpr int M_SLOT = 2048;                       // 16 rows x 128 B: the metadata of 8 pairs
+    static constexpr int WAVE_BYTES = ROWS_DEPTH * A_STAGE + 2 * M_SLOT;
+    static constexpr int X_OPS = 4 * NF;                      // 1 KiB loads per pair: 2 steps x NF fragments x 2 halves
+    static constexpr int X_STAGE = X_OPS * 1024;
+    static constexpr int TOTAL = ROWS_WAVES * WAVE_BYTES + ROWS_DEPTH * X_STAGE;
+};
+
+// The main loop of one wavefront.  XW = how many of the pair's X_OPS token loads this wavefront issues, so that the
+// number of its loads per pair, 2 + XW, is a constant the s_waitcnt immediates can be built from.
+template <int NF, int XW>
+__device__ __forceinline__ void rows_main_loop(const uint8_t* const (&a_src)[2], const uint8_t* const (&m_src)[2],
+                                               const uint8_t* const (&b_src)[NF][2], int wave, uint8_t* mine,
+                                               uint8_t* xring, int pair0, int npairs, int l16, int lq,
+                                               f32x4 (&acc)[NF]) {
+    using S = RowsLds<NF>;
+    constexpr int L = 2 + XW;                                 // loads per pair (the metadata loads come on top, every 8th pair)
+    const int sw = (l16 >> 1) & 7;
+    // pair q of this slice (late ones clamped to the last, so that every call issues its L loads) into stage q % DEPTH
+    auto issue = [&](int q) {
+        const int p = pair0 + (q < npairs ? q : npairs - 1);
+        uint8_t* st = mine + (q % ROWS_DEPTH) * S::A_STAGE;
+        dma16(a_src[0] + (size_t)p * 128, st);
+        dma16(a_src[1] + (size_t)p * 128, st + 1024);
+        uint8_t* xs = xring + (q % ROWS_DEPTH) * S::X_STAGE;
+#pragma unroll
+        for (int x = 0; x < S::X_OPS; ++x)                    // load x = (step e, fragment j, half h), dealt in turn
+            if (x % ROWS_WAVES == wave) {
+                const int e = x / (2 * NF), j = (x / 2) % NF, h = x & 1;
+                dma16(b_src[j][h] + ((size_t)2 * p + e) * 128, xs + x * 1024);
+            }
+    };
+    auto issue_meta = [&](int c) {                            // chunk c of 8 pairs of this slice (clamped) into slot c & 1
+        const int chunks = npairs / 8;
+        const int pc = pair0 / 8 + (c < chunks ? c : chunks - 1);
+        uint8_t* ms = mine + ROWS_DEPTH * S::A_STAGE + (c & 1) * S::M_SLOT;
+        dma16(m_src[0] + (size_t)pc * 128, ms);
+        dma16(m_src[1] + (size_t)pc * 128, ms + 1024);
+    };
+    issue_meta(0);
+#pragma unroll
+    for (int q = 0; q < ROWS_DEPTH - 1; ++q) issue(q);
+    for (int q = 0; q < npairs; ++q) {
+        // Pair q has landed (and the metadata chunk it needs, which is older) once at most the loads of the
+        // DEPTH - 2 younger pairs are outstanding; a metadata load among those only makes the wait stricter.
+        WAIT_HERE(waitcnt_imm((ROWS_DEPTH - 2) * L, 15));
+        wg_barrier();                                         // everybody's share of the pair's tokens has landed, and
+                                                              // everybody is done reading the stage refilled next
+        issue(q + ROWS_DEPTH - 1);
+        if ((q & 7) == 0) issue_meta(q / 8 + 1);
+        const uint8_t* st = mine + (q % ROWS_DEPTH) * S::A_STAGE;
+        const uint8_t* xs = xring + (q % ROWS_DEPTH) * S::X_STAGE;
+        const uint8_t* ms = mine + ROWS_DEPTH * S::A_STAGE + ((q >> 3) & 1) * S::M_SLOT;
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            StB b[NF];
+#pragma unroll
+            for (int j = 0; j < NF; ++j) {
+                b[j].u[0] = *(const u32x4*)(xs + (e * NF + j) * 2048 + l16 * 128 + ((lq ^ sw) * 16));
+                b[j].u[1] = *(const u32x4*)(xs + (e * NF + j) * 2048 + l16 * 128 + (((4 + lq) ^ sw) * 16));
+            }
+            StA a;
+            a.u = *(const u32x4*)(st + l16 * 128 + (((4 * e + lq) ^ sw) * 16));
+            const int idx = *(const uint16_t*)(ms + l16 * 128 + (((q & 7) ^ sw) * 16) + 8 * e + 2 * lq);
+#pragma unroll
+            for (int j = 0; j < NF; ++j) acc[j] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a.v, b[j].v, acc[j], idx, 0, 0);
+        }
+    }
+    WAIT_HERE(waitcnt_imm(0, 15));                            // drain the clamped look-ahead loads
+}
+
+// K % 1024 == 0.  blockIdx.x: block of 48 weight rows; blockIdx.y: slice of slice_pairs pairs of k-steps (a multiple of
+// 8).  partial == nullptr (one slice): C bf16[n][m]; else fp32 sums into partial[slice][n][m].  The adapter term is
+// added by slice 0.
+template <int NF>
+__global__ void __launch_bounds__(ROWS_WAVES * 64) spmm_rows_kernel(const bf16_t* __restrict__ B, int n,
+                                                                   const bf16_t* __restrict__ Av,
+                                                                   const uint8_t* __restrict__ Am, int m, int K,
+                                                                   const bf16_t* __restrict__ T,
+                                                                   const bf16_t* __restrict__ R, int K2,
+                                                                   bf16_t* __restrict__ C, float* __restrict__ partial,
+                                                                   int slice_pairs) {
+    using S = RowsLds<NF>;
+    extern __shared__ __align__(16) uint8_t smem[];
+    const int t = threadIdx.x, lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int l16 = lane & 15, lq = lane >> 4;
+    const int m0 = blockIdx.x * ROWS_BM, mw = m0 + 16 * wave;   // the workgroup's and the wavefront's first row
+    const int kpairs = K / 128;
+    const int pair0 = blockIdx.y * slice_pairs;
+    const int npairs = kpairs - pair0 < slice_pairs ? kpairs - pair0 : slice_pairs;   // > 0 by the launch's grid
+    uint8_t* const mine = smem + wave * S::WAVE_BYTES;
+    uint8_t* const xring = smem + ROWS_WAVES * S::WAVE_BYTES;
+
+    // loader lanes: 8 lanes per row, the 16-byte pieces of a line rotated by (row / 2) % 8; rows and tokens past
+    // the end are read from the last one and never stored
+    const int ld_row = lane >> 3, ld_slot = lane & 7;
+    const uint8_t* a_src[2];
+    const uint8_t* m_src[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int rl = 8 * h + ld_row;
+        const int row = mw + rl < m ? mw + rl : m - 1;
+        a_src[h] = (const uint8_t*)Av + (size_t)row * K + ((ld_slot ^ ((rl >> 1) & 7)) * 16);
+        m_src[h] = Am + (size_t)row * (K / 8) + ((ld_slot ^ ((rl >> 1) & 7)) * 16);
+    }
+    const uint8_t* b_src[NF][2];
+#pragma unroll
+    for (int j = 0; j < NF; ++j)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int rl = 8 * h + ld_row;
+            const int tok = 16 * j + rl < n ? 16 * j + rl : n - 1;
+            b_src[j][h] = (const uint8_t*)B + (size_t)tok * K * 2 + ((ld_slot ^ ((rl >> 1) & 7)) * 16);
+        }
+    f32x4 acc[NF];
+#pragma unroll
+    for (int j = 0; j < NF; ++j) acc[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    // the token loads of a pair go to the wavefronts in turn: wavefront w issues those with x % 3 == w
+    constexpr int XW0 = (S::X_OPS + 2) / 3, XW1 = (S::X_OPS + 1) / 3, XW2 = S::X_OPS / 3;
+    if (wave == 0) rows_main_loop<NF, XW0>(a_src, m_src, b_src, 0, mine, xring, pair0, npairs, l16, lq, acc);
+    else if (wave == 1) rows_main_loop<NF, XW1>(a_src, m_src, b_src, 1, mine, xring, pair0, npairs, l16, lq, acc);
+    else rows_main_loop<NF, XW2>(a_src, m_src, b_src, 2, mine, xring, pair0, npairs, l16, lq, acc);
+    __syncthreads();                                          // the rings are free
+
+    // Adapter term T R on dense MFMA, as in the kernel above: chunks of 128 of the rank, T and the workgroup's
+    // tile of R (as stored, k-major) staged in the rings, R read back with the transposing LDS read.  Wavefront w
+    // owns the fragments of its 16 rows and adds them to its accumulators.
+    if (K2 > 0 && blockIdx.y == 0) {
+        constexpr int TP = 128 * 2 + 16, RP = 160;            // bytes per staged row of T and of R's tile
+        constexpr int SEG = ROWS_BM / 8;                      // 16-byte segments per row of R's tile
+        static_assert(16 * NF * TP + 128 * RP <= S::TOTAL, "adapter operands fit in the rings");
+        uint8_t* const t_lds = smem;                          // [16 NF tokens][TP]
+        uint8_t* const r_lds = smem + 16 * NF * TP;           // [128 k][RP]
+        for (int kc = 0; kc < K2; kc += 128) {
+            const int kn = K2 - kc < 128 ? K2 - kc : 128;     // a multiple of 32
+            for (int idx = t; idx < 16 * NF * 16; idx += ROWS_WAVES * 64) {
+                int tok = idx >> 4, pc = idx & 15;
+                u32x4 v = {0u, 0u, 0u, 0u};
+                if (tok < n && pc * 8 < kn) v = *(const u32x4*)(T + (size_t)tok * K2 + kc + pc * 8);
+                *(u32x4*)(t_lds + tok * TP + pc * 16) = v;
+            }
+            for (int idx = t; idx < 128 * SEG; idx += ROWS_WAVES * 64) {
+                int k = idx / SEG, sg = idx % SEG;
+                u32x4 v = {0u, 0u, 0u, 0u};
+                if (k < kn && m0 + 8 * sg < m) v = *(const u32x4*)(R + (size_t)(kc + k) * m + m0 + 8 * sg);
+                *(u32x4*)(r_lds + k * RP + sg * 16) = v;
+            }
+            __syncthreads();
+            const uint8_t* ra = r_lds + (8 * lq + (l16 >> 2)) * RP + 2 * (16 * wave + 4 * (l16 & 3));
+#pragma unroll
+            for (int j = 0; j < NF; ++j) {
+                const uint8_t* tb = t_lds + (16 * j + l16) * TP + lq * 16;
+                for (int ks = 0; ks * 32 < kn; ++ks) {
+                    union { s16x4 h[2]; bf16x8 v; } a;
+                    a.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (s16x4 __attribute__((address_space(3)))*)(ra + ks * 32 * RP));
+                    a.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (s16x4 __attribute__((address_space(3)))*)(ra + (ks * 32 + 4) * RP));
+                    StA b;
+                    b.u = *(const u32x4*)(tb + ks * 64);
+                    acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, acc[j], 0, 0, 0);
+                }
+            }
+            __syncthreads();                                  // before the next chunk overwrites the operands
+        }
+    }
+
+    // lane (l16, lq) holds token 16 j + l16, rows mw + 4 lq .. + 3 (m is a multiple of 8: the four are inside or outside together)
+    const int row = mw + 4 * lq;
+#pragma unroll
+    for (int j = 0; j < NF; ++j) {
+        const int tok = 16 * j + l16;
+        if (tok >= n || row >= m) continue;
+        if (partial) {
+            *(f32x4*)(partial + ((size_t)blockIdx.y * n + tok) * m + row) = acc[j];
+        } else {
+            union { __bf16 h[4]; u32x2 u; } o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o.h[e] = (__bf16)acc[j][e];
+            *(u32x2*)(C + (size_t)tok * m + row) = o.u;
+        }
+    }
+}
+
+// C = the slices' partial sums added in slice order (bit-identical runs), rounded to bf16; four elements per lane
+__global__ void __launch_bounds__(256) rows_sum_kernel(const f32x4* __restrict__ P, int slices, size_t count4,
+                                                       u32x2* __restrict__ C) {
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= count4) return;
+    f32x4 v = P[idx];
+    for (int sl = 1; sl < slices; ++sl) {
+        const f32x4 w = P[(size_t)sl * count4 + idx];
+        v[0] += w[0]; v[1] += w[1]; v[2] += w[2]; v[3] += w[3];
+    }
+    union { __bf16 h[4]; u32x2 u; } o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o.h[e] = (__bf16)v[e];
+    C[idx] = o.u;
+}
+
 // P[c][t][j] = sum over the rows i of slab c of X[t][i] * L[i][j]   (fp32 partial sums of T = X L for
 // up to XL_SMALL_MAX_TOKENS tokens, on MFMA).  L is k-major (rows = d_in), the wrong way round for an
 // MFMA operand, so a slab of it is staged in LDS as stored and read back with the transposing read
@@ -420,9 +644,58 @@ int spmm_stream_rows(int64_t n, int64_t m, int64_t K) {
     return last_round(b48) > last_round(b32) || b48 % RESIDENT == 0 ? 48 : 32;
 }
 
-// n <= 32, K % 64 == 0, K >= 128; T (bf16[n][K2]) and R (bf16[K2][m]) only when K2 > 0
+// Slices of the row-split kernel for n <= 32 tokens (0: the shape stays with the kernel whose wavefronts split the
+// contraction).  Its workgroups are 48 rows each; about three per compute unit keep the chip busy.  With scratch
+// for partial sums (with_partial) a short matrix is cut along the contraction, in whole chunks of 8 pairs of k-steps.
+int spmm_rows_slices(int64_t n, int64_t m, int64_t K, bool with_partial) {
+    if (n > STREAM_MAX_TOKENS || K % 1024 != 0) return 0;
+    const int64_t blocks = (m + ROWS_BM - 1) / ROWS_BM, chunks = K / 1024;
+    int64_t slices = 1;
+    if (with_partial && blocks < 3 * RESIDENT) {
+        slices = (3 * RESIDENT + blocks - 1) / blocks;
+        if (slices > chunks) slices = chunks;
+        const int64_t per = (chunks + slices - 1) / slices;    // chunks per slice; then no slice is empty
+        slices = (chunks + per - 1) / per;
+    }
+    if (blocks * slices < 2 * RESIDENT) return 0;
+    // 17 to 32 tokens: the token operand is then the larger half of what a workgroup loads, and the kernel above
+    // holds its own except where a long contraction over few rows leaves it with too few workgroups
+    // (measured at 32 tokens: 9216 x 36864 121 -> 114 us, but 36864 x 9216 104 -> 108 us and 9216 x 9216 40 -> 43 us)
+    if (n > 16 && slices < 4) return 0;
+    return (int)slices;
+}
+
+size_t spmm_rows_partial_bytes(int64_t n, int64_t m, int64_t K) {
+    const int slices = spmm_rows_slices(n, m, K, true);
+    return slices > 1 ? (size_t)slices * (size_t)n * (size_t)m * 4 : 0;
+}
+
+template <int NF>
+static hipError_t launch_rows(const bf16_t* B, int64_t n, const bf16_t* Av, const uint8_t* Am, int64_t m, int64_t K,
+                              const bf16_t* T, const bf16_t* R, int64_t K2, bf16_t* C, float* partial, int slices,
+                              hipStream_t s) {
+    using S = RowsLds<NF>;
+    static_assert(S::TOTAL <= 160 * 1024, "LDS budget");
+    hipError_t e = allow_dynamic_lds<spmm_rows_kernel<NF>>(S::TOTAL);
+    if (e != hipSuccess) return e;
+    const int64_t chunks = K / 1024, per = (chunks + slices - 1) / slices;
+    spmm_rows_kernel<NF><<<dim3((unsigned)((m + ROWS_BM - 1) / ROWS_BM), (unsigned)slices), dim3(ROWS_WAVES * 64), S::TOTAL, s>>>(
+        B, (int)n, Av, Am, (int)m, (int)K, T, R, (int)K2, C, slices > 1 ? partial : nullptr, (int)(per * 8));
+    if ((e = hipGetLastError()) != hipSuccess || slices == 1) return e;
+    const size_t count4 = (size_t)n * (size_t)m / 4;
+    rows_sum_kernel<<<dim3((unsigned)((count4 + 255) / 256)), dim3(256), 0, s>>>((const f32x4*)partial, slices, count4, (u32x2*)C);
+    return hipGetLastError();
+}
+
+// n <= 32, K % 64 == 0, K >= 128; T (bf16[n][K2]) and R (bf16[K2][m]) only when K2 > 0; partial_or_null: scratch of
+// spmm_rows_partial_bytes(n, m, K) bytes
 hipError_t launch_spmm_stream(const bf16_t* B, int64_t n, const bf16_t* A_vals, const uint8_t* A_meta, int64_t m,
-                              int64_t K, const bf16_t* T, const bf16_t* R, int64_t K2, bf16_t* C, hipStream_t s) {
+                              int64_t K, const bf16_t* T, const bf16_t* R, int64_t K2, bf16_t* C, float* partial_or_null,
+                              hipStream_t s) {
+    const int slices = spmm_rows_slices(n, m, K, partial_or_null != nullptr);
+    if (slices > 0)
+        return n <= 16 ? launch_rows<1>(B, n, A_vals, A_meta, m, K, T, R, K2, C, partial_or_null, slices, s)
+                       : launch_rows<2>(B, n, A_vals, A_meta, m, K, T, R, K2, C, partial_or_null, slices, s);
     const int rows = spmm_stream_rows(n, m, K);
     if (n <= 16) {
         if (rows == 32) return launch_stream_lds<2, 8, 1>(B, n, A_vals, A_meta, m, K, T, R, K2, C, s);

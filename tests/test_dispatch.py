@@ -5,23 +5,45 @@ import pytest
 
 from paper_2405_16325_amd import binding as sl
 
-STREAM, SLABS, TILE, GENERIC = 0, 1, 2, 3
+STREAM, SLABS, TILE, GENERIC, STREAM_ROWS = 0, 1, 2, 3, 4
 
 
 @pytest.mark.parametrize("b", [1, 7, 16, 17, 32])
 @pytest.mark.parametrize("d_out,d_in", [(9216, 9216), (36864, 9216), (9216, 36864), (512, 128)])
-def test_up_to_32_tokens_take_the_small_batch_kernel(b, d_out, d_in):
+def test_up_to_32_tokens_take_a_small_batch_kernel(b, d_out, d_in):
     p = sl.slope_spmm_fwd_plan(b, d_in, d_out)
-    assert p["product"] == STREAM and p["slabs"] == 1
+    assert p["product"] in (STREAM, STREAM_ROWS)
     assert p["tokens"] == (16 if b <= 16 else 32)
-    assert p["rows"] in ((32, 48, 64) if b <= 16 else (32, 48))
+    if p["product"] == STREAM:
+        assert p["slabs"] == 1 and p["rows"] in ((32, 48, 64) if b <= 16 else (32, 48))
+    else:
+        assert p["rows"] == 48 and d_in % 1024 == 0 and p["slabs"] * -(-d_out // 48) >= 512
+
+
+def test_row_split_form_of_the_small_batch_kernel():
+    # a tall matrix: one workgroup per 48 rows fills the chip three times, no slices
+    p = sl.slope_spmm_fwd_plan(16, 9216, 36864)
+    assert (p["product"], p["slabs"]) == (STREAM_ROWS, 1)
+    assert sl.slope_spmm_fwd_plan(16, 9216, 36864, 0, False)["product"] == STREAM_ROWS
+    # 192 workgroups: cut along the contraction with scratch (9 chunks of 1024 -> 3 slices; 36 -> 4), else the
+    # kernel whose wavefronts split the contraction
+    assert (sl.slope_spmm_fwd_plan(16, 9216, 9216)["product"], sl.slope_spmm_fwd_plan(16, 9216, 9216)["slabs"]) == (STREAM_ROWS, 3)
+    assert sl.slope_spmm_fwd_plan(16, 36864, 9216)["slabs"] == 4
+    assert sl.slope_spmm_fwd_plan(16, 9216, 9216, 0, False)["product"] == STREAM
+    # 17 to 32 tokens: only where a long contraction over few rows wants four slices or more
+    assert sl.slope_spmm_fwd_plan(32, 36864, 9216)["product"] == STREAM_ROWS
+    assert sl.slope_spmm_fwd_plan(32, 9216, 9216)["product"] == STREAM
+    assert sl.slope_spmm_fwd_plan(32, 9216, 36864)["product"] == STREAM
+    # contractions that are no multiple of 1024, and matrices too small to fill the chip either way
+    assert sl.slope_spmm_fwd_plan(16, 2560, 36864)["product"] == STREAM
+    assert sl.slope_spmm_fwd_plan(16, 1024, 2048)["product"] == STREAM
 
 
 def test_small_batch_rows_avoid_a_thin_last_round():
     # 9216 rows: 288 workgroups of 32 rows would leave a last round of 32; 192 of 48 rows fit one round
-    assert sl.slope_spmm_fwd_plan(1, 9216, 9216)["rows"] == 48
+    assert sl.slope_spmm_fwd_plan(1, 9216, 9216, 0, False)["rows"] == 48
     # 8192 rows: 256 workgroups of 32 rows are exactly one round
-    assert sl.slope_spmm_fwd_plan(1, 9216, 8192)["rows"] == 32
+    assert sl.slope_spmm_fwd_plan(1, 9216, 8192, 0, False)["rows"] == 32
 
 
 def test_contraction_shorter_than_two_k_steps_stays_off_the_small_batch_kernel():

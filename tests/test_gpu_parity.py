@@ -126,7 +126,14 @@ SKINNY_SHAPES = [(1, 512, 512), (7, 25600, 256), (100, 512, 768), (128, 25600, 2
                  (100, 768, 4096), (200, 4160, 2048), (48, 512, 8192)]   # split over K with partial sums (forward)
 
 
-@pytest.mark.parametrize("b,d_out,d_in", PRODUCT_SHAPES + SKINNY_SHAPES)
+# few tokens and a contraction that is a multiple of 1024: the row-split small-batch kernel.  Tall matrices in one
+# slice (the last workgroup's rows partly outside); short ones cut along the contraction into equal and unequal slices
+# (17 to 32 tokens take it only with four slices or more)
+ROWS_SHAPES = [(5, 24584, 1024), (1, 36864, 2048), (16, 2056, 16384), (17, 4104, 8192), (32, 4104, 7168),
+               (24, 7688, 9216), (3, 9600, 7168), (9, 8200, 3072)]
+
+
+@pytest.mark.parametrize("b,d_out,d_in", PRODUCT_SHAPES + SKINNY_SHAPES + ROWS_SHAPES)
 def test_spmm_fwd(b, d_out, d_in):
     say(f"spmm_fwd b={b} d_out={d_out} d_in={d_in}")
     t, d, mask_r, _ = layer_on_device(b, d_out, d_in, 0, seed=b + d_out)
@@ -137,7 +144,8 @@ def test_spmm_fwd(b, d_out, d_in):
     say(f"  rel_fro {err:.3e}")
 
 
-@pytest.mark.parametrize("b,d_out,d_in", PRODUCT_SHAPES + SKINNY_SHAPES)
+# (the input gradient has no scratch: the row-split kernel only where the transposed weight is tall enough)
+@pytest.mark.parametrize("b,d_out,d_in", PRODUCT_SHAPES + SKINNY_SHAPES + [(5, 1024, 24584), (16, 2048, 36872)])
 def test_spmm_bwd_x(b, d_out, d_in):
     say(f"spmm_bwd_x b={b} d_out={d_out} d_in={d_in}")
     t, d, _, mask_rc = layer_on_device(b, d_out, d_in, 0, seed=b + d_in)
@@ -171,7 +179,10 @@ def test_wgrad_masked(b, d_out, d_in, ws):
                                             (200, 4160, 2048, 64), (100, 768, 4096, 128), (48, 512, 8192, 32), (32, 8320, 256, 64),
                                             (50, 128, 192, 160),
                                             # the MFMA split of X L: several column groups of the rank, token groups of 128
-                                            (130, 512, 768, 288), (500, 1024, 1024, 512), (40, 768, 512, 160), (20, 4160, 640, 96)])
+                                            (130, 512, 768, 288), (500, 1024, 1024, 512), (40, 768, 512, 160), (20, 4160, 640, 96),
+                                            # the row-split small-batch kernel: one slice, several slices
+                                            (12, 24584, 1024, 160), (16, 2056, 16384, 64), (3, 9600, 7168, 32),
+                                            (20, 4104, 8192, 160)])
 def test_spmm_fwd_with_adapter(b, d_out, d_in, r):
     say(f"spmm_fwd adapter b={b} d_out={d_out} d_in={d_in} r={r}")
     t, d, mask_r, _ = layer_on_device(b, d_out, d_in, r, seed=r + b)
