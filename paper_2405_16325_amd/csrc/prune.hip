@@ -147,6 +147,12 @@ __global__ void __launch_bounds__(DP_THREADS) double_prune_kernel(const bf16_t* 
     // dwords of the group's four columns through two byte permutes, whose selectors depend on the metadata nibble
     // alone: bytes 0, 1 for position a, bytes 2, 3 for position b, the constant zero (selector 12) elsewhere.
     __shared__ uint2 sSel[16];
+    // Ranking by table: the six comparisons of a group's four keys (bit 0: 1 beats 0, then 2 beats 0, 3 beats 0,
+    // 2 beats 1, 3 beats 1, 3 beats 2) decide which two rows are kept.  Entry: .x = the byte-permute selector that
+    // picks the kept pair out of the four rows' values (bytes 2 idx, 2 idx + 1 of the eight), .y = the metadata
+    // nibble | the 4-bit set of kept rows << 8.  sNib: the same selector by metadata nibble, for given metadata.
+    __shared__ uint2 sRank[64];
+    __shared__ uint32_t sNib[16];
 
     const int t = threadIdx.x;
     // Workgroup -> tile.  A tile's rows of metadata are 16-byte pieces of 128-byte lines, which 8 neighbours along
@@ -154,7 +160,7 @@ __global__ void __launch_bounds__(DP_THREADS) double_prune_kernel(const bf16_t* 
     // each XCD has its own L2, so with neighbouring tiles on neighbouring workgroup numbers every XCD fetched every
     // such line: as many bytes again as the values.  Instead an XCD takes chunks of 8 x 8 neighbouring tiles, whose
     // rows are 1 KB runs of values in both arrays (measured: 171 -> 157 us at 36864 x 9216; 8 x 4 163, 16 x 8 166,
-    // 8 x 16 161, 8 x 1 180).
+    // 8 x 16 161, 8 x 1 180; chunk after chunk along d_out instead of d_in: 161).
     const uint32_t xcd = blockIdx.x & 7u, slot = blockIdx.x >> 3;
     const uint32_t chunk = (slot / (DP_CHUNK * DP_CHUNK)) * 8 + xcd, within = slot % (DP_CHUNK * DP_CHUNK);
     const uint32_t chunks_x = ((uint32_t)tiles_x + DP_CHUNK - 1) / DP_CHUNK;
@@ -196,6 +202,19 @@ __global__ void __launch_bounds__(DP_THREADS) double_prune_kernel(const bf16_t* 
 #pragma unroll
         for (uint32_t p = 0; p < 4; ++p) src[p] = p == a ? 0x0100u : (p == b ? 0x0302u : 0x0C0Cu);
         sSel[t] = make_uint2(src[0] | (src[1] << 16), src[2] | (src[3] << 16));
+        sNib[t] = 0x01000100u + a * 0x0202u + ((b * 0x0202u) << 16);
+    }
+    if (!GIVEN && t >= 64 && t < 128) {
+        const uint32_t c = t - 64;
+        const uint32_t c01 = c & 1u, c02 = (c >> 1) & 1u, c03 = (c >> 2) & 1u, c12 = (c >> 3) & 1u, c13 = (c >> 4) & 1u,
+                       c23 = (c >> 5) & 1u;
+        // rank = how many of the others come first (larger key, or equal key and lower index); ranks 0 and 1 stay
+        const uint32_t r0 = c01 + c02 + c03, r1 = (1u - c01) + c12 + c13, r2 = (2u - c02 - c12) + c23,
+                       r3 = 3u - c03 - c13 - c23;
+        const uint32_t set = (uint32_t)(r0 < 2u) | ((uint32_t)(r1 < 2u) << 1) | ((uint32_t)(r2 < 2u) << 2) |
+                             ((uint32_t)(r3 < 2u) << 3);
+        const uint32_t nib = nibble_of_pair(set);              // (comparisons that contradict each other: never looked up)
+        sRank[c] = make_uint2(0x01000100u + (nib & 3u) * 0x0202u + (((nib >> 2) * 0x0202u) << 16), nib | (set << 8));
     }
     __syncthreads();
     if (GIVEN) {   // the tile of the given metadata, one nibble per byte: 128 rows (d_in) x 32 groups along d_out
@@ -254,7 +273,7 @@ __global__ void __launch_bounds__(DP_THREADS) double_prune_kernel(const bf16_t* 
         uint32_t x[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) x[k] = r[k][q];
-        uint32_t set2 = 0;                                         // the two 4-bit sets, at bits 0 and 16
+        uint2 picked[2] = {make_uint2(0u, 0u), make_uint2(0u, 0u)};   // the table's entries of the two columns
         if (!GIVEN) {
             uint32_t key[4];
 #pragma unroll
@@ -262,16 +281,10 @@ __global__ void __launch_bounds__(DP_THREADS) double_prune_kernel(const bf16_t* 
             const uint32_t c01 = pk_beats(key[1], key[0], ones), c02 = pk_beats(key[2], key[0], ones),
                            c03 = pk_beats(key[3], key[0], ones), c12 = pk_beats(key[2], key[1], ones),
                            c13 = pk_beats(key[3], key[1], ones), c23 = pk_beats(key[3], key[2], ones);
-            // rank = how many of the others come first (larger key, or equal key and lower index); the halves
-            // hold at most 3, so plain 32-bit arithmetic never carries from one into the other
-            const uint32_t r0 = c01 + c02 + c03;
-            const uint32_t r1 = (0x00010001u - c01) + c12 + c13;
-            const uint32_t r2 = (0x00020002u - c02 - c12) + c23;
-            const uint32_t r3 = 0x00030003u - c03 - c13 - c23;
-            // rank 2 or 3 = pruned: bit 1 of the rank
-            const uint32_t out = ((r0 >> 1) & 0x00010001u) | (r1 & 0x00020002u) | ((r2 << 1) & 0x00040004u) |
-                                 ((r3 << 2) & 0x00080008u);
-            set2 = out ^ 0x000F000Fu;
+            // the six outcomes of either column as the byte offset of its table entry (8 bytes each)
+            const uint32_t code = (c01 << 3) | (c02 << 4) | (c03 << 5) | (c12 << 6) | (c13 << 7) | (c23 << 8);
+            picked[0] = *(const uint2*)((const uint8_t*)sRank + (code & 0x1F8u));
+            picked[1] = *(const uint2*)((const uint8_t*)sRank + (code >> 16));
         }
         // the four rows' values of either column as one 64-bit word
         const uint32_t qlo[2] = {__builtin_amdgcn_perm(x[1], x[0], 0x05040100u), __builtin_amdgcn_perm(x[3], x[2], 0x05040100u)};
@@ -280,17 +293,17 @@ __global__ void __launch_bounds__(DP_THREADS) double_prune_kernel(const bf16_t* 
         for (int h = 0; h < 2; ++h) {
             const int j = 2 * q + h;
             const uint32_t col = 8 * i8 + j;
-            const uint32_t set = h ? set2 >> 16 : set2 & 0xFu;
-            const uint32_t nib = GIVEN ? sG[col * DP_NPITCH + og] : nibble_of_pair(set);
-            // the values of rows idx0 = nib & 3 and idx1 = nib >> 2: bytes 2 idx, 2 idx + 1 of the eight
-            const uint32_t sel = 0x01000100u + (nib & 3u) * 0x0202u + (((nib >> 2) * 0x0202u) << 16);
+            // the values of rows idx0 = nib & 3 and idx1 = nib >> 2
+            const uint32_t sel = GIVEN ? sNib[sG[col * DP_NPITCH + og]] : picked[h].x;
             // a wave's 16 columns x 4 row groups: columns 64 apart would share banks, so the upper 64 swap
             // neighbouring fours of row groups
             sO[col * DP_OPITCH + (og ^ swz)] = h ? __builtin_amdgcn_perm(qhi[1], qhi[0], sel) : __builtin_amdgcn_perm(qlo[1], qlo[0], sel);
-            if (!GIVEN) sN[col * DP_NPITCH + (og ^ swz)] = (uint8_t)nib;
-            if (MASK)
+            if (!GIVEN) sN[col * DP_NPITCH + (og ^ swz)] = (uint8_t)picked[h].y;   // the low byte: the nibble
+            if (MASK) {
+                const uint32_t set = picked[h].y >> 8;
 #pragma unroll
                 for (int k = 0; k < 4; ++k) keep[k] |= (((set >> k) & 1u) & ((cb[k] >> j) & 1u)) << j;
+            }
         }
     }
     if (MASK) {
