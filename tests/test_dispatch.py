@@ -25,11 +25,12 @@ def test_row_split_form_of_the_small_batch_kernel():
     p = sl.slope_spmm_fwd_plan(16, 9216, 36864)
     assert (p["product"], p["slabs"]) == (STREAM_ROWS, 1)
     assert sl.slope_spmm_fwd_plan(16, 9216, 36864, 0, False)["product"] == STREAM_ROWS
-    # 192 workgroups: cut along the contraction with scratch (9 chunks of 1024 -> 3 slices; 36 -> 4), else the
-    # kernel whose wavefronts split the contraction
-    assert (sl.slope_spmm_fwd_plan(16, 9216, 9216)["product"], sl.slope_spmm_fwd_plan(16, 9216, 9216)["slabs"]) == (STREAM_ROWS, 3)
-    assert sl.slope_spmm_fwd_plan(16, 36864, 9216)["slabs"] == 4
-    assert sl.slope_spmm_fwd_plan(16, 9216, 9216, 0, False)["product"] == STREAM
+    # 192 workgroups and a long contraction (36 chunks of 1024): cut into 4 slices with scratch, else the kernel
+    # whose wavefronts split the contraction; 9 chunks are too few to pay for the second launch
+    p = sl.slope_spmm_fwd_plan(16, 36864, 9216)
+    assert (p["product"], p["slabs"]) == (STREAM_ROWS, 4)
+    assert sl.slope_spmm_fwd_plan(16, 36864, 9216, 0, False)["product"] == STREAM
+    assert sl.slope_spmm_fwd_plan(16, 9216, 9216)["product"] == STREAM
     # 17 to 32 tokens: only where a long contraction over few rows wants four slices or more
     assert sl.slope_spmm_fwd_plan(32, 36864, 9216)["product"] == STREAM_ROWS
     assert sl.slope_spmm_fwd_plan(32, 9216, 9216)["product"] == STREAM

@@ -128,9 +128,9 @@ SKINNY_SHAPES = [(1, 512, 512), (7, 25600, 256), (100, 512, 768), (128, 25600, 2
 
 # few tokens and a contraction that is a multiple of 1024: the row-split small-batch kernel.  Tall matrices in one
 # slice (the last workgroup's rows partly outside); short ones cut along the contraction into equal and unequal slices
-# (17 to 32 tokens take it only with four slices or more)
-ROWS_SHAPES = [(5, 24584, 1024), (1, 36864, 2048), (16, 2056, 16384), (17, 4104, 8192), (32, 4104, 7168),
-               (24, 7688, 9216), (3, 9600, 7168), (9, 8200, 3072)]
+# (slices only for contractions of 16384 or more; 17 to 32 tokens take the kernel only with four slices or more)
+ROWS_SHAPES = [(5, 24584, 1024), (1, 36864, 2048), (16, 2056, 16384), (17, 4104, 16384), (32, 4104, 17408),
+               (3, 9600, 16384)]
 
 
 @pytest.mark.parametrize("b,d_out,d_in", PRODUCT_SHAPES + SKINNY_SHAPES + ROWS_SHAPES)
@@ -181,8 +181,8 @@ def test_wgrad_masked(b, d_out, d_in, ws):
                                             # the MFMA split of X L: several column groups of the rank, token groups of 128
                                             (130, 512, 768, 288), (500, 1024, 1024, 512), (40, 768, 512, 160), (20, 4160, 640, 96),
                                             # the row-split small-batch kernel: one slice, several slices
-                                            (12, 24584, 1024, 160), (16, 2056, 16384, 64), (3, 9600, 7168, 32),
-                                            (20, 4104, 8192, 160)])
+                                            (12, 24584, 1024, 160), (16, 2056, 16384, 64), (3, 9600, 16384, 32),
+                                            (20, 4104, 16384, 160)])
 def test_spmm_fwd_with_adapter(b, d_out, d_in, r):
     say(f"spmm_fwd adapter b={b} d_out={d_out} d_in={d_in} r={r}")
     t, d, mask_r, _ = layer_on_device(b, d_out, d_in, r, seed=r + b)
