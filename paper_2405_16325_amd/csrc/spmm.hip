@@ -774,8 +774,12 @@ int spmm_slab_count(int64_t n, int64_t m, int64_t K) {
     const double weight = 1.125 * (double)m * (double)K, cu = 24.0, hbm = 5.0e3;   // bytes, bytes per ns
     int best = 1;
     double best_ns = 1e300;
+    // (a round is counted full at 7/8 of the compute units: on a 9216 x 36864 layer at 128 tokens 7 slabs, 252
+    // workgroups, took 180 us where 6 slabs, 216 workgroups, take 138 us, and 8, 9 and 12 slabs 172, 170 and 149 us;
+    // the cut tail of the weight gradient shows no such step between 224 and 256 workgroups)
+    const int64_t fit = RESIDENT - RESIDENT / 8;
     for (int sl = 1; sl <= 16 && sl * 4 <= quads; ++sl) {
-        const double rounds = (double)((tiles * sl + RESIDENT - 1) / RESIDENT);
+        const double rounds = (double)((tiles * sl + fit - 1) / fit);
         const double ns = rounds * weight / (double)(tiles * sl) / cu
                           + (sl > 1 ? 2.0 * sl * (double)n * (double)m * 4.0 / hbm : 0.0);
         if (ns < best_ns) { best_ns = ns; best = sl; }
