@@ -12,7 +12,8 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("b,d_out,d_in,r", [(2048, 3072, 768, 64), (16, 512, 768, 64), (100, 768, 4096, 0),
-                                            (100, 768, 4096, 64), (300, 1024, 512, 32)])
+                                            (100, 768, 4096, 64), (300, 1024, 512, 32),
+                                            (16, 2056, 16384, 64)])    # row-split small-batch kernel with slices
 def test_captured_step_replays_bit_identically(b, d_out, d_in, r):
     say(f"graph b={b} d_out={d_out} d_in={d_in} r={r}")
     t = inputs.layer_inputs(b, d_out, d_in, max(r, 32), seed=3)

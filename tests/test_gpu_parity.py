@@ -182,7 +182,7 @@ def test_wgrad_masked(b, d_out, d_in, ws):
                                             (130, 512, 768, 288), (500, 1024, 1024, 512), (40, 768, 512, 160), (20, 4160, 640, 96),
                                             # the row-split small-batch kernel: one slice, several slices
                                             (12, 24584, 1024, 160), (16, 2056, 16384, 64), (3, 9600, 16384, 32),
-                                            (20, 4104, 16384, 160)])
+                                            (20, 4104, 16384, 160), (4, 24584, 1024, 512), (1, 36872, 2048, 32)])
 def test_spmm_fwd_with_adapter(b, d_out, d_in, r):
     say(f"spmm_fwd adapter b={b} d_out={d_out} d_in={d_in} r={r}")
     t, d, mask_r, _ = layer_on_device(b, d_out, d_in, r, seed=r + b)

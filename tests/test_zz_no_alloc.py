@@ -17,8 +17,10 @@ pytestmark = pytest.mark.gpu
 
 # (b, d_out, d_in, r) in call order: split over K with partial sums + adapters; the same layer with fewer
 # tokens (small-batch kernel, T = X L from partial sums); many tokens (copy of L in the buffer); a smaller
-# layer without adapters that still takes the split over K; a single token
-SEQUENCE = [(100, 768, 4096, 128), (16, 768, 4096, 128), (700, 512, 768, 64), (48, 512, 8192, 0), (1, 256, 512, 32)]
+# layer without adapters that still takes the split over K; few tokens on a short matrix with a long contraction
+# (row-split small-batch kernel, slices' partial sums in the buffer); a single token
+SEQUENCE = [(100, 768, 4096, 128), (16, 768, 4096, 128), (700, 512, 768, 64), (48, 512, 8192, 0),
+            (16, 2056, 16384, 64), (1, 256, 512, 32)]
 
 
 def test_static_scratch_matches_the_workspace_call_on_successive_shrinking_calls():
