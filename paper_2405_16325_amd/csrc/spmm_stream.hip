@@ -657,10 +657,10 @@ int spmm_rows_slices(int64_t n, int64_t m, int64_t K, bool with_partial) {
         const int64_t per = (chunks + slices - 1) / slices;    // chunks per slice; then no slice is empty
         slices = (chunks + per - 1) / per;
     }
-    if (blocks * slices < 2 * RESIDENT) return 0;
     // slices cost a second launch: worth it only for long contractions (9216 x 36864 at 16 tokens: 107 -> 85 us;
     // 9216 x 9216 gains nothing in 3 slices and loses 1.4 us when its weight comes from the last-level cache)
-    if (slices > 1 && chunks < 16) return 0;
+    if (slices > 1 && chunks < 16) slices = 1;
+    if (blocks * slices < 2 * RESIDENT) return 0;
     // 17 to 32 tokens: the token operand is then the larger half of what a workgroup loads, and the kernel above
     // holds its own except where a long contraction over few rows leaves it with too few workgroups
     // (measured at 32 tokens: 9216 x 36864 121 -> 114 us, but 36864 x 9216 104 -> 108 us and 9216 x 9216 40 -> 43 us)

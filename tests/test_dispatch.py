@@ -35,6 +35,9 @@ def test_row_split_form_of_the_small_batch_kernel():
     assert sl.slope_spmm_fwd_plan(32, 36864, 9216)["product"] == STREAM_ROWS
     assert sl.slope_spmm_fwd_plan(32, 9216, 9216)["product"] == STREAM
     assert sl.slope_spmm_fwd_plan(32, 9216, 36864)["product"] == STREAM
+    # 625 workgroups fill the chip without slices, which 9 chunks would not pay for: the same with and without scratch
+    assert [sl.slope_spmm_fwd_plan(16, 9216, 30000, 0, ws)["slabs"] for ws in (True, False)] == [1, 1]
+    assert sl.slope_spmm_fwd_plan(16, 9216, 30000)["product"] == STREAM_ROWS
     # contractions that are no multiple of 1024, and matrices too small to fill the chip either way
     assert sl.slope_spmm_fwd_plan(16, 2560, 36864)["product"] == STREAM
     assert sl.slope_spmm_fwd_plan(16, 1024, 2048)["product"] == STREAM
