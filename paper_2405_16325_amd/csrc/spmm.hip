@@ -48,11 +48,11 @@ namespace {
 //  - epilogue: a lane holds four consecutive features of one token.  Stored straight from the registers that
 //    is 8 bytes per lane in pieces of 32 contiguous bytes: sixteen rows per instruction, each a partial
 //    line.  So the workgroup's tile goes through LDS (the rings are idle by then) as [token][feature] rows
-//    and leaves in whole rows: 8 bytes per lane, up to 512 contiguous bytes per instruction.
+//    and leaves in whole rows: 16 bytes per lane, up to 512 contiguous bytes per half wavefront.
 //    BNT = tokens of the workgroup's tile, tile_t0 its first token; every thread must make the call.
 //  - with a slab buffer (a split over k, see launch_spmm_slabs): the fp32 accumulators go to
 //    partial[token][feature] instead, 16 bytes per lane, and a reduction kernel finishes.
-template <int MF, int NF, int BMT, int BNT>
+template <int MF, int NF, int BMT, int BNT, int THREADS>
 __device__ __forceinline__ void extend_and_store(f32x4 (&acc)[MF][NF], int f0, int t0, int m, int n, int l16, int lq,
                                                  const bf16_t* __restrict__ B2, const bf16_t* __restrict__ A2,
                                                  int K2, bf16_t* __restrict__ C, uint8_t* smem, int tile_f0,
@@ -167,10 +167,21 @@ __device__ __forceinline__ void extend_and_store(f32x4 (&acc)[MF][NF], int f0, i
             *(u32x2*)(smem + (t0 - tile_t0 + j * 16 + l16) * CP + (f0 - tile_f0 + i * 16 + lq * 4) * 2) = o.u;
         }
     __syncthreads();
-    for (int idx = (int)threadIdx.x; idx < BNT * LPR; idx += (int)blockDim.x) {
-        int row = idx / LPR, c4 = (idx % LPR) * 4;
-        int tok = tile_t0 + row, col = tile_f0 + c4;
-        if (tok < n && col < m) *(u32x2*)(C + (size_t)tok * m + col) = *(const u32x2*)(smem + row * CP + c4 * 2);
+    // 16-byte pieces, all read from LDS before the first is stored (a loop of read, wait, store per piece took
+    // 2.5 us of every tile); m is a multiple of 8, so a piece is inside the row or outside as a whole
+    constexpr int PPR = BMT / 8, PER_THREAD = BNT * PPR / THREADS;   // THREADS = the workgroup's size
+    static_assert(BNT * PPR % THREADS == 0 && LPR == 2 * PPR, "whole pieces per thread");
+    u32x4 piece[PER_THREAD];
+#pragma unroll
+    for (int u = 0; u < PER_THREAD; ++u) {
+        const int idx = (int)threadIdx.x + u * THREADS;
+        piece[u] = *(const u32x4*)(smem + (idx / PPR) * CP + (idx % PPR) * 16);
+    }
+#pragma unroll
+    for (int u = 0; u < PER_THREAD; ++u) {
+        const int idx = (int)threadIdx.x + u * THREADS;
+        const int tok = tile_t0 + idx / PPR, col = tile_f0 + (idx % PPR) * 8;
+        if (tok < n && col < m) *(u32x4*)(C + (size_t)tok * m + col) = piece[u];
     }
 }
 
@@ -335,7 +346,7 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_kernel(const bf16_t* __rest
 
     // the dense extension is added once, by the first slab
     static_assert(BN * (BM * 2 + 16) <= S::TOTAL, "the staged output tile fits in the rings");
-    extend_and_store<MF, NF, BM, BN>(acc, m0 + wm * MF * 16, n0 + wn * NF * 16, m, n, l16, lq, B2, A2,
+    extend_and_store<MF, NF, BM, BN, SPMM_THREADS>(acc, m0 + wm * MF * 16, n0 + wn * NF * 16, m, n, l16, lq, B2, A2,
                                      blockIdx.y == 0 ? K2 : 0, C, smem, m0, n0,
                                      slabs ? slabs + (size_t)blockIdx.y * (size_t)n * (size_t)m : nullptr);
 }
@@ -564,7 +575,7 @@ __global__ void __launch_bounds__(SPMM_THREADS) spmm_split_kernel(const bf16_t* 
 #undef PF_ISSUE
     WAIT_HERE(waitcnt_imm(0, 15));                            // drain the clamped look-ahead loads
     static_assert(S::BN * (S::BM * 2 + 16) <= S::TOTAL, "the staged output tile fits in the rings");
-    extend_and_store<MF, NF, S::BM, S::BN>(acc, m0 + wm * MF * 16, n0 + wn * NF * 16, m, n, l16, lq, B2, A2, K2, C, smem,
+    extend_and_store<MF, NF, S::BM, S::BN, SPMM_THREADS>(acc, m0 + wm * MF * 16, n0 + wn * NF * 16, m, n, l16, lq, B2, A2, K2, C, smem,
                                            m0, n0);
 }
 
@@ -700,7 +711,7 @@ __global__ void __launch_bounds__(256) spmm_generic_kernel(const bf16_t* __restr
 #undef GEN_LOAD
 #undef GEN_STORE
     static_assert(128 * (128 * 2 + 16) <= 2 * S::STAGE, "the staged output tile fits in the stages");
-    extend_and_store<MF, NF, 128, 128>(acc, m0 + wm * MF * 16, n0 + wn * NF * 16, m, n, l16, lq, B2, A2, K2, C, smem, m0,
+    extend_and_store<MF, NF, 128, 128, 256>(acc, m0 + wm * MF * 16, n0 + wn * NF * 16, m, n, l16, lq, B2, A2, K2, C, smem, m0,
                                        n0);
 }
 

@@ -87,7 +87,7 @@ enum { EPI_MASKED_PACKED = 0, EPI_PLAIN = 1 };
 // columns o0 + 16 j (d_out).  A lane's four accumulators are one group of four along d_in of row o: the
 // group's metadata nibble picks the two that W^R keeps.  Stored straight from the registers a pair is a
 // 4-byte piece and an instruction touches sixteen rows; so the workgroup's tile of pairs goes through LDS
-// (the rings are idle) as [d_out row][pair] and leaves in whole rows, 8 bytes per lane.
+// (the rings are idle) as [d_out row][pair] and leaves in whole rows, 16 bytes per lane.
 // BMT x BNT = the workgroup's tile (d_in x d_out) at (tile_c0, tile_o0); every thread must make the call.
 template <int MF, int NF, int BMT, int BNT>
 __device__ __forceinline__ void store_masked_packed(const f32x4 (&acc)[MF][NF], int m, int n, int c0, int o0,
@@ -123,10 +123,21 @@ __device__ __forceinline__ void store_masked_packed(const f32x4 (&acc)[MF][NF], 
         }
     }
     __syncthreads();
-    for (int idx = (int)threadIdx.x; idx < BNT * LPR; idx += (int)blockDim.x) {
-        int row = idx / LPR, c8 = (idx % LPR) * 8;            // 8 bytes = two pairs = eight columns of W
-        int o = tile_o0 + row, col = tile_c0 + c8;
-        if (o < n && col < m) *(u32x2*)(out + (size_t)o * gpitch + (col >> 1)) = *(const u32x2*)(smem + row * CP + c8);
+    // 16-byte pieces (four pairs = sixteen columns of W), all read from LDS before the first is stored; the layers
+    // that come here have d_in % 32 == 0, so a piece is inside the row or outside as a whole
+    constexpr int PPR = BMT / 16, PER_THREAD = BNT * PPR / TN_THREADS;
+    static_assert(BNT * PPR % TN_THREADS == 0 && LPR == 2 * PPR, "whole pieces per thread");
+    u32x4 piece[PER_THREAD];
+#pragma unroll
+    for (int u = 0; u < PER_THREAD; ++u) {
+        const int idx = (int)threadIdx.x + u * TN_THREADS;
+        piece[u] = *(const u32x4*)(smem + (idx / PPR) * CP + (idx % PPR) * 16);
+    }
+#pragma unroll
+    for (int u = 0; u < PER_THREAD; ++u) {
+        const int idx = (int)threadIdx.x + u * TN_THREADS;
+        const int o = tile_o0 + idx / PPR, col = tile_c0 + (idx % PPR) * 16;
+        if (o < n && col < m) *(u32x4*)(out + (size_t)o * gpitch + (col >> 1)) = piece[u];
     }
 }
 
