@@ -61,44 +61,57 @@ __device__ __forceinline__ void extend_and_store(f32x4 (&acc)[MF][NF], int f0, i
         constexpr int PITCH = BMT * 2 + 32;                   // pitch % 128 == 32: the four rows of a transposing
                                                               // read fall on distinct banks
         constexpr int SEG = BMT / 8;                          // 16-byte pieces per staged row
-        const int KR = -K2, nthreads = (int)blockDim.x, tid = (int)threadIdx.x;
+        const int KR = -K2, tid = (int)threadIdx.x;
         const bf16_t* b_row[NF];
 #pragma unroll
         for (int j = 0; j < NF; ++j) b_row[j] = B2 + (size_t)wrap_row(t0 + j * 16 + l16, n) * KR + lq * 8;
         // lane (s = l16, q = lq) points at staged row 8 q + 4 h + s / 4, column 4 (s % 4) of a fragment
         const uint8_t* tr = smem + (8 * lq + (l16 >> 2)) * PITCH + 2 * (f0 - tile_f0 + 4 * (l16 & 3));
+        // pieces of the staged chunk per thread: a compile-time count, so that all of a thread's global loads are
+        // in flight together (a loop of load, wait, LDS store per piece pays the L2 latency once per piece)
+        constexpr int PER = 128 * SEG / THREADS;
+        static_assert(128 * SEG % THREADS == 0, "whole pieces per thread");
         for (int kc = 0; kc < KR; kc += 128) {
             const int kn = KR - kc < 128 ? KR - kc : 128;     // a multiple of 32
-            __syncthreads();                                  // the rings are drained / the last chunk is consumed
-            for (int idx = tid; idx < kn * SEG; idx += nthreads) {
-                int k = idx / SEG, sg = idx % SEG, col = tile_f0 + 8 * sg;
-                u32x4 v = {0u, 0u, 0u, 0u};
-                if (col < m) v = *(const u32x4*)(A2 + (size_t)(kc + k) * m + col);
-                *(u32x4*)(smem + k * PITCH + sg * 16) = v;
+            // the token-side fragments of the whole chunk come straight from global memory: requested first
+            // (steps past the chunk's end re-read the first, unused)
+            AFrag b2[4][NF];
+#pragma unroll
+            for (int st = 0; st < 2; ++st)
+#pragma unroll
+                for (int j = 0; j < NF; ++j) b2[st][j].u = *(const u32x4*)(b_row[j] + kc + (32 * st < kn ? 32 * st : 0));
+            u32x4 piece[PER];
+#pragma unroll
+            for (int u = 0; u < PER; ++u) {
+                const int idx = tid + u * THREADS, k = idx / SEG, col = tile_f0 + 8 * (idx % SEG);
+                piece[u] = (u32x4){0u, 0u, 0u, 0u};
+                if (k < kn && col < m) piece[u] = *(const u32x4*)(A2 + (size_t)(kc + k) * m + col);
             }
-            AFrag b2[2][NF];
+            __syncthreads();                                  // the rings are drained / the last chunk is consumed
 #pragma unroll
-            for (int j = 0; j < NF; ++j) b2[0][j].u = *(const u32x4*)(b_row[j] + kc);
+            for (int u = 0; u < PER; ++u) {
+                const int idx = tid + u * THREADS;
+                *(u32x4*)(smem + (idx / SEG) * PITCH + (idx % SEG) * 16) = piece[u];
+            }
+#pragma unroll
+            for (int st = 2; st < 4; ++st)                    // in the registers the staged pieces have left
+#pragma unroll
+                for (int j = 0; j < NF; ++j) b2[st][j].u = *(const u32x4*)(b_row[j] + kc + (32 * st < kn ? 32 * st : 0));
             __syncthreads();
-            for (int k0 = 0; k0 < kn; k0 += 64) {
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const int kk = k0 + 32 * h;               // uniform
-                    if (kk >= kn) break;
-                    const int knx = kk + 32 < kn ? kk + 32 : kk;
+            for (int st = 0; st < 4; ++st) {
+                const int kk = 32 * st;
+                if (kk >= kn) break;                          // uniform
 #pragma unroll
-                    for (int j = 0; j < NF; ++j) b2[h ^ 1][j].u = *(const u32x4*)(b_row[j] + kc + knx);
+                for (int i = 0; i < MF; ++i) {
+                    union { s16x4 hh[2]; bf16x8 v; } a;
+                    a.hh[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (s16x4 __attribute__((address_space(3)))*)(tr + kk * PITCH + 32 * i));
+                    a.hh[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (s16x4 __attribute__((address_space(3)))*)(tr + (kk + 4) * PITCH + 32 * i));
 #pragma unroll
-                    for (int i = 0; i < MF; ++i) {
-                        union { s16x4 hh[2]; bf16x8 v; } a;
-                        a.hh[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (s16x4 __attribute__((address_space(3)))*)(tr + kk * PITCH + 32 * i));
-                        a.hh[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                            (s16x4 __attribute__((address_space(3)))*)(tr + (kk + 4) * PITCH + 32 * i));
-#pragma unroll
-                        for (int j = 0; j < NF; ++j)
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b2[h][j].v, acc[i][j], 0, 0, 0);
-                    }
+                    for (int j = 0; j < NF; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b2[st][j].v, acc[i][j], 0, 0, 0);
                 }
             }
         }
