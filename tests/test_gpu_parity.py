@@ -174,6 +174,7 @@ def test_wgrad_masked(b, d_out, d_in, ws):
 
 
 @pytest.mark.parametrize("b,d_out,d_in,r", [(2048, 3072, 768, 64), (300, 448, 320, 32), (4100, 4160, 256, 128), (4000, 4032, 256, 128),
+                                            (4000, 4032, 256, 160),   # 256 x 256 tiles, two chunks of R, the second 32 rows
                                             (16, 512, 768, 64), (1, 1280, 256, 32), (32, 4160, 1024, 128), (7, 448, 320, 288),
                                             (16, 8320, 256, 64), (5, 13696, 256, 512),
                                             (200, 4160, 2048, 64), (100, 768, 4096, 128), (48, 512, 8192, 32), (32, 8320, 256, 64),
